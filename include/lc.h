@@ -1,0 +1,133 @@
+/*
+ * lc.h - C ABI of the locally connected autoencoder kernels for AMD MI355X (gfx950).
+ *
+ * The library computes, on one GPU, the per-GPU share of the network of Ni et al.,
+ * "Large-Scale Deep Learning on the YFCC100M Dataset": layers of untied local receptive
+ * fields (Sec. 3.1) trained with the RICA cost of Eq. 1, followed by pooling and local
+ * contrast normalisation.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every data pointer is DEVICE memory owned by the caller.  The library allocates
+ *    nothing and keeps no pointer after a call returns.  Scratch memory, where an entry
+ *    point needs it, is passed in as `ws` / `ws_bytes` (size from lc_workspace_bytes).
+ *  - Data pointers must be 16-byte aligned (LC_EALIGN otherwise).
+ *  - Activations are [B][H][W][C] with C fastest.  A layer's output is [B][LH][LW][F].
+ *    Weights are [LH][LW][K][F], F fastest, with k = (kh*R + kw)*C + c: one K x F matrix
+ *    per location.  LH = floor((H-R)/S)+1, LW likewise (valid fields, no padding; trailing
+ *    rows/columns that no field covers are ignored by the forward pass and receive zero
+ *    from lc_backward_data).
+ *  - `dtype` names the storage type of the x / w / dy operands: LC_F32, or LC_BF16 (bf16
+ *    operands, fp32 accumulation).  Outputs are always fp32.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    only enqueue work; none synchronises.  Arguments are validated on the host before
+ *    anything is launched, so every error except LC_EHIP is returned without touching
+ *    the GPU.
+ *  - Return value: LC_OK (0) or a negative lc_status.  After LC_EHIP,
+ *    lc_last_error() gives the HIP error string (thread-local).
+ */
+#ifndef LC_H_
+#define LC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Layer geometry as Sec. 3.1 states it: mini-batch B, input H x W x C, receptive field
+ * R x R x C, stride S, F filters per location.  Requires all >= 1, R <= H, R <= W. */
+typedef struct {
+    int32_t B, H, W, C, R, S, F;
+} lc_geom_t;
+
+enum lc_status {
+    LC_OK = 0,
+    LC_EINVAL = -1,       /* impossible geometry or scalar argument */
+    LC_ENULL = -2,        /* a required pointer is NULL */
+    LC_EALIGN = -3,       /* a data pointer is not 16-byte aligned */
+    LC_EWORKSPACE = -4,   /* ws is NULL or smaller than lc_workspace_bytes() */
+    LC_EUNSUPPORTED = -5, /* valid request this build has no kernel for */
+    LC_EHIP = -6          /* a HIP call failed; see lc_last_error() */
+};
+
+enum lc_dtype { LC_F32 = 0, LC_BF16 = 1 };
+
+enum lc_op { LC_OP_FORWARD = 0, LC_OP_BACKWARD_DATA = 1, LC_OP_BACKWARD_WEIGHTS = 2, LC_OP_SAE_STEP = 3 };
+
+/* sae_step flags */
+#define LC_SAE_PROJECT_ROWS 1u /* rescale every filter W[l,:,f] to unit L2 norm after the update (constraint of Eq. 1) */
+#define LC_SAE_LEARN_ALPHA 2u  /* alpha takes an SGD step too; otherwise it is only read */
+
+/* Host only.  Writes LH, LW, K = R*R*C (any of the three may be NULL).  LC_EINVAL on bad geometry. */
+int lc_geom_derive(const lc_geom_t *g, int32_t *LH, int32_t *LW, int32_t *K);
+
+/* Host only.  Bytes of scratch the given lc_op needs for this geometry and dtype (0 = none,
+ * then ws may be NULL).  Returns 0 for invalid arguments as well. */
+size_t lc_workspace_bytes(const lc_geom_t *g, int op, int dtype);
+
+/* Forward encoding of one layer, the "alpha W x" of Eq. 1 with the geometry of Sec. 3.1:
+ *   y[b,i,j,f] = alpha * sum_k w[i,j,k,f] * x[b, i*S+kh, j*S+kw, c]  (+ bias[i,j,f] if bias != NULL)
+ * x [B,H,W,C] and w [LH,LW,K,F] in `dtype`; bias [LH,LW,F] fp32 or NULL; y [B,LH,LW,F] fp32, overwritten. */
+int lc_forward(const lc_geom_t *g, const void *x, const void *w, const float *bias, float alpha, float *y,
+               int dtype, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Reconstruction through the transposed filters, the "W^T (.)" of Eq. 1 (also the gradient of
+ * lc_forward with respect to x for alpha = 1):
+ *   dx[b,p,q,c] = sum over locations (i,j) whose field contains (p,q), sum_f w[i,j,k,f] * dy[b,i,j,f]
+ * dy [B,LH,LW,F], w in `dtype`; dx [B,H,W,C] fp32, overwritten everywhere (zero where no field reaches).
+ * Deterministic: no atomics. */
+int lc_backward_data(const lc_geom_t *g, const void *dy, const void *w, float *dx, int dtype, void *ws,
+                     size_t ws_bytes, void *hip_stream);
+
+/* Weight gradient of Eq. 1's terms with respect to the untied filters:
+ *   dw[i,j,k,f] = beta * dw[i,j,k,f] + sum_b x[b, i*S+kh, j*S+kw, c] * dy[b,i,j,f]
+ * beta must be 0 (dw is overwritten, never read) or 1 (accumulate).  x, dy in `dtype`; dw fp32. */
+int lc_backward_weights(const lc_geom_t *g, const void *x, const void *dy, float beta, float *dw, int dtype,
+                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/* L2 pooling (not part of the paper's network, Sec. 3.1 leaves pooling out; provided because the
+ * benchmark workloads chain it after each layer):
+ *   y[b,i,j,c] = sqrt(eps + sum_{p,q<ksize} x[b, i*stride+p, j*stride+q, c]^2), no padding,
+ * x [B,H,W,C] -> y [B,Ho,Wo,C], Ho = floor((H-ksize)/stride)+1.  fp32.  1 <= ksize <= min(H,W), eps >= 0. */
+int l2pool_fwd(const float *x, float *y, int32_t B, int32_t H, int32_t W, int32_t C, int32_t ksize,
+               int32_t stride, float eps, void *hip_stream);
+
+/* Gradient of l2pool_fwd: dx[q] = x[q] * sum over windows containing q of dy/y.  dx [B,H,W,C] overwritten. */
+int l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int32_t B, int32_t H, int32_t W,
+               int32_t C, int32_t ksize, int32_t stride, void *hip_stream);
+
+/* Local contrast normalisation, applied after each layer (Sec. 3.1 names it without defining it;
+ * this is Gaussian-windowed local standardisation with statistics pooled over all channels):
+ *   g[p] ~ exp(-p^2 / (2 gauss_sigma^2)), p = -(ksize-1)/2 .. (ksize-1)/2, window w[p,q] = g[p] g[q];
+ *   mu = weighted mean of x over the window and all C channels, m2 the same for x^2 (window truncated
+ *   at the border and its weights renormalised); rstd = 1/sqrt(max(m2 - mu^2, 0) + eps);
+ *   y[b,i,j,c] = (x[b,i,j,c] - mu[b,i,j]) * rstd[b,i,j].
+ * y [B,H,W,C]; mu, rstd [B,H,W] are outputs kept for lcn_bwd.  ksize odd, 1 <= ksize <= 15. */
+int lcn_fwd(const float *x, float *y, float *mu, float *rstd, int32_t B, int32_t H, int32_t W, int32_t C,
+            int32_t ksize, float gauss_sigma, float eps, void *hip_stream);
+
+/* Gradient of lcn_fwd with respect to x, given the saved mu and rstd (the clamp of the variance at zero is
+ * taken as inactive).  dx [B,H,W,C] overwritten. */
+int lcn_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B,
+            int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma, void *hip_stream);
+
+/* One SGD step on the RICA cost of Eq. 1 for one layer (fp32):
+ *   h = alpha W x;  xh = W^T h + b;  J = (1/B) [ sum (xh - x)^2 + lambda * sum sqrt(h^2 + eps_sparse) ]
+ *   w -= lr dJ/dw (both uses of the tied weights);  b -= lr dJ/db;  alpha -= lr dJ/dalpha if LC_SAE_LEARN_ALPHA;
+ *   then, if LC_SAE_PROJECT_ROWS, every filter w[l,:,f] is rescaled to unit L2 norm.
+ * x [B,H,W,C] read only; w [LH,LW,K,F], b [H,W,C] and the device scalar alpha are updated in place;
+ * h_out (NULL or [B,LH,LW,F]) receives h computed with the weights from before the update;
+ * cost_out is a device scalar that receives J.  Scratch: lc_workspace_bytes(g, LC_OP_SAE_STEP, LC_F32). */
+int sae_step(const lc_geom_t *g, const float *x, float *w, float *b, float *alpha, float lambda,
+             float eps_sparse, float lr, uint32_t flags, float *h_out, float *cost_out, void *ws,
+             size_t ws_bytes, void *hip_stream);
+
+/* Thread-local description of the last LC_EHIP on this thread ("" if none). */
+const char *lc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LC_H_ */

@@ -1,0 +1,146 @@
+// C ABI of the library: argument validation on the host, then dispatch to the kernel launchers.
+#include <stdio.h>
+#include <string.h>
+
+#include "lc_common.hpp"
+
+namespace lc {
+
+static thread_local char g_err[256] = "";
+
+void set_hip_error(hipError_t e, const char *where) {
+    snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+}
+
+static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace lc
+
+using namespace lc;
+
+#define LC_REQUIRE_PTR(p)                 \
+    do {                                  \
+        if (!(p)) return LC_ENULL;        \
+    } while (0)
+#define LC_REQUIRE_ALIGNED(p)                 \
+    do {                                      \
+        if (!aligned16(p)) return LC_EALIGN;  \
+    } while (0)
+
+extern "C" {
+
+int lc_geom_derive(const lc_geom_t *g, int32_t *LH, int32_t *LW, int32_t *K) {
+    Geom q;
+    if (!make_geom(g, &q)) return LC_EINVAL;
+    if (LH) *LH = q.LH;
+    if (LW) *LW = q.LW;
+    if (K) *K = q.K;
+    return LC_OK;
+}
+
+size_t lc_workspace_bytes(const lc_geom_t *g, int op, int dtype) {
+    Geom q;
+    if (!make_geom(g, &q)) return 0;
+    if (dtype != LC_F32 && dtype != LC_BF16) return 0;
+    if (op == LC_OP_SAE_STEP) return sae_workspace_bytes(q);
+    return 0;
+}
+
+const char *lc_last_error(void) { return g_err; }
+
+int lc_forward(const lc_geom_t *g, const void *x, const void *w, const float *bias, float alpha, float *y, int dtype,
+               void *ws, size_t ws_bytes, void *hip_stream) {
+    (void)ws; (void)ws_bytes;
+    Geom q;
+    if (!make_geom(g, &q)) return LC_EINVAL;
+    if (dtype != LC_F32 && dtype != LC_BF16) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(w); LC_REQUIRE_PTR(y);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(w); LC_REQUIRE_ALIGNED(y); LC_REQUIRE_ALIGNED(bias);
+    if (dtype == LC_BF16) return LC_EUNSUPPORTED;
+    return launch_forward_f32(q, (const float *)x, (const float *)w, bias, alpha, nullptr, y, (hipStream_t)hip_stream);
+}
+
+int lc_backward_data(const lc_geom_t *g, const void *dy, const void *w, float *dx, int dtype, void *ws,
+                     size_t ws_bytes, void *hip_stream) {
+    (void)ws; (void)ws_bytes;
+    Geom q;
+    if (!make_geom(g, &q)) return LC_EINVAL;
+    if (dtype != LC_F32 && dtype != LC_BF16) return LC_EINVAL;
+    LC_REQUIRE_PTR(dy); LC_REQUIRE_PTR(w); LC_REQUIRE_PTR(dx);
+    LC_REQUIRE_ALIGNED(dy); LC_REQUIRE_ALIGNED(w); LC_REQUIRE_ALIGNED(dx);
+    if (dtype == LC_BF16) return LC_EUNSUPPORTED;
+    return launch_backward_data_f32(q, (const float *)dy, (const float *)w, dx, (hipStream_t)hip_stream);
+}
+
+int lc_backward_weights(const lc_geom_t *g, const void *x, const void *dy, float beta, float *dw, int dtype, void *ws,
+                        size_t ws_bytes, void *hip_stream) {
+    (void)ws; (void)ws_bytes;
+    Geom q;
+    if (!make_geom(g, &q)) return LC_EINVAL;
+    if (dtype != LC_F32 && dtype != LC_BF16) return LC_EINVAL;
+    if (!(beta == 0.f || beta == 1.f)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(dy); LC_REQUIRE_PTR(dw);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(dy); LC_REQUIRE_ALIGNED(dw);
+    if (dtype == LC_BF16) return LC_EUNSUPPORTED;
+    return launch_backward_weights_f32(q, (const float *)x, (const float *)dy, nullptr, nullptr, beta, 1.f, dw,
+                                       (hipStream_t)hip_stream);
+}
+
+static int check_map(int32_t B, int32_t H, int32_t W, int32_t C) {
+    if (B < 1 || H < 1 || W < 1 || C < 1) return LC_EINVAL;
+    if ((long long)H * W * C > (1LL << 30) || (long long)B * H * W > (1LL << 40)) return LC_EINVAL;
+    return LC_OK;
+}
+
+int l2pool_fwd(const float *x, float *y, int32_t B, int32_t H, int32_t W, int32_t C, int32_t ksize, int32_t stride,
+               float eps, void *hip_stream) {
+    if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;
+    if (ksize < 1 || stride < 1 || ksize > H || ksize > W || !(eps >= 0.f)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(y);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(y);
+    return launch_l2pool_fwd(x, y, B, H, W, C, ksize, stride, eps, (hipStream_t)hip_stream);
+}
+
+int l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int32_t B, int32_t H, int32_t W, int32_t C,
+               int32_t ksize, int32_t stride, void *hip_stream) {
+    if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;
+    if (ksize < 1 || stride < 1 || ksize > H || ksize > W) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(y); LC_REQUIRE_PTR(dy); LC_REQUIRE_PTR(dx);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(y); LC_REQUIRE_ALIGNED(dy); LC_REQUIRE_ALIGNED(dx);
+    return launch_l2pool_bwd(x, y, dy, dx, B, H, W, C, ksize, stride, (hipStream_t)hip_stream);
+}
+
+int lcn_fwd(const float *x, float *y, float *mu, float *rstd, int32_t B, int32_t H, int32_t W, int32_t C,
+            int32_t ksize, float gauss_sigma, float eps, void *hip_stream) {
+    if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;
+    if (ksize < 1 || ksize > 15 || (ksize & 1) == 0 || !(gauss_sigma > 0.f) || !(eps >= 0.f)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(y); LC_REQUIRE_PTR(mu); LC_REQUIRE_PTR(rstd);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(y); LC_REQUIRE_ALIGNED(mu); LC_REQUIRE_ALIGNED(rstd);
+    return launch_lcn(0, x, nullptr, y, mu, rstd, B, H, W, C, ksize, gauss_sigma, eps, (hipStream_t)hip_stream);
+}
+
+int lcn_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B, int32_t H,
+            int32_t W, int32_t C, int32_t ksize, float gauss_sigma, void *hip_stream) {
+    if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;
+    if (ksize < 1 || ksize > 15 || (ksize & 1) == 0 || !(gauss_sigma > 0.f)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(mu); LC_REQUIRE_PTR(rstd); LC_REQUIRE_PTR(dy); LC_REQUIRE_PTR(dx);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(mu); LC_REQUIRE_ALIGNED(rstd); LC_REQUIRE_ALIGNED(dy); LC_REQUIRE_ALIGNED(dx);
+    return launch_lcn(1, x, dy, dx, const_cast<float *>(mu), const_cast<float *>(rstd), B, H, W, C, ksize, gauss_sigma,
+                      0.f, (hipStream_t)hip_stream);
+}
+
+int sae_step(const lc_geom_t *g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
+             float lr, uint32_t flags, float *h_out, float *cost_out, void *ws, size_t ws_bytes, void *hip_stream) {
+    Geom q;
+    if (!make_geom(g, &q)) return LC_EINVAL;
+    if (!(lambda >= 0.f) || !(eps_sparse >= 0.f) || !(lr == lr) || (flags & ~3u)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(w); LC_REQUIRE_PTR(b); LC_REQUIRE_PTR(alpha); LC_REQUIRE_PTR(cost_out);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(w); LC_REQUIRE_ALIGNED(b); LC_REQUIRE_ALIGNED(h_out);
+    if (((uintptr_t)alpha & 3u) || ((uintptr_t)cost_out & 3u)) return LC_EALIGN;
+    if (!ws || ws_bytes < sae_workspace_bytes(q)) return LC_EWORKSPACE;
+    LC_REQUIRE_ALIGNED(ws);
+    return launch_sae_step(q, x, w, b, alpha, lambda, eps_sparse, lr, flags, h_out, cost_out, ws,
+                           (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,202 @@
+// lc_backward_data: dx[b,p] = sum over fields l containing pixel p, sum_f w[l,k(p,l),f] * dy[b,l,f]
+// (Eq. 1's reconstruction "W^T h": the overlap-add of every field's back-projection).
+//
+// Gather form, no atomics.  The image is cut into S x S x C "cells" (cell (ri,wi) = rows ri*S..ri*S+S-1,
+// columns wi*S..wi*S+S-1).  All pixels of a cell are covered by the same fields (ri-a, wi-a'),
+// a, a' < ceil(R/S), and inside field (ri-a, wi-a') the cell is the patch block kh = S*a+dr,
+// kw = S*a'+dw.  So one cell is a dense contraction
+//     dx_cell[b][n=(dr,dw,c)] = sum_{a,a',f} dy[b][(ri-a,wi-a')][f] * w[(ri-a,wi-a')][k(a,a',n)][f]
+// of length ceil(R/S)^2 * F, in which every weight is used exactly once.
+//
+// A workgroup (4 waves) owns NCELL horizontally adjacent cells x 4/NCELL blocks of 16*NT cell values
+// and a batch tile of 16*MT images.  dy of the covering fields of one field row is staged in LDS and
+// shared by the waves (adjacent cells share most of their fields).  Weights go straight from global
+// memory into the MFMA B operand: lane (n,kk) reads VF consecutive f of row k(n), and the A operand
+// reads the matching f of dy from LDS, so the contraction index of the MFMA is a permutation of f.
+#include "lc_common.hpp"
+
+namespace lc {
+
+template <int MT, int NT, int NCELL, int VF>
+__global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *__restrict__ dy,
+                                                          const float *__restrict__ w, float *__restrict__ dx,
+                                                          int strips_per_row, int AP, int fcs, int rs) {
+    constexpr int BT = 16 * MT, NNW = 4 / NCELL;
+    extern __shared__ __attribute__((aligned(16))) float dys[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, kk = lane >> 4;
+    const int FC = 1 << fcs, JW = NCELL + AP - 1, SC = g.S * g.C, NCV = g.S * SC;
+    const int work = remap_xcd(blockIdx.x, gridDim.x);
+    const int ri = work / strips_per_row, wi0 = (work - ri * strips_per_row) * NCELL;
+    const int b0 = blockIdx.z * BT;
+    const int wc = wave % NCELL, wn = wave / NCELL;
+    const int wi = wi0 + wc;
+    const int CW = (g.W + g.S - 1) / g.S;
+    const int n0 = (blockIdx.y * NNW + wn) * NT * 16;
+    const bool active = (wi < CW) && (n0 < NCV);
+
+    // per-lane decomposition of the cell values this lane supplies weights for
+    int dr[NT], dwv[NT], kn[NT];
+    bool nok[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int n = n0 + nt * 16 + m;
+        nok[nt] = active && n < NCV;
+        const int nc = nok[nt] ? n : 0;
+        dr[nt] = nc / SC;
+        const int rem = nc - dr[nt] * SC;
+        dwv[nt] = rem / g.C;
+        kn[nt] = dr[nt] * g.RC + rem;
+    }
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const int rowlen = JW * FC;                            // staged floats per image
+    const int q_first = tid % rowlen, b_first = tid / rowlen, dq = 256 % rowlen, db = 256 / rowlen;
+    const int jlo = wi0 - (AP - 1);
+    const size_t dyimg = (size_t)g.L * g.F;
+
+    for (int a = 0; a < AP; ++a) {
+        const int i = ri - a;
+        if (i < 0 || i >= g.LH) continue;                  // uniform over the workgroup
+        for (int fc0 = 0; fc0 < g.F; fc0 += FC) {
+            __syncthreads();
+            {
+                int q = q_first, bb = b_first;
+                while (bb < BT) {
+                    const int js = q >> fcs, f = fc0 + (q & (FC - 1)), j = jlo + js;
+                    float v = 0.f;
+                    if (j >= 0 && j < g.LW && f < g.F && b0 + bb < g.B)
+                        v = dy[(size_t)(b0 + bb) * dyimg + (size_t)(i * g.LW + j) * g.F + f];
+                    dys[bb * rs + q] = v;
+                    q += dq;
+                    bb += db;
+                    if (q >= rowlen) { q -= rowlen; ++bb; }
+                }
+            }
+            __syncthreads();
+            if (!active) continue;
+            for (int ap = 0; ap < AP; ++ap) {
+                const int j = wi - ap;
+                if (j < 0 || j >= g.LW) continue;          // uniform over the wave
+                const int js = wc - ap + AP - 1;
+                const float *wl = w + ((size_t)(i * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F + fc0;
+                bool ok[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    ok[nt] = nok[nt] && (g.S * a + dr[nt] < g.R) && (g.S * ap + dwv[nt] < g.R);
+                const float *arow = dys + m * rs + js * FC + VF * kk;
+                for (int fq = 0; fq < FC; fq += 4 * VF) {
+                    if (fc0 + fq >= g.F) break;
+                    float av[MT][VF], bv[NT][VF];
+                    const int fl = fq + VF * kk;           // this lane's first f inside the chunk
+                    if (VF == 4) {
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                            if (ok[nt] && fc0 + fl < g.F) t = *(const float4 *)(wl + (size_t)kn[nt] * g.F + fl);
+                            bv[nt][0] = t.x; bv[nt][1 % VF] = t.y; bv[nt][2 % VF] = t.z; bv[nt][3 % VF] = t.w;
+                        }
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) {
+                            const float4 t = *(const float4 *)(arow + mt * 16 * rs + fq);
+                            av[mt][0] = t.x; av[mt][1 % VF] = t.y; av[mt][2 % VF] = t.z; av[mt][3 % VF] = t.w;
+                        }
+                    } else {
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            bv[nt][0] = (ok[nt] && fc0 + fl < g.F) ? wl[(size_t)kn[nt] * g.F + fl] : 0.f;
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) av[mt][0] = arow[mt * 16 * rs + fq];
+                    }
+#pragma unroll
+                    for (int t = 0; t < VF; ++t)
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16(av[mt][t], bv[nt][t], acc[mt][nt]);
+                }
+            }
+        }
+    }
+
+    if (!active) return;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        if (!nok[nt]) continue;
+        const int row = ri * g.S + dr[nt], col = wi * g.S + dwv[nt];
+        if (row >= g.H || col >= g.W) continue;
+        const int rem = kn[nt] - dr[nt] * g.RC;            // dw*C + c
+        const size_t pix = ((size_t)row * g.W + wi * g.S) * g.C + rem;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int b = b0 + mt * 16 + 4 * kk + r;
+                if (b < g.B) dx[(size_t)b * g.H * g.W * g.C + pix] = acc[mt][nt][r];
+            }
+    }
+}
+
+namespace {
+
+constexpr size_t kLdsTarget = 78 * 1024;
+
+int row_stride(int rowlen, int vf) {
+    // VF=4: lanes of one image row read 16 B each; stride == 4 (mod 32) spreads 8 rows over all banks.
+    // VF=1: stride == 2 (mod 32), as in the forward kernel.
+    const int res = vf == 4 ? 4 : 2;
+    return ((rowlen + 31) / 32) * 32 + res;
+}
+
+template <int MT, int NT, int NCELL, int VF>
+int launch_one(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    constexpr int BT = 16 * MT, NNW = 4 / NCELL;
+    const int AP = (g.R + g.S - 1) / g.S, JW = NCELL + AP - 1;
+    const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
+    const int NCV = g.S * g.S * g.C;
+    // f chunk: the largest power of two (>= 4*VF) that covers F or still fits the LDS budget
+    int fcs = VF == 4 ? 4 : 2;
+    while ((1 << fcs) < g.F && (size_t)BT * row_stride(JW << (fcs + 1), VF) * 4 <= kLdsTarget) ++fcs;
+    const int rs = row_stride(JW << fcs, VF);
+    const size_t lds = (size_t)BT * rs * sizeof(float);
+    if (lds > 160 * 1024) return LC_EUNSUPPORTED;
+    auto kern = lc_bwd_data_kernel<MT, NT, NCELL, VF>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) { set_hip_error(e, "lc_backward_data: hipFuncSetAttribute"); return LC_EHIP; }
+    }
+    const int strips = (CW + NCELL - 1) / NCELL;
+    dim3 grid(strips * CH, (NCV + NNW * NT * 16 - 1) / (NNW * NT * 16), (g.B + BT - 1) / BT);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, AP, fcs, rs);
+    LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
+    return LC_OK;
+}
+
+template <int MT>
+int launch_mt(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    const int ntt = (g.S * g.S * g.C + 15) / 16;  // tiles of 16 cell values
+    if ((g.F & 3) != 0) return launch_one<MT, 4, 1, 1>(g, dy, w, dx, s);
+    if (ntt == 1) return launch_one<MT, 1, 4, 4>(g, dy, w, dx, s);
+    if (ntt == 2) return launch_one<MT, 2, 4, 4>(g, dy, w, dx, s);
+    if (ntt == 3) return launch_one<MT, 3, 4, 4>(g, dy, w, dx, s);
+    if (ntt == 4) return launch_one<MT, 4, 4, 4>(g, dy, w, dx, s);
+    if (ntt <= 8) return launch_one<MT, 4, 2, 4>(g, dy, w, dx, s);
+    if (ntt % 16 > 12 || ntt % 16 == 0) return launch_one<MT, 4, 1, 4>(g, dy, w, dx, s);
+    return launch_one<MT, 3, 1, 4>(g, dy, w, dx, s);
+}
+
+}  // namespace
+
+int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    if (g.B > 64) return launch_mt<8>(g, dy, w, dx, s);
+    if (g.B > 32) return launch_mt<4>(g, dy, w, dx, s);
+    if (g.B > 16) return launch_mt<2>(g, dy, w, dx, s);
+    return launch_mt<1>(g, dy, w, dx, s);
+}
+
+}  // namespace lc

@@ -1,0 +1,87 @@
+// Shared host/device helpers of the HIP path: derived geometry, MFMA wrappers, launch bookkeeping.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/lc.h"
+
+namespace lc {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Layer geometry with the derived sizes (Sec. 3.1: valid fields of size R at stride S).
+struct Geom {
+    int B, H, W, C, R, S, F;
+    int LH, LW, L, K, RC;  // RC = R*C: one patch row, contiguous in an [H][W][C] image
+};
+
+inline bool make_geom(const lc_geom_t *g, Geom *o) {
+    if (!g) return false;
+    if (g->B < 1 || g->H < 1 || g->W < 1 || g->C < 1 || g->R < 1 || g->S < 1 || g->F < 1) return false;
+    if (g->R > g->H || g->R > g->W) return false;
+    o->B = g->B; o->H = g->H; o->W = g->W; o->C = g->C; o->R = g->R; o->S = g->S; o->F = g->F;
+    o->LH = (g->H - g->R) / g->S + 1;
+    o->LW = (g->W - g->R) / g->S + 1;
+    o->L = o->LH * o->LW;
+    const long long K = (long long)g->R * g->R * g->C;
+    if (K > (1 << 24)) return false;
+    o->K = (int)K;
+    o->RC = g->R * g->C;
+    // element counts must stay inside 31-bit indices (the kernels index with 32-bit offsets per image / location
+    // and 64-bit bases)
+    const long long img = (long long)g->H * g->W * g->C;
+    const long long wl = K * g->F;
+    if (img > (1LL << 30) || wl > (1LL << 30) || (long long)o->L * g->F > (1LL << 30)) return false;
+    return true;
+}
+
+// MI355X: 256 compute units in 8 XCDs; consecutive workgroup ids go to consecutive XCDs.
+// remap_xcd turns a hardware workgroup id into a work index such that each XCD walks a
+// contiguous range of work (neighbouring work items share image rows and thus L2 lines).
+constexpr int kXcds = 8;
+__device__ __forceinline__ int remap_xcd(int wg, int n_wg) {
+    const int per = (n_wg + kXcds - 1) / kXcds;
+    const int full = n_wg - (per - 1) * kXcds;  // number of XCDs that get `per` items (1..8)
+    const int xcd = wg % kXcds, slot = wg / kXcds;
+    // XCDs [0,full) own `per` items each, the rest own per-1
+    const int start = xcd < full ? xcd * per : full * per + (xcd - full) * (per - 1);
+    return start + slot;
+}
+
+// v_mfma_f32_16x16x4_f32: D[16x16] += A[16x4] * B[4x16].
+// Lane l supplies A[l%16][l/16] and B[l/16][l%16]; it receives D[4*(l/16)+r][l%16] in component r.
+__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+void set_hip_error(hipError_t e, const char *where);
+
+#define LC_HIP_LAUNCH_CHECK(where)                       \
+    do {                                                 \
+        hipError_t e__ = hipGetLastError();              \
+        if (e__ != hipSuccess) {                         \
+            lc::set_hip_error(e__, where);               \
+            return LC_EHIP;                              \
+        }                                                \
+    } while (0)
+
+// kernels' host launchers (one per translation unit)
+// alpha_dev (nullable): device scalar that overrides alpha
+int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                       const float *alpha_dev, float *y, hipStream_t s);
+int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int ks, int st, float eps, hipStream_t s);
+int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int B, int H, int W, int C, int ks,
+                      int st, hipStream_t s);
+// mode 0: forward (out = y; mu, rstd written).  mode 1: backward (out = dx; mu, rstd read).
+int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
+               int C, int ks, float sigma, float eps, hipStream_t s);
+size_t sae_workspace_bytes(const Geom &g);
+int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
+                    float lr, uint32_t flags, float *h_out, float *cost_out, void *ws, hipStream_t s);
+int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s);
+// out[l,k,f] = beta*out + gamma * sum over pairs p of sum_b patch(x_p)[b,l,k] * dy_p[b,l,f]; x2/dy2 may be NULL
+int launch_backward_weights_f32(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2,
+                                float beta, float gamma, float *out, hipStream_t s);
+
+}  // namespace lc

@@ -1,0 +1,321 @@
+// L2 pooling and local contrast normalisation, forward and backward.  Bandwidth-bound stencils over
+// [B][H][W][C] activations: every kernel reads its inputs once from HBM (neighbour re-reads are served
+// by L1/L2) and writes its output once.
+//
+// Pooling is not part of the paper's network (Sec. 3.1 leaves it out); LCN is applied after each layer
+// (Sec. 3.1) and is taken here as Gaussian-windowed local standardisation with statistics pooled over
+// the channels: the channel sums are wavefront reductions, the window sums a small LDS stencil.
+#include "lc_common.hpp"
+
+namespace lc {
+
+// ------------------------------------------------------------------ L2 pooling
+template <int VEC>
+__global__ __launch_bounds__(256) void l2pool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int B,
+                                                         int H, int W, int C, int Ho, int Wo, int ks, int st,
+                                                         float eps, long long total) {
+    const int CV = C / VEC;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const int cv = (int)(e % CV);
+        long long t = e / CV;
+        const int j = (int)(t % Wo);
+        t /= Wo;
+        const int i = (int)(t % Ho), b = (int)(t / Ho);
+        const float *xp = x + (((size_t)b * H + (size_t)i * st) * W + (size_t)j * st) * C + cv * VEC;
+        float s[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) s[v] = 0.f;
+        for (int p = 0; p < ks; ++p)
+            for (int q = 0; q < ks; ++q) {
+                const float *src = xp + ((size_t)p * W + q) * C;
+                if (VEC == 4) {
+                    const float4 t4 = *(const float4 *)src;
+                    s[0] += t4.x * t4.x; s[1 % VEC] += t4.y * t4.y; s[2 % VEC] += t4.z * t4.z; s[3 % VEC] += t4.w * t4.w;
+                } else {
+                    s[0] += src[0] * src[0];
+                }
+            }
+        float *dst = y + (size_t)e * VEC;
+        if (VEC == 4)
+            *(float4 *)dst = make_float4(sqrtf(eps + s[0]), sqrtf(eps + s[1 % VEC]), sqrtf(eps + s[2 % VEC]),
+                                         sqrtf(eps + s[3 % VEC]));
+        else
+            dst[0] = sqrtf(eps + s[0]);
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(256) void l2pool_bwd_kernel(const float *__restrict__ x, const float *__restrict__ y,
+                                                         const float *__restrict__ dy, float *__restrict__ dx, int B,
+                                                         int H, int W, int C, int Ho, int Wo, int ks, int st,
+                                                         long long total) {
+    const int CV = C / VEC;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const int cv = (int)(e % CV);
+        long long t = e / CV;
+        const int col = (int)(t % W);
+        t /= W;
+        const int row = (int)(t % H), b = (int)(t / H);
+        // windows (i,j) with i*st <= row < i*st+ks
+        const int i_hi = min(row / st, Ho - 1), j_hi = min(col / st, Wo - 1);
+        const int i_lo = max(0, (row - ks + st) / st), j_lo = max(0, (col - ks + st) / st);
+        float s[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) s[v] = 0.f;
+        for (int i = i_lo; i <= i_hi; ++i)
+            for (int j = j_lo; j <= j_hi; ++j) {
+                const size_t o = (((size_t)b * Ho + i) * Wo + j) * C + cv * VEC;
+                if (VEC == 4) {
+                    const float4 g4 = *(const float4 *)(dy + o), y4 = *(const float4 *)(y + o);
+                    s[0] += g4.x / y4.x; s[1 % VEC] += g4.y / y4.y; s[2 % VEC] += g4.z / y4.z; s[3 % VEC] += g4.w / y4.w;
+                } else {
+                    s[0] += dy[o] / y[o];
+                }
+            }
+        const size_t xo = (size_t)e * VEC;
+        if (VEC == 4) {
+            const float4 x4 = *(const float4 *)(x + xo);
+            *(float4 *)(dx + xo) = make_float4(x4.x * s[0], x4.y * s[1 % VEC], x4.z * s[2 % VEC], x4.w * s[3 % VEC]);
+        } else {
+            dx[xo] = x[xo] * s[0];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------ LCN
+constexpr int kLcnTile = 16;   // output tile edge
+constexpr int kLcnMaxK = 15;   // largest window
+constexpr int kLcnHalo = kLcnTile + kLcnMaxK - 1;
+
+struct GaussTaps { float g[kLcnMaxK]; };
+
+__device__ __forceinline__ float group_sum(float v, int lpp) {
+    for (int o = lpp >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// sum of the taps that stay inside [0,n) around position p
+__device__ __forceinline__ float tap_norm(const GaussTaps &t, int p, int n, int r) {
+    float z = 0.f;
+    for (int d = -r; d <= r; ++d)
+        if (p + d >= 0 && p + d < n) z += t.g[d + r];
+    return z;
+}
+
+// MODE 0: forward.  MODE 1: backward (x, mu, rstd, dy -> dx).
+template <int VEC, int MODE>
+__global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, const float *__restrict__ dy,
+                                                  float *__restrict__ out, float *__restrict__ mu,
+                                                  float *__restrict__ rstd, int H, int W, int C, int ks, float eps,
+                                                  GaussTaps taps, int lpp, int tiles_w, int tiles_per_img) {
+    __shared__ float m1[kLcnHalo * kLcnHalo], m2[kLcnHalo * kLcnHalo];
+    __shared__ float t1[kLcnTile * kLcnTile], t2[kLcnTile * kLcnTile];
+    const int r = (ks - 1) / 2, halo = kLcnTile + 2 * r;
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x / tiles_per_img, tile = blockIdx.x - b * tiles_per_img;
+    const int ti = (tile / tiles_w) * kLcnTile, tj = (tile % tiles_w) * kLcnTile;
+    const int CV = C / VEC;
+    const size_t img = (size_t)b * H * W;
+
+    // phase 1: per-pixel channel sums over the tile and its halo; lpp lanes share a pixel
+    const int grp = tid / lpp, gl = tid % lpp, ngrp = 256 / lpp;
+    for (int hp = grp; hp < halo * halo; hp += ngrp) {
+        const int hi = hp / halo, hj = hp - hi * halo;
+        const int row = ti - r + hi, col = tj - r + hj;
+        float a = 0.f, c2 = 0.f;
+        const bool in = row >= 0 && row < H && col >= 0 && col < W;
+        if (in) {
+            const size_t pix = img + (size_t)row * W + col;
+            const float *xp = x + pix * C;
+            if (MODE == 0) {
+                for (int cv = gl; cv < CV; cv += lpp) {
+                    if (VEC == 4) {
+                        const float4 v = *(const float4 *)(xp + cv * 4);
+                        a += (v.x + v.y) + (v.z + v.w);
+                        c2 += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+                    } else {
+                        a += xp[cv];
+                        c2 += xp[cv] * xp[cv];
+                    }
+                }
+            } else {
+                const float *gp = dy + pix * C;
+                const float mp = mu[pix];
+                for (int cv = gl; cv < CV; cv += lpp) {
+                    if (VEC == 4) {
+                        const float4 v = *(const float4 *)(xp + cv * 4), d = *(const float4 *)(gp + cv * 4);
+                        a += (d.x + d.y) + (d.z + d.w);
+                        c2 += (d.x * (v.x - mp) + d.y * (v.y - mp)) + (d.z * (v.z - mp) + d.w * (v.w - mp));
+                    } else {
+                        a += gp[cv];
+                        c2 += gp[cv] * (xp[cv] - mp);
+                    }
+                }
+            }
+        }
+        a = group_sum(a, lpp);
+        c2 = group_sum(c2, lpp);
+        if (gl == 0) {
+            if (MODE == 0) {
+                m1[hp] = a;
+                m2[hp] = c2;
+            } else {
+                // backward: fold this pixel's own normaliser and statistics into the two maps the
+                // transposed window sums need
+                float p1 = 0.f, p2 = 0.f;
+                if (in) {
+                    const size_t pix = img + (size_t)row * W + col;
+                    const float rs = rstd[pix], mp = mu[pix];
+                    const float z = tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r) * (float)C;
+                    const float bc = rs * rs * rs * c2;
+                    p1 = (bc * mp - rs * a) / z;
+                    p2 = bc / z;
+                }
+                m1[hp] = p1;
+                m2[hp] = p2;
+            }
+        }
+    }
+    __syncthreads();
+
+    // phase 2: window sums, one thread per output pixel
+    {
+        const int oi = tid / kLcnTile, oj = tid % kLcnTile;
+        const int row = ti + oi, col = tj + oj;
+        if (row < H && col < W) {
+            float s1 = 0.f, s2 = 0.f;
+            for (int p = 0; p < ks; ++p)
+                for (int q = 0; q < ks; ++q) {
+                    const float wt = taps.g[p] * taps.g[q];
+                    const int hp = (oi + p) * halo + oj + q;
+                    s1 += wt * m1[hp];   // out-of-image halo entries are zero
+                    s2 += wt * m2[hp];
+                }
+            if (MODE == 0) {
+                const float z = tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r) * (float)C;
+                const float m = s1 / z, q2 = s2 / z;
+                const float var = fmaxf(q2 - m * m, 0.f);
+                const float rs = 1.0f / sqrtf(var + eps);
+                const size_t pix = img + (size_t)row * W + col;
+                mu[pix] = m;
+                rstd[pix] = rs;
+                t1[tid] = m;
+                t2[tid] = rs;
+            } else {
+                t1[tid] = s1;
+                t2[tid] = s2;
+            }
+        }
+    }
+    __syncthreads();
+
+    // phase 3: elementwise pass over the tile
+    for (int e = tid; e < kLcnTile * kLcnTile * CV; e += 256) {
+        const int cv = e % CV, op = e / CV;
+        const int oi = op / kLcnTile, oj = op % kLcnTile;
+        const int row = ti + oi, col = tj + oj;
+        if (row >= H || col >= W) continue;
+        const size_t pix = img + (size_t)row * W + col;
+        const size_t o = pix * C + cv * VEC;
+        const float u = t1[op], v = t2[op];
+        if (MODE == 0) {
+            if (VEC == 4) {
+                const float4 xv = *(const float4 *)(x + o);
+                *(float4 *)(out + o) = make_float4((xv.x - u) * v, (xv.y - u) * v, (xv.z - u) * v, (xv.w - u) * v);
+            } else {
+                out[o] = (x[o] - u) * v;
+            }
+        } else {
+            const float rs = rstd[pix];
+            if (VEC == 4) {
+                const float4 xv = *(const float4 *)(x + o), d = *(const float4 *)(dy + o);
+                *(float4 *)(out + o) = make_float4(d.x * rs + u - xv.x * v, d.y * rs + u - xv.y * v,
+                                                   d.z * rs + u - xv.z * v, d.w * rs + u - xv.w * v);
+            } else {
+                out[o] = dy[o] * rs + u - x[o] * v;
+            }
+        }
+    }
+}
+
+namespace {
+
+int grid_for(long long total) {
+    long long blocks = (total + 255) / 256;
+    const long long cap = 256LL * 32;  // 32 workgroups per compute unit, grid-stride beyond that
+    return (int)(blocks < cap ? (blocks > 0 ? blocks : 1) : cap);
+}
+
+bool make_taps(int ks, float sigma, GaussTaps *t) {
+    if (ks < 1 || ks > kLcnMaxK || (ks & 1) == 0 || !(sigma > 0.f)) return false;
+    const int r = (ks - 1) / 2;
+    double s = 0.0, g[kLcnMaxK];
+    for (int p = -r; p <= r; ++p) {
+        g[p + r] = exp(-(double)(p * p) / (2.0 * (double)sigma * (double)sigma));
+        s += g[p + r];
+    }
+    for (int p = 0; p < kLcnMaxK; ++p) t->g[p] = p < ks ? (float)(g[p] / s) : 0.f;
+    return true;
+}
+
+int lanes_per_pixel(int cv) {
+    int l = 1;
+    while (l < cv && l < 64) l <<= 1;
+    return l;
+}
+
+}  // namespace
+
+int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int ks, int st, float eps,
+                      hipStream_t s) {
+    const int Ho = (H - ks) / st + 1, Wo = (W - ks) / st + 1;
+    if (C % 4 == 0) {
+        const long long total = (long long)B * Ho * Wo * (C / 4);
+        hipLaunchKernelGGL(l2pool_fwd_kernel<4>, dim3(grid_for(total)), dim3(256), 0, s, x, y, B, H, W, C, Ho, Wo, ks,
+                           st, eps, total);
+    } else {
+        const long long total = (long long)B * Ho * Wo * C;
+        hipLaunchKernelGGL(l2pool_fwd_kernel<1>, dim3(grid_for(total)), dim3(256), 0, s, x, y, B, H, W, C, Ho, Wo, ks,
+                           st, eps, total);
+    }
+    LC_HIP_LAUNCH_CHECK("l2pool_fwd launch");
+    return LC_OK;
+}
+
+int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int B, int H, int W, int C, int ks,
+                      int st, hipStream_t s) {
+    const int Ho = (H - ks) / st + 1, Wo = (W - ks) / st + 1;
+    if (C % 4 == 0) {
+        const long long total = (long long)B * H * W * (C / 4);
+        hipLaunchKernelGGL(l2pool_bwd_kernel<4>, dim3(grid_for(total)), dim3(256), 0, s, x, y, dy, dx, B, H, W, C, Ho,
+                           Wo, ks, st, total);
+    } else {
+        const long long total = (long long)B * H * W * C;
+        hipLaunchKernelGGL(l2pool_bwd_kernel<1>, dim3(grid_for(total)), dim3(256), 0, s, x, y, dy, dx, B, H, W, C, Ho,
+                           Wo, ks, st, total);
+    }
+    LC_HIP_LAUNCH_CHECK("l2pool_bwd launch");
+    return LC_OK;
+}
+
+int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
+               int C, int ks, float sigma, float eps, hipStream_t s) {
+    GaussTaps taps;
+    if (!make_taps(ks, sigma, &taps)) return LC_EINVAL;
+    const int tiles_h = (H + kLcnTile - 1) / kLcnTile, tiles_w = (W + kLcnTile - 1) / kLcnTile;
+    const long long nblk = (long long)B * tiles_h * tiles_w;
+    if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
+    const int vec = (C % 4 == 0) ? 4 : 1;
+    const int lpp = lanes_per_pixel(C / vec);
+    dim3 grid((unsigned)nblk), block(256);
+#define LC_LCN(VEC_, MODE_)                                                                                       \
+    hipLaunchKernelGGL((lcn_kernel<VEC_, MODE_>), grid, block, 0, s, x, dy, out, mu, rstd, H, W, C, ks, eps, taps, \
+                       lpp, tiles_w, tiles_h * tiles_w)
+    if (mode == 0) { if (vec == 4) LC_LCN(4, 0); else LC_LCN(1, 0); }
+    else           { if (vec == 4) LC_LCN(4, 1); else LC_LCN(1, 1); }
+#undef LC_LCN
+    LC_HIP_LAUNCH_CHECK("lcn launch");
+    return LC_OK;
+}
+
+}  // namespace lc

@@ -1,0 +1,167 @@
+// sae_step: one SGD step on the RICA cost of Eq. 1 for one layer of untied receptive fields.
+//
+//   h  = alpha W x                      (lc_forward)
+//   xh = W^T h + b, r = xh - x          (lc_backward_data, then the residual kernel below)
+//   J  = (1/B) [ sum r^2 + lambda sum sqrt(h^2 + eps) ]
+//   u  = 2 r / B,  db = sum_b u
+//   gh = W u + (lambda/B) h / sqrt(h^2+eps)          (lc_forward, then the sparsity kernel below)
+//   W <- W - lr [ patch(u) h^T + patch(x) (alpha gh)^T ]   (one weight-gradient kernel over both pairs,
+//                                                          the update fused into its epilogue)
+// The sparsity term needs no second pass over the data (Sec. 3.1): its gradient is an elementwise
+// function of h that is added to W u in place.
+#include "lc_common.hpp"
+
+namespace lc {
+
+namespace {
+
+constexpr int kPartials = 1024;  // per-block partial sums of each reduction
+
+__device__ __forceinline__ float block_sum(float v, float *sh) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) sh[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+    if (threadIdx.x == 0)
+        for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sh[i];
+    __syncthreads();
+    return t;  // valid in thread 0
+}
+
+// r = xh + b - x;  u = (2/B) r (written over xh);  b -= lr * sum_b u;  part[block] = sum r^2.
+// One thread per image element, looping over the batch (coalesced across threads).
+__global__ __launch_bounds__(256) void sae_residual_kernel(float *__restrict__ xh_u, const float *__restrict__ x,
+                                                           float *__restrict__ b, int B, int img, float lr,
+                                                           float *__restrict__ part) {
+    __shared__ float sh[4];
+    float sq = 0.f;
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < img; e += gridDim.x * 256) {
+        const float be = b[e];
+        const float scale = 2.0f / (float)B;
+        float db = 0.f;
+        for (int n = 0; n < B; ++n) {
+            const size_t o = (size_t)n * img + e;
+            const float r = xh_u[o] + be - x[o];
+            sq += r * r;
+            const float u = scale * r;
+            xh_u[o] = u;
+            db += u;
+        }
+        b[e] = be - lr * db;
+    }
+    const float t = block_sum(sq, sh);
+    if (threadIdx.x == 0) part[blockIdx.x] = t;
+}
+
+// s = sqrt(h^2+eps);  gh <- alpha * (gh + (lambda/B) h / s);  part0 += s;  part1 += h * gh_before_alpha.
+__global__ __launch_bounds__(256) void sae_sparsity_kernel(const float *__restrict__ h, float *__restrict__ gh,
+                                                           const float *__restrict__ alpha_dev, float lam_over_b,
+                                                           float eps, long long n, float *__restrict__ part_s,
+                                                           float *__restrict__ part_hg) {
+    __shared__ float sh[4];
+    const float alpha = *alpha_dev;
+    float ss = 0.f, hg = 0.f;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256) {
+        const float hv = h[e];
+        const float s = sqrtf(hv * hv + eps);
+        const float g = gh[e] + lam_over_b * hv / s;
+        ss += s;
+        hg += hv * g;
+        gh[e] = alpha * g;
+    }
+    const float t0 = block_sum(ss, sh);
+    const float t1 = block_sum(hg, sh);
+    if (threadIdx.x == 0) { part_s[blockIdx.x] = t0; part_hg[blockIdx.x] = t1; }
+}
+
+// cost = (sum r^2 + lambda sum s) / B;  optionally alpha -= lr * (sum h*gh) / alpha   (d h / d alpha = h / alpha)
+__global__ __launch_bounds__(256) void sae_finalize_kernel(const float *__restrict__ part_r, int n_r,
+                                                           const float *__restrict__ part_s,
+                                                           const float *__restrict__ part_hg, int n_s, float lambda,
+                                                           int B, float lr, int learn_alpha, float *alpha_dev,
+                                                           float *__restrict__ cost_out) {
+    __shared__ float sh[4];
+    float a = 0.f, b = 0.f, c = 0.f;
+    for (int i = threadIdx.x; i < n_r; i += 256) a += part_r[i];
+    for (int i = threadIdx.x; i < n_s; i += 256) { b += part_s[i]; c += part_hg[i]; }
+    const float ta = block_sum(a, sh), tb = block_sum(b, sh), tc = block_sum(c, sh);
+    if (threadIdx.x == 0) {
+        *cost_out = (ta + lambda * tb) / (float)B;
+        if (learn_alpha) {
+            const float al = *alpha_dev;
+            *alpha_dev = al - lr * tc / al;
+        }
+    }
+}
+
+// Rescale every filter w[l,:,f] to unit Euclidean norm (the constraint of Eq. 1).  One workgroup per
+// location; filters are handled in blocks of FB = min(F,256) columns, 256/FB threads per column.
+__global__ __launch_bounds__(256) void sae_project_kernel(float *__restrict__ w, int K, int F) {
+    __shared__ float part[256];
+    extern __shared__ float inv[];  // F floats
+    float *wl = w + (size_t)blockIdx.x * K * F;
+    const int FB = F < 256 ? F : 256, KG = 256 / FB;
+    const int fl = threadIdx.x % FB, kg = threadIdx.x / FB;
+    for (int f0 = 0; f0 < F; f0 += FB) {
+        float s = 0.f;
+        if (kg < KG && f0 + fl < F)
+            for (int k = kg; k < K; k += KG) { const float v = wl[(size_t)k * F + f0 + fl]; s += v * v; }
+        part[threadIdx.x] = s;
+        __syncthreads();
+        if (threadIdx.x < FB && f0 + threadIdx.x < F) {
+            float t = 0.f;
+            for (int q = 0; q < KG; ++q) t += part[q * FB + threadIdx.x];
+            inv[f0 + threadIdx.x] = 1.0f / sqrtf(t);
+        }
+        __syncthreads();
+    }
+    for (int e = threadIdx.x; e < K * F; e += 256) wl[e] *= inv[e % F];
+}
+
+}  // namespace
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+size_t sae_workspace_bytes(const Geom &g) {
+    const size_t nh = (size_t)g.B * g.L * g.F, nx = (size_t)g.B * g.H * g.W * g.C;
+    return 2 * align256(nh * 4) + align256(nx * 4) + 3 * align256(kPartials * 4);
+}
+
+int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
+                    float lr, uint32_t flags, float *h_out, float *cost_out, void *ws, hipStream_t s) {
+    const size_t nh = (size_t)g.B * g.L * g.F, nx = (size_t)g.B * g.H * g.W * g.C;
+    const int img = g.H * g.W * g.C;
+    char *p = (char *)ws;
+    float *h_ws = (float *)p; p += align256(nh * 4);
+    float *gh = (float *)p;   p += align256(nh * 4);
+    float *u = (float *)p;    p += align256(nx * 4);
+    float *part_r = (float *)p; p += align256(kPartials * 4);
+    float *part_s = (float *)p; p += align256(kPartials * 4);
+    float *part_hg = (float *)p;
+    float *h = h_out ? h_out : h_ws;
+
+    int rc;
+    if ((rc = launch_forward_f32(g, x, w, nullptr, 1.f, alpha, h, s)) != LC_OK) return rc;
+    if ((rc = launch_backward_data_f32(g, h, w, u, s)) != LC_OK) return rc;
+    const int n_r = (int)((img + 255) / 256 < kPartials ? (img + 255) / 256 : kPartials);
+    hipLaunchKernelGGL(sae_residual_kernel, dim3(n_r), dim3(256), 0, s, u, x, b, g.B, img, lr, part_r);
+    LC_HIP_LAUNCH_CHECK("sae_step residual launch");
+    if ((rc = launch_forward_f32(g, u, w, nullptr, 1.f, nullptr, gh, s)) != LC_OK) return rc;
+    const int n_s = (int)((nh + 255) / 256 < (size_t)kPartials ? (nh + 255) / 256 : kPartials);
+    hipLaunchKernelGGL(sae_sparsity_kernel, dim3(n_s), dim3(256), 0, s, h, gh, alpha, lambda / (float)g.B, eps_sparse,
+                       (long long)nh, part_s, part_hg);
+    LC_HIP_LAUNCH_CHECK("sae_step sparsity launch");
+    // w <- w - lr * ( patch(u) h^T + patch(x) (alpha gh)^T )
+    if ((rc = launch_backward_weights_f32(g, u, h, x, gh, 1.f, -lr, w, s)) != LC_OK) return rc;
+    if (flags & LC_SAE_PROJECT_ROWS) {
+        hipLaunchKernelGGL(sae_project_kernel, dim3(g.L), dim3(256), g.F * sizeof(float), s, w, g.K, g.F);
+        LC_HIP_LAUNCH_CHECK("sae_step projection launch");
+    }
+    hipLaunchKernelGGL(sae_finalize_kernel, dim3(1), dim3(256), 0, s, part_r, n_r, part_s, part_hg, n_s, lambda, g.B,
+                       lr, (flags & LC_SAE_LEARN_ALPHA) ? 1 : 0, alpha, cost_out);
+    LC_HIP_LAUNCH_CHECK("sae_step finalize launch");
+    return LC_OK;
+}
+
+}  // namespace lc

@@ -1,0 +1,231 @@
+"""GPU parity: every entry point of the C ABI against the fp64 oracle, element by element, on the same
+seeded inputs.  Bar (fp32): relative Frobenius error <= 1e-4 per output tensor."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1502_03409_amd as lc
+import workloads as wl
+from conftest import rel_fro
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def run_forward(g, x, w, bias=None, alpha=1.0):
+    G = lc.geom(*g.as_tuple())
+    y = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
+    lc.lc_forward(G, dev(x), dev(w), None if bias is None else dev(bias), alpha, y)
+    return host(y)
+
+
+def run_backward_data(g, dy, w):
+    G = lc.geom(*g.as_tuple())
+    dx = torch.full((g.B, g.H, g.W, g.C), float("nan"), device="cuda")
+    lc.lc_backward_data(G, dev(dy), dev(w), dx)
+    return host(dx)
+
+
+def run_backward_weights(g, x, dy, beta=0.0, prev=None):
+    G = lc.geom(*g.as_tuple())
+    dw = torch.full((g.LH, g.LW, g.K, g.F), float("nan"), device="cuda") if prev is None else dev(prev)
+    lc.lc_backward_weights(G, dev(x), dev(dy), beta, dw)
+    return host(dw)
+
+
+SMALL = {
+    "cfg1": (wl.CONFIG_GEOM["cfg1"], "gaussian"),
+    "cfg2": (wl.CONFIG_GEOM["cfg2"], "pink"),
+    # ragged everything: batch, filters and patch rows off the tile sizes, floor geometry
+    "ragged_a": (wl.LCGeom(B=5, H=23, W=26, C=2, R=5, S=3, F=10), "gaussian"),
+    "ragged_b": (wl.LCGeom(B=37, H=19, W=33, C=3, R=7, S=2, F=40), "pink"),
+    "ragged_c": (wl.LCGeom(B=70, H=14, W=15, C=5, R=4, S=4, F=19), "gaussian"),   # stride = field, no overlap
+    "gaps": (wl.LCGeom(B=9, H=17, W=20, C=1, R=3, S=5, F=7), "gaussian"),         # stride > field
+    "one_loc": (wl.LCGeom(B=20, H=6, W=6, C=4, R=6, S=1, F=33), "gaussian"),      # single location = plain GEMM
+    "wide_c": (wl.LCGeom(B=33, H=12, W=12, C=32, R=4, S=2, F=48), "halfnormal"),
+    "many_f": (wl.LCGeom(B=16, H=10, W=10, C=3, R=4, S=2, F=200), "gaussian"),
+    "s5_stage2": (wl.LCGeom(B=24, H=15, W=15, C=16, R=6, S=2, F=32), "halfnormal"),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_lc_primitives_match_oracle(name):
+    g, kind = SMALL[name]
+    print(f"case {name} geom {g}", flush=True)
+    x, w, dy, bias = wl.lc_inputs(g, kind, seed=0, with_bias=True)
+    t = g.as_tuple()
+    y = run_forward(g, x, w, bias, 0.75)
+    assert rel_fro(y, oracle.lc_forward(t, x, w, bias, 0.75)) <= TOL
+    y0 = run_forward(g, x, w)
+    assert rel_fro(y0, oracle.lc_forward(t, x, w)) <= TOL
+    dx = run_backward_data(g, dy, w)
+    ref_dx = oracle.lc_backward_data(t, dy, w)
+    assert rel_fro(dx, ref_dx) <= TOL
+    assert np.all(dx[ref_dx == 0.0] == 0.0)          # uncovered pixels are written as exact zeros
+    dw = run_backward_weights(g, x, dy)
+    ref_dw = oracle.lc_backward_weights(t, x, dy)
+    assert rel_fro(dw, ref_dw) <= TOL
+    prev = np.random.default_rng(5).standard_normal(ref_dw.shape).astype(np.float32)
+    dw1 = run_backward_weights(g, x, dy, 1.0, prev)
+    assert rel_fro(dw1, ref_dw + prev) <= TOL
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4"])
+def test_lc_primitives_full_size_sampled(name):
+    """Full-size workloads in the launch configuration the benchmark times: a sample of outputs
+    against the oracle's single-output evaluators, plus the adjoint identities on the GPU results."""
+    g, kind = wl.CONFIG_GEOM[name], wl.CONFIG_IMAGE_KIND[name]
+    print(f"case {name} geom {g}", flush=True)
+    x, w, dy = wl.lc_inputs(g, kind, seed=0)
+    t = g.as_tuple()
+    G = lc.geom(*t)
+    xd, wd, dyd = dev(x), dev(w), dev(dy)
+    y = torch.empty((g.B, g.LH, g.LW, g.F), device="cuda")
+    dx = torch.empty((g.B, g.H, g.W, g.C), device="cuda")
+    dw = torch.empty((g.LH, g.LW, g.K, g.F), device="cuda")
+    lc.lc_forward(G, xd, wd, None, 1.0, y)
+    lc.lc_backward_data(G, dyd, wd, dx)
+    lc.lc_backward_weights(G, xd, dyd, 0.0, dw)
+    # adjoint identities, evaluated in fp64 on the device results
+    lhs = torch.dot(y.double().flatten(), dyd.double().flatten()).item()
+    rhs = torch.dot(xd.double().flatten(), dx.double().flatten()).item()
+    rhw = torch.dot(wd.double().flatten(), dw.double().flatten()).item()
+    scale = (y.double().norm() * dyd.double().norm()).item()
+    assert abs(lhs - rhs) <= 1e-5 * scale and abs(lhs - rhw) <= 1e-5 * scale
+    yh, dxh, dwh = host(y), host(dx), host(dw)
+    r = np.random.default_rng(11)
+    n = 160
+    gy, ry, gx, rx, gw, rw = ([] for _ in range(6))
+    corners_l = [(0, 0), (g.LH - 1, g.LW - 1), (0, g.LW - 1), (g.LH - 1, 0)]
+    for s in range(n):
+        b = int(r.integers(g.B)) if s >= 4 else (0 if s % 2 else g.B - 1)
+        i, j = (int(r.integers(g.LH)), int(r.integers(g.LW))) if s >= 4 else corners_l[s]
+        f, k = int(r.integers(g.F)), int(r.integers(g.K))
+        row, col, c = int(r.integers(g.H)), int(r.integers(g.W)), int(r.integers(g.C))
+        if s < 4:
+            row, col = [(0, 0), (g.H - 1, g.W - 1), (0, g.W - 1), (g.H - 1, 0)][s]
+        gy.append(yh[b, i, j, f]); ry.append(oracle.lc_forward_at(t, x, w, None, 1.0, b, i, j, f))
+        gx.append(dxh[b, row, col, c]); rx.append(oracle.lc_backward_data_at(t, dy, w, b, row, col, c))
+        gw.append(dwh[i, j, k, f]); rw.append(oracle.lc_backward_weights_at(t, x, dy, i, j, k, f))
+    assert rel_fro(gy, ry) <= TOL
+    assert rel_fro(gx, rx) <= TOL
+    assert rel_fro(gw, rw) <= TOL
+
+
+def test_forward_determinism_and_empty_tail():
+    g = wl.LCGeom(B=17, H=21, W=21, C=3, R=6, S=3, F=24)
+    x, w, dy = wl.lc_inputs(g, "gaussian", seed=2)
+    a, b = run_forward(g, x, w), run_forward(g, x, w)
+    np.testing.assert_array_equal(a, b)
+    a, b = run_backward_data(g, dy, w), run_backward_data(g, dy, w)
+    np.testing.assert_array_equal(a, b)
+    a, b = run_backward_weights(g, x, dy), run_backward_weights(g, x, dy)
+    np.testing.assert_array_equal(a, b)
+
+
+POOL_SHAPES = [((3, 9, 11, 5), 3, 1), ((2, 12, 12, 32), 3, 1), ((2, 10, 9, 8), 2, 2), ((1, 7, 7, 3), 3, 2),
+               ((4, 46, 46, 32), 3, 1)]
+
+
+@pytest.mark.parametrize("shape,ks,st", POOL_SHAPES)
+def test_l2pool_matches_oracle(shape, ks, st):
+    print(f"case pool {shape} {ks} {st}", flush=True)
+    x = wl.feature_maps(*shape, seed=1)
+    eps = wl.POOL_EPS
+    ref = oracle.l2pool_fwd(x, ks, st, eps)
+    xd = dev(x)
+    y = torch.full(ref.shape, float("nan"), device="cuda")
+    lc.l2pool_fwd(xd, y, ks, st, eps)
+    assert rel_fro(host(y), ref) <= TOL
+    dy = wl.feature_maps(*ref.shape, seed=2)
+    dx = torch.full(shape, float("nan"), device="cuda")
+    lc.l2pool_bwd(xd, y, dev(dy), dx, ks, st)
+    assert rel_fro(host(dx), oracle.l2pool_bwd(x, ref, dy, ks, st)) <= TOL
+
+
+LCN_SHAPES = [((2, 9, 10, 3), 5), ((3, 20, 37, 32), 5), ((2, 16, 16, 8), 3), ((1, 3, 2, 5), 5), ((2, 33, 17, 6), 7),
+              ((1, 5, 40, 130), 5), ((4, 44, 44, 32), 5)]
+
+
+@pytest.mark.parametrize("shape,ks", LCN_SHAPES)
+def test_lcn_matches_oracle(shape, ks):
+    print(f"case lcn {shape} {ks}", flush=True)
+    x = wl.feature_maps(*shape, seed=3, signed=False)
+    ref_y, ref_mu, ref_rstd = oracle.lcn_fwd(x, ks, wl.LCN_SIGMA, wl.LCN_EPS)
+    xd = dev(x)
+    y = torch.full(shape, float("nan"), device="cuda")
+    mu = torch.full(shape[:3], float("nan"), device="cuda")
+    rstd = torch.full(shape[:3], float("nan"), device="cuda")
+    lc.lcn_fwd(xd, y, mu, rstd, ks, wl.LCN_SIGMA, wl.LCN_EPS)
+    assert rel_fro(host(mu), ref_mu) <= TOL
+    assert rel_fro(host(rstd), ref_rstd) <= TOL
+    assert rel_fro(host(y), ref_y) <= TOL
+    dy = wl.feature_maps(*shape, seed=4)
+    dx = torch.full(shape, float("nan"), device="cuda")
+    # backward from the oracle's saved statistics, so that only lcn_bwd itself is under test
+    lc.lcn_bwd(xd, dev(ref_mu.astype(np.float32)), dev(ref_rstd.astype(np.float32)), dev(dy), dx, ks, wl.LCN_SIGMA)
+    assert rel_fro(host(dx), oracle.lcn_bwd(x, ref_mu, ref_rstd, dy, ks, wl.LCN_SIGMA)) <= TOL
+
+
+def run_sae(g, x, w, b, alpha, lam, eps_s, lr, flags, with_h=True):
+    G = lc.geom(*g.as_tuple())
+    wd, bd = dev(w), dev(b)
+    ad = torch.tensor([alpha], device="cuda", dtype=torch.float32)
+    cost = torch.full((1,), float("nan"), device="cuda")
+    h = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda") if with_h else None
+    ws = torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda")
+    lc.sae_step(G, dev(x), wd, bd, ad, lam, eps_s, lr, flags, h, cost, ws)
+    return host(cost)[0], host(wd), host(bd), host(ad)[0], (host(h) if with_h else None)
+
+
+SAE_CASES = {
+    "cfg1": (wl.CONFIG_GEOM["cfg1"], "gaussian"),
+    "floor": (wl.LCGeom(B=12, H=23, W=23, C=4, R=6, S=2, F=8), "halfnormal"),
+    "ragged": (wl.LCGeom(B=7, H=14, W=17, C=3, R=5, S=3, F=10), "gaussian"),
+    "stage_like": (wl.LCGeom(B=32, H=32, W=32, C=3, R=16, S=2, F=16), "pink"),
+}
+
+
+@pytest.mark.parametrize("name", list(SAE_CASES))
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+def test_sae_step_matches_oracle(name, flags):
+    g, kind = SAE_CASES[name]
+    print(f"case sae {name} flags {flags}", flush=True)
+    x, w, _ = wl.lc_inputs(g, kind, seed=1)
+    b = (0.05 * np.random.default_rng(3).standard_normal((g.H, g.W, g.C))).astype(np.float32)
+    alpha, lam, eps_s, lr = 0.9, wl.SAE_LAMBDA, wl.SAE_EPS, 1e-2
+    J, w2, b2, a2, h = run_sae(g, x, w, b, alpha, lam, eps_s, lr, flags)
+    Jo, wo, bo, ao, ho = oracle.sae_step(g.as_tuple(), x, w, b, alpha, lam, eps_s, lr, flags)
+    assert abs(J - Jo) <= TOL * abs(Jo)
+    assert rel_fro(h, ho) <= TOL
+    # compare the updates, not the updated values, so a small step cannot hide an error
+    assert rel_fro(w2.astype(np.float64) - w, wo - w) <= 5e-4, "dW"   # fp32 cancellation in w2-w: see the design doc
+    assert rel_fro(b2.astype(np.float64) - b, bo - b) <= 5e-4, "db"
+    if flags & 2:
+        assert abs((a2 - alpha) - (ao - alpha)) <= 5e-4 * abs(ao - alpha)
+    else:
+        assert a2 == np.float32(alpha)
+    if flags & 1:
+        np.testing.assert_allclose(np.linalg.norm(w2.astype(np.float64), axis=2), 1.0, rtol=1e-5)
+
+
+def test_sae_step_without_h_out_and_descent():
+    g, kind = SAE_CASES["cfg1"]
+    x, w, _ = wl.lc_inputs(g, kind, seed=1)
+    b = np.zeros((g.H, g.W, g.C), dtype=np.float32)
+    costs = []
+    for _ in range(5):
+        J, w, b, _, h = run_sae(g, x, w, b, 1.0, wl.SAE_LAMBDA, wl.SAE_EPS, 1e-2, 0, with_h=False)
+        assert h is None
+        costs.append(J)
+    assert all(c1 < c0 for c0, c1 in zip(costs, costs[1:])), costs
