@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the locally connected autoencoder hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-sae]
+
+One "step" is one pass of the whole hot path over one synthetic mini-batch of workload cfg3 (one GPU's
+share of a first layer: B=128, 200x200x3 pink-noise images, 20x20x3 fields at stride 4, 32 filters per
+location), inputs already resident in HBM:
+
+    lc_forward -> l2pool_fwd -> lcn_fwd -> lcn_bwd -> l2pool_bwd -> lc_backward_data -> lc_backward_weights
+
+`value` is the algorithmic flop of the three layer contractions (3 x 2*B*K*F*L) divided by the time of
+the whole step.  The JSON line also carries per-kernel times (HIP events on the launch stream), the
+roofline of the dominant kernel, the three-stage RICA training step of workload cfg5 (images/s), and
+the fp64 CPU oracle timed on the host cores as a scale reference.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sae", action="store_true")
+    return ap.parse_args()
+
+
+def main() -> int:
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (one GPU's share of a layer at its real shape); "
+              "--gpus N with N > 1 is not supported.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_1502_03409_amd as lc
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback for the product path.", file=sys.stderr)
+        return 3
+    lc.lib()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    # ---------------------------------------------------------------- workload cfg3
+    g = wl.CONFIG_GEOM["cfg3"]
+    G = lc.geom(*g.as_tuple())
+    x, w, dy = wl.lc_inputs(g, wl.CONFIG_IMAGE_KIND["cfg3"], seed=0)
+    xd, wd = dev(x), dev(w)
+    Hp, Wp = g.LH - wl.POOL_KSIZE + 1, g.LW - wl.POOL_KSIZE + 1
+    y = torch.empty((g.B, g.LH, g.LW, g.F), device="cuda")
+    p = torch.empty((g.B, Hp, Wp, g.F), device="cuda")
+    n = torch.empty_like(p)
+    mu = torch.empty((g.B, Hp, Wp), device="cuda")
+    rstd = torch.empty_like(mu)
+    dn = dev(np.random.default_rng(1).standard_normal(tuple(p.shape)).astype(np.float32))  # upstream gradient
+    dp = torch.empty_like(p)
+    dyd = torch.empty_like(y)
+    dx = torch.empty((g.B, g.H, g.W, g.C), device="cuda")
+    dw = torch.empty((g.LH, g.LW, g.K, g.F), device="cuda")
+
+    names = ["lc_forward", "l2pool_fwd", "lcn_fwd", "lcn_bwd", "l2pool_bwd", "lc_backward_data",
+             "lc_backward_weights"]
+    calls = [
+        lambda: lc.lc_forward(G, xd, wd, None, 1.0, y),
+        lambda: lc.l2pool_fwd(y, p, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS),
+        lambda: lc.lcn_fwd(p, n, mu, rstd, wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS),
+        lambda: lc.lcn_bwd(p, mu, rstd, dn, dp, wl.LCN_KSIZE, wl.LCN_SIGMA),
+        lambda: lc.l2pool_bwd(y, p, dp, dyd, wl.POOL_KSIZE, wl.POOL_STRIDE),
+        lambda: lc.lc_backward_data(G, dyd, wd, dx),
+        lambda: lc.lc_backward_weights(G, xd, dyd, 0.0, dw),
+    ]
+
+    def step(events=None):
+        for i, c in enumerate(calls):
+            if events is not None:
+                events[i].record(stream)
+            c()
+        if events is not None:
+            events[len(calls)].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = {nm: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
+               for i, nm in enumerate(names)}
+
+    flop_pass = g.flop_per_pass
+    lc_flop = 3 * flop_pass
+    value = lc_flop / (ms_per_step * 1e-3) / 1e9
+    lc_ms = kern_ms["lc_forward"] + kern_ms["lc_backward_data"] + kern_ms["lc_backward_weights"]
+    lc_tflops = lc_flop / (lc_ms * 1e-3) / 1e12
+
+    # roofline of the dominant kernel (largest share of the step)
+    dom = max(("lc_forward", "lc_backward_data", "lc_backward_weights"), key=lambda k: kern_ms[k])
+    achieved = flop_pass / (kern_ms[dom] * 1e-3) / 1e12
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic_cfg3.json")
+    if os.path.exists(tfile):
+        traffic = json.load(open(tfile)).get(dom)
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": traffic}
+    nbytes = {
+        "l2pool_fwd": 4 * (y.numel() + p.numel()),
+        "lcn_fwd": 4 * (2 * p.numel() + 2 * mu.numel()),
+        "lcn_bwd": 4 * (3 * p.numel() + 2 * mu.numel()),
+        "l2pool_bwd": 4 * (2 * y.numel() + 2 * p.numel()),
+    }
+    kernels = {}
+    for nm in names:
+        e = {"ms": round(kern_ms[nm], 4)}
+        if nm in nbytes:
+            gbs = nbytes[nm] / (kern_ms[nm] * 1e-3) / 1e9
+            e.update({"GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)})
+        else:
+            tf = flop_pass / (kern_ms[nm] * 1e-3) / 1e12
+            e.update({"TFLOP/s": round(tf, 2), "frac_fp32_mfma": round(tf / FP32_MFMA_PEAK_TFLOPS, 4)})
+        kernels[nm] = e
+
+    out = {
+        "metric": "LC layer fwd+bwd GFLOP/s (3 x 2BKFL flop per whole hot-path step)",
+        "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cfg3: B=128 200x200x3 pink-noise, R=20 S=4 F=32 (L=2116, K=1200), "
+                               "then 3x3/1 L2 pool and 5x5 LCN, forward and backward",
+                   "B": g.B, "H": g.H, "W": g.W, "C": g.C, "R": g.R, "S": g.S, "F": g.F},
+        "images_per_s": round(g.B / (ms_per_step * 1e-3), 1),
+        "lc_fwd_bwd": {"ms": round(lc_ms, 4), "TFLOP/s": round(lc_tflops, 2),
+                       "frac_fp32_mfma_peak": round(lc_tflops / FP32_MFMA_PEAK_TFLOPS, 4)},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    del dw, dx, dyd, dp, dn, n, p, y, xd, wd
+
+    # ---------------------------------------------------------------- workload cfg5: three-stage RICA step
+    if not args.no_sae:
+        out["sae_step"] = bench_sae(lc, wl, np, torch, dev, max(3, args.steps // 2), max(2, args.warmup // 2))
+
+    # ---------------------------------------------------------------- CPU oracle, as a scale reference
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(np, wl, x, w, dy)
+
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_sae(lc, wl, np, torch, dev, steps, warmup):
+    """cfg5: all three stages take one SGD step on the same mini-batch; stage s+1 reads
+    lcn_fwd(l2pool_fwd(h_s)).  Returns images/s of the whole three-stage step."""
+    stages = []
+    x1 = wl.pink_images(np.random.default_rng(0), 128, 128, 128, 3)
+    inp = dev(x1)
+    for si, key in enumerate(("cfg5_s1", "cfg5_s2", "cfg5_s3")):
+        g = wl.CONFIG_GEOM[key]
+        G = lc.geom(*g.as_tuple())
+        rw = np.random.default_rng(100 + si)
+        st = {
+            "g": g, "G": G, "x": inp,
+            "w": dev((rw.standard_normal((g.LH, g.LW, g.K, g.F)) / np.sqrt(g.K)).astype(np.float32)),
+            "b": torch.zeros((g.H, g.W, g.C), device="cuda"),
+            "alpha": torch.ones(1, device="cuda"), "cost": torch.zeros(1, device="cuda"),
+            "h": torch.empty((g.B, g.LH, g.LW, g.F), device="cuda"),
+            "ws": torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda"),
+            "p": torch.empty((g.B, g.LH - 2, g.LW - 2, g.F), device="cuda"),
+        }
+        st["n"] = torch.empty_like(st["p"])
+        st["mu"] = torch.empty(st["p"].shape[:3], device="cuda")
+        st["rstd"] = torch.empty_like(st["mu"])
+        stages.append(st)
+        inp = st["n"]
+
+    def step():
+        for st in stages:
+            lc.sae_step(st["G"], st["x"], st["w"], st["b"], st["alpha"], wl.SAE_LAMBDA, wl.SAE_EPS, wl.SAE_LR, 0,
+                        st["h"], st["cost"], st["ws"])
+            lc.l2pool_fwd(st["h"], st["p"], wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS)
+            lc.lcn_fwd(st["p"], st["n"], st["mu"], st["rstd"], wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    flop = sum(5 * st["g"].flop_per_pass for st in stages)
+    tf = flop / (ms * 1e-3) / 1e12
+    return {"workload": "cfg5: three-stage RICA step, B=128 128x128x3", "ms_per_step": round(ms, 4),
+            "images_per_s": round(128 / (ms * 1e-3), 1), "TFLOP/s": round(tf, 2),
+            "frac_fp32_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4), "steps": steps,
+            "costs": [round(float(st["cost"].item()), 4) for st in stages]}
+
+
+def cpu_baseline(np, wl, x, w, dy):
+    """The fp64 oracle as it stands, on the host cores, over one whole cfg3 step (bounded: one
+    repetition, every primitive once).  A scale reference, not a target."""
+    import oracle
+
+    g = wl.CONFIG_GEOM["cfg3"]
+    t = g.as_tuple()
+    xd, wd, dyd = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+    t0 = time.perf_counter()
+    y = oracle.lc_forward(t, xd, wd)
+    p = oracle.l2pool_fwd(y, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS)
+    n, mu, rstd = oracle.lcn_fwd(p, wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)
+    dp = oracle.lcn_bwd(p, mu, rstd, n, wl.LCN_KSIZE, wl.LCN_SIGMA)
+    dyy = oracle.l2pool_bwd(y, p, dp, wl.POOL_KSIZE, wl.POOL_STRIDE)
+    oracle.lc_backward_data(t, dyd, wd)
+    oracle.lc_backward_weights(t, xd, dyd)
+    dt = time.perf_counter() - t0
+    del dyy
+    return {"value": round(3 * g.flop_per_pass / dt / 1e9, 2), "unit": "GFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": "one whole cfg3 step (all seven primitives once, B=128), fp64 naive loops, OpenMP"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())
