@@ -100,6 +100,141 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const float
         }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Fast path (aligned shapes).  Same decomposition, but every global access covers whole cache
+// lines, by permuting which rows/columns of the MFMA tiles a lane owns:
+//   A: lane (m,kk) loads VA consecutive patch elements k = kg + VA*m .. +VA-1 of image b0+kk in one
+//      dwordxVA load; element t of that vector is row m of M-tile t (tile t holds k = kg + VA*m + t).
+//      16 lanes x VA floats are contiguous in the image row.
+//   B: lane (n,kk) loads NT consecutive filters f = f0 + NT*n .. of image b0+kk; element u is column
+//      n of N-tile u.  16 lanes x NT floats are contiguous in dy.
+//   D: lane (n, 4*(l/16)+r) of tile (t,u) is out[k = kg + VA*(4*(l/16)+r) + t][f0 + NT*n + u]: the
+//      NT tiles of one row are stored as one dwordxNT, 16 lanes covering a contiguous run of w.
+// Loads run PF batch steps ahead of the MFMAs in a register ring.
+template <int N> struct VecT;
+template <> struct VecT<1> { typedef float T; };
+template <> struct VecT<2> { typedef float T __attribute__((ext_vector_type(2))); };
+template <> struct VecT<4> { typedef float T __attribute__((ext_vector_type(4))); };
+
+template <int N>
+__device__ __forceinline__ float vget(const typename VecT<N>::T &v, int i) {
+    if constexpr (N == 1) return v; else return v[i];
+}
+
+template <int G, int VA, int NT, int PF>
+__global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const float *__restrict__ x1,
+                                                                  const float *__restrict__ dy1,
+                                                                  const float *__restrict__ x2,
+                                                                  const float *__restrict__ dy2, float beta,
+                                                                  float gamma, float *__restrict__ out, int kblocks,
+                                                                  int ntasks) {
+    typedef typename VecT<VA>::T AV;
+    typedef typename VecT<NT>::T BV;
+    typedef __attribute__((address_space(1))) AV GAV;   // global address space: plain global_load, not flat
+    typedef __attribute__((address_space(1))) BV GBV;
+    typedef const __attribute__((address_space(1))) float *gfloat_ptr;
+    constexpr int KB = G * VA * 16;  // patch elements per task
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, kk = lane >> 4;
+    const int task = remap_xcd(blockIdx.x, gridDim.x) * 4 + wave;
+    if (task >= ntasks) return;
+    const int loc = task / kblocks, k0 = (task - loc * kblocks) * KB;
+    const int i = loc / g.LW, j = loc - i * g.LW;
+    const int f0 = blockIdx.y * NT * 16;
+    const size_t img = (size_t)g.H * g.W * g.C;
+
+    // Rows of the A tiles that fall beyond K are loaded from a valid address (element 0 of the patch)
+    // and never masked: row m of A only reaches row m of D, and those rows are not stored.
+    int off[G];
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) {
+        const int k = k0 + gg * VA * 16 + VA * m;
+        const int kc = k < g.K ? k : 0;
+        const int kh = kc / g.RC, rem = kc - kh * g.RC;
+        off[gg] = ((i * g.S + kh) * g.W + j * g.S) * g.C + rem;
+    }
+
+    f32x4 acc[G][VA][NT];
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg)
+#pragma unroll
+        for (int t = 0; t < VA; ++t)
+#pragma unroll
+            for (int u = 0; u < NT; ++u) acc[gg][t][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const int nsteps = g.B >> 2;                 // B % (4*PF) == 0 on this path
+    const size_t xstep = 4 * img, dstep = (size_t)4 * g.L * g.F;
+    for (int p = 0; p < 2; ++p) {
+        const float *x = p ? x2 : x1;
+        const float *dy = p ? dy2 : dy1;
+        if (!x) break;
+        gfloat_ptr xa[G];
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) xa[gg] = (gfloat_ptr)x + ((size_t)kk * img + off[gg]);
+        gfloat_ptr da = (gfloat_ptr)dy + (((size_t)kk * g.L + loc) * g.F + f0 + NT * m);
+        AV a[PF][G];
+        BV bv[PF];
+        // ring prologue: steps 0 .. PF-1
+#pragma unroll
+        for (int ss = 0; ss < PF; ++ss) {
+#pragma unroll
+            for (int gg = 0; gg < G; ++gg) { a[ss][gg] = *(const GAV *)xa[gg]; xa[gg] += xstep; }
+            bv[ss] = *(const GBV *)da; da += dstep;
+        }
+        // steady state: consume slot ss, then refill it with step s+PF
+        for (int s0 = PF; s0 < nsteps; s0 += PF) {
+#pragma unroll
+            for (int ss = 0; ss < PF; ++ss) {
+#pragma unroll
+                for (int gg = 0; gg < G; ++gg)
+#pragma unroll
+                    for (int t = 0; t < VA; ++t)
+#pragma unroll
+                        for (int u = 0; u < NT; ++u)
+                            acc[gg][t][u] = mfma16(vget<VA>(a[ss][gg], t), vget<NT>(bv[ss], u), acc[gg][t][u]);
+#pragma unroll
+                for (int gg = 0; gg < G; ++gg) { a[ss][gg] = *(const GAV *)xa[gg]; xa[gg] += xstep; }
+                bv[ss] = *(const GBV *)da; da += dstep;
+                // keep the refill of slot ss right behind the MFMAs that consumed it: the loads then run
+                // PF-1 slots ahead of their use instead of being sunk to the end of the iteration
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // drain
+#pragma unroll
+        for (int ss = 0; ss < PF; ++ss)
+#pragma unroll
+            for (int gg = 0; gg < G; ++gg)
+#pragma unroll
+                for (int t = 0; t < VA; ++t)
+#pragma unroll
+                    for (int u = 0; u < NT; ++u)
+                        acc[gg][t][u] = mfma16(vget<VA>(a[ss][gg], t), vget<NT>(bv[ss], u), acc[gg][t][u]);
+    }
+
+    float *ol = out + (size_t)loc * g.K * g.F + f0 + NT * m;
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int t = 0; t < VA; ++t) {
+                const int k = k0 + gg * VA * 16 + VA * (4 * kk + r) + t;
+                if (k >= g.K) continue;
+                BV *o = (BV *)(ol + (size_t)k * g.F);
+                BV v;
+                if constexpr (NT == 1) {
+                    v = gamma * acc[gg][t][0][r];
+                } else {
+#pragma unroll
+                    for (int u = 0; u < NT; ++u) v[u] = gamma * acc[gg][t][u][r];
+                }
+                if (beta != 0.f) v += beta * *o;
+                *o = v;
+            }
+}
+
 namespace {
 
 template <int MTW, int NT>
@@ -137,8 +272,52 @@ int launch_nt(const Geom &g, const float *x1, const float *dy1, const float *x2,
 
 }  // namespace
 
+namespace {
+
+template <int G, int VA, int NT, int PF>
+int launch_fast(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2, float beta,
+                float gamma, float *out, hipStream_t s) {
+    constexpr int KB = G * VA * 16;
+    const int kblocks = (g.K + KB - 1) / KB;
+    const long long ntasks = (long long)g.L * kblocks;
+    if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
+    dim3 grid((unsigned)((ntasks + 3) / 4), g.F / (NT * 16));
+    hipLaunchKernelGGL((lc_bwd_weights_fast_kernel<G, VA, NT, PF>), grid, dim3(256), 0, s, g, x1, dy1, x2, dy2, beta,
+                       gamma, out, kblocks, (int)ntasks);
+    LC_HIP_LAUNCH_CHECK("lc_backward_weights launch");
+    return LC_OK;
+}
+
+// widest vector (4, 2, 1 floats) that keeps every patch-row access of the layer aligned
+int patch_vector_width(const Geom &g) {
+    for (int v = 4; v > 1; v >>= 1)
+        if (g.RC % v == 0 && (g.S * g.C) % v == 0 && (g.W * g.C) % v == 0) return v;
+    return 1;
+}
+
+template <int G, int VA, int NT>
+int launch_fast_pf(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2, float beta,
+                   float gamma, float *out, hipStream_t s) {
+    if (g.B % 16 == 0) return launch_fast<G, VA, NT, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+    if (g.B % 8 == 0) return launch_fast<G, VA, NT, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+    return launch_fast<G, VA, NT, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+}
+
+}  // namespace
+
 int launch_backward_weights_f32(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2,
                                 float beta, float gamma, float *out, hipStream_t s) {
+    const int va = patch_vector_width(g);
+    if ((g.B & 3) == 0 && va == 4) {
+        if (g.F % 64 == 0) return launch_fast_pf<1, 4, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+        if (g.F % 32 == 0) return launch_fast_pf<2, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+        if (g.F % 16 == 0) return launch_fast_pf<2, 4, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+    }
+    if ((g.B & 3) == 0 && va == 2) {
+        if (g.F % 64 == 0) return launch_fast_pf<2, 2, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+        if (g.F % 32 == 0) return launch_fast_pf<4, 2, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+        if (g.F % 16 == 0) return launch_fast_pf<4, 2, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+    }
     if (g.F <= 16) return launch_nt<1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
     if (g.F <= 32) return launch_nt<2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
     return launch_nt<4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
