@@ -118,6 +118,177 @@ __global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const float *__
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Fast path (aligned shapes: patch rows, strides and filter counts that allow whole-line vector
+// accesses).  Same decomposition as above, re-arranged so that the MFMA pipe never waits:
+//   * the image strip of the NEXT chunk is fetched into registers (one dwordx4 per lane and slot)
+//     while the current chunk is multiplied out of LDS; a chunk is CQ floats of one patch row for
+//     all fields of the strip;
+//   * the weights run ahead of their use in a register ring of UNR k-steps that is never drained:
+//     w[l] is contiguous in k, so the ring simply walks through the whole K x F matrix of the field;
+//   * lane (n,kk) of a weight load holds NT consecutive filters f0+NT*n.. of row k+kk, i.e. column n
+//     of NT different N-tiles: 16 lanes cover a whole run of w, and the epilogue stores NT filters
+//     of one image as one vector.
+// Rows of A are images and are never masked (images beyond B are staged as zeros).
+template <int N> struct FVec;
+template <> struct FVec<1> { typedef float T; };
+template <> struct FVec<2> { typedef float T __attribute__((ext_vector_type(2))); };
+template <> struct FVec<4> { typedef float T __attribute__((ext_vector_type(4))); };
+template <int N>
+__device__ __forceinline__ float fget(const typename FVec<N>::T &v, int i) {
+    if constexpr (N == 1) return v; else return v[i];
+}
+
+constexpr int kFwdStageSlots = 12;  // dwordx4 staging registers per lane: chunk <= 12*256*16 B = 48 KB
+
+template <int MT, int NT, int NLOC, int UNR>
+__global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const float *__restrict__ x,
+                                                              const float *__restrict__ w,
+                                                              const float *__restrict__ bias, float alpha,
+                                                              const float *__restrict__ alpha_dev,
+                                                              float *__restrict__ y, int strips_per_row, int CQ,
+                                                              int sq4, int RS, int work_offset) {
+    typedef typename FVec<NT>::T WV;
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef const __attribute__((address_space(1))) WV *gw_ptr;
+    typedef const __attribute__((address_space(1))) f32x4 *gx4_ptr;
+    constexpr int BT = 16 * MT, NFW = 4 / NLOC;
+    extern __shared__ __attribute__((aligned(16))) float xs[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, kk = lane >> 4;
+    const int work = work_offset + remap_xcd(blockIdx.x, gridDim.x);
+    const int i = work / strips_per_row, j0 = (work - i * strips_per_row) * NLOC;
+    const int b0 = blockIdx.z * BT;
+    const int wl = wave % NLOC, wf = wave / NLOC;
+    const int j = j0 + wl;
+    const int f0 = (blockIdx.y * NFW + wf) * NT * 16;
+    const bool active = j < g.LW;
+    const int loc = i * g.LW + (active ? j : g.LW - 1);   // idle waves shadow the last field of the row
+    const int SC = g.S * g.C, WC = g.W * g.C;
+    const size_t img = (size_t)g.H * WC;
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) acc[mt][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // staging map: slot q of this thread copies dwordx4 number e = tid + 256*q of the [BT][sq4] chunk.
+    // sb[q] = image << 16 | float offset inside the chunk; bit 31: past the end of the chunk (slot unused),
+    // bit 30: image beyond the batch (its LDS row is filled with zeros).
+    const int nslots = (BT * sq4 + 255) >> 8;
+    int sb[kFwdStageSlots];
+    {
+        int v = tid % sq4, b = tid / sq4;
+        const int dv = 256 % sq4, db = 256 / sq4;
+#pragma unroll
+        for (int q = 0; q < kFwdStageSlots; ++q) {
+            sb[q] = (b << 16) | (v * 4);
+            if (b >= BT) sb[q] = (int)0x80000000;
+            else if (b0 + b >= g.B) sb[q] |= 0x40000000;
+            v += dv; b += db;
+            if (v >= sq4) { v -= sq4; ++b; }
+        }
+    }
+    const int col0 = j0 * SC;
+    f32x4 st[kFwdStageSlots];
+    auto stage_load = [&](int kh, int sc) {
+        const float *row = x + (size_t)b0 * img + (size_t)(i * g.S + kh) * WC + col0 + sc * CQ;
+        const int lim = WC - col0 - sc * CQ;          // floats of this image row that exist from the chunk start on
+#pragma unroll
+        for (int q = 0; q < kFwdStageSlots; ++q) {
+            if (q < nslots) {
+                const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xffff;
+                f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if ((sb[q] & 0xc0000000) == 0 && v < lim) t = *(gx4_ptr)(row + (size_t)b * img + v);
+                st[q] = t;
+            }
+        }
+    };
+    auto stage_store = [&]() {
+#pragma unroll
+        for (int q = 0; q < kFwdStageSlots; ++q) {
+            if (q < nslots && sb[q] >= 0) {
+                const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xffff;
+                float *dst = xs + b * RS + ((b >> 2) & 2) + v;       // rows of images 8..15 (mod 16) sit 2 floats to the right
+                *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
+                *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
+            }
+        }
+    };
+
+    // weight ring: slot s holds k-step S = s (mod UNR); w[loc] is walked linearly in k
+    const int nsteps = g.K >> 2;
+    gw_ptr wp = (gw_ptr)(w + (size_t)loc * g.K * g.F + (size_t)kk * g.F + f0 + NT * n);
+    const size_t wstep = (size_t)g.F;           // in units of float: 4 rows per k-step -> 4*F floats
+    WV wr[UNR];
+    int wleft = nsteps;                         // k-steps not yet requested
+#pragma unroll
+    for (int s = 0; s < UNR; ++s) {
+        wr[s] = *wp;
+        --wleft;
+        wp = (gw_ptr)((const __attribute__((address_space(1))) float *)wp + (wleft > 0 ? 4 * wstep : 0));
+    }
+
+    // LDS bank layout: RS == 4 (mod 32) puts images m and m+8 of an A operand on the same banks; shifting
+    // the rows of images 8..15 by two floats makes the 32 (image, k) pairs of a half-wave hit 32 banks.
+    const float *xwin = xs + (size_t)(lane & 15) * RS + ((lane >> 2) & 2) + wl * SC + kk;
+    const int spc = CQ >> 2;                    // k-steps per chunk, a multiple of UNR
+    const int nsub = g.RC / CQ;
+    stage_load(0, 0);
+    for (int kh = 0; kh < g.R; ++kh) {
+        for (int sc = 0; sc < nsub; ++sc) {
+            __syncthreads();                    // all waves are done reading the previous chunk
+            stage_store();
+            __syncthreads();
+            {
+                int nsc = sc + 1, nkh = kh;
+                if (nsc == nsub) { nsc = 0; ++nkh; }
+                if (nkh < g.R) stage_load(nkh, nsc);
+            }
+            for (int s0 = 0; s0 < spc; s0 += UNR) {
+#pragma unroll
+                for (int ss = 0; ss < UNR; ++ss) {
+                    float a[MT];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) a[mt] = xwin[mt * 16 * RS + 4 * (s0 + ss)];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int u = 0; u < NT; ++u) acc[mt][u] = mfma16(a[mt], fget<NT>(wr[ss], u), acc[mt][u]);
+                    wr[ss] = *wp;
+                    --wleft;
+                    wp = (gw_ptr)((const __attribute__((address_space(1))) float *)wp + (wleft > 0 ? 4 * wstep : 0));
+                    // MFMAs and global loads keep their order (LDS reads and address arithmetic may move across)
+                    __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
+                }
+            }
+        }
+    }
+
+    if (!active) return;
+    if (alpha_dev) alpha = *alpha_dev;
+    WV bv;
+    if constexpr (NT == 1) bv = 0.f; else bv = (WV)(0.f);
+    if (bias) bv = *(const WV *)(bias + (size_t)loc * g.F + f0 + NT * n);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int b = b0 + mt * 16 + 4 * kk + r;
+            if (b >= g.B) continue;
+            WV o;
+            if constexpr (NT == 1) {
+                o = alpha * acc[mt][0][r] + bv;
+            } else {
+#pragma unroll
+                for (int u = 0; u < NT; ++u) o[u] = alpha * acc[mt][u][r] + bv[u];
+            }
+            *(WV *)(y + ((size_t)b * g.L + loc) * g.F + f0 + NT * n) = o;
+        }
+}
+
 namespace {
 
 struct FwdPlan { int MT, NT, NLOC; };
@@ -154,8 +325,106 @@ int launch_one(const Geom &g, const float *x, const float *w, const float *bias,
 
 }  // namespace
 
+namespace {
+
+int fast_row_stride(int sqc) {
+    // stride == 4 (mod 32) floats: the 16 images x 4 k-offsets a wave reads per A operand spread over the banks
+    return ((sqc + 31) / 32) * 32 + 4;
+}
+
+template <int MT, int NT, int NLOC, int UNR>
+int launch_fast(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                const float *alpha_dev, float *y, int CQ, int work_first, int work_count, hipStream_t s) {
+    constexpr int BT = 16 * MT, NFW = 4 / NLOC;
+    const int sqc = CQ + (NLOC - 1) * g.S * g.C;
+    const int RS = fast_row_stride(sqc);
+    const size_t lds = (size_t)BT * RS * sizeof(float);
+    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) { set_hip_error(e, "lc_forward: hipFuncSetAttribute"); return LC_EHIP; }
+    }
+    const int strips = (g.LW + NLOC - 1) / NLOC;
+    dim3 grid(work_count, g.F / (NFW * NT * 16), (g.B + BT - 1) / BT);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS,
+                       work_first);
+    LC_HIP_LAUNCH_CHECK("lc_forward launch");
+    return LC_OK;
+}
+
+// Workgroups of the big tile are long (a strip of fields times the whole batch tile) and only two fit a
+// compute unit, so a grid that is not a multiple of 2 x 256 ends in a round that leaves most of the
+// chip idle.  The strips of that last partial round are therefore issued as a second launch whose
+// workgroups take a quarter of the batch tile each: four times as many, a quarter as long.
+constexpr int kComputeUnits = 256, kBigTilesPerCu = 2;
+
+template <int MT, int NT, int NLOC, int UNR>
+int launch_fast_tiered(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                       const float *alpha_dev, float *y, int CQ, hipStream_t s) {
+    const int strips = (g.LW + NLOC - 1) / NLOC;
+    const int ntask = strips * g.LH, slots = kComputeUnits * kBigTilesPerCu;
+    const int zb = (g.B + 16 * MT - 1) / (16 * MT) * (g.F / ((4 / NLOC) * NT * 16));
+    const int rounds = (ntask * zb) / slots, rem = ntask * zb - rounds * slots;
+    if constexpr (MT == 8) {
+        if (zb == 1 && rounds >= 1 && rounds <= 6 && rem > 0 && rem <= slots * 3 / 4) {
+            const int first = rounds * slots;
+            int rc = launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 0, first, s);
+            if (rc != LC_OK) return rc;
+            return launch_fast<2, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, first, ntask - first, s);
+        }
+    }
+    return launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 0, ntask, s);
+}
+
+// Picks the chunk (CQ floats of a patch row, a divisor of RC and multiple of 4*UNR) so that the staged
+// strip of BT images fits the staging registers and the LDS budget.  Returns 0 if none does.
+int pick_chunk(const Geom &g, int BT, int NLOC, int UNR, size_t lds_budget) {
+    const int SC = g.S * g.C;
+    for (int nsub = 1; nsub <= g.RC / (4 * UNR); ++nsub) {
+        if (g.RC % nsub) continue;
+        const int CQ = g.RC / nsub;
+        if (CQ % (4 * UNR)) continue;
+        const int sqc = CQ + (NLOC - 1) * SC;
+        if ((size_t)BT * (sqc / 4) > (size_t)kFwdStageSlots * 256) continue;
+        if ((size_t)BT * fast_row_stride(sqc) * 4 > lds_budget) continue;
+        if (sqc / 4 > 0xffff / 4) continue;
+        return CQ;
+    }
+    return 0;
+}
+
+template <int MT, int NT, int NLOC>
+int launch_fast_unr(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                    const float *alpha_dev, float *y, hipStream_t s, bool *done) {
+    const size_t budget = 52 * 1024;  // three workgroups per compute unit
+    *done = true;
+    const int spr = g.RC / 4;
+    int CQ;
+    if (spr % 8 == 0 && (CQ = pick_chunk(g, 16 * MT, NLOC, 8, budget)))
+        return launch_fast_tiered<MT, NT, NLOC, 8>(g, x, w, bias, alpha, alpha_dev, y, CQ, s);
+    if (spr % 6 == 0 && (CQ = pick_chunk(g, 16 * MT, NLOC, 6, budget)))
+        return launch_fast_tiered<MT, NT, NLOC, 6>(g, x, w, bias, alpha, alpha_dev, y, CQ, s);
+    if (spr % 5 == 0 && (CQ = pick_chunk(g, 16 * MT, NLOC, 5, budget)))
+        return launch_fast_tiered<MT, NT, NLOC, 5>(g, x, w, bias, alpha, alpha_dev, y, CQ, s);
+    *done = false;
+    return LC_OK;
+}
+
+}  // namespace
+
 int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
                        const float *alpha_dev, float *y, hipStream_t s) {
+    // aligned shapes take the pipelined kernel
+    const bool aligned = g.RC % 4 == 0 && (g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.K / 4 >= 8;
+    if (aligned && g.B > 64) {
+        bool done = false;
+        int rc = LC_OK;
+        if (g.F % 128 == 0) rc = launch_fast_unr<8, 4, 2>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        else if (g.F % 64 == 0) rc = launch_fast_unr<8, 4, 4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        else if (g.F % 32 == 0) rc = launch_fast_unr<8, 2, 4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        else if (g.F % 16 == 0) rc = launch_fast_unr<8, 1, 4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        if (done) return rc;
+    }
     // Pick the tile: as many images per wave as the batch offers (weights are re-read once per batch
     // tile), then as many filters as fit the accumulator budget, then the widest strip that fits LDS.
     const int mt = g.B > 64 ? 8 : g.B > 32 ? 4 : g.B > 16 ? 2 : 1;
