@@ -142,6 +142,162 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Fast path (F % 16 == 0, R % S == 0).  Same cell-gather decomposition with the pipeline of the forward
+// kernel: a chunk is one field row (a) and 16 filters (fh) of every field the strip of cells touches;
+// the next chunk's dy travels through registers into LDS while the current one is multiplied; the
+// weights of step a'+1 are in flight while step a' runs.  Per step a' a wave multiplies
+// dy[128 images][16 f] of field (ri-a, wi-a') with the S x S x C block of that field's filters:
+// lane (n,kk) loads w[k(n)][fh*16 + 4kk .. +3] as one dwordx4, and lane (m,kk) reads the same four f
+// of image m from LDS, so component t of both vectors is contraction index 4kk+t of MFMA number t.
+// Fields outside the grid are staged as zeros (their weights are read from a clamped, valid address),
+// so the inner loop has no branches.
+template <int MT, int NT, int NCELL, int AP>
+__global__ __launch_bounds__(256) void lc_bwd_data_fast_kernel(Geom g, const float *__restrict__ dy,
+                                                               const float *__restrict__ w,
+                                                               float *__restrict__ dx, int strips_per_row, int RS,
+                                                               int work_offset, int nbt) {
+    typedef const __attribute__((address_space(1))) f32x4 *g4_ptr;
+    typedef const __attribute__((address_space(1))) float *gf_ptr;
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 4;   // R4: dwordx4 per image and chunk
+    constexpr int NSLOT = (BT * R4 + 255) / 256;
+    extern __shared__ __attribute__((aligned(16))) float dys[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, kk = lane >> 4;
+    const int SC = g.S * g.C, NCV = g.S * SC;
+    // batch tiles of one strip are neighbours in dispatch order on the same XCD: the second one finds
+    // the strip's weights in that XCD's L2
+    const int t_id = remap_xcd(blockIdx.x, gridDim.x);
+    const int work = work_offset + t_id / nbt;
+    const int ri = work / strips_per_row, wi0 = (work - ri * strips_per_row) * NCELL;
+    const int b0 = (t_id % nbt) * BT;
+    const int wc = wave % NCELL;
+    const int wi = wi0 + wc;
+    const int n0 = (blockIdx.y * (4 / NCELL) + wave / NCELL) * NT * 16;
+    const int nfh = g.F >> 4;
+
+    // cell values this lane supplies weights for / stores
+    int kn[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int nn = n0 + nt * 16 + m;
+        const int nc = nn < NCV ? nn : 0;
+        const int dr = nc / SC;
+        kn[nt] = (dr * g.RC + (nc - dr * SC)) * g.F + 4 * kk;    // float offset inside a field's K x F matrix
+    }
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // chunks: (a, fh) with a valid field row i = ri - a
+    const int a_lo = max(0, ri - (g.LH - 1)), a_hi = min(AP - 1, ri);   // inclusive; empty if a_lo > a_hi
+    const int nchunks = a_hi >= a_lo ? (a_hi - a_lo + 1) * nfh : 0;
+    const int jlo = wi0 - (AP - 1);
+    const size_t dyimg = (size_t)g.L * g.F;
+
+    const int v0 = tid % R4, bq0 = tid / R4;
+    constexpr int DV = 256 % R4, DB = 256 / R4;
+    f32x4 st[NSLOT];
+    auto stage_load = [&](int c) {
+        const int a = a_lo + c / nfh, fh = c - (c / nfh) * nfh;
+        const float *base = dy + (size_t)b0 * dyimg + (size_t)((ri - a) * g.LW) * g.F + fh * 16;
+        int v = v0, b = bq0;
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) {
+            const int j = jlo + (v >> 2);
+            f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (b < BT && b0 + b < g.B && j >= 0 && j < g.LW)
+                t = *(g4_ptr)(base + (size_t)b * dyimg + j * g.F + (v & 3) * 4);
+            st[q] = t;
+            v += DV; b += DB;
+            if (v >= R4) { v -= R4; ++b; }
+        }
+    };
+    auto stage_store = [&]() {
+        int v = v0, b = bq0;
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) {
+            if (b < BT) {
+                // two 8-byte stores: 16-byte LDS stores of a row-major tile run into bank conflicts
+                float *dst = dys + b * RS + v * 4;
+                *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
+                *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
+            }
+            v += DV; b += DB;
+            if (v >= R4) { v -= R4; ++b; }
+        }
+    };
+    // weights of step (chunk c, a'): field (ri-a, wi-a') clamped into the grid
+    auto wbase = [&](int c, int ap) -> gf_ptr {
+        const int a = a_lo + c / nfh, fh = c - (c / nfh) * nfh;
+        int j = wi - ap;
+        j = j < 0 ? 0 : (j >= g.LW ? g.LW - 1 : j);
+        return (gf_ptr)w + ((size_t)((ri - a) * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F +
+               fh * 16;
+    };
+
+    if (nchunks > 0) {
+        // weight ring: slot a' holds the weights of step a' of the current chunk and is refilled, right
+        // after its use, with step a' of the next chunk: loads run one whole chunk ahead of the MFMAs
+        f32x4 wb[AP][NT];
+#pragma unroll
+        for (int ap = 0; ap < AP; ++ap) {
+            gf_ptr p0 = wbase(0, ap);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = *(g4_ptr)(p0 + kn[nt]);
+        }
+        stage_load(0);
+        const float *arow = dys + m * RS + 4 * kk;
+        for (int c = 0; c < nchunks; ++c) {
+            __syncthreads();
+            stage_store();
+            __syncthreads();
+            const int cn = c + 1 < nchunks ? c + 1 : c;
+            if (c + 1 < nchunks) stage_load(c + 1);
+#pragma unroll
+            for (int ap = 0; ap < AP; ++ap) {
+                const int js = wc - ap + AP - 1;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const f32x4 av = *(const f32x4 *)(arow + mt * 16 * RS + js * 16);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[mt][nt] = mfma16(av[t], wb[ap][nt][t], acc[mt][nt]);
+                }
+                gf_ptr pn = wbase(cn, ap);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = *(g4_ptr)(pn + kn[nt]);
+                __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
+            }
+        }
+    }
+
+    if (wi * g.S >= g.W) return;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int nn = n0 + nt * 16 + m;
+        if (nn >= NCV) continue;
+        const int dr = nn / SC, rem = nn - dr * SC;
+        const int row = ri * g.S + dr, col = wi * g.S + rem / g.C;
+        if (row >= g.H || col >= g.W) continue;
+        const size_t pix = ((size_t)row * g.W + wi * g.S) * g.C + rem;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int b = b0 + mt * 16 + 4 * kk + r;
+                if (b < g.B) dx[(size_t)b * g.H * g.W * g.C + pix] = acc[mt][nt][r];
+            }
+    }
+}
+
 namespace {
 
 constexpr size_t kLdsTarget = 78 * 1024;
@@ -192,7 +348,36 @@ int launch_mt(const Geom &g, const float *dy, const float *w, float *dx, hipStre
 
 }  // namespace
 
+namespace {
+
+template <int MT, int NT, int NCELL, int AP>
+int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
+    const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
+    const int NCV = g.S * g.S * g.C;
+    const int RS = ((JW * 16 + 31) / 32) * 32 + 4;
+    const size_t lds = (size_t)BT * RS * sizeof(float);
+    auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) { set_hip_error(e, "lc_backward_data: hipFuncSetAttribute"); return LC_EHIP; }
+    }
+    const int strips = (CW + NCELL - 1) / NCELL;
+    const int nblk = (4 / NCELL) * NT * 16;
+    const int nbt = (g.B + BT - 1) / BT;
+    dim3 grid(strips * CH * nbt, (NCV + nblk - 1) / nblk);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, RS, 0, nbt);
+    LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
+    return LC_OK;
+}
+
+}  // namespace
+
 int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    if (g.F % 16 == 0 && g.R % g.S == 0 && g.B > 64) {
+        const int ap = g.R / g.S, ntt = (g.S * g.S * g.C + 15) / 16;
+        if (ap == 5 && ntt == 3) return launch_fast<4, 3, 4, 5>(g, dy, w, dx, s);
+    }
     if (g.B > 64) return launch_mt<8>(g, dy, w, dx, s);
     if (g.B > 32) return launch_mt<4>(g, dy, w, dx, s);
     if (g.B > 16) return launch_mt<2>(g, dy, w, dx, s);

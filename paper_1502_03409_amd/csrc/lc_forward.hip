@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
                                                               const float *__restrict__ bias, float alpha,
                                                               const float *__restrict__ alpha_dev,
                                                               float *__restrict__ y, int strips_per_row, int CQ,
-                                                              int sq4, int RS, int work_offset) {
+                                                              int sq4, int RS, int work_offset, int nbt) {
     typedef typename FVec<NT>::T WV;
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     typedef const __attribute__((address_space(1))) WV *gw_ptr;
@@ -157,9 +157,12 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
     extern __shared__ __attribute__((aligned(16))) float xs[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kk = lane >> 4;
-    const int work = work_offset + remap_xcd(blockIdx.x, gridDim.x);
+    // batch tiles of one strip are neighbours in dispatch order on the same XCD: the later ones find
+    // the strip's weights in that XCD's L2
+    const int t_id = remap_xcd(blockIdx.x, gridDim.x);
+    const int work = work_offset + t_id / nbt;
     const int i = work / strips_per_row, j0 = (work - i * strips_per_row) * NLOC;
-    const int b0 = blockIdx.z * BT;
+    const int b0 = (t_id % nbt) * BT;
     const int wl = wave % NLOC, wf = wave / NLOC;
     const int j = j0 + wl;
     const int f0 = (blockIdx.y * NFW + wf) * NT * 16;
@@ -345,9 +348,10 @@ int launch_fast(const Geom &g, const float *x, const float *w, const float *bias
         if (e != hipSuccess) { set_hip_error(e, "lc_forward: hipFuncSetAttribute"); return LC_EHIP; }
     }
     const int strips = (g.LW + NLOC - 1) / NLOC;
-    dim3 grid(work_count, g.F / (NFW * NT * 16), (g.B + BT - 1) / BT);
+    const int nbt = (g.B + BT - 1) / BT;
+    dim3 grid(work_count * nbt, g.F / (NFW * NT * 16));
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS,
-                       work_first);
+                       work_first, nbt);
     LC_HIP_LAUNCH_CHECK("lc_forward launch");
     return LC_OK;
 }
