@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
                                                               const float *__restrict__ bias, float alpha,
                                                               const float *__restrict__ alpha_dev,
                                                               float *__restrict__ y, int strips_per_row, int CQ,
-                                                              int sq4, int RS, int work_offset, int nbt) {
+                                                              int sq4, int RS, int NR, int work_offset, int nbt) {
     typedef typename FVec<NT>::T WV;
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     typedef const __attribute__((address_space(1))) WV *gw_ptr;
@@ -177,21 +177,23 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
 #pragma unroll
         for (int u = 0; u < NT; ++u) acc[mt][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // staging map: slot q of this thread copies dwordx4 number e = tid + 256*q of the [BT][sq4] chunk.
-    // sb[q] = image << 16 | float offset inside the chunk; bit 31: past the end of the chunk (slot unused),
-    // bit 30: image beyond the batch (its LDS row is filled with zeros).
-    const int nslots = (BT * sq4 + 255) >> 8;
+    // staging map: a chunk is NR patch rows x sq4 dwordx4 per image; slot q of this thread copies dwordx4
+    // number e = tid + 256*q of the [BT][NR][sq4] chunk.  sb[q] = image << 16 | row << 12 | float offset in
+    // the row; bit 31: past the end of the chunk (slot unused), bit 30: image beyond the batch (zeros).
+    const int per_img = NR * sq4, sqc = sq4 * 4;
+    const int nslots = (BT * per_img + 255) >> 8;
     int sb[kFwdStageSlots];
     {
-        int v = tid % sq4, b = tid / sq4;
-        const int dv = 256 % sq4, db = 256 / sq4;
+        int vv = tid % per_img, b = tid / per_img;
+        const int dv = 256 % per_img, db = 256 / per_img;
 #pragma unroll
         for (int q = 0; q < kFwdStageSlots; ++q) {
-            sb[q] = (b << 16) | (v * 4);
+            const int r = vv / sq4, v = vv - r * sq4;
+            sb[q] = (b << 16) | (r << 12) | (v * 4);
             if (b >= BT) sb[q] = (int)0x80000000;
             else if (b0 + b >= g.B) sb[q] |= 0x40000000;
-            v += dv; b += db;
-            if (v >= sq4) { v -= sq4; ++b; }
+            vv += dv; b += db;
+            if (vv >= per_img) { vv -= per_img; ++b; }
         }
     }
     const int col0 = j0 * SC;
@@ -202,9 +204,9 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
 #pragma unroll
         for (int q = 0; q < kFwdStageSlots; ++q) {
             if (q < nslots) {
-                const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xffff;
+                const int b = (sb[q] >> 16) & 0x3fff, r = (sb[q] >> 12) & 15, v = sb[q] & 0xfff;
                 f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if ((sb[q] & 0xc0000000) == 0 && v < lim) t = *(gx4_ptr)(row + (size_t)b * img + v);
+                if ((sb[q] & 0xc0000000) == 0 && v < lim) t = *(gx4_ptr)(row + (size_t)b * img + r * WC + v);
                 st[q] = t;
             }
         }
@@ -213,8 +215,9 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
 #pragma unroll
         for (int q = 0; q < kFwdStageSlots; ++q) {
             if (q < nslots && sb[q] >= 0) {
-                const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xffff;
-                float *dst = xs + b * RS + ((b >> 2) & 2) + v;       // rows of images 8..15 (mod 16) sit 2 floats to the right
+                const int b = (sb[q] >> 16) & 0x3fff, r = (sb[q] >> 12) & 15, v = sb[q] & 0xfff;
+                // rows of images 8..15 (mod 16) sit 2 floats to the right (see xwin below)
+                float *dst = xs + b * RS + r * sqc + ((b >> 2) & 2) + v;
                 *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
                 *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
             }
@@ -237,34 +240,38 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
     // LDS bank layout: RS == 4 (mod 32) puts images m and m+8 of an A operand on the same banks; shifting
     // the rows of images 8..15 by two floats makes the 32 (image, k) pairs of a half-wave hit 32 banks.
     const float *xwin = xs + (size_t)(lane & 15) * RS + ((lane >> 2) & 2) + wl * SC + kk;
-    const int spc = CQ >> 2;                    // k-steps per chunk, a multiple of UNR
-    const int nsub = g.RC / CQ;
+    const int spc = CQ >> 2;                    // k-steps per patch row of a chunk, a multiple of UNR
+    const int nsub = g.RC / CQ;                 // NR > 1 only with whole rows (nsub == 1)
     stage_load(0, 0);
-    for (int kh = 0; kh < g.R; ++kh) {
+    for (int kh = 0; kh < g.R; kh += NR) {
         for (int sc = 0; sc < nsub; ++sc) {
             __syncthreads();                    // all waves are done reading the previous chunk
             stage_store();
             __syncthreads();
             {
                 int nsc = sc + 1, nkh = kh;
-                if (nsc == nsub) { nsc = 0; ++nkh; }
+                if (nsc == nsub) { nsc = 0; nkh += NR; }
                 if (nkh < g.R) stage_load(nkh, nsc);
             }
-            for (int s0 = 0; s0 < spc; s0 += UNR) {
+            for (int r = 0; r < NR; ++r) {
+                const float *xrow = xwin + r * sqc;
+                for (int s0 = 0; s0 < spc; s0 += UNR) {
 #pragma unroll
-                for (int ss = 0; ss < UNR; ++ss) {
-                    float a[MT];
+                    for (int ss = 0; ss < UNR; ++ss) {
+                        float a[MT];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) a[mt] = xwin[mt * 16 * RS + 4 * (s0 + ss)];
+                        for (int mt = 0; mt < MT; ++mt) a[mt] = xrow[mt * 16 * RS + 4 * (s0 + ss)];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
+                        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                        for (int u = 0; u < NT; ++u) acc[mt][u] = mfma16(a[mt], fget<NT>(wr[ss], u), acc[mt][u]);
-                    wr[ss] = *wp;
-                    --wleft;
-                    wp = (gw_ptr)((const __attribute__((address_space(1))) float *)wp + (wleft > 0 ? 4 * wstep : 0));
-                    // MFMAs and global loads keep their order (LDS reads and address arithmetic may move across)
-                    __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
+                            for (int u = 0; u < NT; ++u)
+                                acc[mt][u] = mfma16(a[mt], fget<NT>(wr[ss], u), acc[mt][u]);
+                        wr[ss] = *wp;
+                        --wleft;
+                        wp = (gw_ptr)((const __attribute__((address_space(1))) float *)wp + (wleft > 0 ? 4 * wstep : 0));
+                        // MFMAs and global loads keep their order (LDS reads and address arithmetic may move across)
+                        __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
+                    }
                 }
             }
         }
@@ -337,10 +344,10 @@ int fast_row_stride(int sqc) {
 
 template <int MT, int NT, int NLOC, int UNR>
 int launch_fast(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
-                const float *alpha_dev, float *y, int CQ, int work_first, int work_count, hipStream_t s) {
+                const float *alpha_dev, float *y, int CQ, int NR, int work_first, int work_count, hipStream_t s) {
     constexpr int BT = 16 * MT, NFW = 4 / NLOC;
     const int sqc = CQ + (NLOC - 1) * g.S * g.C;
-    const int RS = fast_row_stride(sqc);
+    const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
     auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR>;
     if (lds > 48 * 1024) {
@@ -350,7 +357,7 @@ int launch_fast(const Geom &g, const float *x, const float *w, const float *bias
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(work_count * nbt, g.F / (NFW * NT * 16));
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS,
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS, NR,
                        work_first, nbt);
     LC_HIP_LAUNCH_CHECK("lc_forward launch");
     return LC_OK;
@@ -372,12 +379,24 @@ int launch_fast_tiered(const Geom &g, const float *x, const float *w, const floa
     if constexpr (MT == 8) {
         if (zb == 1 && rounds >= 1 && rounds <= 6 && rem > 0 && rem <= slots * 3 / 4) {
             const int first = rounds * slots;
-            int rc = launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 0, first, s);
+            int rc = launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s);
             if (rc != LC_OK) return rc;
-            return launch_fast<2, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, first, ntask - first, s);
+            // the short workgroups stage four patch rows at a time (same LDS footprint as the long ones),
+            // so that a chunk's MFMAs still cover the latency of fetching the next one
+            int nr = 1;
+            if (CQ == g.RC) {
+                for (int c : {4, 3, 2})
+                    if (g.R % c == 0) { nr = c; break; }
+            }
+            // their k-steps are short (2 x NT MFMAs), so the weight ring is made as deep as a whole patch row
+            if ((CQ >> 2) % 15 == 0)
+                return launch_fast<2, NT, NLOC, 15>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, first, ntask - first, s);
+            if ((CQ >> 2) % 16 == 0)
+                return launch_fast<2, NT, NLOC, 16>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, first, ntask - first, s);
+            return launch_fast<2, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, first, ntask - first, s);
         }
     }
-    return launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 0, ntask, s);
+    return launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
 }
 
 // Picks the chunk (CQ floats of a patch row, a divisor of RC and multiple of 4*UNR) so that the staged
