@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sae", action="store_true")
+    ap.add_argument("--hbm-calibration", action="store_true",
+                    help="only run a plain device-to-device copy of 1 GiB five times (reference for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
     return ap.parse_args()
 
 
@@ -59,6 +62,14 @@ def main() -> int:
     lc.lib()
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
+    if args.hbm_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"hbm_calibration": "copy", "bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4}))
+        return 0
 
     def dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()

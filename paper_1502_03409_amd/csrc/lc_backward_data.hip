@@ -262,14 +262,17 @@ __global__ __launch_bounds__(256) void lc_bwd_data_fast_kernel(Geom g, const flo
 #pragma unroll
             for (int ap = 0; ap < AP; ++ap) {
                 const int js = wc - ap + AP - 1;
+                // a field column outside the grid contributes nothing: skip its MFMAs (uniform over the wave)
+                if (wi - ap >= 0 && wi - ap < g.LW) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const f32x4 av = *(const f32x4 *)(arow + mt * 16 * RS + js * 16);
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const f32x4 av = *(const f32x4 *)(arow + mt * 16 * RS + js * 16);
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
+                        for (int t = 0; t < 4; ++t)
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
-                            acc[mt][nt] = mfma16(av[t], wb[ap][nt][t], acc[mt][nt]);
+                            for (int nt = 0; nt < NT; ++nt)
+                                acc[mt][nt] = mfma16(av[t], wb[ap][nt][t], acc[mt][nt]);
+                    }
                 }
                 gf_ptr pn = wbase(cn, ap);
 #pragma unroll
