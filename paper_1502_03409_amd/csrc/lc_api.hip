@@ -56,7 +56,7 @@ int lc_forward(const lc_geom_t *g, const void *x, const void *w, const float *bi
     if (dtype != LC_F32 && dtype != LC_BF16) return LC_EINVAL;
     LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(w); LC_REQUIRE_PTR(y);
     LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(w); LC_REQUIRE_ALIGNED(y); LC_REQUIRE_ALIGNED(bias);
-    if (dtype == LC_BF16) return LC_EUNSUPPORTED;
+    if (dtype == LC_BF16) return launch_forward_bf16(q, x, w, bias, alpha, y, (hipStream_t)hip_stream);
     return launch_forward_f32(q, (const float *)x, (const float *)w, bias, alpha, nullptr, y, (hipStream_t)hip_stream);
 }
 
@@ -68,7 +68,7 @@ int lc_backward_data(const lc_geom_t *g, const void *dy, const void *w, float *d
     if (dtype != LC_F32 && dtype != LC_BF16) return LC_EINVAL;
     LC_REQUIRE_PTR(dy); LC_REQUIRE_PTR(w); LC_REQUIRE_PTR(dx);
     LC_REQUIRE_ALIGNED(dy); LC_REQUIRE_ALIGNED(w); LC_REQUIRE_ALIGNED(dx);
-    if (dtype == LC_BF16) return LC_EUNSUPPORTED;
+    if (dtype == LC_BF16) return launch_backward_data_bf16(q, dy, w, dx, (hipStream_t)hip_stream);
     return launch_backward_data_f32(q, (const float *)dy, (const float *)w, dx, (hipStream_t)hip_stream);
 }
 
@@ -81,7 +81,7 @@ int lc_backward_weights(const lc_geom_t *g, const void *x, const void *dy, float
     if (!(beta == 0.f || beta == 1.f)) return LC_EINVAL;
     LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(dy); LC_REQUIRE_PTR(dw);
     LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(dy); LC_REQUIRE_ALIGNED(dw);
-    if (dtype == LC_BF16) return LC_EUNSUPPORTED;
+    if (dtype == LC_BF16) return launch_backward_weights_bf16(q, x, dy, beta, dw, (hipStream_t)hip_stream);
     return launch_backward_weights_f32(q, (const float *)x, (const float *)dy, nullptr, nullptr, beta, 1.f, dw,
                                        (hipStream_t)hip_stream);
 }

@@ -76,6 +76,11 @@ int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx
 // mode 0: forward (out = y; mu, rstd written).  mode 1: backward (out = dx; mu, rstd read).
 int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
                int C, int ks, float sigma, float eps, hipStream_t s);
+// bf16 operands (raw 16-bit patterns), fp32 results; LC_EUNSUPPORTED for shapes outside the aligned set
+int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
+                        hipStream_t s);
+int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s);
+int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, float beta, float *dw, hipStream_t s);
 size_t sae_workspace_bytes(const Geom &g);
 int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
                     float lr, uint32_t flags, float *h_out, float *cost_out, void *ws, hipStream_t s);

@@ -122,6 +122,90 @@ def test_lc_primitives_full_size_sampled(name):
     assert rel_fro(gw, rw) <= TOL
 
 
+BF16_CASES = {
+    "small": (wl.LCGeom(B=32, H=12, W=14, C=8, R=4, S=2, F=64), "halfnormal"),
+    "two_fblocks": (wl.LCGeom(B=48, H=10, W=10, C=16, R=6, S=2, F=128), "halfnormal"),
+    "cfg4_quarter": (wl.LCGeom(B=144, H=20, W=22, C=32, R=8, S=2, F=128), "halfnormal"),
+}
+
+
+@pytest.mark.parametrize("name", list(BF16_CASES))
+def test_lc_primitives_bf16_match_oracle(name):
+    """bf16 operands, fp32 accumulation: the oracle takes the unrounded fp32 inputs; bar 2e-2."""
+    g, kind = BF16_CASES[name]
+    print(f"case bf16 {name} geom {g}", flush=True)
+    x, w, dy, bias = wl.lc_inputs(g, kind, seed=0, with_bias=True)
+    t = g.as_tuple()
+    G = lc.geom(*t)
+    bf = lambda a: torch.from_numpy(wl.to_bf16_round(a).view(np.int16)).cuda().view(torch.bfloat16)
+    xd, wd, dyd = bf(x), bf(w), bf(dy)
+    y = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
+    dx = torch.full((g.B, g.H, g.W, g.C), float("nan"), device="cuda")
+    dw = torch.full((g.LH, g.LW, g.K, g.F), float("nan"), device="cuda")
+    lc.lc_forward(G, xd, wd, dev(bias), 0.75, y, lc.LC_BF16)
+    lc.lc_backward_data(G, dyd, wd, dx, lc.LC_BF16)
+    lc.lc_backward_weights(G, xd, dyd, 0.0, dw, lc.LC_BF16)
+    assert rel_fro(host(y), oracle.lc_forward(t, x, w, bias, 0.75)) <= 2e-2
+    assert rel_fro(host(dx), oracle.lc_backward_data(t, dy, w)) <= 2e-2
+    ref_dw = oracle.lc_backward_weights(t, x, dy)
+    assert rel_fro(host(dw), ref_dw) <= 2e-2
+    # against the oracle fed with the same rounded operands the remaining error is fp32 accumulation only
+    rnd = lambda a: (wl.to_bf16_round(a).astype(np.uint32) << 16).view(np.float32)
+    assert rel_fro(host(y), oracle.lc_forward(t, rnd(x), rnd(w), bias, 0.75)) <= 1e-4
+    assert rel_fro(host(dx), oracle.lc_backward_data(t, rnd(dy), rnd(w))) <= 1e-4
+    assert rel_fro(host(dw), oracle.lc_backward_weights(t, rnd(x), rnd(dy))) <= 1e-4
+    prev = np.random.default_rng(5).standard_normal(ref_dw.shape).astype(np.float32)
+    dw1 = dev(prev)
+    lc.lc_backward_weights(G, xd, dyd, 1.0, dw1, lc.LC_BF16)
+    assert rel_fro(host(dw1), ref_dw + prev) <= 2e-2
+
+
+def test_cfg4_bf16_full_size_sampled():
+    """Workload cfg4 with bf16 operands at full size: sampled outputs against the oracle's single-output
+    evaluators on the unrounded fp32 inputs (bar 2e-2), and the adjoint identities on the device results."""
+    g = wl.CONFIG_GEOM["cfg4"]
+    print(f"case cfg4 bf16 geom {g}", flush=True)
+    x, w, dy = wl.lc_inputs(g, wl.CONFIG_IMAGE_KIND["cfg4"], seed=0)
+    t = g.as_tuple()
+    G = lc.geom(*t)
+    bf = lambda a: torch.from_numpy(wl.to_bf16_round(a).view(np.int16)).cuda().view(torch.bfloat16)
+    xd, wd, dyd = bf(x), bf(w), bf(dy)
+    y = torch.empty((g.B, g.LH, g.LW, g.F), device="cuda")
+    dx = torch.empty((g.B, g.H, g.W, g.C), device="cuda")
+    dw = torch.empty((g.LH, g.LW, g.K, g.F), device="cuda")
+    lc.lc_forward(G, xd, wd, None, 1.0, y, lc.LC_BF16)
+    lc.lc_backward_data(G, dyd, wd, dx, lc.LC_BF16)
+    lc.lc_backward_weights(G, xd, dyd, 0.0, dw, lc.LC_BF16)
+    lhs = torch.dot(y.double().flatten(), dyd.double().flatten()).item()
+    rhs = torch.dot(xd.double().flatten(), dx.double().flatten()).item()
+    rhw = torch.dot(wd.double().flatten(), dw.double().flatten()).item()
+    scale = (y.double().norm() * dyd.double().norm()).item()
+    assert abs(lhs - rhs) <= 1e-5 * scale and abs(lhs - rhw) <= 1e-5 * scale
+    yh, dxh, dwh = host(y), host(dx), host(dw)
+    r = np.random.default_rng(12)
+    gy, ry, gx, rx, gw, rw = ([] for _ in range(6))
+    for s in range(120):
+        b, i, j = int(r.integers(g.B)), int(r.integers(g.LH)), int(r.integers(g.LW))
+        f, k = int(r.integers(g.F)), int(r.integers(g.K))
+        row, col, c = int(r.integers(g.H)), int(r.integers(g.W)), int(r.integers(g.C))
+        gy.append(yh[b, i, j, f]); ry.append(oracle.lc_forward_at(t, x, w, None, 1.0, b, i, j, f))
+        gx.append(dxh[b, row, col, c]); rx.append(oracle.lc_backward_data_at(t, dy, w, b, row, col, c))
+        gw.append(dwh[i, j, k, f]); rw.append(oracle.lc_backward_weights_at(t, x, dy, i, j, k, f))
+    assert rel_fro(gy, ry) <= 2e-2
+    assert rel_fro(gx, rx) <= 2e-2
+    assert rel_fro(gw, rw) <= 2e-2
+
+
+def test_bf16_unsupported_shape_is_reported():
+    g = wl.LCGeom(B=8, H=9, W=9, C=3, R=3, S=2, F=10)
+    G = lc.geom(*g.as_tuple())
+    z = lambda *s: torch.zeros(s, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_forward(G, z(g.B, g.H, g.W, g.C), z(g.LH, g.LW, g.K, g.F), None, 1.0,
+                      torch.zeros((g.B, g.LH, g.LW, g.F), device="cuda"), lc.LC_BF16)
+    assert e.value.code == lc.LC_EUNSUPPORTED
+
+
 def test_forward_determinism_and_empty_tail():
     g = wl.LCGeom(B=17, H=21, W=21, C=3, R=6, S=3, F=24)
     x, w, dy = wl.lc_inputs(g, "gaussian", seed=2)
