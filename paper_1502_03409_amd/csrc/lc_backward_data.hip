@@ -377,9 +377,29 @@ int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipSt
 }  // namespace
 
 int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
-    if (g.F % 16 == 0 && g.R % g.S == 0 && g.B > 64) {
-        const int ap = g.R / g.S, ntt = (g.S * g.S * g.C + 15) / 16;
-        if (ap == 5 && ntt == 3) return launch_fast<4, 3, 4, 5>(g, dy, w, dx, s);
+    // pipelined kernel: filters in blocks of 16, fields that tile the cells exactly, a batch tile of 64 images
+    if (g.F % 16 == 0 && g.R % g.S == 0 && g.B > 32) {
+        const int ap = g.R / g.S, ntt = (g.S * g.S * g.C + 15) / 16;   // steps per chunk, tiles of 16 cell values
+#define LC_BD(AP_, NT_, NCELL_) return launch_fast<4, NT_, NCELL_, AP_>(g, dy, w, dx, s)
+        if (ap == 2) {
+            if (ntt <= 3) LC_BD(2, 3, 4);
+            if (ntt == 4) LC_BD(2, 4, 4);
+            LC_BD(2, 3, 1);
+        } else if (ap == 3) {
+            if (ntt <= 2) LC_BD(3, 2, 4);
+            if (ntt <= 4) LC_BD(3, 4, 4);
+            LC_BD(3, 4, 2);
+        } else if (ap == 4) {
+            if (ntt <= 2) LC_BD(4, 2, 4);
+            if (ntt <= 4) LC_BD(4, 4, 4);
+            LC_BD(4, 4, 2);
+        } else if (ap == 5) {
+            if (ntt <= 3) LC_BD(5, 3, 4);
+            if (ntt == 4) LC_BD(5, 4, 4);
+        } else if (ap == 8) {
+            if (ntt == 1) LC_BD(8, 1, 4);
+        }
+#undef LC_BD
     }
     if (g.B > 64) return launch_mt<8>(g, dy, w, dx, s);
     if (g.B > 32) return launch_mt<4>(g, dy, w, dx, s);

@@ -346,7 +346,7 @@ template <int MT, int NT, int NLOC, int UNR>
 int launch_fast(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
                 const float *alpha_dev, float *y, int CQ, int NR, int work_first, int work_count, hipStream_t s) {
     constexpr int BT = 16 * MT, NFW = 4 / NLOC;
-    const int sqc = CQ + (NLOC - 1) * g.S * g.C;
+    const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;   // staged floats per image and patch row
     const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
     auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR>;
@@ -407,7 +407,7 @@ int pick_chunk(const Geom &g, int BT, int NLOC, int UNR, size_t lds_budget) {
         if (g.RC % nsub) continue;
         const int CQ = g.RC / nsub;
         if (CQ % (4 * UNR)) continue;
-        const int sqc = CQ + (NLOC - 1) * SC;
+        const int sqc = (CQ + (NLOC - 1) * SC + 3) & ~3;
         if ((size_t)BT * (sqc / 4) > (size_t)kFwdStageSlots * 256) continue;
         if ((size_t)BT * fast_row_stride(sqc) * 4 > lds_budget) continue;
         if (sqc / 4 > 0xffff / 4) continue;
@@ -433,19 +433,32 @@ int launch_fast_unr(const Geom &g, const float *x, const float *w, const float *
     return LC_OK;
 }
 
+// filters per wave / fields per workgroup by F, then the largest batch tile whose strip fits
+template <int MT>
+int launch_fast_mt(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                   const float *alpha_dev, float *y, hipStream_t s, bool *done) {
+    *done = false;
+    if (g.F % 128 == 0) return launch_fast_unr<MT, 4, 2>(g, x, w, bias, alpha, alpha_dev, y, s, done);
+    if (g.F % 64 == 0) return launch_fast_unr<MT, 4, 4>(g, x, w, bias, alpha, alpha_dev, y, s, done);
+    if (g.F % 32 == 0) return launch_fast_unr<MT, 2, 4>(g, x, w, bias, alpha, alpha_dev, y, s, done);
+    if (g.F % 16 == 0) return launch_fast_unr<MT, 1, 4>(g, x, w, bias, alpha, alpha_dev, y, s, done);
+    return LC_OK;
+}
+
 }  // namespace
 
 int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
                        const float *alpha_dev, float *y, hipStream_t s) {
-    // aligned shapes take the pipelined kernel
-    const bool aligned = g.RC % 4 == 0 && (g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.K / 4 >= 8;
-    if (aligned && g.B > 64) {
+    // aligned shapes take the pipelined kernel: patch rows that are whole dwordx4 runs, strips that start on a
+    // 16-byte boundary (4 fields x S x C floats, or 2 when 128 filters are split over the waves)
+    const int nloc = g.F % 128 == 0 ? 2 : 4;
+    const bool aligned = g.RC % 4 == 0 && (nloc * g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.K / 4 >= 16;
+    if (aligned && g.B > 16) {
         bool done = false;
         int rc = LC_OK;
-        if (g.F % 128 == 0) rc = launch_fast_unr<8, 4, 2>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
-        else if (g.F % 64 == 0) rc = launch_fast_unr<8, 4, 4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
-        else if (g.F % 32 == 0) rc = launch_fast_unr<8, 2, 4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
-        else if (g.F % 16 == 0) rc = launch_fast_unr<8, 1, 4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        if (g.B > 64) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        if (!done && g.B > 32) rc = launch_fast_mt<4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        if (!done) rc = launch_fast_mt<2>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
         if (done) return rc;
     }
     // Pick the tile: as many images per wave as the batch offers (weights are re-read once per batch
