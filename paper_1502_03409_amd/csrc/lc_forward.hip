@@ -377,7 +377,7 @@ int launch_fast_tiered(const Geom &g, const float *x, const float *w, const floa
     const int zb = (g.B + 16 * MT - 1) / (16 * MT) * (g.F / ((4 / NLOC) * NT * 16));
     const int rounds = (ntask * zb) / slots, rem = ntask * zb - rounds * slots;
     if constexpr (MT == 8) {
-        if (zb == 1 && rounds >= 1 && rounds <= 6 && rem > 0 && rem <= slots * 3 / 4) {
+        if (zb == 1 && rounds >= 1 && rounds <= 6 && rem > 0 && rem <= slots / 4) {
             const int first = rounds * slots;
             int rc = launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s);
             if (rc != LC_OK) return rc;

@@ -15,7 +15,8 @@ namespace lc {
 
 namespace {
 
-constexpr int kPartials = 1024;  // per-block partial sums of each reduction
+constexpr int kPartials = 1024;     // per-block partial sums of the sparsity reductions
+constexpr int kPartialsMax = 65536;  // upper bound of the residual pass's partial sums
 
 __device__ __forceinline__ float block_sum(float v, float *sh) {
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -29,11 +30,48 @@ __device__ __forceinline__ float block_sum(float v, float *sh) {
     return t;  // valid in thread 0
 }
 
-// r = xh + b - x;  u = (2/B) r (written over xh);  b -= lr * sum_b u;  part[block] = sum r^2.
-// One thread per image element, looping over the batch (coalesced across threads).
+// r = xh + b - x;  u = (2/B) r (written over xh);  part[block] = sum r^2;  dbp[chunk][e] = sum over the
+// chunk's images of u.  Grid: x over image elements (float4 per thread), y over chunks of the batch.
 __global__ __launch_bounds__(256) void sae_residual_kernel(float *__restrict__ xh_u, const float *__restrict__ x,
-                                                           float *__restrict__ b, int B, int img, float lr,
-                                                           float *__restrict__ part) {
+                                                           const float *__restrict__ b, int B, int img4, int bchunk,
+                                                           float *__restrict__ dbp, float *__restrict__ part) {
+    __shared__ float sh[4];
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    float sq = 0.f;
+    if (e < img4) {
+        const f32x4 be = ((const f32x4 *)b)[e];
+        const float scale = 2.0f / (float)B;
+        f32x4 db = (f32x4){0.f, 0.f, 0.f, 0.f};
+        const int n0 = blockIdx.y * bchunk, n1 = min(B, n0 + bchunk);
+        for (int n = n0; n < n1; ++n) {
+            const size_t o = (size_t)n * img4 + e;
+            const f32x4 r = ((const f32x4 *)xh_u)[o] + be - ((const f32x4 *)x)[o];
+            sq += (r[0] * r[0] + r[1] * r[1]) + (r[2] * r[2] + r[3] * r[3]);
+            const f32x4 u = scale * r;
+            ((f32x4 *)xh_u)[o] = u;
+            db += u;
+        }
+        ((f32x4 *)dbp)[(size_t)blockIdx.y * img4 + e] = db;
+    }
+    const float t = block_sum(sq, sh);
+    if (threadIdx.x == 0) part[blockIdx.y * gridDim.x + blockIdx.x] = t;
+}
+
+// b -= lr * sum over chunks of dbp (fixed order: deterministic)
+__global__ __launch_bounds__(256) void sae_bias_kernel(float *__restrict__ b, const float *__restrict__ dbp, int img,
+                                                       int nchunk, float lr) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= img) return;
+    float s = 0.f;
+    for (int c = 0; c < nchunk; ++c) s += dbp[(size_t)c * img + e];
+    b[e] -= lr * s;
+}
+
+// Same pass for images whose element count is not a multiple of 4: one thread per image element, looping
+// over the whole batch; b is updated in place.
+__global__ __launch_bounds__(256) void sae_residual_scalar_kernel(float *__restrict__ xh_u,
+                                                                  const float *__restrict__ x, float *__restrict__ b,
+                                                                  int B, int img, float lr, float *__restrict__ part) {
     __shared__ float sh[4];
     float sq = 0.f;
     for (int e = blockIdx.x * 256 + threadIdx.x; e < img; e += gridDim.x * 256) {
@@ -123,9 +161,14 @@ __global__ __launch_bounds__(256) void sae_project_kernel(float *__restrict__ w,
 
 static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
+// the batch is cut into at most kBatchChunks chunks for the residual pass (more workgroups in flight)
+constexpr int kBatchChunks = 16;
+
 size_t sae_workspace_bytes(const Geom &g) {
     const size_t nh = (size_t)g.B * g.L * g.F, nx = (size_t)g.B * g.H * g.W * g.C;
-    return 2 * align256(nh * 4) + align256(nx * 4) + 3 * align256(kPartials * 4);
+    const size_t img = (size_t)g.H * g.W * g.C;
+    return 2 * align256(nh * 4) + align256(nx * 4) + align256(kBatchChunks * img * 4) +
+           3 * align256(kPartialsMax * 4);
 }
 
 int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
@@ -136,17 +179,30 @@ int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *al
     float *h_ws = (float *)p; p += align256(nh * 4);
     float *gh = (float *)p;   p += align256(nh * 4);
     float *u = (float *)p;    p += align256(nx * 4);
-    float *part_r = (float *)p; p += align256(kPartials * 4);
-    float *part_s = (float *)p; p += align256(kPartials * 4);
+    float *dbp = (float *)p;  p += align256((size_t)kBatchChunks * img * 4);
+    float *part_r = (float *)p; p += align256(kPartialsMax * 4);
+    float *part_s = (float *)p; p += align256(kPartialsMax * 4);
     float *part_hg = (float *)p;
     float *h = h_out ? h_out : h_ws;
 
     int rc;
     if ((rc = launch_forward_f32(g, x, w, nullptr, 1.f, alpha, h, s)) != LC_OK) return rc;
     if ((rc = launch_backward_data_f32(g, h, w, u, s)) != LC_OK) return rc;
-    const int n_r = (int)((img + 255) / 256 < kPartials ? (img + 255) / 256 : kPartials);
-    hipLaunchKernelGGL(sae_residual_kernel, dim3(n_r), dim3(256), 0, s, u, x, b, g.B, img, lr, part_r);
-    LC_HIP_LAUNCH_CHECK("sae_step residual launch");
+    int n_r;
+    if ((img & 3) == 0 && (img / 4 + 255) / 256 * kBatchChunks <= kPartialsMax) {
+        const int img4 = img / 4, gx = (img4 + 255) / 256;
+        const int nchunk = g.B < kBatchChunks ? g.B : kBatchChunks, bchunk = (g.B + nchunk - 1) / nchunk;
+        const int gy = (g.B + bchunk - 1) / bchunk;
+        hipLaunchKernelGGL(sae_residual_kernel, dim3(gx, gy), dim3(256), 0, s, u, x, b, g.B, img4, bchunk, dbp, part_r);
+        LC_HIP_LAUNCH_CHECK("sae_step residual launch");
+        hipLaunchKernelGGL(sae_bias_kernel, dim3((img + 255) / 256), dim3(256), 0, s, b, dbp, img, gy, lr);
+        LC_HIP_LAUNCH_CHECK("sae_step bias launch");
+        n_r = gx * gy;
+    } else {
+        n_r = (int)((img + 255) / 256 < kPartials ? (img + 255) / 256 : kPartials);
+        hipLaunchKernelGGL(sae_residual_scalar_kernel, dim3(n_r), dim3(256), 0, s, u, x, b, g.B, img, lr, part_r);
+        LC_HIP_LAUNCH_CHECK("sae_step residual launch");
+    }
     if ((rc = launch_forward_f32(g, u, w, nullptr, 1.f, nullptr, gh, s)) != LC_OK) return rc;
     const int n_s = (int)((nh + 255) / 256 < (size_t)kPartials ? (nh + 255) / 256 : kPartials);
     hipLaunchKernelGGL(sae_sparsity_kernel, dim3(n_s), dim3(256), 0, s, h, gh, alpha, lambda / (float)g.B, eps_sparse,
