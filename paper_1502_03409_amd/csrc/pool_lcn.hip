@@ -82,6 +82,94 @@ __global__ __launch_bounds__(256) void l2pool_bwd_kernel(const float *__restrict
     }
 }
 
+// Stride-1 windows, C % 4 == 0: a thread owns OW consecutive output columns of one (image, row, channel
+// quad) and keeps the per-column partial sums in registers, so every input is loaded ks times (once
+// per output row it belongs to) instead of ks*ks times.
+constexpr int kPoolOW = 4;
+constexpr int kPoolMaxK = 5;
+
+__global__ __launch_bounds__(256) void l2pool_fwd_rows_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                              int H, int W, int C, int Ho, int Wo, int ks, float eps,
+                                                              int groups) {
+    // grid: x over (output row, column group, channel quad) of one image, y = image
+    const int CV = C >> 2;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= Ho * groups * CV) return;
+    const int t = e / CV, cv = e - t * CV;
+    const int i = t / groups, jg = t - i * groups;
+    const int b = blockIdx.y;
+    const int j0 = jg * kPoolOW;
+    const int ncol = min(kPoolOW, Wo - j0) + ks - 1;          // input columns this thread needs
+    f32x4 col[kPoolOW + kPoolMaxK - 1];
+#pragma unroll
+    for (int c = 0; c < kPoolOW + kPoolMaxK - 1; ++c) col[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const float *xp = x + (((size_t)b * H + i) * W + j0) * C + cv * 4;
+    for (int p = 0; p < ks; ++p) {
+#pragma unroll
+        for (int c = 0; c < kPoolOW + kPoolMaxK - 1; ++c) {
+            if (c < ncol) {
+                const f32x4 v = *(const f32x4 *)(xp + ((size_t)p * W + c) * C);
+                col[c] += v * v;
+            }
+        }
+    }
+    float *yp = y + (((size_t)b * Ho + i) * Wo + j0) * C + cv * 4;
+#pragma unroll
+    for (int o = 0; o < kPoolOW; ++o) {
+        if (j0 + o < Wo) {
+            f32x4 sacc = (f32x4){eps, eps, eps, eps};
+#pragma unroll
+            for (int q = 0; q < kPoolMaxK; ++q)
+                if (q < ks) sacc += col[o + q];
+            *(f32x4 *)(yp + (size_t)o * C) =
+                (f32x4){sqrtf(sacc[0]), sqrtf(sacc[1]), sqrtf(sacc[2]), sqrtf(sacc[3])};
+        }
+    }
+}
+
+// Backward, same shapes: a thread owns OW consecutive input columns of one (image, row, channel quad); the
+// per-column sums of dy/y over the output rows that cover this input row are kept in registers.
+__global__ __launch_bounds__(256) void l2pool_bwd_rows_kernel(const float *__restrict__ x, const float *__restrict__ y,
+                                                              const float *__restrict__ dy, float *__restrict__ dx,
+                                                              int H, int W, int C, int Ho, int Wo, int ks, int groups) {
+    // grid: x over (input row, column group, channel quad) of one image, y = image
+    const int CV = C >> 2;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= H * groups * CV) return;
+    const int t = e / CV, cv = e - t * CV;
+    const int row = t / groups, jg = t - row * groups;
+    const int b = blockIdx.y;
+    const int c0 = jg * kPoolOW;                               // first input column
+    const int i_lo = max(0, row - ks + 1), i_hi = min(row, Ho - 1);
+    // output columns jo in [c0-ks+1, c0+OW-1] may cover this thread's inputs
+    f32x4 col[kPoolOW + kPoolMaxK - 1];
+#pragma unroll
+    for (int c = 0; c < kPoolOW + kPoolMaxK - 1; ++c) col[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int i = i_lo; i <= i_hi; ++i) {
+        const size_t rb = (((size_t)b * Ho + i) * Wo) * C + cv * 4;
+#pragma unroll
+        for (int c = 0; c < kPoolOW + kPoolMaxK - 1; ++c) {
+            const int jo = c0 - (ks - 1) + c;
+            if (c < kPoolOW + ks - 1 && jo >= 0 && jo < Wo) {
+                const f32x4 g = *(const f32x4 *)(dy + rb + (size_t)jo * C), yy = *(const f32x4 *)(y + rb + (size_t)jo * C);
+                col[c] += g / yy;
+            }
+        }
+    }
+    const size_t xo = (((size_t)b * H + row) * W + c0) * C + cv * 4;
+#pragma unroll
+    for (int o = 0; o < kPoolOW; ++o) {
+        if (c0 + o < W) {
+            // input column c0+o is covered by output columns jo = c0+o-ks+1 .. c0+o, i.e. col[o .. o+ks-1]
+            f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 0; q < kPoolMaxK; ++q)
+                if (q < ks) sacc += col[o + q];
+            *(f32x4 *)(dx + xo + (size_t)o * C) = *(const f32x4 *)(x + xo + (size_t)o * C) * sacc;
+        }
+    }
+}
+
 // ------------------------------------------------------------------------ LCN
 constexpr int kLcnTile = 16;   // output tile edge
 constexpr int kLcnMaxK = 15;   // largest window
@@ -269,7 +357,11 @@ int lanes_per_pixel(int cv) {
 int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int ks, int st, float eps,
                       hipStream_t s) {
     const int Ho = (H - ks) / st + 1, Wo = (W - ks) / st + 1;
-    if (C % 4 == 0) {
+    if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && B <= 65535 && (long long)H * W * C < (1LL << 30)) {
+        const int groups = (Wo + kPoolOW - 1) / kPoolOW;
+        hipLaunchKernelGGL(l2pool_fwd_rows_kernel, dim3((Ho * groups * (C / 4) + 255) / 256, B), dim3(256), 0, s, x, y, H,
+                           W, C, Ho, Wo, ks, eps, groups);
+    } else if (C % 4 == 0) {
         const long long total = (long long)B * Ho * Wo * (C / 4);
         hipLaunchKernelGGL(l2pool_fwd_kernel<4>, dim3(grid_for(total)), dim3(256), 0, s, x, y, B, H, W, C, Ho, Wo, ks,
                            st, eps, total);
@@ -285,7 +377,11 @@ int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int 
 int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int B, int H, int W, int C, int ks,
                       int st, hipStream_t s) {
     const int Ho = (H - ks) / st + 1, Wo = (W - ks) / st + 1;
-    if (C % 4 == 0) {
+    if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && B <= 65535 && (long long)H * W * C < (1LL << 30)) {
+        const int groups = (W + kPoolOW - 1) / kPoolOW;
+        hipLaunchKernelGGL(l2pool_bwd_rows_kernel, dim3((H * groups * (C / 4) + 255) / 256, B), dim3(256), 0, s, x, y, dy,
+                           dx, H, W, C, Ho, Wo, ks, groups);
+    } else if (C % 4 == 0) {
         const long long total = (long long)B * H * W * (C / 4);
         hipLaunchKernelGGL(l2pool_bwd_kernel<4>, dim3(grid_for(total)), dim3(256), 0, s, x, y, dy, dx, B, H, W, C, Ho,
                            Wo, ks, st, total);
