@@ -170,6 +170,79 @@ __global__ __launch_bounds__(256) void l2pool_bwd_rows_kernel(const float *__res
     }
 }
 
+// Tiled variant for stride-1 windows and C % 4 == 0: a workgroup stages the (TH+ks-1) x (TW+ks-1) patch its
+// TH x TW tile needs in LDS once (forward: x^2; backward: dy/y), so every input leaves L2 about once instead
+// of once per window row, and the window sums come out of LDS.
+constexpr int kPoolTH = 8, kPoolTW = 16;
+
+// MODE 0: y = sqrt(eps + window sum of x^2) on a tile of outputs.
+// MODE 1: dx = x * (window sum of dy/y) on a tile of inputs; the patch holds dy/y at outputs
+//         (row-ks+1 .. row, col-ks+1 .. col), zero where no such output exists.
+template <int MODE>
+__global__ __launch_bounds__(256) void l2pool_tile_kernel(const float *__restrict__ x, const float *__restrict__ y,
+                                                          const float *__restrict__ dy, float *__restrict__ out,
+                                                          int H, int W, int C, int Ho, int Wo, int ks, float eps,
+                                                          int tiles_w, int tiles_per_img) {
+    extern __shared__ __attribute__((aligned(16))) float patch[];   // [(TH+ks-1)*(TW+ks-1)][C]
+    const int tid = threadIdx.x, CV = C >> 2;
+    const int b = blockIdx.x / tiles_per_img, tile = blockIdx.x - b * tiles_per_img;
+    const int ti = (tile / tiles_w) * kPoolTH, tj = (tile % tiles_w) * kPoolTW;
+    const int PH = kPoolTH + ks - 1, PW = kPoolTW + ks - 1;
+    // patch origin in the source grid: forward reads inputs (ti.., tj..); backward reads outputs (ti-ks+1.., tj-ks+1..)
+    const int oi0 = MODE == 0 ? ti : ti - (ks - 1), oj0 = MODE == 0 ? tj : tj - (ks - 1);
+    const int SH = MODE == 0 ? H : Ho, SW = MODE == 0 ? W : Wo;
+    const size_t sbase = (size_t)b * SH * SW;
+    for (int e = tid; e < PH * PW * CV; e += 256) {
+        const int cv = e % CV, pp = e / CV;
+        const int pi = pp / PW, pj = pp - pi * PW;
+        const int r = oi0 + pi, c = oj0 + pj;
+        f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (r >= 0 && r < SH && c >= 0 && c < SW) {
+            const size_t o = (sbase + (size_t)r * SW + c) * C + cv * 4;
+            if (MODE == 0) {
+                const f32x4 t = *(const f32x4 *)(x + o);
+                v = t * t;
+            } else {
+                v = *(const f32x4 *)(dy + o) / *(const f32x4 *)(y + o);
+            }
+        }
+        *(f32x4 *)(patch + (size_t)pp * C + cv * 4) = v;
+    }
+    __syncthreads();
+    // a thread owns 4 consecutive columns of one tile row and channel quad
+    const int OH = MODE == 0 ? Ho : H, OWid = MODE == 0 ? Wo : W;
+    for (int e = tid; e < kPoolTH * (kPoolTW / 4) * CV; e += 256) {
+        const int cv = e % CV, t = e / CV;
+        const int cg = t % (kPoolTW / 4), tr = t / (kPoolTW / 4);
+        const int row = ti + tr, col0 = tj + cg * 4;
+        if (row >= OH || col0 >= OWid) continue;
+        f32x4 col[4 + kPoolMaxK - 1];
+#pragma unroll
+        for (int c = 0; c < 4 + kPoolMaxK - 1; ++c) col[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < ks; ++p) {
+            const float *prow = patch + ((size_t)(tr + p) * PW + cg * 4) * C + cv * 4;
+#pragma unroll
+            for (int c = 0; c < 4 + kPoolMaxK - 1; ++c)
+                if (c < 4 + ks - 1) col[c] += *(const f32x4 *)(prow + (size_t)c * C);
+        }
+        const size_t o = (((size_t)b * OH + row) * OWid + col0) * C + cv * 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (col0 + q >= OWid) continue;
+            f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < kPoolMaxK; ++k)
+                if (k < ks) sacc += col[q + k];
+            if (MODE == 0) {
+                *(f32x4 *)(out + o + (size_t)q * C) =
+                    (f32x4){sqrtf(eps + sacc[0]), sqrtf(eps + sacc[1]), sqrtf(eps + sacc[2]), sqrtf(eps + sacc[3])};
+            } else {
+                *(f32x4 *)(out + o + (size_t)q * C) = *(const f32x4 *)(x + o + (size_t)q * C) * sacc;
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------ LCN
 constexpr int kLcnTile = 16;   // output tile edge
 constexpr int kLcnMaxK = 15;   // largest window
@@ -357,7 +430,20 @@ int lanes_per_pixel(int cv) {
 int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int ks, int st, float eps,
                       hipStream_t s) {
     const int Ho = (H - ks) / st + 1, Wo = (W - ks) / st + 1;
-    if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && B <= 65535 && (long long)H * W * C < (1LL << 30)) {
+    const size_t patch_bytes = (size_t)(kPoolTH + ks - 1) * (kPoolTW + ks - 1) * C * sizeof(float);
+    if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && patch_bytes <= 64 * 1024) {
+        const int th = (Ho + kPoolTH - 1) / kPoolTH, tw = (Wo + kPoolTW - 1) / kPoolTW;
+        const long long nblk = (long long)B * th * tw;
+        if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
+        auto kern = l2pool_tile_kernel<0>;
+        if (patch_bytes > 32 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)patch_bytes);
+            if (e != hipSuccess) { set_hip_error(e, "l2pool_fwd: hipFuncSetAttribute"); return LC_EHIP; }
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), patch_bytes, s, x, (const float *)nullptr,
+                           (const float *)nullptr, y, H, W, C, Ho, Wo, ks, eps, tw, th * tw);
+    } else if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && B <= 65535 && (long long)H * W * C < (1LL << 30)) {
         const int groups = (Wo + kPoolOW - 1) / kPoolOW;
         hipLaunchKernelGGL(l2pool_fwd_rows_kernel, dim3((Ho * groups * (C / 4) + 255) / 256, B), dim3(256), 0, s, x, y, H,
                            W, C, Ho, Wo, ks, eps, groups);
@@ -377,7 +463,20 @@ int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int 
 int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int B, int H, int W, int C, int ks,
                       int st, hipStream_t s) {
     const int Ho = (H - ks) / st + 1, Wo = (W - ks) / st + 1;
-    if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && B <= 65535 && (long long)H * W * C < (1LL << 30)) {
+    const size_t patch_bytes = (size_t)(kPoolTH + ks - 1) * (kPoolTW + ks - 1) * C * sizeof(float);
+    if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && patch_bytes <= 64 * 1024) {
+        const int th = (H + kPoolTH - 1) / kPoolTH, tw = (W + kPoolTW - 1) / kPoolTW;
+        const long long nblk = (long long)B * th * tw;
+        if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
+        auto kern = l2pool_tile_kernel<1>;
+        if (patch_bytes > 32 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)patch_bytes);
+            if (e != hipSuccess) { set_hip_error(e, "l2pool_bwd: hipFuncSetAttribute"); return LC_EHIP; }
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), patch_bytes, s, x, y, dy, dx, H, W, C, Ho, Wo, ks,
+                           0.f, tw, th * tw);
+    } else if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && B <= 65535 && (long long)H * W * C < (1LL << 30)) {
         const int groups = (W + kPoolOW - 1) / kPoolOW;
         hipLaunchKernelGGL(l2pool_bwd_rows_kernel, dim3((H * groups * (C / 4) + 255) / 256, B), dim3(256), 0, s, x, y, dy,
                            dx, H, W, C, Ho, Wo, ks, groups);
