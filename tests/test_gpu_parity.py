@@ -55,6 +55,13 @@ SMALL = {
     "wide_c": (wl.LCGeom(B=33, H=12, W=12, C=32, R=4, S=2, F=48), "halfnormal"),
     "many_f": (wl.LCGeom(B=16, H=10, W=10, C=3, R=4, S=2, F=200), "gaussian"),
     "s5_stage2": (wl.LCGeom(B=24, H=15, W=15, C=16, R=6, S=2, F=32), "halfnormal"),
+    # shapes that take the pipelined kernels, with every kind of raggedness they allow
+    "fast_b65": (wl.LCGeom(B=65, H=28, W=44, C=4, R=8, S=4, F=32), "gaussian"),     # batch tile + 1 image
+    "fast_b130": (wl.LCGeom(B=130, H=24, W=30, C=3, R=8, S=4, F=16), "pink"),       # two batch tiles, F=16
+    "fast_floor": (wl.LCGeom(B=72, H=27, W=31, C=4, R=6, S=2, F=64), "halfnormal"), # floor geometry, F=64
+    "fast_f128": (wl.LCGeom(B=80, H=14, W=18, C=8, R=4, S=2, F=128), "halfnormal"), # filters split over waves
+    "fast_lw1": (wl.LCGeom(B=96, H=20, W=8, C=4, R=8, S=4, F=32), "gaussian"),      # one field per row
+    "single_img": (wl.LCGeom(B=1, H=9, W=9, C=2, R=3, S=3, F=5), "gaussian"),
 }
 
 
@@ -218,7 +225,8 @@ def test_forward_determinism_and_empty_tail():
 
 
 POOL_SHAPES = [((3, 9, 11, 5), 3, 1), ((2, 12, 12, 32), 3, 1), ((2, 10, 9, 8), 2, 2), ((1, 7, 7, 3), 3, 2),
-               ((4, 46, 46, 32), 3, 1)]
+               ((4, 46, 46, 32), 3, 1), ((2, 19, 35, 16), 5, 1), ((1, 3, 3, 4), 3, 1), ((2, 9, 9, 8), 1, 1),
+               ((1, 8, 8, 600), 3, 1), ((2, 57, 57, 16), 3, 1)]
 
 
 @pytest.mark.parametrize("shape,ks,st", POOL_SHAPES)
