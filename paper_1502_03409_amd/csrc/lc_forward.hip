@@ -456,7 +456,10 @@ int launch_forward_f32(const Geom &g, const float *x, const float *w, const floa
     if (aligned && g.B > 16) {
         bool done = false;
         int rc = LC_OK;
-        if (g.B > 64) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        // 128 images x 64 filters per wave would need 128 accumulator registers and leave room for one wave
+        // per SIMD only: wide layers take the 64-image tile (two waves per SIMD; the second batch tile of a
+        // strip finds the weights in L2)
+        if (g.B > 64 && g.F % 64 != 0) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
         if (!done && g.B > 32) rc = launch_fast_mt<4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
         if (!done) rc = launch_fast_mt<2>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
         if (done) return rc;
