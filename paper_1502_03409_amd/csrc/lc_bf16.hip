@@ -255,8 +255,7 @@ int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float
         hipLaunchKernelGGL(kern, dim3((unsigned)((ntasks + 3) / 4)), dim3(256), 0, s, g, (const unsigned short *)x,
                            (const unsigned short *)w, bias, alpha, y, fblocks, btiles, (int)ntasks);
     };
-    if (g.B >= 128) go(lc_forward_bf16_kernel<8>, 8);
-    else if (g.B >= 64) go(lc_forward_bf16_kernel<4>, 4);
+    if (g.B >= 64) go(lc_forward_bf16_kernel<4>, 4);
     else go(lc_forward_bf16_kernel<1>, 1);
     LC_HIP_LAUNCH_CHECK("lc_forward (bf16) launch");
     return LC_OK;

@@ -87,13 +87,19 @@ def test_lc_primitives_match_oracle(name):
     assert rel_fro(dw1, ref_dw + prev) <= TOL
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg4"])
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "paper_layer1"])
 def test_lc_primitives_full_size_sampled(name):
     """Full-size workloads in the launch configuration the benchmark times: a sample of outputs
-    against the oracle's single-output evaluators, plus the adjoint identities on the GPU results."""
-    g, kind = wl.CONFIG_GEOM[name], wl.CONFIG_IMAGE_KIND[name]
-    print(f"case {name} geom {g}", flush=True)
-    x, w, dy = wl.lc_inputs(g, kind, seed=0)
+    against the oracle's single-output evaluators, plus the adjoint identities on the GPU results.
+    paper_layer1 is the first layer at the size the architecture section states (Sec. 3.1)."""
+    if name == "paper_layer1":
+        g, kind = wl.PAPER_LAYER1, "pink"
+        print(f"case {name} geom {g}", flush=True)
+        x, w, dy = wl.lc_inputs_blocked(g, kind, seed=0)
+    else:
+        g, kind = wl.CONFIG_GEOM[name], wl.CONFIG_IMAGE_KIND[name]
+        print(f"case {name} geom {g}", flush=True)
+        x, w, dy = wl.lc_inputs(g, kind, seed=0)
     t = g.as_tuple()
     G = lc.geom(*t)
     xd, wd, dyd = dev(x), dev(w), dev(dy)

@@ -75,6 +75,11 @@ CONFIG_GEOM: Dict[str, LCGeom] = {
     "cfg5_s2": LCGeom(B=128, H=55, W=55, C=16, R=6, S=2, F=32),
     "cfg5_s3": LCGeom(B=128, H=23, W=23, C=32, R=6, S=2, F=32),
 }
+# The first layer exactly as the architecture section states it (Sec. 3.1: 300x300x3 input, 16x16
+# receptive field, stride 4 -> 72x72 fields, a 4x4x24 output block = 384 filters per field; the
+# mini-batch of 192 is the one the training section gives).  1.53e9 parameters: fits one GPU whole.
+PAPER_LAYER1 = LCGeom(B=192, H=300, W=300, C=3, R=16, S=4, F=384)
+
 CONFIG_IMAGE_KIND = {
     "cfg1": "gaussian", "cfg2": "pink", "cfg3": "pink", "cfg4": "halfnormal",
     "cfg5_s1": "pink", "cfg5_s2": "halfnormal", "cfg5_s3": "halfnormal",
@@ -141,6 +146,31 @@ def lc_inputs(g: LCGeom, kind: str = "pink", seed: int = 0, with_bias: bool = Fa
     if with_bias:
         bias = (0.1 * rb.standard_normal((g.LH, g.LW, g.F))).astype(np.float32)
         return x, w, dy, bias
+    return x, w, dy
+
+
+def lc_inputs_blocked(g: LCGeom, kind: str = "pink", seed: int = 0, threads: int = 8):
+    """x, w, dy for a layer too large for `lc_inputs` to draw in fp64 in one piece.
+
+    w and dy are drawn directly in fp32, one row of fields (fixed i) per sub-stream, so the values
+    do not depend on the number of worker threads; x comes from the same image generators.
+    """
+    from concurrent.futures import ThreadPoolExecutor
+
+    rx, rw, rdy = np.random.default_rng(seed).spawn(3)
+    x = images(kind, rx, g.B, g.H, g.W, g.C)
+    w = np.empty((g.LH, g.LW, g.K, g.F), dtype=np.float32)
+    dy = np.empty((g.B, g.LH, g.LW, g.F), dtype=np.float32)
+    scale = np.float32(1.0 / np.sqrt(g.K))
+
+    def fill_row(args):
+        i, r_w, r_dy = args
+        r_w.standard_normal(out=w[i], dtype=np.float32)
+        w[i] *= scale
+        dy[:, i] = r_dy.standard_normal((g.B, g.LW, g.F), dtype=np.float32)
+
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        list(pool.map(fill_row, zip(range(g.LH), rw.spawn(g.LH), rdy.spawn(g.LH))))
     return x, w, dy
 
 
