@@ -248,6 +248,7 @@ bool bf16_shape_supported(const Geom &g) {
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s) {
     if (!bf16_shape_supported(g)) return LC_EUNSUPPORTED;
+    if (bf16_tiled_forward_supported(g)) return launch_forward_bf16_tiled(g, x, w, bias, alpha, y, s);
     const int fblocks = g.F / 64;
     auto go = [&](auto kern, int MT) {
         const int btiles = (g.B + 16 * MT - 1) / (16 * MT);

@@ -80,6 +80,10 @@ int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu,
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s);
 int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s);
+// workgroup-tiled bf16 forward for wide layers; LC_EUNSUPPORTED outside bf16_tiled_forward_supported()
+bool bf16_tiled_forward_supported(const Geom &g);
+int launch_forward_bf16_tiled(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
+                              hipStream_t s);
 int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, float beta, float *dw, hipStream_t s);
 size_t sae_workspace_bytes(const Geom &g);
 int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
