@@ -264,6 +264,7 @@ int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float
 
 int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
     if (!bf16_shape_supported(g)) return LC_EUNSUPPORTED;
+    if (bf16_tiled_backward_data_supported(g)) return launch_backward_data_bf16_tiled(g, dy, w, dx, s);
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int nblocks = (g.S * g.S * g.C + 63) / 64;
     auto go = [&](auto kern, int MT) {

@@ -1,7 +1,7 @@
 // bf16-operand forward contraction, workgroup-tiled (Eq. 1 encoder term, Sec. 3.1 geometry).
 //
-// A workgroup owns one field, 128 of its filters and a batch tile of 32*MT images; its four waves form a
-// 2 x 2 grid (16*MT images x 64 filters each).  The field's patch rows reach the waves through LDS in
+// A workgroup owns one field, 128 of its filters and a batch tile of 16*MT*WM images; its waves form a
+// WM x 2 grid (16*MT images x 64 filters each).  The field's patch rows reach the waves through LDS in
 // chunks of 64 contraction indices (128 contiguous bytes per image, two buffers, one barrier per chunk);
 // the filters go straight from global memory to registers, one step of 32 indices ahead: lane (n, kk)
 // loads rows 8kk..8kk+7 of the step at filters 4n..4n+3 (16 lanes cover whole 128-byte lines) and two
@@ -40,13 +40,18 @@ __device__ __forceinline__ void transpose8x4_bf16(const u32x2 (&r)[8], u32x4 (&o
 constexpr int kChunk = 64;          // contraction indices per LDS chunk
 constexpr int kRowBytes = 144;      // 128 bytes of a chunk + 16: eight rows' 16-byte reads cover all banks
 
-template <int MT>
-__global__ __launch_bounds__(256) void lc_forward_bf16_tiled_kernel(Geom g, const unsigned short *__restrict__ x,
+// PD = chunks of lookahead: PD register sets hold the patch chunks c+1 .. c+PD on their way to LDS and the
+// filter ring holds the 2*PD steps after the current one, so a load has PD chunks of MFMA work to land.
+template <int MT, int PD, int WM>
+__global__ __launch_bounds__(128 * WM) void lc_forward_bf16_tiled_kernel(Geom g, const unsigned short *__restrict__ x,
                                                                     const unsigned short *__restrict__ w,
                                                                     const float *__restrict__ bias, float alpha,
                                                                     float *__restrict__ y, int fblocks, int btiles) {
-    constexpr int BT = 32 * MT, NS = MT;          // NS: 16-byte staging slots per thread and chunk
+    static_assert(PD == 1 || PD % 2 == 0, "the chunk loop is unrolled PD times and alternates two LDS buffers");
+    constexpr int BT = 16 * MT * WM, NS = MT;     // NS: 16-byte staging slots per thread and chunk
+    constexpr int SR = 16 * WM;                   // image rows one staging slot of the workgroup covers
     constexpr int BUF = BT * kRowBytes;
+    constexpr int UN = PD == 1 ? 2 : PD;          // chunks per trip of the unrolled loop
     extern __shared__ __attribute__((aligned(16))) unsigned char xs[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kk = lane >> 4;
@@ -67,67 +72,68 @@ __global__ __launch_bounds__(256) void lc_forward_bf16_tiled_kernel(Geom g, cons
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc[mt][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // staging: slot s moves 16 bytes (segment tid&7) of image (tid>>3) + 32 s; images beyond the batch
+    // staging: slot s moves 16 bytes (segment tid&7) of image (tid>>3) + SR s; images beyond the batch
     // repeat image B-1 and their results are never stored
     const int seg = tid & 7, brow = tid >> 3;
     int xoff[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-        const int b = min(b0 + brow + 32 * s, g.B - 1);
+        const int b = min(b0 + brow + SR * s, g.B - 1);
         xoff[s] = (b * g.H + i * g.S) * WC + j * g.S * g.C + seg * 8;
     }
-    u32x4 st[NS];
-    auto stage_load = [&](int c) {
+    auto stage_load = [&](int c, u32x4 (&st)[NS]) {
         const int kh = c / cpr;
         const int o = kh * WC + (c - kh * cpr) * kChunk;
 #pragma unroll
         for (int s = 0; s < NS; ++s) st[s] = *(g4_ptr)((gh_ptr)x + xoff[s] + o);
     };
-    auto stage_store = [&](int buf) {
+    auto stage_store = [&](int buf, const u32x4 (&st)[NS]) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s) *(u32x4 *)(xs + buf * BUF + (brow + 32 * s) * kRowBytes + seg * 16) = st[s];
+        for (int s = 0; s < NS; ++s) *(u32x4 *)(xs + buf * BUF + (brow + SR * s) * kRowBytes + seg * 16) = st[s];
     };
     // filters: the chunks tile k contiguously, so step q covers rows 32q .. 32q+31 of the field's K x F matrix
     gh_ptr wl = (gh_ptr)w + (size_t)loc * g.K * g.F + f0 + 4 * n + (size_t)(8 * kk) * g.F;
     auto wload = [&](int q, u32x2 (&r)[8]) {
-        gh_ptr p = wl + (size_t)(32 * q) * g.F;
+        gh_ptr p = wl + (size_t)(32 * min(q, nsteps - 1)) * g.F;
 #pragma unroll
         for (int t = 0; t < 8; ++t) r[t] = *(g2_ptr)(p + t * g.F);
     };
 
-    u32x2 wr0[8], wr1[8];
-    stage_load(0);
-    wload(0, wr0);
-    wload(1, wr1);
-    stage_store(0);
-    if (nchunks > 1) stage_load(1);
+    u32x4 st[PD][NS];
+    u32x2 wr[2 * PD][8];
+#pragma unroll
+    for (int q = 0; q < 2 * PD; ++q) wload(q, wr[q]);
+    stage_load(0, st[0]);
+    stage_store(0, st[0]);
+#pragma unroll
+    for (int p = 0; p < PD; ++p) stage_load(min(p + 1, nchunks - 1), st[p]);      // set p: chunk p+1
     __syncthreads();
     const int arow = (wm * 16 * MT + n) * kRowBytes + 16 * kk;
-    for (int c = 0; c < nchunks; ++c) {
-        const unsigned char *ab = xs + (c & 1) * BUF + arow;
-        u32x4 bo[4];
-        transpose8x4_bf16(wr0, bo);
-        wload(min(2 * c + 2, nsteps - 1), wr0);
+    for (int c0 = 0; c0 < nchunks; c0 += UN) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const u32x4 a = *(const u32x4 *)(ab + mt * 16 * kRowBytes);
+        for (int p = 0; p < UN; ++p) {
+            const int c = c0 + p;               // chunk c lives in buffer p & 1 (c0 is even)
+            const int sp = p % PD;              // register set that holds chunk c+1
+            if (c < nchunks) {
+                const unsigned char *ab = xs + (p & 1) * BUF + arow;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc[mt][u] = mfma32_bf16(a, bo[u], acc[mt][u]);
+                for (int h = 0; h < 2; ++h) {
+                    u32x4 bo[4];
+                    transpose8x4_bf16(wr[2 * sp + h], bo);
+                    wload(2 * c + h + 2 * PD, wr[2 * sp + h]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const u32x4 a = *(const u32x4 *)(ab + mt * 16 * kRowBytes + 64 * h);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) acc[mt][u] = mfma32_bf16(a, bo[u], acc[mt][u]);
+                    }
+                }
+                // the other buffer was last read in chunk c-1, which every wave left at the previous barrier
+                if (c + 1 < nchunks) stage_store((p + 1) & 1, st[sp]);
+                if (c + 1 + PD < nchunks) stage_load(c + 1 + PD, st[sp]);
+            }
+            __syncthreads();
         }
-        transpose8x4_bf16(wr1, bo);
-        wload(min(2 * c + 3, nsteps - 1), wr1);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const u32x4 a = *(const u32x4 *)(ab + mt * 16 * kRowBytes + 64);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) acc[mt][u] = mfma32_bf16(a, bo[u], acc[mt][u]);
-        }
-        // the other buffer was last read in chunk c-1, which every wave left at the previous barrier
-        if (c + 1 < nchunks) {
-            stage_store((c + 1) & 1);
-            if (c + 2 < nchunks) stage_load(c + 2);
-        }
-        __syncthreads();
     }
 
     f32x4 bv = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -145,20 +151,179 @@ __global__ __launch_bounds__(256) void lc_forward_bf16_tiled_kernel(Geom g, cons
         }
 }
 
-template <int MT>
+template <int MT, int PD, int WM>
 int launch_tiled(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                  hipStream_t s) {
-    constexpr int BT = 32 * MT;
+    constexpr int BT = 16 * MT * WM;
     const size_t lds = (size_t)2 * BT * kRowBytes;
-    auto kern = lc_forward_bf16_tiled_kernel<MT>;
+    auto kern = lc_forward_bf16_tiled_kernel<MT, PD, WM>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { set_hip_error(e, "lc_forward (bf16): hipFuncSetAttribute"); return LC_EHIP; }
     }
     const int fblocks = g.F / 128, btiles = (g.B + BT - 1) / BT;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(g.L * fblocks * btiles)), dim3(256), lds, s, g,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(g.L * fblocks * btiles)), dim3(128 * WM), lds, s, g,
                        (const unsigned short *)x, (const unsigned short *)w, bias, alpha, y, fblocks, btiles);
     LC_HIP_LAUNCH_CHECK("lc_forward (bf16, tiled) launch");
+    return LC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------------
+// Backward data (Eq. 1 decoder term): the same tiling with the operands' roles changed.  A workgroup owns
+// one S x S x C cell of the input (128 of its values) and a batch tile; the contraction runs over the
+// fields that cover the cell and over their filters.  A chunk is 64 filters of one field: 128 contiguous
+// bytes of dy per image, staged through LDS.  The filters are contiguous in memory along the contraction
+// index, so lane (n, kk) loads the operand of cell value n as it is: 16 bytes at filters 32h + 8kk of
+// the weight row that cell value has in the field.  Fields outside the grid are not in the chunk list; a
+// cell no field covers gets zeros.
+template <int MT, int PD>
+__global__ __launch_bounds__(256) void lc_bwd_data_bf16_tiled_kernel(Geom g, const unsigned short *__restrict__ dy,
+                                                                     const unsigned short *__restrict__ w,
+                                                                     float *__restrict__ dx, int CW, int nblk,
+                                                                     int btiles) {
+    static_assert(PD == 1 || PD % 2 == 0, "the chunk loop is unrolled PD times and alternates two LDS buffers");
+    constexpr int BT = 32 * MT, NS = MT, SR = 32;
+    constexpr int BUF = BT * kRowBytes;
+    constexpr int UN = PD == 1 ? 2 : PD;
+    extern __shared__ __attribute__((aligned(16))) unsigned char xs[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, kk = lane >> 4;
+    const int wm = wave >> 1, wn = wave & 1;
+    int t_id = remap_xcd(blockIdx.x, gridDim.x);
+    const int bt = t_id % btiles;
+    t_id /= btiles;
+    const int nb = t_id % nblk, cell = t_id / nblk;
+    const int ri = cell / CW, wi = cell - ri * CW;
+    const int b0 = bt * BT;
+    const int SC = g.S * g.C, AP = g.R / g.S;
+    // fields (ri - a, wi - ap) inside the grid
+    const int a_lo = max(0, ri - (g.LH - 1)), a_hi = min(AP - 1, ri);
+    const int p_lo = max(0, wi - (g.LW - 1)), p_hi = min(AP - 1, wi);
+    const int cpf = g.F / kChunk;
+    const int nchunks = (a_hi >= a_lo && p_hi >= p_lo) ? (a_hi - a_lo + 1) * (p_hi - p_lo + 1) * cpf : 0;
+
+    f32x4 acc[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[mt][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // a cursor walks the chunk list in order and stays on the last chunk once it gets there
+    struct Cursor { int a, ap, hf; };
+    auto advance = [&](Cursor &q) {
+        if (q.a == a_hi && q.ap == p_hi && q.hf == cpf - 1) return;
+        if (++q.hf == cpf) {
+            q.hf = 0;
+            if (++q.ap > p_hi) { q.ap = p_lo; ++q.a; }
+        }
+    };
+
+    const int seg = tid & 7, brow = tid >> 3;
+    const int LF = g.L * g.F;
+    int doff[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) doff[s] = min(b0 + brow + SR * s, g.B - 1) * LF + seg * 8;
+    Cursor sq = {a_lo, p_lo, 0};
+    auto stage_load = [&](u32x4 (&st)[NS]) {
+        const int o = ((ri - sq.a) * g.LW + (wi - sq.ap)) * g.F + sq.hf * kChunk;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) st[s] = *(g4_ptr)((gh_ptr)dy + doff[s] + o);
+        advance(sq);
+    };
+    auto stage_store = [&](int buf, const u32x4 (&st)[NS]) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) *(u32x4 *)(xs + buf * BUF + (brow + SR * s) * kRowBytes + seg * 16) = st[s];
+    };
+    // weight row of this lane's cell value in tile nt, relative to the cell's corner in a field
+    int kn[4];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        const int nn = nb * 128 + wn * 64 + nt * 16 + n;
+        const int dr = nn / SC;
+        kn[nt] = (dr * g.RC + (nn - dr * SC)) * g.F + 8 * kk;
+    }
+    Cursor wq = {a_lo, p_lo, 0};
+    int wh = 0;
+    auto wload = [&](u32x4 (&r)[4]) {
+        const size_t loc = (size_t)((ri - wq.a) * g.LW + (wi - wq.ap));
+        gh_ptr p = (gh_ptr)w + (loc * g.K + (size_t)g.S * wq.a * g.RC + g.S * wq.ap * g.C) * g.F + wq.hf * kChunk +
+                   32 * wh;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) r[nt] = *(g4_ptr)(p + kn[nt]);
+        if (wh == 1) advance(wq);
+        wh ^= 1;
+    };
+
+    if (nchunks > 0) {
+        u32x4 st[PD][NS];
+        u32x4 wr[2 * PD][4];
+#pragma unroll
+        for (int q = 0; q < 2 * PD; ++q) wload(wr[q]);
+        stage_load(st[0]);
+        stage_store(0, st[0]);
+#pragma unroll
+        for (int p = 0; p < PD; ++p) stage_load(st[p]);          // set p: chunk p+1
+        __syncthreads();
+        const int arow = (wm * 16 * MT + n) * kRowBytes + 16 * kk;
+        for (int c0 = 0; c0 < nchunks; c0 += UN) {
+#pragma unroll
+            for (int p = 0; p < UN; ++p) {
+                const int c = c0 + p;               // chunk c lives in buffer p & 1 (c0 is even)
+                const int sp = p % PD;              // register set that holds chunk c+1
+                if (c < nchunks) {
+                    const unsigned char *ab = xs + (p & 1) * BUF + arow;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        u32x4 bo[4];
+#pragma unroll
+                        for (int nt = 0; nt < 4; ++nt) bo[nt] = wr[2 * sp + h][nt];
+                        wload(wr[2 * sp + h]);
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) {
+                            const u32x4 a = *(const u32x4 *)(ab + mt * 16 * kRowBytes + 64 * h);
+#pragma unroll
+                            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma32_bf16(a, bo[nt], acc[mt][nt]);
+                        }
+                    }
+                    if (c + 1 < nchunks) stage_store((p + 1) & 1, st[sp]);
+                    if (c + 1 + PD < nchunks) stage_load(st[sp]);
+                }
+                __syncthreads();
+            }
+        }
+    }
+
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        const int nn = nb * 128 + wn * 64 + nt * 16 + n;
+        const int dr = nn / SC, rem = nn - dr * SC;
+        const int row = ri * g.S + dr, col = wi * g.S + rem / g.C;
+        if (row >= g.H || col >= g.W) continue;
+        const size_t pix = ((size_t)row * g.W + wi * g.S) * g.C + rem;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int b = b0 + wm * 16 * MT + mt * 16 + 4 * kk + r;
+                if (b < g.B) dx[(size_t)b * g.H * g.W * g.C + pix] = acc[mt][nt][r];
+            }
+    }
+}
+
+template <int MT, int PD>
+int launch_bwd_data_tiled(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
+    constexpr int BT = 32 * MT;
+    const size_t lds = (size_t)2 * BT * kRowBytes;
+    auto kern = lc_bwd_data_bf16_tiled_kernel<MT, PD>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) { set_hip_error(e, "lc_backward_data (bf16): hipFuncSetAttribute"); return LC_EHIP; }
+    }
+    const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
+    const int nblk = g.S * g.S * g.C / 128, btiles = (g.B + BT - 1) / BT;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(CH * CW * nblk * btiles)), dim3(256), lds, s, g,
+                       (const unsigned short *)dy, (const unsigned short *)w, dx, CW, nblk, btiles);
+    LC_HIP_LAUNCH_CHECK("lc_backward_data (bf16, tiled) launch");
     return LC_OK;
 }
 
@@ -174,10 +339,22 @@ bool bf16_tiled_forward_supported(const Geom &g) {
 int launch_forward_bf16_tiled(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                               hipStream_t s) {
     if (!bf16_tiled_forward_supported(g)) return LC_EUNSUPPORTED;
-#ifndef LC_TILED_FORCE_MT4
-    if (g.B > 128) return launch_tiled<8>(g, x, w, bias, alpha, y, s);
-#endif
-    return launch_tiled<4>(g, x, w, bias, alpha, y, s);
+    // 128-image tiles with a 2 x 2 wave grid measured best: 256-image tiles (WM = 4, or MT = 8) halve the
+    // filter traffic but leave one workgroup per CU
+    return launch_tiled<4, 2, 2>(g, x, w, bias, alpha, y, s);
+}
+
+// Tiled backward data: fields that tile the cells exactly, filters in chunks of 64, cells of 128-value blocks.
+bool bf16_tiled_backward_data_supported(const Geom &g) {
+    const long long cells = (long long)((g.H + g.S - 1) / g.S) * ((g.W + g.S - 1) / g.S);
+    return g.R % g.S == 0 && g.F % kChunk == 0 && (g.S * g.S * g.C) % 128 == 0 && g.B > 64 &&
+           (long long)g.B * g.L * g.F < (1ll << 31) && (long long)g.K * g.F < (1ll << 31) &&
+           cells * (g.S * g.S * g.C / 128) * ((g.B + 127) / 128) < (1ll << 31);
+}
+
+int launch_backward_data_bf16_tiled(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
+    if (!bf16_tiled_backward_data_supported(g)) return LC_EUNSUPPORTED;
+    return launch_bwd_data_tiled<4, 2>(g, dy, w, dx, s);
 }
 
 }  // namespace lc
