@@ -283,6 +283,7 @@ int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, floa
 int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, float beta, float *dw,
                                  hipStream_t s) {
     if (!bf16_shape_supported(g)) return LC_EUNSUPPORTED;
+    if (bf16_tiled_backward_weights_supported(g)) return launch_backward_weights_bf16_tiled(g, x, dy, beta, dw, s);
     const int kblocks = (g.K + 127) / 128;
     const long long ntasks = (long long)g.L * kblocks;
     hipLaunchKernelGGL(lc_bwd_weights_bf16_kernel, dim3((unsigned)((ntasks + 3) / 4), g.F / 64), dim3(256), 0, s, g,

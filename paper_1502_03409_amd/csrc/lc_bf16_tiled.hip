@@ -327,6 +327,138 @@ int launch_bwd_data_tiled(const Geom &g, const void *dy, const void *w, float *d
     return LC_OK;
 }
 
+// ------------------------------------------------------------------------------------------------------
+// Backward weights (gradient of Eq. 1 with respect to W): dW[k][f] = sum_b x[b][k] dy[b][f] per field.
+// A workgroup owns one field, 128 filters and a range of 64-row blocks of k; its waves take the blocks in
+// turn.  The batch is the contraction index and the slow index of both operands, so both need 8 x 4
+// register transposes.  dy serves every row block: it is transposed once and kept in LDS as
+// [filter][image], and the waves read their operands from there (filter f sits in row (f%4)*32 + f/4, so
+// that a lane's four tiles are four consecutive filters and neither the staging writes nor the operand
+// reads run into bank conflicts).  Patch values are private to a wave: lane (m, kk) loads images
+// 8kk..8kk+7 of the step at k = 4m..4m+3, which makes row m of tile u the weight row 4m+u; the loads run
+// RING steps ahead, across block boundaries.
+template <int RING>
+__global__ __launch_bounds__(256, 2) void lc_bwd_weights_bf16_tiled_kernel(Geom g, const unsigned short *__restrict__ x,
+                                                                        const unsigned short *__restrict__ dy,
+                                                                        float beta, float *__restrict__ out,
+                                                                        int fblocks, int ksplit, int nst, int rowb) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char xs[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, kk = lane >> 4;
+    int t_id = remap_xcd(blockIdx.x, gridDim.x);
+    const int ks = t_id % ksplit;
+    t_id /= ksplit;
+    const int fb = t_id % fblocks, loc = t_id / fblocks;
+    const int i = loc / g.LW, j = loc - i * g.LW;
+    const int nkb = g.K / 64;
+    const int kb_lo = (nkb * ks) / ksplit, kb_hi = (nkb * (ks + 1)) / ksplit;
+
+    // dy of the field, transposed into LDS; images beyond the batch are zeros
+    {
+        const int fg = tid & 31;
+        gh_ptr dl = (gh_ptr)dy + (size_t)loc * g.F + fb * 128 + 4 * fg;
+        const size_t dyimg = (size_t)g.L * g.F;
+        for (int bg = tid >> 5; bg < nst * 4; bg += 8) {
+            u32x2 r[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int b = 8 * bg + t;
+                r[t] = (u32x2){0u, 0u};
+                if (b < g.B) r[t] = *(g2_ptr)(dl + (size_t)b * dyimg);
+            }
+            u32x4 o[4];
+            transpose8x4_bf16(r, o);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) *(u32x4 *)(xs + (c * 32 + fg) * rowb + bg * 16) = o[c];
+        }
+    }
+    __syncthreads();
+
+    // patch operand: a cursor (row block, step) that stays on the wave's last block once it gets there
+    const int WC = g.W * g.C, img = g.H * WC;
+    int ckb = min(kb_lo + wave, nkb - 1), csb = 0;
+    auto xload = [&](u32x2 (&r)[8]) {
+        const int k0 = ckb * 64, kh = k0 / g.RC;
+        gh_ptr p = (gh_ptr)x + ((i * g.S + kh) * WC + j * g.S * g.C + (k0 - kh * g.RC) + 4 * n);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) r[t] = *(g2_ptr)(p + (size_t)(min(32 * csb + 8 * kk + t, g.B - 1) * img));
+        if (++csb == nst) {
+            csb = 0;
+            if (ckb + 4 < kb_hi) ckb += 4;
+        }
+    };
+    u32x2 ring[RING][8];
+#pragma unroll
+    for (int p = 0; p < RING; ++p) xload(ring[p]);
+
+    const unsigned char *bbase = xs + n * rowb + 16 * kk;
+    for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
+        f32x4 acc[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int v = 0; v < 8; ++v) acc[u][v] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int sb0 = 0; sb0 < nst; sb0 += RING) {
+#pragma unroll
+            for (int p = 0; p < RING; ++p) {
+                u32x4 ao[4];
+                transpose8x4_bf16(ring[p], ao);
+                xload(ring[p]);
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    const u32x4 bf = *(const u32x4 *)(bbase + ((v & 3) * 32 + (v >> 2) * 16) * rowb + (sb0 + p) * 64);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) acc[u][v] = mfma32_bf16(ao[u], bf, acc[u][v]);
+                }
+            }
+        }
+        float *ol = out + ((size_t)loc * g.K + (size_t)kb * 64) * g.F + fb * 128 + 4 * n;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                f32x4 *o = (f32x4 *)(ol + (size_t)(4 * (4 * kk + r) + u) * g.F);
+                f32x4 v0, v1;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) { v0[c] = acc[u][c][r]; v1[c] = acc[u][4 + c][r]; }
+                if (beta != 0.f) {
+                    v0 += beta * o[0];
+                    v1 += beta * o[16];
+                }
+                o[0] = v0;
+                o[16] = v1;
+                // keeps the read-modify-write of one row from being hoisted over the others' (registers)
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    }
+}
+
+template <int RING>
+int launch_bwd_weights_tiled(const Geom &g, const void *x, const void *dy, float beta, float *dw, hipStream_t s) {
+    const int nst = ((g.B + 31) / 32 + RING - 1) / RING * RING;
+    const int rowb = nst * 64 + 16;
+    const size_t lds = (size_t)128 * rowb;
+    auto kern = lc_bwd_weights_bf16_tiled_kernel<RING>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) { set_hip_error(e, "lc_backward_weights (bf16): hipFuncSetAttribute"); return LC_EHIP; }
+    }
+    // split the row blocks of a field over 1..4 workgroups, whichever fills whole rounds of the chip best
+    const int fblocks = g.F / 128, nkb = g.K / 64;
+    const long long base = (long long)g.L * fblocks, slots = 512;
+    int ksplit = 1;
+    double best = 0.0;
+    for (int ks = 1; ks <= 4 && ks * 4 <= nkb; ++ks) {
+        const long long tasks = base * ks, rounds = (tasks + slots - 1) / slots;
+        const double eff = (double)tasks / (double)(rounds * slots);
+        if (eff > best + 0.02) { best = eff; ksplit = ks; }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(base * ksplit)), dim3(256), lds, s, g, (const unsigned short *)x,
+                       (const unsigned short *)dy, beta, dw, fblocks, ksplit, nst, rowb);
+    LC_HIP_LAUNCH_CHECK("lc_backward_weights (bf16, tiled) launch");
+    return LC_OK;
+}
+
 }  // namespace
 
 // Shapes of the tiled kernel: filter blocks of 128, patch rows that split into 64-index chunks, 16-byte
@@ -355,6 +487,18 @@ bool bf16_tiled_backward_data_supported(const Geom &g) {
 int launch_backward_data_bf16_tiled(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
     if (!bf16_tiled_backward_data_supported(g)) return LC_EUNSUPPORTED;
     return launch_bwd_data_tiled<4, 2>(g, dy, w, dx, s);
+}
+
+// Tiled backward weights: 64-row blocks inside one patch row, filter blocks of 128, a batch that fits LDS.
+bool bf16_tiled_backward_weights_supported(const Geom &g) {
+    return g.RC % 64 == 0 && g.F % 128 == 0 && (g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.B > 64 &&
+           g.B <= 512 && (long long)g.B * g.H * g.W * g.C < (1ll << 31) && (long long)g.L * (g.F / 128) * 4 < (1ll << 31);
+}
+
+int launch_backward_weights_bf16_tiled(const Geom &g, const void *x, const void *dy, float beta, float *dw,
+                                       hipStream_t s) {
+    if (!bf16_tiled_backward_weights_supported(g)) return LC_EUNSUPPORTED;
+    return launch_bwd_weights_tiled<2>(g, x, dy, beta, dw, s);
 }
 
 }  // namespace lc

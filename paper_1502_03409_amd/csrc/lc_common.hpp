@@ -86,6 +86,9 @@ int launch_forward_bf16_tiled(const Geom &g, const void *x, const void *w, const
                               hipStream_t s);
 bool bf16_tiled_backward_data_supported(const Geom &g);
 int launch_backward_data_bf16_tiled(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s);
+bool bf16_tiled_backward_weights_supported(const Geom &g);
+int launch_backward_weights_bf16_tiled(const Geom &g, const void *x, const void *dy, float beta, float *dw,
+                                       hipStream_t s);
 int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, float beta, float *dw, hipStream_t s);
 size_t sae_workspace_bytes(const Geom &g);
 int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
