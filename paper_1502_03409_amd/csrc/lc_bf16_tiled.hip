@@ -43,7 +43,7 @@ constexpr int kRowBytes = 144;      // 128 bytes of a chunk + 16: eight rows' 16
 // PD = chunks of lookahead: PD register sets hold the patch chunks c+1 .. c+PD on their way to LDS and the
 // filter ring holds the 2*PD steps after the current one, so a load has PD chunks of MFMA work to land.
 template <int MT, int PD, int WM>
-__global__ __launch_bounds__(128 * WM) void lc_forward_bf16_tiled_kernel(Geom g, const unsigned short *__restrict__ x,
+__global__ __launch_bounds__(128 * WM, 2) void lc_forward_bf16_tiled_kernel(Geom g, const unsigned short *__restrict__ x,
                                                                     const unsigned short *__restrict__ w,
                                                                     const float *__restrict__ bias, float alpha,
                                                                     float *__restrict__ y, int fblocks, int btiles) {
@@ -177,7 +177,7 @@ int launch_tiled(const Geom &g, const void *x, const void *w, const float *bias,
 // the weight row that cell value has in the field.  Fields outside the grid are not in the chunk list; a
 // cell no field covers gets zeros.
 template <int MT, int PD>
-__global__ __launch_bounds__(256) void lc_bwd_data_bf16_tiled_kernel(Geom g, const unsigned short *__restrict__ dy,
+__global__ __launch_bounds__(256, 2) void lc_bwd_data_bf16_tiled_kernel(Geom g, const unsigned short *__restrict__ dy,
                                                                      const unsigned short *__restrict__ w,
                                                                      float *__restrict__ dx, int CW, int nblk,
                                                                      int btiles) {
@@ -471,8 +471,8 @@ bool bf16_tiled_forward_supported(const Geom &g) {
 int launch_forward_bf16_tiled(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                               hipStream_t s) {
     if (!bf16_tiled_forward_supported(g)) return LC_EUNSUPPORTED;
-    // 128-image tiles with a 2 x 2 wave grid measured best: 256-image tiles (WM = 4, or MT = 8) halve the
-    // filter traffic but leave one workgroup per CU
+    // 256-image tiles read the filters once; they fit two workgroups per CU only with one chunk of lookahead
+    if (g.B > 128) return launch_tiled<8, 1, 2>(g, x, w, bias, alpha, y, s);
     return launch_tiled<4, 2, 2>(g, x, w, bias, alpha, y, s);
 }
 
@@ -486,6 +486,7 @@ bool bf16_tiled_backward_data_supported(const Geom &g) {
 
 int launch_backward_data_bf16_tiled(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
     if (!bf16_tiled_backward_data_supported(g)) return LC_EUNSUPPORTED;
+    if (g.B > 128) return launch_bwd_data_tiled<8, 1>(g, dy, w, dx, s);
     return launch_bwd_data_tiled<4, 2>(g, dy, w, dx, s);
 }
 
