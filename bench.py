@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sae", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the per-kernel timings of the other workloads (cfg2, cfg4 fp32/bf16, the paper's layer 1)")
     ap.add_argument("--hbm-calibration", action="store_true",
                     help="only run a plain device-to-device copy of 1 GiB five times (reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
@@ -177,6 +179,10 @@ def main() -> int:
     if not args.no_sae:
         out["sae_step"] = bench_sae(lc, wl, np, torch, dev, max(3, args.steps // 2), max(2, args.warmup // 2))
 
+    # ---------------------------------------------------------------- the three contractions on the other shapes
+    if not args.no_others:
+        out["other_workloads"] = bench_others(lc, wl, torch, max(3, args.steps // 4))
+
     # ---------------------------------------------------------------- CPU oracle, as a scale reference
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, wl, x, w, dy)
@@ -231,6 +237,58 @@ def bench_sae(lc, wl, np, torch, dev, steps, warmup):
             "images_per_s": round(128 / (ms * 1e-3), 1), "TFLOP/s": round(tf, 2),
             "frac_fp32_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4), "steps": steps,
             "costs": [round(float(st["cost"].item()), 4) for st in stages]}
+
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+
+
+def bench_others(lc, wl, torch, iters):
+    """lc_forward / lc_backward_data / lc_backward_weights alone on the other workloads (random device
+    tensors of the workload's shape; parity at these shapes is the tests' business), HIP events on the
+    launch stream.  bf16 lines also give the time the mandatory HBM traffic would take at 8 TB/s."""
+    stream = torch.cuda.current_stream()
+    shapes = [("cfg2", wl.CONFIG_GEOM["cfg2"], "f32"), ("cfg4", wl.CONFIG_GEOM["cfg4"], "f32"),
+              ("cfg4", wl.CONFIG_GEOM["cfg4"], "bf16"), ("paper_layer1", wl.PAPER_LAYER1, "f32")]
+    res = {}
+    for name, g, dt in shapes:
+        G = lc.geom(*g.as_tuple())
+        x = torch.randn((g.B, g.H, g.W, g.C), device="cuda")
+        w = torch.randn((g.LH, g.LW, g.K, g.F), device="cuda") / g.K ** 0.5
+        dy = torch.randn((g.B, g.LH, g.LW, g.F), device="cuda")
+        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+        code = lc.LC_F32
+        if dt == "bf16":
+            x, w, dy, code = x.bfloat16(), w.bfloat16(), dy.bfloat16(), lc.LC_BF16
+        fns = {"lc_forward": lambda: lc.lc_forward(G, x, w, None, 1.0, y, code),
+               "lc_backward_data": lambda: lc.lc_backward_data(G, dy, w, dx, code),
+               "lc_backward_weights": lambda: lc.lc_backward_weights(G, x, dy, 0.0, dw, code)}
+        esz = 2 if dt == "bf16" else 4
+        min_bytes = {"lc_forward": esz * (w.numel() + x.numel()) + 4 * y.numel(),
+                     "lc_backward_data": esz * (w.numel() + dy.numel()) + 4 * dx.numel(),
+                     "lc_backward_weights": esz * (x.numel() + dy.numel()) + 4 * dw.numel()}
+        peak = BF16_MFMA_PEAK_TFLOPS if dt == "bf16" else FP32_MFMA_PEAK_TFLOPS
+        entry, total = {}, 0.0
+        for kn, f in fns.items():
+            for _ in range(2):
+                f()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(iters):
+                f()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / iters
+            total += ms
+            tf = g.flop_per_pass / (ms * 1e-3) / 1e12
+            entry[kn] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1), "frac_mfma_peak": round(tf / peak, 4),
+                         "frac_hbm_roof": round(min_bytes[kn] / (HBM_PEAK_GBS * 1e9) / (ms * 1e-3), 4)}
+        tf = 3 * g.flop_per_pass / (total * 1e-3) / 1e12
+        entry["fwd_bwd"] = {"ms": round(total, 4), "TFLOP/s": round(tf, 1), "frac_mfma_peak": round(tf / peak, 4)}
+        entry["shape"] = dict(zip("BHWCRSF", g.as_tuple()))
+        res[f"{name}_{dt}"] = entry
+        del x, w, dy, y, dx, dw
+        torch.cuda.empty_cache()
+    return res
 
 
 def cpu_baseline(np, wl, x, w, dy):
