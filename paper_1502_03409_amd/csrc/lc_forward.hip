@@ -433,16 +433,24 @@ int launch_fast_unr(const Geom &g, const float *x, const float *w, const float *
     return LC_OK;
 }
 
-// filters per wave / fields per workgroup by F, then the largest batch tile whose strip fits
+// filters per wave / fields per workgroup by F (at most nt_cap tiles of 16 filters per wave)
 template <int MT>
 int launch_fast_mt(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
-                   const float *alpha_dev, float *y, hipStream_t s, bool *done) {
+                   const float *alpha_dev, float *y, hipStream_t s, bool *done, int nt_cap) {
     *done = false;
-    if (g.F % 128 == 0) return launch_fast_unr<MT, 4, 2>(g, x, w, bias, alpha, alpha_dev, y, s, done);
-    if (g.F % 64 == 0) return launch_fast_unr<MT, 4, 4>(g, x, w, bias, alpha, alpha_dev, y, s, done);
-    if (g.F % 32 == 0) return launch_fast_unr<MT, 2, 4>(g, x, w, bias, alpha, alpha_dev, y, s, done);
+    if (g.F % 128 == 0 && nt_cap >= 4) return launch_fast_unr<MT, 4, 2>(g, x, w, bias, alpha, alpha_dev, y, s, done);
+    if (g.F % 64 == 0 && nt_cap >= 4) return launch_fast_unr<MT, 4, 4>(g, x, w, bias, alpha, alpha_dev, y, s, done);
+    if (g.F % 32 == 0 && nt_cap >= 2) return launch_fast_unr<MT, 2, 4>(g, x, w, bias, alpha, alpha_dev, y, s, done);
     if (g.F % 16 == 0) return launch_fast_unr<MT, 1, 4>(g, x, w, bias, alpha, alpha_dev, y, s, done);
     return LC_OK;
+}
+
+// workgroups of the pipelined kernel for a wave tile of 16*mt images x 16*nt filters
+long long fast_workgroups(const Geom &g, int mt, int nt) {
+    const int ntf = g.F % 128 == 0 && nt >= 4 ? 4 : g.F % 64 == 0 && nt >= 4 ? 4 : g.F % 32 == 0 && nt >= 2 ? 2 : 1;
+    const int nloc = g.F % 128 == 0 && nt >= 4 ? 2 : 4;
+    const long long strips = (g.LW + nloc - 1) / nloc;
+    return strips * g.LH * ((g.B + 16 * mt - 1) / (16 * mt)) * (g.F / ((4 / nloc) * ntf * 16));
 }
 
 }  // namespace
@@ -458,10 +466,19 @@ int launch_forward_f32(const Geom &g, const float *x, const float *w, const floa
         int rc = LC_OK;
         // 128 images x 64 filters per wave would need 128 accumulator registers and leave room for one wave
         // per SIMD only: wide layers take the 64-image tile (two waves per SIMD; the second batch tile of a
-        // strip finds the weights in L2)
-        if (g.B > 64 && g.F % 64 != 0) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
-        if (!done && g.B > 32) rc = launch_fast_mt<4>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
-        if (!done) rc = launch_fast_mt<2>(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        // strip finds the weights in L2).  A layer too small to give every CU a workgroup at that tile size
+        // steps down to smaller wave tiles until it does.
+        int mt = g.B > 64 && g.F % 64 != 0 ? 8 : g.B > 32 ? 4 : 2, nt = 4;
+#if defined(LC_FWD_FORCE_MT)
+        mt = LC_FWD_FORCE_MT; nt = LC_FWD_FORCE_NT;
+#else
+        while (fast_workgroups(g, mt, nt) < kComputeUnits && (mt > 2 || nt > 1)) {
+            if (nt > 1 && (nt >= mt || mt == 2)) nt >>= 1; else mt >>= 1;
+        }
+#endif
+        if (mt == 8) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
+        if (!done && mt >= 4 && g.B > 32) rc = launch_fast_mt<4>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
+        if (!done) rc = launch_fast_mt<2>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
         if (done) return rc;
     }
     // Pick the tile: as many images per wave as the batch offers (weights are re-read once per batch
