@@ -13,6 +13,8 @@
 // shared by the waves (adjacent cells share most of their fields).  Weights go straight from global
 // memory into the MFMA B operand: lane (n,kk) reads VF consecutive f of row k(n), and the A operand
 // reads the matching f of dy from LDS, so the contraction index of the MFMA is a permutation of f.
+#include <algorithm>
+
 #include "lc_common.hpp"
 
 namespace lc {
@@ -20,12 +22,12 @@ namespace lc {
 template <int MT, int NT, int NCELL, int VF>
 __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *__restrict__ dy,
                                                           const float *__restrict__ w, float *__restrict__ dx,
-                                                          int strips_per_row, int AP, int fcs, int rs) {
+                                                          int strips_per_row, int AP, int JW, int fcs, int rs) {
     constexpr int BT = 16 * MT, NNW = 4 / NCELL;
     extern __shared__ __attribute__((aligned(16))) float dys[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, kk = lane >> 4;
-    const int FC = 1 << fcs, JW = NCELL + AP - 1, SC = g.S * g.C, NCV = g.S * SC;
+    const int FC = 1 << fcs, SC = g.S * g.C, NCV = g.S * SC;
     const int work = remap_xcd(blockIdx.x, gridDim.x);
     const int ri = work / strips_per_row, wi0 = (work - ri * strips_per_row) * NCELL;
     const int b0 = blockIdx.z * BT;
@@ -57,7 +59,9 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
 
     const int rowlen = JW * FC;                            // staged floats per image
     const int q_first = tid % rowlen, b_first = tid / rowlen, dq = 256 % rowlen, db = 256 / rowlen;
-    const int jlo = wi0 - (AP - 1);
+    // staged window of JW = min(NCELL + AP - 1, LW) field columns: it starts at the strip's first covering
+    // field, moved into the grid (a layer with few fields per row stages no columns that do not exist)
+    const int jlo = min(max(wi0 - (AP - 1), 0), g.LW - JW);
     const size_t dyimg = (size_t)g.L * g.F;
 
     for (int a = 0; a < AP; ++a) {
@@ -83,7 +87,7 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
             for (int ap = 0; ap < AP; ++ap) {
                 const int j = wi - ap;
                 if (j < 0 || j >= g.LW) continue;          // uniform over the wave
-                const int js = wc - ap + AP - 1;
+                const int js = j - jlo;
                 const float *wl = w + ((size_t)(i * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F + fc0;
                 bool ok[NT];
 #pragma unroll
@@ -315,7 +319,7 @@ int row_stride(int rowlen, int vf) {
 template <int MT, int NT, int NCELL, int VF>
 int launch_one(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     constexpr int BT = 16 * MT, NNW = 4 / NCELL;
-    const int AP = (g.R + g.S - 1) / g.S, JW = NCELL + AP - 1;
+    const int AP = (g.R + g.S - 1) / g.S, JW = std::min(NCELL + AP - 1, g.LW);
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int NCV = g.S * g.S * g.C;
     // f chunk: the largest power of two (>= 4*VF) that covers F or still fits the LDS budget
@@ -331,7 +335,7 @@ int launch_one(const Geom &g, const float *dy, const float *w, float *dx, hipStr
     }
     const int strips = (CW + NCELL - 1) / NCELL;
     dim3 grid(strips * CH, (NCV + NNW * NT * 16 - 1) / (NNW * NT * 16), (g.B + BT - 1) / BT);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, AP, fcs, rs);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, AP, JW, fcs, rs);
     LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
     return LC_OK;
 }

@@ -87,13 +87,15 @@ def test_lc_primitives_match_oracle(name):
     assert rel_fro(dw1, ref_dw + prev) <= TOL
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg4", "paper_layer1"])
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "paper_layer1", "paper_layer3"])
 def test_lc_primitives_full_size_sampled(name):
     """Full-size workloads in the launch configuration the benchmark times: a sample of outputs
     against the oracle's single-output evaluators, plus the adjoint identities on the GPU results.
-    paper_layer1 is the first layer at the size the architecture section states (Sec. 3.1)."""
-    if name == "paper_layer1":
-        g, kind = wl.PAPER_LAYER1, "pink"
+    paper_layer1 / paper_layer3 are the first and the dense last layer at the sizes the architecture
+    section states (Sec. 3.1)."""
+    if name in ("paper_layer1", "paper_layer3"):
+        # paper_layer3: the dense last layer as a single field covering its whole input (Sec. 3.1)
+        g, kind = (wl.PAPER_LAYER1, "pink") if name == "paper_layer1" else (wl.PAPER_LAYER3, "halfnormal")
         print(f"case {name} geom {g}", flush=True)
         x, w, dy = wl.lc_inputs_blocked(g, kind, seed=0)
     else:

@@ -80,6 +80,10 @@ CONFIG_GEOM: Dict[str, LCGeom] = {
 # mini-batch of 192 is the one the training section gives).  1.53e9 parameters: fits one GPU whole.
 PAPER_LAYER1 = LCGeom(B=192, H=300, W=300, C=3, R=16, S=4, F=384)
 
+# The dense third layer of the same section (62x62x24 responses -> 4096 units) is the one-field case of
+# the same contraction: R = H = W, so L = 1, K = 92,256 and F = 4096 (3.8e8 parameters).
+PAPER_LAYER3 = LCGeom(B=192, H=62, W=62, C=24, R=62, S=1, F=4096)
+
 CONFIG_IMAGE_KIND = {
     "cfg1": "gaussian", "cfg2": "pink", "cfg3": "pink", "cfg4": "halfnormal",
     "cfg5_s1": "pink", "cfg5_s2": "halfnormal", "cfg5_s3": "halfnormal",
