@@ -77,7 +77,7 @@ CONFIG_GEOM: Dict[str, LCGeom] = {
 }
 # The first layer exactly as the architecture section states it (Sec. 3.1: 300x300x3 input, 16x16
 # receptive field, stride 4 -> 72x72 fields, a 4x4x24 output block = 384 filters per field; the
-# mini-batch of 192 is the one the training section gives).  1.53e9 parameters: fits one GPU whole.
+# mini-batch of 192 is the one the same section's training paragraph gives).  1.53e9 parameters: fits one GPU whole.
 PAPER_LAYER1 = LCGeom(B=192, H=300, W=300, C=3, R=16, S=4, F=384)
 
 # The dense third layer of the same section (62x62x24 responses -> 4096 units) is the one-field case of
