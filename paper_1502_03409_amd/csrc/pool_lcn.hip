@@ -192,21 +192,33 @@ __global__ __launch_bounds__(256) void l2pool_tile_kernel(const float *__restric
     const int oi0 = MODE == 0 ? ti : ti - (ks - 1), oj0 = MODE == 0 ? tj : tj - (ks - 1);
     const int SH = MODE == 0 ? H : Ho, SW = MODE == 0 ? W : Wo;
     const size_t sbase = (size_t)b * SH * SW;
-    for (int e = tid; e < PH * PW * CV; e += 256) {
-        const int cv = e % CV, pp = e / CV;
-        const int pi = pp / PW, pj = pp - pi * PW;
-        const int r = oi0 + pi, c = oj0 + pj;
-        f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (r >= 0 && r < SH && c >= 0 && c < SW) {
-            const size_t o = (sbase + (size_t)r * SW + c) * C + cv * 4;
-            if (MODE == 0) {
-                const f32x4 t = *(const f32x4 *)(x + o);
-                v = t * t;
-            } else {
-                v = *(const f32x4 *)(dy + o) / *(const f32x4 *)(y + o);
+    // eight loads in flight per thread before the first goes to LDS
+    const int npatch = PH * PW * CV;
+    for (int e0 = tid; e0 < npatch; e0 += 256 * 8) {
+        f32x4 v[8], v2[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int e = e0 + 256 * q;
+            const int cv = e % CV, pp = e / CV;
+            const int pi = pp / PW, pj = pp - pi * PW;
+            const int r = oi0 + pi, c = oj0 + pj;
+            v[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            v2[q] = (f32x4){1.f, 1.f, 1.f, 1.f};
+            if (e < npatch && r >= 0 && r < SH && c >= 0 && c < SW) {
+                const size_t o = (sbase + (size_t)r * SW + c) * C + cv * 4;
+                if (MODE == 0) {
+                    v[q] = *(const f32x4 *)(x + o);
+                } else {
+                    v[q] = *(const f32x4 *)(dy + o);
+                    v2[q] = *(const f32x4 *)(y + o);
+                }
             }
         }
-        *(f32x4 *)(patch + (size_t)pp * C + cv * 4) = v;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int e = e0 + 256 * q;
+            if (e < npatch) *(f32x4 *)(patch + (size_t)e * 4) = MODE == 0 ? v[q] * v[q] : v[q] / v2[q];
+        }
     }
     __syncthreads();
     // a thread owns 4 consecutive columns of one tile row and channel quad
