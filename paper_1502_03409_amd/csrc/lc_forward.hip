@@ -140,10 +140,11 @@ __device__ __forceinline__ float fget(const typename FVec<N>::T &v, int i) {
     if constexpr (N == 1) return v; else return v[i];
 }
 
+constexpr int kFwdStageSlotsWide = 6;   // eight-wave workgroups: half the registers per lane
 constexpr int kFwdStageSlots = 12;  // dwordx4 staging registers per lane: chunk <= 12*256*16 B = 48 KB
 
-template <int MT, int NT, int NLOC, int UNR>
-__global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const float *__restrict__ x,
+template <int MT, int NT, int NLOC, int UNR, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kernel(Geom g, const float *__restrict__ x,
                                                               const float *__restrict__ w,
                                                               const float *__restrict__ bias, float alpha,
                                                               const float *__restrict__ alpha_dev,
@@ -153,7 +154,8 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     typedef const __attribute__((address_space(1))) WV *gw_ptr;
     typedef const __attribute__((address_space(1))) f32x4 *gx4_ptr;
-    constexpr int BT = 16 * MT, NFW = 4 / NLOC;
+    constexpr int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW;   // NW waves: NLOC fields x NFW filter blocks
+    constexpr int SLOTS = NW == 8 ? kFwdStageSlotsWide : kFwdStageSlots;
     extern __shared__ __attribute__((aligned(16))) float xs[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kk = lane >> 4;
@@ -178,16 +180,16 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
         for (int u = 0; u < NT; ++u) acc[mt][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     // staging map: a chunk is NR patch rows x sq4 dwordx4 per image; slot q of this thread copies dwordx4
-    // number e = tid + 256*q of the [BT][NR][sq4] chunk.  sb[q] = image << 16 | row << 12 | float offset in
+    // number e = tid + NTHR*q of the [BT][NR][sq4] chunk.  sb[q] = image << 16 | row << 12 | float offset in
     // the row; bit 31: past the end of the chunk (slot unused), bit 30: image beyond the batch (zeros).
     const int per_img = NR * sq4, sqc = sq4 * 4;
-    const int nslots = (BT * per_img + 255) >> 8;
-    int sb[kFwdStageSlots];
+    const int nslots = (BT * per_img + NTHR - 1) / NTHR;
+    int sb[SLOTS];
     {
         int vv = tid % per_img, b = tid / per_img;
-        const int dv = 256 % per_img, db = 256 / per_img;
+        const int dv = NTHR % per_img, db = NTHR / per_img;
 #pragma unroll
-        for (int q = 0; q < kFwdStageSlots; ++q) {
+        for (int q = 0; q < SLOTS; ++q) {
             const int r = vv / sq4, v = vv - r * sq4;
             sb[q] = (b << 16) | (r << 12) | (v * 4);
             if (b >= BT) sb[q] = (int)0x80000000;
@@ -197,12 +199,12 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
         }
     }
     const int col0 = j0 * SC;
-    f32x4 st[kFwdStageSlots];
+    f32x4 st[SLOTS];
     auto stage_load = [&](int kh, int sc) {
         const float *row = x + (size_t)b0 * img + (size_t)(i * g.S + kh) * WC + col0 + sc * CQ;
         const int lim = WC - col0 - sc * CQ;          // floats of this image row that exist from the chunk start on
 #pragma unroll
-        for (int q = 0; q < kFwdStageSlots; ++q) {
+        for (int q = 0; q < SLOTS; ++q) {
             if (q < nslots) {
                 const int b = (sb[q] >> 16) & 0x3fff, r = (sb[q] >> 12) & 15, v = sb[q] & 0xfff;
                 f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -213,7 +215,7 @@ __global__ __launch_bounds__(256) void lc_forward_fast_kernel(Geom g, const floa
     };
     auto stage_store = [&]() {
 #pragma unroll
-        for (int q = 0; q < kFwdStageSlots; ++q) {
+        for (int q = 0; q < SLOTS; ++q) {
             if (q < nslots && sb[q] >= 0) {
                 const int b = (sb[q] >> 16) & 0x3fff, r = (sb[q] >> 12) & 15, v = sb[q] & 0xfff;
                 // rows of images 8..15 (mod 16) sit 2 floats to the right (see xwin below)
@@ -342,14 +344,14 @@ int fast_row_stride(int sqc) {
     return ((sqc + 31) / 32) * 32 + 4;
 }
 
-template <int MT, int NT, int NLOC, int UNR>
+template <int MT, int NT, int NLOC, int UNR, int NW = 4>
 int launch_fast(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
                 const float *alpha_dev, float *y, int CQ, int NR, int work_first, int work_count, hipStream_t s) {
-    constexpr int BT = 16 * MT, NFW = 4 / NLOC;
+    constexpr int BT = 16 * MT, NFW = NW / NLOC;
     const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;   // staged floats per image and patch row
     const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
-    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR>;
+    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { set_hip_error(e, "lc_forward: hipFuncSetAttribute"); return LC_EHIP; }
@@ -357,7 +359,7 @@ int launch_fast(const Geom &g, const float *x, const float *w, const float *bias
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(work_count * nbt, g.F / (NFW * NT * 16));
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS, NR,
+    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS, NR,
                        work_first, nbt);
     LC_HIP_LAUNCH_CHECK("lc_forward launch");
     return LC_OK;
@@ -401,14 +403,15 @@ int launch_fast_tiered(const Geom &g, const float *x, const float *w, const floa
 
 // Picks the chunk (CQ floats of a patch row, a divisor of RC and multiple of 4*UNR) so that the staged
 // strip of BT images fits the staging registers and the LDS budget.  Returns 0 if none does.
-int pick_chunk(const Geom &g, int BT, int NLOC, int UNR, size_t lds_budget) {
+int pick_chunk(const Geom &g, int BT, int NLOC, int UNR, size_t lds_budget, int nthr = 256,
+               int slots = kFwdStageSlots) {
     const int SC = g.S * g.C;
     for (int nsub = 1; nsub <= g.RC / (4 * UNR); ++nsub) {
         if (g.RC % nsub) continue;
         const int CQ = g.RC / nsub;
         if (CQ % (4 * UNR)) continue;
         const int sqc = (CQ + (NLOC - 1) * SC + 3) & ~3;
-        if ((size_t)BT * (sqc / 4) > (size_t)kFwdStageSlots * 256) continue;
+        if ((size_t)BT * (sqc / 4) > (size_t)slots * nthr) continue;
         if ((size_t)BT * fast_row_stride(sqc) * 4 > lds_budget) continue;
         if (sqc / 4 > 0xffff / 4) continue;
         return CQ;
@@ -429,6 +432,25 @@ int launch_fast_unr(const Geom &g, const float *x, const float *w, const float *
         return launch_fast_tiered<MT, NT, NLOC, 6>(g, x, w, bias, alpha, alpha_dev, y, CQ, s);
     if (spr % 5 == 0 && (CQ = pick_chunk(g, 16 * MT, NLOC, 5, budget)))
         return launch_fast_tiered<MT, NT, NLOC, 5>(g, x, w, bias, alpha, alpha_dev, y, CQ, s);
+    *done = false;
+    return LC_OK;
+}
+
+// Layers with 16 filters per field give a wave one filter tile, so a staged strip feeds few MFMAs.  Eight
+// waves (eight fields) per workgroup share a strip that is only about a third longer than the one four
+// fields need, and with so few accumulators two such workgroups still fit a compute unit.
+int launch_fast_wide(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                     const float *alpha_dev, float *y, hipStream_t s, bool *done) {
+    const size_t budget = 78 * 1024;
+    const int spr = g.RC / 4, ntask = ((g.LW + 7) / 8) * g.LH;
+    *done = true;
+    int CQ;
+    if (spr % 8 == 0 && (CQ = pick_chunk(g, 128, 8, 8, budget, 512, kFwdStageSlotsWide)))
+        return launch_fast<8, 1, 8, 8, 8>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
+    if (spr % 6 == 0 && (CQ = pick_chunk(g, 128, 8, 6, budget, 512, kFwdStageSlotsWide)))
+        return launch_fast<8, 1, 8, 6, 8>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
+    if (spr % 5 == 0 && (CQ = pick_chunk(g, 128, 8, 5, budget, 512, kFwdStageSlotsWide)))
+        return launch_fast<8, 1, 8, 5, 8>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
     *done = false;
     return LC_OK;
 }
@@ -476,7 +498,10 @@ int launch_forward_f32(const Geom &g, const float *x, const float *w, const floa
             if (nt > 1 && (nt >= mt || mt == 2)) nt >>= 1; else mt >>= 1;
         }
 #endif
-        if (mt == 8) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
+        const bool one_tile = g.F % 32 != 0 || nt == 1;
+        if (mt == 8 && one_tile && g.LW >= 8 && (8 * g.S * g.C) % 4 == 0)
+            rc = launch_fast_wide(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        if (!done && mt == 8) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
         if (!done && mt >= 4 && g.B > 32) rc = launch_fast_mt<4>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
         if (!done) rc = launch_fast_mt<2>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
         if (done) return rc;

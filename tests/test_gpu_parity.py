@@ -61,6 +61,7 @@ SMALL = {
     "fast_floor": (wl.LCGeom(B=72, H=27, W=31, C=4, R=6, S=2, F=64), "halfnormal"), # floor geometry, F=64
     "fast_f128": (wl.LCGeom(B=80, H=14, W=18, C=8, R=4, S=2, F=128), "halfnormal"), # filters split over waves
     "fast_lw1": (wl.LCGeom(B=96, H=20, W=8, C=4, R=8, S=4, F=32), "gaussian"),      # one field per row
+    "wide_f16": (wl.LCGeom(B=100, H=132, W=136, C=3, R=8, S=4, F=16), "pink"),      # eight fields per workgroup, ragged strip
     "single_img": (wl.LCGeom(B=1, H=9, W=9, C=2, R=3, S=3, F=5), "gaussian"),
 }
 
