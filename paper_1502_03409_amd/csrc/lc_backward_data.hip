@@ -157,16 +157,16 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
 // of image m from LDS, so component t of both vectors is contraction index 4kk+t of MFMA number t.
 // Fields outside the grid are staged as zeros (their weights are read from a clamped, valid address),
 // so the inner loop has no branches.
-template <int MT, int NT, int NCELL, int AP>
-__global__ __launch_bounds__(256) void lc_bwd_data_fast_kernel(Geom g, const float *__restrict__ dy,
-                                                               const float *__restrict__ w,
-                                                               float *__restrict__ dx, int strips_per_row, int RS,
-                                                               int work_offset, int nbt) {
+template <int MT, int NT, int NCELL, int AP, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_kernel(
+    Geom g, const float *__restrict__ dy, const float *__restrict__ w, float *__restrict__ dx, int strips_per_row,
+    int RS, int work_offset, int nbt) {
     typedef const __attribute__((address_space(1))) f32x4 *g4_ptr;
     typedef const __attribute__((address_space(1))) float *gf_ptr;
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 4;   // R4: dwordx4 per image and chunk
-    constexpr int NSLOT = (BT * R4 + 255) / 256;
+    constexpr int NTHR = 64 * NW;                                   // NW waves: NCELL cells x NW/NCELL value blocks
+    constexpr int NSLOT = (BT * R4 + NTHR - 1) / NTHR;
     extern __shared__ __attribute__((aligned(16))) float dys[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, kk = lane >> 4;
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void lc_bwd_data_fast_kernel(Geom g, const flo
     const int b0 = (t_id % nbt) * BT;
     const int wc = wave % NCELL;
     const int wi = wi0 + wc;
-    const int n0 = (blockIdx.y * (4 / NCELL) + wave / NCELL) * NT * 16;
+    const int n0 = (blockIdx.y * (NW / NCELL) + wave / NCELL) * NT * 16;
     const int nfh = g.F >> 4;
 
     // cell values this lane supplies weights for / stores
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void lc_bwd_data_fast_kernel(Geom g, const flo
     const size_t dyimg = (size_t)g.L * g.F;
 
     const int v0 = tid % R4, bq0 = tid / R4;
-    constexpr int DV = 256 % R4, DB = 256 / R4;
+    constexpr int DV = NTHR % R4, DB = NTHR / R4;
     f32x4 st[NSLOT];
     auto stage_load = [&](int c) {
         const int a = a_lo + c / nfh, fh = c - (c / nfh) * nfh;
@@ -357,23 +357,23 @@ int launch_mt(const Geom &g, const float *dy, const float *w, float *dx, hipStre
 
 namespace {
 
-template <int MT, int NT, int NCELL, int AP>
+template <int MT, int NT, int NCELL, int AP, int NW = 4>
 int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int NCV = g.S * g.S * g.C;
     const int RS = ((JW * 16 + 31) / 32) * 32 + 4;
     const size_t lds = (size_t)BT * RS * sizeof(float);
-    auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP>;
+    auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP, NW>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { set_hip_error(e, "lc_backward_data: hipFuncSetAttribute"); return LC_EHIP; }
     }
     const int strips = (CW + NCELL - 1) / NCELL;
-    const int nblk = (4 / NCELL) * NT * 16;
+    const int nblk = (NW / NCELL) * NT * 16;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(strips * CH * nbt, (NCV + nblk - 1) / nblk);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, RS, 0, nbt);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, g, dy, w, dx, strips, RS, 0, nbt);
     LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
     return LC_OK;
 }
@@ -401,7 +401,8 @@ int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, flo
             if (ntt <= 3) LC_BD(5, 3, 4);
             if (ntt == 4) LC_BD(5, 4, 4);
         } else if (ap == 8) {
-            if (ntt == 1) LC_BD(8, 1, 4);
+            // one tile of cell values per wave: eight cells per workgroup share the staged fields
+            if (ntt == 1) return launch_fast<4, 1, 8, 8, 8>(g, dy, w, dx, s);
         }
 #undef LC_BD
     }
