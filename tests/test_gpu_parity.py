@@ -334,3 +334,47 @@ def test_sae_step_without_h_out_and_descent():
         assert h is None
         costs.append(J)
     assert all(c1 < c0 for c0, c1 in zip(costs, costs[1:])), costs
+
+
+@pytest.mark.parametrize("flags", [0, 3])
+def test_cfg5_three_stage_step_full_size(flags):
+    """Workload cfg5 at full size, in the launch configuration the benchmark times: every stage takes one
+    SGD step (Eq. 1) and hands l2pool -> LCN of its features to the next.  The oracle runs its own chain
+    from the same images and initial weights; each stage's cost, features and updates are compared."""
+    x_ref = wl.pink_images(np.random.default_rng(0), 128, 128, 128, 3)
+    x_gpu = dev(x_ref)
+    alpha, lam, eps_s = 0.9, wl.SAE_LAMBDA, wl.SAE_EPS
+    for si, key in enumerate(("cfg5_s1", "cfg5_s2", "cfg5_s3")):
+        g = wl.CONFIG_GEOM[key]
+        t = g.as_tuple()
+        print(f"case cfg5 stage {si + 1} flags {flags} geom {g}", flush=True)
+        assert tuple(x_gpu.shape) == (g.B, g.H, g.W, g.C)
+        rw = np.random.default_rng(100 + si)
+        w = (rw.standard_normal((g.LH, g.LW, g.K, g.F)) / np.sqrt(g.K)).astype(np.float32)
+        b = (0.05 * rw.standard_normal((g.H, g.W, g.C))).astype(np.float32)
+        lr = 10.0 * wl.SAE_LR        # a step large enough for the update to stand clear of fp32 rounding of w
+        G = lc.geom(*t)
+        wd, bd = dev(w), dev(b)
+        ad = torch.tensor([alpha], device="cuda", dtype=torch.float32)
+        cost = torch.full((1,), float("nan"), device="cuda")
+        h = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
+        ws = torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda")
+        lc.sae_step(G, x_gpu, wd, bd, ad, lam, eps_s, lr, flags, h, cost, ws)
+        Jo, wo, bo, ao, ho = oracle.sae_step(t, x_ref, w, b, alpha, lam, eps_s, lr, flags)
+        assert abs(host(cost)[0] - Jo) <= TOL * abs(Jo)
+        assert rel_fro(host(h), ho) <= TOL
+        assert rel_fro(host(wd).astype(np.float64) - w, wo - w) <= 5e-4, "dW"
+        assert rel_fro(host(bd).astype(np.float64) - b, bo - b) <= 5e-4, "db"
+        if flags & 2:
+            assert abs((host(ad)[0] - alpha) - (ao - alpha)) <= 5e-4 * abs(ao - alpha)
+        # next stage's input, each side from its own features
+        p = torch.empty((g.B, g.LH - 2, g.LW - 2, g.F), device="cuda")
+        n = torch.empty_like(p)
+        mu = torch.empty(p.shape[:3], device="cuda")
+        rstd = torch.empty_like(mu)
+        lc.l2pool_fwd(h, p, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS)
+        lc.lcn_fwd(p, n, mu, rstd, wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)
+        n_ref = oracle.lcn_fwd(oracle.l2pool_fwd(ho, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS),
+                               wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)[0]
+        assert rel_fro(host(n), n_ref) <= TOL
+        x_gpu, x_ref = n, n_ref.astype(np.float32)
