@@ -239,7 +239,8 @@ def test_forward_determinism_and_empty_tail():
 
 POOL_SHAPES = [((3, 9, 11, 5), 3, 1), ((2, 12, 12, 32), 3, 1), ((2, 10, 9, 8), 2, 2), ((1, 7, 7, 3), 3, 2),
                ((4, 46, 46, 32), 3, 1), ((2, 19, 35, 16), 5, 1), ((1, 3, 3, 4), 3, 1), ((2, 9, 9, 8), 1, 1),
-               ((1, 8, 8, 600), 3, 1), ((2, 57, 57, 16), 3, 1)]
+               ((1, 8, 8, 600), 3, 1), ((2, 57, 57, 16), 3, 1),
+               ((128, 46, 46, 32), 3, 1)]    # the last one: cfg3's pooling call at full size
 
 
 @pytest.mark.parametrize("shape,ks,st", POOL_SHAPES)
@@ -259,7 +260,7 @@ def test_l2pool_matches_oracle(shape, ks, st):
 
 
 LCN_SHAPES = [((2, 9, 10, 3), 5), ((3, 20, 37, 32), 5), ((2, 16, 16, 8), 3), ((1, 3, 2, 5), 5), ((2, 33, 17, 6), 7),
-              ((1, 5, 40, 130), 5), ((4, 44, 44, 32), 5)]
+              ((1, 5, 40, 130), 5), ((4, 44, 44, 32), 5), ((128, 44, 44, 32), 5)]   # last: cfg3 at full size
 
 
 @pytest.mark.parametrize("shape,ks", LCN_SHAPES)
@@ -378,3 +379,37 @@ def test_cfg5_three_stage_step_full_size(flags):
                                wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)[0]
         assert rel_fro(host(n), n_ref) <= TOL
         x_gpu, x_ref = n, n_ref.astype(np.float32)
+
+
+def _sweep_geometries(n, seed):
+    """Seeded random layer geometries: half of them aligned (C a multiple of 4, F of 16, R of S), so that
+    the pipelined kernels and their tile rules are exercised as well as the generic ones."""
+    r = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        aligned = len(out) % 2 == 0
+        S = int(r.integers(1, 5))
+        R = S * int(r.integers(1, 6)) if aligned else int(r.integers(1, 9))
+        C = int(r.choice([4, 8, 16])) if aligned else int(r.integers(1, 7))
+        F = int(r.choice([16, 32, 48, 64, 128])) if aligned else int(r.integers(1, 41))
+        B = int(r.choice([17, 33, 64, 65, 96, 129, 140])) if aligned else int(r.integers(1, 70))
+        H, W = R + int(r.integers(0, 14)), R + int(r.integers(0, 22))
+        g = wl.LCGeom(B=B, H=H, W=W, C=C, R=R, S=S, F=F)
+        if g.flop_per_pass > 3e8 or g.params > 4e6:
+            continue
+        out.append(g)
+    return out
+
+
+@pytest.mark.parametrize("idx", range(28))
+def test_lc_primitives_geometry_sweep(idx):
+    g = _sweep_geometries(28, seed=2024)[idx]
+    print(f"case sweep {idx} geom {g}", flush=True)
+    x, w, dy, bias = wl.lc_inputs(g, "gaussian", seed=idx, with_bias=True)
+    t = g.as_tuple()
+    assert rel_fro(run_forward(g, x, w, bias, 1.25), oracle.lc_forward(t, x, w, bias, 1.25)) <= TOL
+    dx = run_backward_data(g, dy, w)
+    ref_dx = oracle.lc_backward_data(t, dy, w)
+    assert rel_fro(dx, ref_dx) <= TOL
+    assert np.all(dx[ref_dx == 0.0] == 0.0)
+    assert rel_fro(run_backward_weights(g, x, dy), oracle.lc_backward_weights(t, x, dy)) <= TOL
