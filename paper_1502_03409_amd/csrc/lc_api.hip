@@ -2,6 +2,10 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "lc_common.hpp"
 
 namespace lc {
@@ -10,6 +14,24 @@ static thread_local char g_err[256] = "";
 
 void set_hip_error(hipError_t e, const char *where) {
     snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+}
+
+// Kernels that stage more than 48 KB need their dynamic LDS limit raised; the attribute is set once per
+// (kernel, device) and remembered, so a launch costs a table lookup instead of a runtime call.
+int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where) {
+    if (bytes <= 48 * 1024) return LC_OK;
+    static std::mutex mu;
+    static std::map<std::pair<const void *, int>, size_t> granted;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_hip_error(e, where); return LC_EHIP; }
+    std::lock_guard<std::mutex> lock(mu);
+    size_t &have = granted[{kernel, dev}];
+    if (bytes <= have) return LC_OK;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) { set_hip_error(e, where); return LC_EHIP; }
+    have = bytes;
+    return LC_OK;
 }
 
 static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }

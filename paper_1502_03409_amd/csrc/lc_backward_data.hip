@@ -329,10 +329,7 @@ int launch_one(const Geom &g, const float *dy, const float *w, float *dx, hipStr
     const size_t lds = (size_t)BT * rs * sizeof(float);
     if (lds > 160 * 1024) return LC_EUNSUPPORTED;
     auto kern = lc_bwd_data_kernel<MT, NT, NCELL, VF>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) { set_hip_error(e, "lc_backward_data: hipFuncSetAttribute"); return LC_EHIP; }
-    }
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
     const int strips = (CW + NCELL - 1) / NCELL;
     dim3 grid(strips * CH, (NCV + NNW * NT * 16 - 1) / (NNW * NT * 16), (g.B + BT - 1) / BT);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, AP, JW, fcs, rs);
@@ -365,10 +362,7 @@ int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipSt
     const int RS = ((JW * 16 + 31) / 32) * 32 + 4;
     const size_t lds = (size_t)BT * RS * sizeof(float);
     auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP, NW>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) { set_hip_error(e, "lc_backward_data: hipFuncSetAttribute"); return LC_EHIP; }
-    }
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
     const int strips = (CW + NCELL - 1) / NCELL;
     const int nblk = (NW / NCELL) * NT * 16;
     const int nbt = (g.B + BT - 1) / BT;

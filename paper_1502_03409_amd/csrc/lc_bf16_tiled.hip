@@ -157,10 +157,7 @@ int launch_tiled(const Geom &g, const void *x, const void *w, const float *bias,
     constexpr int BT = 16 * MT * WM;
     const size_t lds = (size_t)2 * BT * kRowBytes;
     auto kern = lc_forward_bf16_tiled_kernel<MT, PD, WM>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) { set_hip_error(e, "lc_forward (bf16): hipFuncSetAttribute"); return LC_EHIP; }
-    }
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward (bf16): hipFuncSetAttribute")) return rc_lds;
     const int fblocks = g.F / 128, btiles = (g.B + BT - 1) / BT;
     hipLaunchKernelGGL(kern, dim3((unsigned)(g.L * fblocks * btiles)), dim3(128 * WM), lds, s, g,
                        (const unsigned short *)x, (const unsigned short *)w, bias, alpha, y, fblocks, btiles);
@@ -315,10 +312,7 @@ int launch_bwd_data_tiled(const Geom &g, const void *dy, const void *w, float *d
     constexpr int BT = 32 * MT;
     const size_t lds = (size_t)2 * BT * kRowBytes;
     auto kern = lc_bwd_data_bf16_tiled_kernel<MT, PD>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) { set_hip_error(e, "lc_backward_data (bf16): hipFuncSetAttribute"); return LC_EHIP; }
-    }
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data (bf16): hipFuncSetAttribute")) return rc_lds;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int nblk = g.S * g.S * g.C / 128, btiles = (g.B + BT - 1) / BT;
     hipLaunchKernelGGL(kern, dim3((unsigned)(CH * CW * nblk * btiles)), dim3(256), lds, s, g,
@@ -439,10 +433,7 @@ int launch_bwd_weights_tiled(const Geom &g, const void *x, const void *dy, float
     const int rowb = nst * 64 + 16;
     const size_t lds = (size_t)128 * rowb;
     auto kern = lc_bwd_weights_bf16_tiled_kernel<RING>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) { set_hip_error(e, "lc_backward_weights (bf16): hipFuncSetAttribute"); return LC_EHIP; }
-    }
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_weights (bf16): hipFuncSetAttribute")) return rc_lds;
     // split the row blocks of a field over 1..4 workgroups, whichever fills whole rounds of the chip best
     const int fblocks = g.F / 128, nkb = g.K / 64;
     const long long base = (long long)g.L * fblocks, slots = 512;

@@ -56,6 +56,8 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
 }
 
 void set_hip_error(hipError_t e, const char *where);
+// raises a kernel's dynamic LDS limit when `bytes` needs it (once per kernel and device); LC_OK or LC_EHIP
+int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where);
 
 #define LC_HIP_LAUNCH_CHECK(where)                       \
     do {                                                 \

@@ -325,10 +325,7 @@ int launch_one(const Geom &g, const float *x, const float *w, const float *bias,
     const size_t lds = ((size_t)BT * rs + 8) * sizeof(float);
     if (lds > 160 * 1024) return LC_EUNSUPPORTED;
     auto kern = lc_forward_kernel<MT, NT, NLOC>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) { set_hip_error(e, "lc_forward: hipFuncSetAttribute"); return LC_EHIP; }
-    }
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward: hipFuncSetAttribute")) return rc_lds;
     dim3 grid(strips * g.LH, (g.F + NFW * NT * 16 - 1) / (NFW * NT * 16), (g.B + BT - 1) / BT);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, sq, rs);
     LC_HIP_LAUNCH_CHECK("lc_forward launch");
@@ -352,10 +349,7 @@ int launch_fast(const Geom &g, const float *x, const float *w, const float *bias
     const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
     auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) { set_hip_error(e, "lc_forward: hipFuncSetAttribute"); return LC_EHIP; }
-    }
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward: hipFuncSetAttribute")) return rc_lds;
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(work_count * nbt, g.F / (NFW * NT * 16));

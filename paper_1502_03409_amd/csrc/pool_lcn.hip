@@ -448,11 +448,7 @@ int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int 
         const long long nblk = (long long)B * th * tw;
         if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
         auto kern = l2pool_tile_kernel<0>;
-        if (patch_bytes > 32 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               (int)patch_bytes);
-            if (e != hipSuccess) { set_hip_error(e, "l2pool_fwd: hipFuncSetAttribute"); return LC_EHIP; }
-        }
+        if (int rc_lds = allow_dynamic_lds((const void *)kern, patch_bytes, "l2pool_fwd: hipFuncSetAttribute")) return rc_lds;
         hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), patch_bytes, s, x, (const float *)nullptr,
                            (const float *)nullptr, y, H, W, C, Ho, Wo, ks, eps, tw, th * tw);
     } else if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && B <= 65535 && (long long)H * W * C < (1LL << 30)) {
@@ -481,11 +477,7 @@ int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx
         const long long nblk = (long long)B * th * tw;
         if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
         auto kern = l2pool_tile_kernel<1>;
-        if (patch_bytes > 32 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               (int)patch_bytes);
-            if (e != hipSuccess) { set_hip_error(e, "l2pool_bwd: hipFuncSetAttribute"); return LC_EHIP; }
-        }
+        if (int rc_lds = allow_dynamic_lds((const void *)kern, patch_bytes, "l2pool_bwd: hipFuncSetAttribute")) return rc_lds;
         hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), patch_bytes, s, x, y, dy, dx, H, W, C, Ho, Wo, ks,
                            0.f, tw, th * tw);
     } else if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && B <= 65535 && (long long)H * W * C < (1LL << 30)) {
