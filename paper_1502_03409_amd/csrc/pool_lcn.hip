@@ -411,6 +411,99 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
     }
 }
 
+// Forward pass for C = 4*LPP channels with LPP in {2, 4, 8}: a pixel is exactly one float4 per lane of its group,
+// so the tile's own pixels are loaded once, in phase 1, and stay in registers for phase 3; only the halo ring is
+// read a second time by the neighbouring tiles.  (The backward pass would keep twice the registers and measured
+// slower this way than re-reading the tile.)
+template <int LPP>
+__global__ __launch_bounds__(256) void lcn_fwd_cached_kernel(const float *__restrict__ x, float *__restrict__ out,
+                                                             float *__restrict__ mu, float *__restrict__ rstd, int H,
+                                                             int W, int ks, float eps, GaussTaps taps, int tiles_w,
+                                                             int tiles_per_img) {
+    constexpr int C = 4 * LPP, NG = 256 / LPP, NI = LPP;   // NG pixel groups; NI passes cover the 256 tile pixels
+    __shared__ float m1[kLcnHalo * kLcnHalo], m2[kLcnHalo * kLcnHalo];
+    __shared__ float t1[kLcnTile * kLcnTile], t2[kLcnTile * kLcnTile];
+    const int r = (ks - 1) / 2, halo = kLcnTile + 2 * r;
+    const int tid = threadIdx.x, grp = tid / LPP, gl = tid % LPP;
+    const int b = blockIdx.x / tiles_per_img, tile = blockIdx.x - b * tiles_per_img;
+    const int ti = (tile / tiles_w) * kLcnTile, tj = (tile % tiles_w) * kLcnTile;
+    const size_t img = (size_t)b * H * W;
+
+    // one halo pixel's channel sums -> the two maps of phase 2 (lane 0 of the group writes)
+    auto put = [&](int hp, const float4 &v) {
+        const float a = group_sum((v.x + v.y) + (v.z + v.w), LPP);
+        const float c2 = group_sum((v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w), LPP);
+        if (gl == 0) {
+            m1[hp] = a;
+            m2[hp] = c2;
+        }
+    };
+
+    // phase 1a: the tile's own pixels, kept in registers (zeros outside the image)
+    float4 xv[NI];
+    bool inv[NI];
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        const int op = grp + it * NG, oi = op / kLcnTile, oj = op % kLcnTile;
+        const int row = ti + oi, col = tj + oj;
+        inv[it] = row < H && col < W;
+        xv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (inv[it]) xv[it] = *(const float4 *)(x + (img + (size_t)row * W + col) * C + gl * 4);
+    }
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        const int op = grp + it * NG, oi = op / kLcnTile, oj = op % kLcnTile;
+        put((oi + r) * halo + oj + r, xv[it]);
+    }
+    // phase 1b: the halo ring around the tile
+    for (int hp = grp; hp < halo * halo; hp += NG) {
+        const int hi = hp / halo, hj = hp - hi * halo;
+        if (hi >= r && hi < r + kLcnTile && hj >= r && hj < r + kLcnTile) continue;   // uniform over the group
+        const int row = ti - r + hi, col = tj - r + hj;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row >= 0 && row < H && col >= 0 && col < W) v = *(const float4 *)(x + (img + (size_t)row * W + col) * C + gl * 4);
+        put(hp, v);
+    }
+    __syncthreads();
+
+    // phase 2: window sums and statistics, one thread per output pixel
+    {
+        const int oi = tid / kLcnTile, oj = tid % kLcnTile;
+        const int row = ti + oi, col = tj + oj;
+        if (row < H && col < W) {
+            float s1 = 0.f, s2 = 0.f;
+            for (int p = 0; p < ks; ++p)
+                for (int q = 0; q < ks; ++q) {
+                    const float wt = taps.g[p] * taps.g[q];
+                    const int hp = (oi + p) * halo + oj + q;
+                    s1 += wt * m1[hp];   // out-of-image halo entries are zero
+                    s2 += wt * m2[hp];
+                }
+            const float z = tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r) * (float)C;
+            const float m = s1 / z, q2 = s2 / z;
+            const float var = fmaxf(q2 - m * m, 0.f);
+            const float rs = 1.0f / sqrtf(var + eps);
+            const size_t pix = img + (size_t)row * W + col;
+            mu[pix] = m;
+            rstd[pix] = rs;
+            t1[tid] = m;
+            t2[tid] = rs;
+        }
+    }
+    __syncthreads();
+
+    // phase 3: normalise the registers of phase 1a
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        if (!inv[it]) continue;
+        const int op = grp + it * NG, oi = op / kLcnTile, oj = op % kLcnTile;
+        const size_t pix = img + (size_t)(ti + oi) * W + tj + oj;
+        const float u = t1[op], v = t2[op];
+        const float4 xq = xv[it];
+        *(float4 *)(out + pix * C + gl * 4) = make_float4((xq.x - u) * v, (xq.y - u) * v, (xq.z - u) * v, (xq.w - u) * v);
+    }
+}
+
 namespace {
 
 int grid_for(long long total) {
@@ -510,8 +603,15 @@ int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu,
 #define LC_LCN(VEC_, MODE_)                                                                                       \
     hipLaunchKernelGGL((lcn_kernel<VEC_, MODE_>), grid, block, 0, s, x, dy, out, mu, rstd, H, W, C, ks, eps, taps, \
                        lpp, tiles_w, tiles_h * tiles_w)
-    if (mode == 0) { if (vec == 4) LC_LCN(4, 0); else LC_LCN(1, 0); }
-    else           { if (vec == 4) LC_LCN(4, 1); else LC_LCN(1, 1); }
+#define LC_LCN_CACHED(LPP_)                                                                                    \
+    hipLaunchKernelGGL((lcn_fwd_cached_kernel<LPP_>), grid, block, 0, s, x, out, mu, rstd, H, W, ks, eps, taps, \
+                       tiles_w, tiles_h * tiles_w)
+    if (mode == 0 && C == 32) LC_LCN_CACHED(8);
+    else if (mode == 0 && C == 16) LC_LCN_CACHED(4);
+    else if (mode == 0 && C == 8) LC_LCN_CACHED(2);
+    else if (mode == 0) { if (vec == 4) LC_LCN(4, 0); else LC_LCN(1, 0); }
+    else                { if (vec == 4) LC_LCN(4, 1); else LC_LCN(1, 1); }
+#undef LC_LCN_CACHED
 #undef LC_LCN
     LC_HIP_LAUNCH_CHECK("lcn launch");
     return LC_OK;
