@@ -297,6 +297,12 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
         const int row = ti - r + hi, col = tj - r + hj;
         float a = 0.f, c2 = 0.f;
         const bool in = row >= 0 && row < H && col >= 0 && col < W;
+        // backward: the pixel's own statistics are fetched with its values, not after the reduction
+        float mp = 0.f, rsp = 0.f;
+        if (MODE == 1 && in) {
+            mp = mu[img + (size_t)row * W + col];
+            rsp = rstd[img + (size_t)row * W + col];
+        }
         if (in) {
             const size_t pix = img + (size_t)row * W + col;
             const float *xp = x + pix * C;
@@ -313,7 +319,6 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
                 }
             } else {
                 const float *gp = dy + pix * C;
-                const float mp = mu[pix];
                 for (int cv = gl; cv < CV; cv += lpp) {
                     if (VEC == 4) {
                         const float4 v = *(const float4 *)(xp + cv * 4), d = *(const float4 *)(gp + cv * 4);
@@ -337,11 +342,9 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
                 // transposed window sums need
                 float p1 = 0.f, p2 = 0.f;
                 if (in) {
-                    const size_t pix = img + (size_t)row * W + col;
-                    const float rs = rstd[pix], mp = mu[pix];
                     const float z = tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r) * (float)C;
-                    const float bc = rs * rs * rs * c2;
-                    p1 = (bc * mp - rs * a) / z;
+                    const float bc = rsp * rsp * rsp * c2;
+                    p1 = (bc * mp - rsp * a) / z;
                     p2 = bc / z;
                 }
                 m1[hp] = p1;
