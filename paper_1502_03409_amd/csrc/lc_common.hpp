@@ -78,6 +78,10 @@ int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx
 // mode 0: forward (out = y; mu, rstd written).  mode 1: backward (out = dx; mu, rstd read).
 int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
                int C, int ks, float sigma, float eps, hipStream_t s);
+// wide layers (128-filter blocks): workgroup-tiled forward; LC_EUNSUPPORTED outside forward_wide_supported()
+bool forward_wide_supported(const Geom &g);
+int launch_forward_wide_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                            const float *alpha_dev, float *y, hipStream_t s);
 // bf16 operands (raw 16-bit patterns), fp32 results; LC_EUNSUPPORTED for shapes outside the aligned set
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s);
