@@ -387,11 +387,13 @@ int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, flo
             LC_BD(2, 3, 1);
         } else if (ap == 3) {
             if (ntt <= 2) LC_BD(3, 2, 4);
-            if (ntt <= 4) LC_BD(3, 4, 4);
+            if (ntt == 3) LC_BD(3, 3, 4);
+            if (ntt == 4) LC_BD(3, 4, 4);
             LC_BD(3, 4, 2);
         } else if (ap == 4) {
             if (ntt <= 2) LC_BD(4, 2, 4);
-            if (ntt <= 4) LC_BD(4, 4, 4);
+            if (ntt == 3) LC_BD(4, 3, 4);
+            if (ntt == 4) LC_BD(4, 4, 4);
             LC_BD(4, 4, 2);
         } else if (ap == 5) {
             if (ntt <= 3) LC_BD(5, 3, 4);

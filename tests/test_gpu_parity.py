@@ -65,6 +65,8 @@ SMALL = {
     "bd_ap8": (wl.LCGeom(B=80, H=40, W=44, C=3, R=16, S=2, F=16), "pink"),           # 64 fields per cell, eight cells per workgroup
     "wide_f256": (wl.LCGeom(B=150, H=10, W=12, C=16, R=4, S=2, F=256), "halfnormal"),  # workgroup-tiled forward, ragged batch tile
     "wide_bd_c64": (wl.LCGeom(B=80, H=11, W=13, C=64, R=4, S=2, F=64), "halfnormal"),  # workgroup-tiled backward data, uncovered edge
+    "bd_ap4_n48": (wl.LCGeom(B=72, H=28, W=32, C=3, R=16, S=4, F=32), "pink"),       # 4x4 covering fields, 48-value cells
+    "bd_ap3_n48": (wl.LCGeom(B=72, H=20, W=24, C=3, R=12, S=4, F=16), "pink"),       # 3x3 covering fields
     "single_img": (wl.LCGeom(B=1, H=9, W=9, C=2, R=3, S=3, F=5), "gaussian"),
 }
 
