@@ -484,13 +484,13 @@ int launch_forward_f32(const Geom &g, const float *x, const float *w, const floa
         int rc = LC_OK;
         // 128 images x 64 filters per wave would need 128 accumulator registers and leave room for one wave
         // per SIMD only: wide layers take the 64-image tile (two waves per SIMD; the second batch tile of a
-        // strip finds the weights in L2).  A layer too small to give every CU a workgroup at that tile size
-        // steps down to smaller wave tiles until it does.
+        // strip finds the weights in L2).  A layer too small to fill one round of two workgroups per CU at that
+        // tile size steps down to smaller wave tiles until it does: finer workgroups spread evenly over the CUs.
         int mt = g.B > 64 && g.F % 64 != 0 ? 8 : g.B > 32 ? 4 : 2, nt = 4;
 #if defined(LC_FWD_FORCE_MT)
         mt = LC_FWD_FORCE_MT; nt = LC_FWD_FORCE_NT;
 #else
-        while (fast_workgroups(g, mt, nt) < kComputeUnits && (mt > 2 || nt > 1)) {
+        while (fast_workgroups(g, mt, nt) < kComputeUnits * kBigTilesPerCu && (mt > 2 || nt > 1)) {
             if (nt > 1 && (nt >= mt || mt == 2)) nt >>= 1; else mt >>= 1;
         }
 #endif
