@@ -288,7 +288,8 @@ def bench_others(lc, wl, torch, iters):
     tensors of the workload's shape; parity at these shapes is the tests' business), HIP events on the
     launch stream.  bf16 lines also give the time the mandatory HBM traffic would take at 8 TB/s."""
     stream = torch.cuda.current_stream()
-    shapes = [("cfg2", wl.CONFIG_GEOM["cfg2"], "f32"), ("cfg4", wl.CONFIG_GEOM["cfg4"], "f32"),
+    shapes = [("cfg2", wl.CONFIG_GEOM["cfg2"], "f32"), ("cfg2", wl.CONFIG_GEOM["cfg2"], "bf16"),
+              ("cfg4", wl.CONFIG_GEOM["cfg4"], "f32"),
               ("cfg4", wl.CONFIG_GEOM["cfg4"], "bf16"), ("paper_layer1", wl.PAPER_LAYER1, "f32"), ("paper_layer3_dense", wl.PAPER_LAYER3, "f32")]
     res = {}
     for name, g, dt in shapes:

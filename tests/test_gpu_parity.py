@@ -147,6 +147,7 @@ BF16_CASES = {
     "small": (wl.LCGeom(B=32, H=12, W=14, C=8, R=4, S=2, F=64), "halfnormal"),
     "two_fblocks": (wl.LCGeom(B=48, H=10, W=10, C=16, R=6, S=2, F=128), "halfnormal"),
     "cfg4_quarter": (wl.LCGeom(B=144, H=20, W=22, C=32, R=8, S=2, F=128), "halfnormal"),
+    "cfg2": (wl.CONFIG_GEOM["cfg2"], "pink"),                                          # workload cfg2 with bf16 operands
     "tiled_b80": (wl.LCGeom(B=80, H=12, W=14, C=16, R=4, S=2, F=128), "halfnormal"),   # 128-image tiles, ragged
     "tiled_bd_c64": (wl.LCGeom(B=80, H=11, W=13, C=64, R=4, S=2, F=64), "halfnormal"),  # two cell blocks, uncovered edge
     "tiled_f256": (wl.LCGeom(B=272, H=10, W=10, C=16, R=4, S=2, F=256), "halfnormal"), # two filter blocks, two batch tiles
