@@ -18,7 +18,9 @@
  *    rows/columns that no field covers are ignored by the forward pass and receive zero
  *    from lc_backward_data).
  *  - `dtype` names the storage type of the x / w / dy operands: LC_F32, or LC_BF16 (bf16
- *    operands, fp32 accumulation).  Outputs are always fp32.
+ *    operands, fp32 accumulation).  Outputs are always fp32.  LC_BF16 covers the aligned
+ *    shapes R*C % 16 == 0, S*C % 4 == 0, W*C % 4 == 0, F % 64 == 0, B % 16 == 0, R % S == 0
+ *    (LC_EUNSUPPORTED otherwise, returned before anything is launched).
  *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    only enqueue work; none synchronises.  Arguments are validated on the host before
  *    anything is launched, so every error except LC_EHIP is returned without touching
