@@ -57,16 +57,6 @@ __global__ __launch_bounds__(256) void sae_residual_kernel(float *__restrict__ x
     if (threadIdx.x == 0) part[blockIdx.y * gridDim.x + blockIdx.x] = t;
 }
 
-// b -= lr * sum over chunks of dbp (fixed order: deterministic)
-__global__ __launch_bounds__(256) void sae_bias_kernel(float *__restrict__ b, const float *__restrict__ dbp, int img,
-                                                       int nchunk, float lr) {
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= img) return;
-    float s = 0.f;
-    for (int c = 0; c < nchunk; ++c) s += dbp[(size_t)c * img + e];
-    b[e] -= lr * s;
-}
-
 // Same pass for images whose element count is not a multiple of 4: one thread per image element, looping
 // over the whole batch; b is updated in place.
 __global__ __launch_bounds__(256) void sae_residual_scalar_kernel(float *__restrict__ xh_u,
@@ -113,12 +103,23 @@ __global__ __launch_bounds__(256) void sae_sparsity_kernel(const float *__restri
     if (threadIdx.x == 0) { part_s[blockIdx.x] = t0; part_hg[blockIdx.x] = t1; }
 }
 
-// cost = (sum r^2 + lambda sum s) / B;  optionally alpha -= lr * (sum h*gh) / alpha   (d h / d alpha = h / alpha)
+// Last kernel of a step.  Block 0: cost = (sum r^2 + lambda sum s) / B and optionally
+// alpha -= lr * (sum h*gh) / alpha (d h / d alpha = h / alpha).  Blocks 1..: b -= lr * sum over the batch chunks
+// of dbp, in a fixed order (deterministic); b is not read any more after the residual pass.
 __global__ __launch_bounds__(256) void sae_finalize_kernel(const float *__restrict__ part_r, int n_r,
                                                            const float *__restrict__ part_s,
                                                            const float *__restrict__ part_hg, int n_s, float lambda,
                                                            int B, float lr, int learn_alpha, float *alpha_dev,
-                                                           float *__restrict__ cost_out) {
+                                                           float *__restrict__ cost_out, float *__restrict__ bias,
+                                                           const float *__restrict__ dbp, int img, int nchunk) {
+    if (blockIdx.x > 0) {
+        const int e = (blockIdx.x - 1) * 256 + threadIdx.x;
+        if (e >= img) return;
+        float s = 0.f;
+        for (int c = 0; c < nchunk; ++c) s += dbp[(size_t)c * img + e];
+        bias[e] -= lr * s;
+        return;
+    }
     __shared__ float sh[4];
     float a = 0.f, b = 0.f, c = 0.f;
     for (int i = threadIdx.x; i < n_r; i += 256) a += part_r[i];
@@ -188,15 +189,14 @@ int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *al
     int rc;
     if ((rc = launch_forward_f32(g, x, w, nullptr, 1.f, alpha, h, s)) != LC_OK) return rc;
     if ((rc = launch_backward_data_f32(g, h, w, u, s)) != LC_OK) return rc;
-    int n_r;
+    int n_r, bias_chunks = 0;     // bias_chunks > 0: the b update waits for the finalize kernel
     if ((img & 3) == 0 && (img / 4 + 255) / 256 * kBatchChunks <= kPartialsMax) {
         const int img4 = img / 4, gx = (img4 + 255) / 256;
         const int nchunk = g.B < kBatchChunks ? g.B : kBatchChunks, bchunk = (g.B + nchunk - 1) / nchunk;
         const int gy = (g.B + bchunk - 1) / bchunk;
         hipLaunchKernelGGL(sae_residual_kernel, dim3(gx, gy), dim3(256), 0, s, u, x, b, g.B, img4, bchunk, dbp, part_r);
         LC_HIP_LAUNCH_CHECK("sae_step residual launch");
-        hipLaunchKernelGGL(sae_bias_kernel, dim3((img + 255) / 256), dim3(256), 0, s, b, dbp, img, gy, lr);
-        LC_HIP_LAUNCH_CHECK("sae_step bias launch");
+        bias_chunks = gy;
         n_r = gx * gy;
     } else {
         n_r = (int)((img + 255) / 256 < kPartials ? (img + 255) / 256 : kPartials);
@@ -214,8 +214,10 @@ int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *al
         hipLaunchKernelGGL(sae_project_kernel, dim3(g.L), dim3(256), g.F * sizeof(float), s, w, g.K, g.F);
         LC_HIP_LAUNCH_CHECK("sae_step projection launch");
     }
-    hipLaunchKernelGGL(sae_finalize_kernel, dim3(1), dim3(256), 0, s, part_r, n_r, part_s, part_hg, n_s, lambda, g.B,
-                       lr, (flags & LC_SAE_LEARN_ALPHA) ? 1 : 0, alpha, cost_out);
+    const int bias_blocks = bias_chunks > 0 ? (int)((img + 255) / 256) : 0;
+    hipLaunchKernelGGL(sae_finalize_kernel, dim3(1 + bias_blocks), dim3(256), 0, s, part_r, n_r, part_s, part_hg, n_s,
+                       lambda, g.B, lr, (flags & LC_SAE_LEARN_ALPHA) ? 1 : 0, alpha, cost_out, b, dbp, (int)img,
+                       bias_chunks);
     LC_HIP_LAUNCH_CHECK("sae_step finalize launch");
     return LC_OK;
 }
