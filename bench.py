@@ -301,7 +301,9 @@ def bench_others(lc, wl, torch, iters):
         code = lc.LC_F32
         if dt == "bf16":
             x, w, dy, code = x.bfloat16(), w.bfloat16(), dy.bfloat16(), lc.LC_BF16
-        fns = {"lc_forward": lambda: lc.lc_forward(G, x, w, None, 1.0, y, code),
+        nws = lc.workspace_bytes(G, lc.LC_OP_FORWARD, code)      # optional: layers with very few fields
+        ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+        fns = {"lc_forward": lambda: lc.lc_forward(G, x, w, None, 1.0, y, code, ws),
                "lc_backward_data": lambda: lc.lc_backward_data(G, dy, w, dx, code),
                "lc_backward_weights": lambda: lc.lc_backward_weights(G, x, dy, 0.0, dw, code)}
         esz = 2 if dt == "bf16" else 4

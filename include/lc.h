@@ -65,13 +65,18 @@ enum lc_op { LC_OP_FORWARD = 0, LC_OP_BACKWARD_DATA = 1, LC_OP_BACKWARD_WEIGHTS 
 /* Host only.  Writes LH, LW, K = R*R*C (any of the three may be NULL).  LC_EINVAL on bad geometry. */
 int lc_geom_derive(const lc_geom_t *g, int32_t *LH, int32_t *LW, int32_t *K);
 
-/* Host only.  Bytes of scratch the given lc_op needs for this geometry and dtype (0 = none,
- * then ws may be NULL).  Returns 0 for invalid arguments as well. */
+/* Host only.  Bytes of scratch the given lc_op uses for this geometry and dtype (0 = none,
+ * then ws may be NULL).  Returns 0 for invalid arguments as well.  LC_OP_SAE_STEP requires its
+ * workspace (LC_EWORKSPACE otherwise).  For LC_OP_FORWARD the workspace is optional: a layer with
+ * very few fields (the dense last layer of Sec. 3.1 is the one-field case R = H = W) reports a
+ * size here, and lc_forward given at least that much cuts the contraction into slices that run
+ * side by side; without it the call computes the same result with less of the chip. */
 size_t lc_workspace_bytes(const lc_geom_t *g, int op, int dtype);
 
 /* Forward encoding of one layer, the "alpha W x" of Eq. 1 with the geometry of Sec. 3.1:
  *   y[b,i,j,f] = alpha * sum_k w[i,j,k,f] * x[b, i*S+kh, j*S+kw, c]  (+ bias[i,j,f] if bias != NULL)
- * x [B,H,W,C] and w [LH,LW,K,F] in `dtype`; bias [LH,LW,F] fp32 or NULL; y [B,LH,LW,F] fp32, overwritten. */
+ * x [B,H,W,C] and w [LH,LW,K,F] in `dtype`; bias [LH,LW,F] fp32 or NULL; y [B,LH,LW,F] fp32, overwritten.
+ * ws: optional, see lc_workspace_bytes; its contents are clobbered; must be 16-byte aligned if given. */
 int lc_forward(const lc_geom_t *g, const void *x, const void *w, const float *bias, float alpha, float *y,
                int dtype, void *ws, size_t ws_bytes, void *hip_stream);
 

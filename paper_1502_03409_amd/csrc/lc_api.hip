@@ -65,6 +65,7 @@ size_t lc_workspace_bytes(const lc_geom_t *g, int op, int dtype) {
     if (!make_geom(g, &q)) return 0;
     if (dtype != LC_F32 && dtype != LC_BF16) return 0;
     if (op == LC_OP_SAE_STEP) return sae_workspace_bytes(q);
+    if (op == LC_OP_FORWARD && dtype == LC_F32) return forward_wide_workspace_bytes(q);
     return 0;
 }
 
@@ -72,14 +73,15 @@ const char *lc_last_error(void) { return g_err; }
 
 int lc_forward(const lc_geom_t *g, const void *x, const void *w, const float *bias, float alpha, float *y, int dtype,
                void *ws, size_t ws_bytes, void *hip_stream) {
-    (void)ws; (void)ws_bytes;
     Geom q;
     if (!make_geom(g, &q)) return LC_EINVAL;
     if (dtype != LC_F32 && dtype != LC_BF16) return LC_EINVAL;
     LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(w); LC_REQUIRE_PTR(y);
+    LC_REQUIRE_ALIGNED(ws);
     LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(w); LC_REQUIRE_ALIGNED(y); LC_REQUIRE_ALIGNED(bias);
     if (dtype == LC_BF16) return launch_forward_bf16(q, x, w, bias, alpha, y, (hipStream_t)hip_stream);
-    return launch_forward_f32(q, (const float *)x, (const float *)w, bias, alpha, nullptr, y, (hipStream_t)hip_stream);
+    return launch_forward_f32(q, (const float *)x, (const float *)w, bias, alpha, nullptr, y, (hipStream_t)hip_stream, ws,
+                              ws_bytes);
 }
 
 int lc_backward_data(const lc_geom_t *g, const void *dy, const void *w, float *dx, int dtype, void *ws,

@@ -71,7 +71,7 @@ int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where);
 // kernels' host launchers (one per translation unit)
 // alpha_dev (nullable): device scalar that overrides alpha
 int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
-                       const float *alpha_dev, float *y, hipStream_t s);
+                       const float *alpha_dev, float *y, hipStream_t s, void *ws = nullptr, size_t ws_bytes = 0);
 int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int ks, int st, float eps, hipStream_t s);
 int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int B, int H, int W, int C, int ks,
                       int st, hipStream_t s);
@@ -80,8 +80,9 @@ int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu,
                int C, int ks, float sigma, float eps, hipStream_t s);
 // wide layers (128-filter blocks): workgroup-tiled forward; LC_EUNSUPPORTED outside forward_wide_supported()
 bool forward_wide_supported(const Geom &g);
+size_t forward_wide_workspace_bytes(const Geom &g);   // optional workspace: K-slices for layers with few fields
 int launch_forward_wide_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
-                            const float *alpha_dev, float *y, hipStream_t s);
+                            const float *alpha_dev, float *y, void *ws, size_t ws_bytes, hipStream_t s);
 // cells of 128-value blocks: workgroup-tiled backward data; LC_EUNSUPPORTED outside backward_data_wide_supported()
 bool backward_data_wide_supported(const Geom &g);
 int launch_backward_data_wide_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s);

@@ -472,11 +472,11 @@ long long fast_workgroups(const Geom &g, int mt, int nt) {
 }  // namespace
 
 int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
-                       const float *alpha_dev, float *y, hipStream_t s) {
+                       const float *alpha_dev, float *y, hipStream_t s, void *ws, size_t ws_bytes) {
     // aligned shapes take the pipelined kernel: patch rows that are whole dwordx4 runs, strips that start on a
     // 16-byte boundary (4 fields x S x C floats, or 2 when 128 filters are split over the waves)
     // layers with 128-filter blocks: one field per workgroup, patches through LDS, 128 x 128 output tiles
-    if (forward_wide_supported(g)) return launch_forward_wide_f32(g, x, w, bias, alpha, alpha_dev, y, s);
+    if (forward_wide_supported(g)) return launch_forward_wide_f32(g, x, w, bias, alpha, alpha_dev, y, ws, ws_bytes, s);
     const int nloc = g.F % 128 == 0 ? 2 : 4;
     const bool aligned = g.RC % 4 == 0 && (nloc * g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.K / 4 >= 16;
     if (aligned && g.B > 16) {

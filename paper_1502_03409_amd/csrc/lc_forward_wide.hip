@@ -1,4 +1,4 @@
-// lc_forward for wide layers (F a multiple of 128, patch rows that split into chunks of 32 values): Eq. 1's
+// lc_forward for wide layers (F a multiple of 128, patch rows that split into chunks of 32 or 16 values): Eq. 1's
 // encoder term with a workgroup tile of one field x 128 filters x 32*MT images.
 //
 // The four waves form a 2 x 2 grid (16*MT images x 64 filters each).  The field's patch rows reach the waves
@@ -7,6 +7,8 @@
 // serves the second.  A chunk is two groups of 16 indices: lane (m, kk) reads indices 4kk..4kk+3 of a group as
 // one 16-byte LDS read and uses component t in MFMA step t, and lane (n, kk) loads the weight rows 4kk+t at
 // filters 4n..4n+3 (16 lanes cover 256 contiguous bytes), which makes column n of filter tile u filter 4n+u.
+#include <algorithm>
+
 #include "lc_common.hpp"
 
 namespace lc {
@@ -16,18 +18,25 @@ namespace {
 typedef const __attribute__((address_space(1))) f32x4 *g4_ptr;
 typedef const __attribute__((address_space(1))) float *gf_ptr;
 
-constexpr int kChunk = 32;          // contraction indices per LDS chunk
-constexpr int kRowFloats = 36;      // 32 floats of a chunk + 4: eight rows' 16-byte reads cover all banks
-
-template <int MT, int PD>
+// KCH = contraction indices per LDS chunk (32, or 16 for patch rows that are only a multiple of 16): KCH*4
+// contiguous bytes per image, rows padded by 16 bytes so that eight rows' 16-byte reads cover all banks.
+//
+// A layer with few fields (the dense last layer of Sec. 3.1 is a single one) gives too few workgroups; its
+// contraction is then cut into `nslices` ranges of chunks, each range a workgroup of its own that writes a partial
+// result into the caller's workspace, and a second kernel adds the slices in a fixed order and applies alpha and
+// the bias.
+template <int MT, int PD, int KCH>
 __global__ __launch_bounds__(256, 2) void lc_forward_wide_kernel(Geom g, const float *__restrict__ x,
                                                                  const float *__restrict__ w,
                                                                  const float *__restrict__ bias, float alpha,
                                                                  const float *__restrict__ alpha_dev,
-                                                                 float *__restrict__ y, int fblocks, int btiles) {
+                                                                 float *__restrict__ y, float *__restrict__ partial,
+                                                                 int fblocks, int btiles, int nslices) {
     static_assert(PD == 1 || PD == 2, "one or two chunks of lookahead");
-    constexpr int BT = 32 * MT, NS = MT;          // NS: 16-byte staging slots per thread and chunk
-    constexpr int BUF = BT * kRowFloats;
+    constexpr int ROWF = KCH + 4, SEGS = KCH / 4, SR = 256 / SEGS, GPC = KCH / 16;
+    constexpr int BT = 32 * MT, NS = BT / SR;     // NS: 16-byte staging slots per thread and chunk
+    constexpr int BUF = BT * ROWF;
+    static_assert(NS >= 1, "batch tile too small for the staging map");
     extern __shared__ __attribute__((aligned(16))) float xs[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kk = lane >> 4;
@@ -36,11 +45,17 @@ __global__ __launch_bounds__(256, 2) void lc_forward_wide_kernel(Geom g, const f
     int t_id = remap_xcd(blockIdx.x, gridDim.x);
     const int bt = t_id % btiles;
     t_id /= btiles;
-    const int fb = t_id % fblocks, loc = t_id / fblocks;
+    const int fb = t_id % fblocks;
+    t_id /= fblocks;
+    const int loc = t_id % g.L, slice = t_id / g.L;
     const int i = loc / g.LW, j = loc - i * g.LW;
     const int b0 = bt * BT, f0 = fb * 128 + wn * 64;
     const int WC = g.W * g.C;
-    const int cpr = g.RC / kChunk, nchunks = g.R * cpr;
+    const int cpr = g.RC / KCH, nchunks_all = g.R * cpr;
+    // this workgroup's range of chunks
+    const int c_lo = (int)((long long)nchunks_all * slice / nslices);
+    const int c_hi = (int)((long long)nchunks_all * (slice + 1) / nslices);
+    const int nchunks = c_hi - c_lo;
 
     f32x4 acc[MT][4];
 #pragma unroll
@@ -48,77 +63,82 @@ __global__ __launch_bounds__(256, 2) void lc_forward_wide_kernel(Geom g, const f
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc[mt][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // staging: slot s moves 16 bytes (segment tid&7) of image (tid>>3) + 32 s; images beyond the batch
+    // staging: slot s moves 16 bytes (segment tid % SEGS) of image tid / SEGS + SR s; images beyond the batch
     // repeat image B-1 and their results are never stored
-    const int seg = tid & 7, brow = tid >> 3;
+    const int seg = tid % SEGS, brow = tid / SEGS;
     int xoff[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-        const int b = min(b0 + brow + 32 * s, g.B - 1);
+        const int b = min(b0 + brow + SR * s, g.B - 1);
         xoff[s] = (b * g.H + i * g.S) * WC + j * g.S * g.C + seg * 4;
     }
-    auto stage_load = [&](int c, f32x4 (&st)[NS]) {
-        const int kh = c / cpr;
-        const int o = kh * WC + (c - kh * cpr) * kChunk;
+    auto stage_load = [&](int c, f32x4 (&st)[NS]) {          // c: chunk index relative to c_lo
+        const int ca = c_lo + min(c, nchunks - 1), kh = ca / cpr;
+        const int o = kh * WC + (ca - kh * cpr) * KCH;
 #pragma unroll
         for (int s = 0; s < NS; ++s) st[s] = *(g4_ptr)((gf_ptr)x + xoff[s] + o);
     };
     auto stage_store = [&](int buf, const f32x4 (&st)[NS]) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s) *(f32x4 *)(xs + buf * BUF + (brow + 32 * s) * kRowFloats + seg * 4) = st[s];
+        for (int s = 0; s < NS; ++s) *(f32x4 *)(xs + buf * BUF + (brow + SR * s) * ROWF + seg * 4) = st[s];
     };
     // filters: the chunks tile k contiguously; group q covers rows 16q .. 16q+15 of the field's K x F matrix
     gf_ptr wl = (gf_ptr)w + (size_t)loc * g.K * g.F + f0 + 4 * n + (size_t)(4 * kk) * g.F;
-    const int ngroups = 2 * nchunks;
-    auto wload = [&](int q, f32x4 (&r)[4]) {
-        gf_ptr p = wl + (size_t)(16 * min(q, ngroups - 1)) * g.F;
+    const int q_lo = c_lo * GPC, ngroups = nchunks * GPC;
+    auto wload = [&](int q, f32x4 (&r)[4]) {                // q: group index relative to q_lo
+        gf_ptr p = wl + (size_t)(16 * (q_lo + min(q, ngroups - 1))) * g.F;
 #pragma unroll
         for (int t = 0; t < 4; ++t) r[t] = *(g4_ptr)(p + t * g.F);
     };
 
-    f32x4 st[PD][NS];
-    f32x4 wr[2 * PD][4];
+    if (nchunks > 0) {
+        f32x4 st[PD][NS];
+        f32x4 wr[GPC * PD][4];
 #pragma unroll
-    for (int q = 0; q < 2 * PD; ++q) wload(q, wr[q]);
-    stage_load(0, st[0]);
-    stage_store(0, st[0]);
+        for (int q = 0; q < GPC * PD; ++q) wload(q, wr[q]);
+        stage_load(0, st[0]);
+        stage_store(0, st[0]);
 #pragma unroll
-    for (int p = 0; p < PD; ++p) stage_load(min(p + 1, nchunks - 1), st[p]);      // set p: chunk p+1
-    __syncthreads();
-    const int arow = (wm * 16 * MT + n) * kRowFloats + 4 * kk;
-    for (int c0 = 0; c0 < nchunks; c0 += 2) {
+        for (int p = 0; p < PD; ++p) stage_load(p + 1, st[p]);      // set p: chunk p+1
+        __syncthreads();
+        const int arow = (wm * 16 * MT + n) * ROWF + 4 * kk;
+        for (int c0 = 0; c0 < nchunks; c0 += 2) {
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int c = c0 + p;               // chunk c lives in buffer p (c0 is even)
-            const int sp = p % PD;              // register set that holds chunk c+1
-            if (c < nchunks) {
-                const float *ab = xs + p * BUF + arow;
+            for (int p = 0; p < 2; ++p) {
+                const int c = c0 + p;               // chunk c lives in buffer p (c0 is even)
+                const int sp = p % PD;              // register set that holds chunk c+1
+                if (c < nchunks) {
+                    const float *ab = xs + p * BUF + arow;
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    f32x4 bo[4];
+                    for (int h = 0; h < GPC; ++h) {
+                        f32x4 bo[4];
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) bo[t] = wr[2 * sp + h][t];
-                    wload(2 * c + h + 2 * PD, wr[2 * sp + h]);
+                        for (int t = 0; t < 4; ++t) bo[t] = wr[GPC * sp + h][t];
+                        wload(GPC * c + h + GPC * PD, wr[GPC * sp + h]);
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const f32x4 a = *(const f32x4 *)(ab + mt * 16 * kRowFloats + 16 * h);
+                        for (int mt = 0; mt < MT; ++mt) {
+                            const f32x4 a = *(const f32x4 *)(ab + mt * 16 * ROWF + 16 * h);
 #pragma unroll
-                        for (int t = 0; t < 4; ++t)
+                            for (int t = 0; t < 4; ++t)
 #pragma unroll
-                            for (int u = 0; u < 4; ++u) acc[mt][u] = mfma16(a[t], bo[t][u], acc[mt][u]);
+                                for (int u = 0; u < 4; ++u) acc[mt][u] = mfma16(a[t], bo[t][u], acc[mt][u]);
+                        }
                     }
+                    // the other buffer was last read in chunk c-1, which every wave left at the previous barrier
+                    if (c + 1 < nchunks) stage_store(p ^ 1, st[sp]);
+                    if (c + 1 + PD < nchunks) stage_load(c + 1 + PD, st[sp]);
                 }
-                // the other buffer was last read in chunk c-1, which every wave left at the previous barrier
-                if (c + 1 < nchunks) stage_store(p ^ 1, st[sp]);
-                if (c + 1 + PD < nchunks) stage_load(c + 1 + PD, st[sp]);
+                __syncthreads();
             }
-            __syncthreads();
         }
     }
 
-    if (alpha_dev) alpha = *alpha_dev;
+    const bool whole = nslices == 1;
+    if (whole && alpha_dev) alpha = *alpha_dev;
     f32x4 bv = (f32x4){0.f, 0.f, 0.f, 0.f};
-    if (bias) bv = *(const f32x4 *)(bias + (size_t)loc * g.F + f0 + 4 * n);
+    if (whole && bias) bv = *(const f32x4 *)(bias + (size_t)loc * g.F + f0 + 4 * n);
+    float *yo = whole ? y : partial + (size_t)slice * g.B * g.L * g.F;
+    const float sc = whole ? alpha : 1.f;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -127,38 +147,84 @@ __global__ __launch_bounds__(256, 2) void lc_forward_wide_kernel(Geom g, const f
             if (b >= g.B) continue;
             f32x4 o;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) o[u] = alpha * acc[mt][u][rr] + bv[u];
-            *(f32x4 *)(y + ((size_t)b * g.L + loc) * g.F + f0 + 4 * n) = o;
+            for (int u = 0; u < 4; ++u) o[u] = sc * acc[mt][u][rr] + bv[u];
+            *(f32x4 *)(yo + ((size_t)b * g.L + loc) * g.F + f0 + 4 * n) = o;
         }
 }
 
-template <int MT, int PD>
+// y = alpha * (sum of the slices, in order) + bias
+__global__ __launch_bounds__(256) void lc_forward_slices_kernel(const float *__restrict__ partial, int nslices,
+                                                                size_t n4, int LF4, const float *__restrict__ bias,
+                                                                float alpha, const float *__restrict__ alpha_dev,
+                                                                float *__restrict__ y) {
+    if (alpha_dev) alpha = *alpha_dev;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n4; e += (size_t)gridDim.x * 256) {
+        f32x4 s = ((const f32x4 *)partial)[e];
+        for (int k = 1; k < nslices; ++k) s += ((const f32x4 *)partial)[(size_t)k * n4 + e];
+        f32x4 bv = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (bias) bv = ((const f32x4 *)bias)[e % (size_t)LF4];
+        ((f32x4 *)y)[e] = alpha * s + bv;
+    }
+}
+
+int chunk_floats(const Geom &g) { return g.RC % 32 == 0 ? 32 : 16; }
+
+// slices that would give a layer with few fields about two rounds of workgroups; 1 = no split
+int wide_slices(const Geom &g) {
+    const long long wgs = (long long)g.L * (g.F / 128) * ((g.B + 127) / 128);
+    if (wgs >= 256) return 1;
+    const int nchunks = g.R * (g.RC / chunk_floats(g));
+    int ns = (int)((1024 + wgs - 1) / wgs);
+    if (ns > 16) ns = 16;
+    if (ns > nchunks / 8) ns = nchunks / 8;      // keep slices long enough to amortise their pipeline fill
+    return ns < 2 ? 1 : ns;
+}
+
+template <int KCH>
 int launch_wide(const Geom &g, const float *x, const float *w, const float *bias, float alpha, const float *alpha_dev,
-                float *y, hipStream_t s) {
-    constexpr int BT = 32 * MT;
-    const size_t lds = (size_t)2 * BT * kRowFloats * sizeof(float);
-    auto kern = lc_forward_wide_kernel<MT, PD>;
+                float *y, float *partial, int nslices, hipStream_t s) {
+    constexpr int MT = 4, PD = 2, BT = 32 * MT;
+    const size_t lds = (size_t)2 * BT * (KCH + 4) * sizeof(float);
+    auto kern = lc_forward_wide_kernel<MT, PD, KCH>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward (wide): hipFuncSetAttribute")) return rc_lds;
     const int fblocks = g.F / 128, btiles = (g.B + BT - 1) / BT;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(g.L * fblocks * btiles)), dim3(256), lds, s, g, x, w, bias, alpha,
-                       alpha_dev, y, fblocks, btiles);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(g.L * fblocks * btiles * nslices)), dim3(256), lds, s, g, x, w, bias, alpha,
+                       alpha_dev, y, partial, fblocks, btiles, nslices);
     LC_HIP_LAUNCH_CHECK("lc_forward (wide) launch");
+    if (nslices > 1) {
+        const size_t n4 = (size_t)g.B * g.L * g.F / 4;
+        const unsigned blocks = (unsigned)std::min<size_t>((n4 + 255) / 256, 256 * 16);
+        hipLaunchKernelGGL(lc_forward_slices_kernel, dim3(blocks), dim3(256), 0, s, partial, nslices, n4, g.L * g.F / 4,
+                           bias, alpha, alpha_dev, y);
+        LC_HIP_LAUNCH_CHECK("lc_forward (slices) launch");
+    }
     return LC_OK;
 }
 
 }  // namespace
 
+// 128-filter blocks, patch rows that split into chunks of 16 values with 16-byte aligned starts, offsets in 32 bits
 bool forward_wide_supported(const Geom &g) {
-    return g.F % 128 == 0 && g.RC % kChunk == 0 && (g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.B > 64 &&
+    return g.F % 128 == 0 && g.RC % 16 == 0 && (g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.B > 64 &&
            (long long)g.B * g.H * g.W * g.C < (1ll << 31) &&
-           (long long)g.L * (g.F / 128) * ((g.B + 127) / 128) < (1ll << 31);
+           (long long)g.L * (g.F / 128) * ((g.B + 127) / 128) * 16 < (1ll << 31);
+}
+
+// workspace that lets lc_forward cut the contraction of a layer with few fields into slices (0: not needed)
+size_t forward_wide_workspace_bytes(const Geom &g) {
+    if (!forward_wide_supported(g)) return 0;
+    const int ns = wide_slices(g);
+    return ns > 1 ? (size_t)ns * g.B * g.L * g.F * sizeof(float) : 0;
 }
 
 int launch_forward_wide_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
-                            const float *alpha_dev, float *y, hipStream_t s) {
+                            const float *alpha_dev, float *y, void *ws, size_t ws_bytes, hipStream_t s) {
     if (!forward_wide_supported(g)) return LC_EUNSUPPORTED;
     // 128-image tiles measured faster than 256-image ones here (1062 vs 1116 us on 256 x 64x64x32, 128 filters)
-    return launch_wide<4, 2>(g, x, w, bias, alpha, alpha_dev, y, s);
+    int ns = wide_slices(g);
+    if (ns > 1 && (!ws || ws_bytes < forward_wide_workspace_bytes(g))) ns = 1;   // no workspace: one slice
+    if (chunk_floats(g) == 32) return launch_wide<32>(g, x, w, bias, alpha, alpha_dev, y, (float *)ws, ns, s);
+    return launch_wide<16>(g, x, w, bias, alpha, alpha_dev, y, (float *)ws, ns, s);
 }
 
 }  // namespace lc

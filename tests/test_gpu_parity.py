@@ -22,10 +22,19 @@ def host(t):
     return t.cpu().numpy()
 
 
-def run_forward(g, x, w, bias=None, alpha=1.0):
+def forward_workspace(G):
+    """The optional workspace of lc_forward (layers with few fields), NaN-filled, or None."""
+    nbytes = lc.workspace_bytes(G, lc.LC_OP_FORWARD)
+    if nbytes == 0:
+        return None
+    return torch.full((nbytes // 4,), float("nan"), device="cuda").view(torch.uint8)
+
+
+def run_forward(g, x, w, bias=None, alpha=1.0, use_ws=True):
     G = lc.geom(*g.as_tuple())
     y = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
-    lc.lc_forward(G, dev(x), dev(w), None if bias is None else dev(bias), alpha, y)
+    ws = forward_workspace(G) if use_ws else None
+    lc.lc_forward(G, dev(x), dev(w), None if bias is None else dev(bias), alpha, y, lc.LC_F32, ws)
     return host(y)
 
 
@@ -67,6 +76,9 @@ SMALL = {
     "wide_bd_c64": (wl.LCGeom(B=80, H=11, W=13, C=64, R=4, S=2, F=64), "halfnormal"),  # workgroup-tiled backward data, uncovered edge
     "bd_ap4_n48": (wl.LCGeom(B=72, H=28, W=32, C=3, R=16, S=4, F=32), "pink"),       # 4x4 covering fields, 48-value cells
     "bd_ap3_n48": (wl.LCGeom(B=72, H=20, W=24, C=3, R=12, S=4, F=16), "pink"),       # 3x3 covering fields
+    "dense_small": (wl.LCGeom(B=80, H=24, W=24, C=8, R=24, S=1, F=128), "halfnormal"),  # one field: contraction cut into slices
+    "dense_k16": (wl.LCGeom(B=72, H=12, W=12, C=4, R=12, S=1, F=128), "halfnormal"),    # one field, 16-value chunks
+    "wide_k16": (wl.LCGeom(B=72, H=14, W=16, C=4, R=4, S=2, F=128), "halfnormal"),      # 16-value chunks, many fields
     "single_img": (wl.LCGeom(B=1, H=9, W=9, C=2, R=3, S=3, F=5), "gaussian"),
 }
 
@@ -79,7 +91,7 @@ def test_lc_primitives_match_oracle(name):
     t = g.as_tuple()
     y = run_forward(g, x, w, bias, 0.75)
     assert rel_fro(y, oracle.lc_forward(t, x, w, bias, 0.75)) <= TOL
-    y0 = run_forward(g, x, w)
+    y0 = run_forward(g, x, w, use_ws=False)          # without the optional workspace
     assert rel_fro(y0, oracle.lc_forward(t, x, w)) <= TOL
     dx = run_backward_data(g, dy, w)
     ref_dx = oracle.lc_backward_data(t, dy, w)
@@ -114,7 +126,7 @@ def test_lc_primitives_full_size_sampled(name):
     y = torch.empty((g.B, g.LH, g.LW, g.F), device="cuda")
     dx = torch.empty((g.B, g.H, g.W, g.C), device="cuda")
     dw = torch.empty((g.LH, g.LW, g.K, g.F), device="cuda")
-    lc.lc_forward(G, xd, wd, None, 1.0, y)
+    lc.lc_forward(G, xd, wd, None, 1.0, y, lc.LC_F32, forward_workspace(G))
     lc.lc_backward_data(G, dyd, wd, dx)
     lc.lc_backward_weights(G, xd, dyd, 0.0, dw)
     # adjoint identities, evaluated in fp64 on the device results
