@@ -203,9 +203,13 @@ int launch_wide(const Geom &g, const float *x, const float *w, const float *bias
 
 }  // namespace
 
-// 128-filter blocks, patch rows that split into chunks of 16 values with 16-byte aligned starts, offsets in 32 bits
+// 128-filter blocks, patch rows that split into chunks with 16-byte aligned starts, offsets in 32 bits.  Chunks of
+// 32 values always; chunks of 16 only for layers with few fields: with many overlapping fields of few channels
+// (the paper's first layer) the strip-sharing kernel reads the patches far less often and is the faster one.
 bool forward_wide_supported(const Geom &g) {
-    return g.F % 128 == 0 && g.RC % 16 == 0 && (g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.B > 64 &&
+    const bool few_fields = (long long)g.L * (g.F / 128) * ((g.B + 127) / 128) < 256;
+    return g.F % 128 == 0 && (g.RC % 32 == 0 || (g.RC % 16 == 0 && few_fields)) && (g.S * g.C) % 4 == 0 &&
+           (g.W * g.C) % 4 == 0 && g.B > 64 &&
            (long long)g.B * g.H * g.W * g.C < (1ll << 31) &&
            (long long)g.L * (g.F / 128) * ((g.B + 127) / 128) * 16 < (1ll << 31);
 }
