@@ -376,7 +376,8 @@ int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipSt
 
 int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     // cells of 128-value blocks: one cell per workgroup, dy through LDS, 128 x 128 output tiles
-    if (backward_data_wide_supported(g)) return launch_backward_data_wide_f32(g, dy, w, dx, s);
+    if (backward_data_wide_supported(g) || backward_data_dense_supported(g))
+        return launch_backward_data_wide_f32(g, dy, w, dx, s);
     // pipelined kernel: filters in blocks of 16, fields that tile the cells exactly, a batch tile of 64 images
     if (g.F % 16 == 0 && g.R % g.S == 0 && g.B > 32) {
         const int ap = g.R / g.S, ntt = (g.S * g.S * g.C + 15) / 16;   // steps per chunk, tiles of 16 cell values

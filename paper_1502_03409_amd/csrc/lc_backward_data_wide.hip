@@ -20,7 +20,10 @@ typedef const __attribute__((address_space(1))) float *gf_ptr;
 constexpr int kChunk = 32;          // filters per LDS chunk
 constexpr int kRowFloats = 36;      // 32 floats of a chunk + 4: eight rows' 16-byte reads cover all banks
 
-template <int MT, int PD>
+// DENSE: a layer of one field that covers its whole input (R = H = W, the dense last layer of Sec. 3.1).  Every
+// input value then has the same single covering field, so a "cell" is any block of 128 consecutive values k and
+// dx[b][k] = sum_f w[k][f] dy[b][f].
+template <int MT, int PD, bool DENSE>
 __global__ __launch_bounds__(256, 2) void lc_bwd_data_wide_kernel(Geom g, const float *__restrict__ dy,
                                                                   const float *__restrict__ w,
                                                                   float *__restrict__ dx, int CW, int nblk,
@@ -35,8 +38,8 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_wide_kernel(Geom g, const 
     int t_id = remap_xcd(blockIdx.x, gridDim.x);
     const int bt = t_id % btiles;
     t_id /= btiles;
-    const int nb = t_id % nblk, cell = t_id / nblk;
-    const int ri = cell / CW, wi = cell - ri * CW;
+    const int nb = DENSE ? 0 : t_id % nblk, cell = DENSE ? t_id : t_id / nblk;
+    const int ri = DENSE ? 0 : cell / CW, wi = DENSE ? 0 : cell - ri * CW;
     const int b0 = bt * BT;
     const int SC = g.S * g.C, AP = g.R / g.S;
     // fields (ri - a, wi - ap) inside the grid
@@ -84,6 +87,8 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_wide_kernel(Geom g, const 
         const int nn = nb * 128 + wn * 64 + nt * 16 + n;
         const int dr = nn / SC;
         kn[nt] = (dr * g.RC + (nn - dr * SC)) * g.F + 4 * kk;
+        // dense: row k of the only K x F matrix (rows beyond K repeat the last one and are not stored)
+        if (DENSE) kn[nt] = min(cell * 128 + wn * 64 + nt * 16 + n, g.K - 1) * g.F + 4 * kk;
     }
     Cursor wq = {a_lo, p_lo, 0};
     int wh = 0;
@@ -143,8 +148,14 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_wide_kernel(Geom g, const 
         const int nn = nb * 128 + wn * 64 + nt * 16 + n;
         const int dr = nn / SC, rem = nn - dr * SC;
         const int row = ri * g.S + dr, col = wi * g.S + rem / g.C;
-        if (row >= g.H || col >= g.W) continue;
-        const size_t pix = ((size_t)row * g.W + wi * g.S) * g.C + rem;
+        size_t pix = ((size_t)row * g.W + wi * g.S) * g.C + rem;
+        if (DENSE) {
+            const int k = cell * 128 + wn * 64 + nt * 16 + n;
+            if (k >= g.K) continue;
+            pix = (size_t)k;                     // R = H = W: the patch index is the pixel index
+        } else if (row >= g.H || col >= g.W) {
+            continue;
+        }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -155,16 +166,17 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_wide_kernel(Geom g, const 
     }
 }
 
-template <int MT, int PD>
+template <int MT, int PD, bool DENSE>
 int launch_wide(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     constexpr int BT = 32 * MT;
     const size_t lds = (size_t)2 * BT * kRowFloats * sizeof(float);
-    auto kern = lc_bwd_data_wide_kernel<MT, PD>;
+    auto kern = lc_bwd_data_wide_kernel<MT, PD, DENSE>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data (wide): hipFuncSetAttribute"))
         return rc_lds;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
-    const int nblk = g.S * g.S * g.C / 128, btiles = (g.B + BT - 1) / BT;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(CH * CW * nblk * btiles)), dim3(256), lds, s, g, dy, w, dx, CW, nblk,
+    const int nblk = DENSE ? 1 : g.S * g.S * g.C / 128, btiles = (g.B + BT - 1) / BT;
+    const long long cells = DENSE ? (g.K + 127) / 128 : (long long)CH * CW;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(cells * nblk * btiles)), dim3(256), lds, s, g, dy, w, dx, CW, nblk,
                        btiles);
     LC_HIP_LAUNCH_CHECK("lc_backward_data (wide) launch");
     return LC_OK;
@@ -179,9 +191,16 @@ bool backward_data_wide_supported(const Geom &g) {
            cells * (g.S * g.S * g.C / 128) * ((g.B + 127) / 128) < (1ll << 31);
 }
 
+// one field covering the whole input: any K, filters in chunks of 32
+bool backward_data_dense_supported(const Geom &g) {
+    return g.L == 1 && g.R == g.H && g.R == g.W && g.F % kChunk == 0 && g.B > 64 &&
+           (long long)g.B * g.F < (1ll << 31) && (long long)g.K * g.F < (1ll << 31);
+}
+
 int launch_backward_data_wide_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    if (backward_data_dense_supported(g)) return launch_wide<4, 2, true>(g, dy, w, dx, s);
     if (!backward_data_wide_supported(g)) return LC_EUNSUPPORTED;
-    return launch_wide<4, 2>(g, dy, w, dx, s);
+    return launch_wide<4, 2, false>(g, dy, w, dx, s);
 }
 
 }  // namespace lc

@@ -85,6 +85,7 @@ int launch_forward_wide_f32(const Geom &g, const float *x, const float *w, const
                             const float *alpha_dev, float *y, void *ws, size_t ws_bytes, hipStream_t s);
 // cells of 128-value blocks: workgroup-tiled backward data; LC_EUNSUPPORTED outside backward_data_wide_supported()
 bool backward_data_wide_supported(const Geom &g);
+bool backward_data_dense_supported(const Geom &g);   // one field covering the whole input
 int launch_backward_data_wide_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s);
 // bf16 operands (raw 16-bit patterns), fp32 results; LC_EUNSUPPORTED for shapes outside the aligned set
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
