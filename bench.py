@@ -332,6 +332,32 @@ def bench_others(lc, wl, torch, iters):
         res[f"{name}_{dt}"] = entry
         del x, w, dy, y, dx, dw
         torch.cuda.empty_cache()
+
+    # one whole RICA step (Eq. 1) on the paper's first layer: 1.53e9 weights trained in place on one GPU
+    g = wl.PAPER_LAYER1
+    G = lc.geom(*g.as_tuple())
+    x = torch.randn((g.B, g.H, g.W, g.C), device="cuda")
+    w = torch.randn((g.LH, g.LW, g.K, g.F), device="cuda") / g.K ** 0.5
+    b = torch.zeros((g.H, g.W, g.C), device="cuda")
+    a, cost = torch.ones(1, device="cuda"), torch.zeros(1, device="cuda")
+    h = torch.empty((g.B, g.LH, g.LW, g.F), device="cuda")
+    ws = torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda")
+    f = lambda: lc.sae_step(G, x, w, b, a, wl.SAE_LAMBDA, wl.SAE_EPS, wl.SAE_LR, 0, h, cost, ws)
+    for _ in range(2):
+        f()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(iters):
+        f()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    tf = 5 * g.flop_per_pass / (ms * 1e-3) / 1e12
+    res["paper_layer1_sae_step"] = {"ms": round(ms, 3), "images_per_s": round(g.B / (ms * 1e-3), 1),
+                                    "TFLOP/s": round(tf, 1), "frac_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4),
+                                    "shape": dict(zip("BHWCRSF", g.as_tuple()))}
+    del x, w, b, h, ws
+    torch.cuda.empty_cache()
     return res
 
 
