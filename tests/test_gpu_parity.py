@@ -316,6 +316,8 @@ SAE_CASES = {
     "floor": (wl.LCGeom(B=12, H=23, W=23, C=4, R=6, S=2, F=8), "halfnormal"),
     "ragged": (wl.LCGeom(B=7, H=14, W=17, C=3, R=5, S=3, F=10), "gaussian"),
     "stage_like": (wl.LCGeom(B=32, H=32, W=32, C=3, R=16, S=2, F=16), "pink"),
+    "wide": (wl.LCGeom(B=80, H=12, W=14, C=8, R=4, S=2, F=128), "halfnormal"),       # the workgroup-tiled forward inside the step
+    "cells128": (wl.LCGeom(B=72, H=10, W=12, C=32, R=4, S=2, F=32), "halfnormal"),   # the workgroup-tiled backward data inside the step
 }
 
 
