@@ -392,7 +392,18 @@ int launch_fast_tiered(const Geom &g, const float *x, const float *w, const floa
             return launch_fast<2, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, first, ntask - first, s);
         }
     }
-    return launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
+    // 32-image tiles (small layers) are latency-bound: several patch rows per chunk halve the barriers and let
+    // more loads fly at once, as far as the staging registers and the LDS budget allow
+    int nr = 1;
+    if constexpr (MT <= 2) {
+        if (CQ == g.RC) {
+            const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;
+            for (int c : {4, 3, 2})
+                if (g.R % c == 0 && (size_t)16 * MT * c * (sqc / 4) <= (size_t)kFwdStageSlots * 256 &&
+                    (size_t)16 * MT * fast_row_stride(c * sqc) * 4 <= 52 * 1024 && c <= 15) { nr = c; break; }
+        }
+    }
+    return launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, 0, ntask, s);
 }
 
 // Picks the chunk (CQ floats of a patch row, a divisor of RC and multiple of 4*UNR) so that the staged
