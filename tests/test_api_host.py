@@ -47,6 +47,13 @@ def test_workspace_query():
     assert n >= 4 * (2 * 8 * 49 * 16 + 8 * 32 * 32 * 3)
     assert lc.workspace_bytes(lc.geom(0, 1, 1, 1, 1, 1, 1), B.LC_OP_SAE_STEP) == 0
     assert lc.workspace_bytes(g, B.LC_OP_SAE_STEP, 7) == 0
+    # lc_forward's optional workspace: only layers with very few fields ask for one (the dense last layer of
+    # Sec. 3.1 is a single field: up to 16 slices of a [B, L, F] fp32 result)
+    dense = lc.geom(192, 62, 62, 24, 62, 1, 4096)
+    n = lc.workspace_bytes(dense, B.LC_OP_FORWARD)
+    assert n > 0 and n % (4 * 192 * 4096) == 0 and n // (4 * 192 * 4096) <= 16
+    assert lc.workspace_bytes(dense, B.LC_OP_FORWARD, B.LC_BF16) == 0
+    assert lc.workspace_bytes(lc.geom(128, 200, 200, 3, 20, 4, 32), B.LC_OP_FORWARD) == 0
 
 
 def test_argument_validation_happens_before_any_launch():
@@ -60,6 +67,7 @@ def test_argument_validation_happens_before_any_launch():
     assert L.lc_forward(gp, FAKE + 4, FAKE, None, 1.0, FAKE, 0, None, 0, None) == B.LC_EALIGN
     assert L.lc_forward(gp, FAKE, FAKE, FAKE + 8, 1.0, FAKE, 0, None, 0, None) == B.LC_EALIGN
     assert L.lc_forward(gp, FAKE, FAKE, None, 1.0, FAKE, 5, None, 0, None) == B.LC_EINVAL
+    assert L.lc_forward(gp, FAKE, FAKE, None, 1.0, FAKE, 0, FAKE + 4, 64, None) == B.LC_EALIGN   # workspace
     assert L.lc_backward_data(gp, FAKE, None, FAKE, 0, None, 0, None) == B.LC_ENULL
     assert L.lc_backward_data(gp, FAKE, FAKE, FAKE + 2, 0, None, 0, None) == B.LC_EALIGN
     assert L.lc_backward_weights(gp, FAKE, FAKE, 0.5, FAKE, 0, None, 0, None) == B.LC_EINVAL
