@@ -150,9 +150,9 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
 // ---------------------------------------------------------------------------------------------
 // Fast path (F % 16 == 0, R % S == 0).  Same cell-gather decomposition with the pipeline of the forward
 // kernel: a chunk is one field row (a) and 16 filters (fh) of every field the strip of cells touches;
-// the next chunk's dy travels through registers into LDS while the current one is multiplied; the
-// weights of step a'+1 are in flight while step a' runs.  Per step a' a wave multiplies
-// dy[128 images][16 f] of field (ri-a, wi-a') with the S x S x C block of that field's filters:
+// the next chunk's dy travels through registers into the second LDS buffer while the current one is
+// multiplied (one barrier per chunk); the weights of a whole chunk are in flight ahead of their use.
+// Per step a' a wave multiplies dy[16*MT images][16 f] of field (ri-a, wi-a') with the S x S x C block of that field's filters:
 // lane (n,kk) loads w[k(n)][fh*16 + 4kk .. +3] as one dwordx4, and lane (m,kk) reads the same four f
 // of image m from LDS, so component t of both vectors is contraction index 4kk+t of MFMA number t.
 // Fields outside the grid are staged as zeros (their weights are read from a clamped, valid address),
@@ -222,13 +222,13 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
             if (v >= R4) { v -= R4; ++b; }
         }
     };
-    auto stage_store = [&]() {
+    auto stage_store = [&](int buf) {
         int v = v0, b = bq0;
 #pragma unroll
         for (int q = 0; q < NSLOT; ++q) {
             if (b < BT) {
                 // two 8-byte stores: 16-byte LDS stores of a row-major tile run into bank conflicts
-                float *dst = dys + b * RS + v * 4;
+                float *dst = dys + buf * BT * RS + b * RS + v * 4;
                 *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
                 *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
             }
@@ -255,14 +255,16 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = *(g4_ptr)(p0 + kn[nt]);
         }
+        // two LDS buffers: chunk c is read from buffer c & 1 while chunk c+1, whose loads were issued a whole
+        // chunk earlier, goes from the staging registers into the other one; one barrier per chunk
+        const int BUF = BT * RS;
         stage_load(0);
-        const float *arow = dys + m * RS + 4 * kk;
+        stage_store(0);
+        if (nchunks > 1) stage_load(1);
+        __syncthreads();
         for (int c = 0; c < nchunks; ++c) {
-            __syncthreads();
-            stage_store();
-            __syncthreads();
+            const float *arow = dys + (c & 1) * BUF + m * RS + 4 * kk;
             const int cn = c + 1 < nchunks ? c + 1 : c;
-            if (c + 1 < nchunks) stage_load(c + 1);
 #pragma unroll
             for (int ap = 0; ap < AP; ++ap) {
                 const int js = wc - ap + AP - 1;
@@ -283,6 +285,10 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
                 for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = *(g4_ptr)(pn + kn[nt]);
                 __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
             }
+            // the other buffer was last read in chunk c-1, which every wave left at the previous barrier
+            if (c + 1 < nchunks) stage_store((c + 1) & 1);
+            if (c + 2 < nchunks) stage_load(c + 2);
+            __syncthreads();
         }
     }
 
@@ -360,7 +366,7 @@ int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipSt
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int NCV = g.S * g.S * g.C;
     const int RS = ((JW * 16 + 31) / 32) * 32 + 4;
-    const size_t lds = (size_t)BT * RS * sizeof(float);
+    const size_t lds = (size_t)2 * BT * RS * sizeof(float);      // two buffers
     auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP, NW>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
     const int strips = (CW + NCELL - 1) / NCELL;
