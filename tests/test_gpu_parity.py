@@ -432,3 +432,42 @@ def test_lc_primitives_geometry_sweep(idx):
     assert rel_fro(dx, ref_dx) <= TOL
     assert np.all(dx[ref_dx == 0.0] == 0.0)
     assert rel_fro(run_backward_weights(g, x, dy), oracle.lc_backward_weights(t, x, dy)) <= TOL
+
+
+def _bf16_sweep_geometries(n, seed):
+    """Seeded random geometries inside the aligned set the bf16 kernels cover."""
+    r = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        S = int(r.choice([1, 2, 4]))
+        R = S * int(r.integers(1, 5))
+        C = int(r.choice([4, 8, 16, 32, 64]))
+        F = int(r.choice([64, 128, 256]))
+        B = 16 * int(r.integers(1, 18))
+        H, W = R + int(r.integers(0, 12)), R + 4 * int(r.integers(0, 6))
+        g = wl.LCGeom(B=B, H=H, W=W, C=C, R=R, S=S, F=F)
+        if (R * C) % 16 or (S * C) % 4 or (W * C) % 4 or g.flop_per_pass > 1e9 or g.params > 8e6:
+            continue
+        out.append(g)
+    return out
+
+
+@pytest.mark.parametrize("idx", range(14))
+def test_lc_primitives_bf16_geometry_sweep(idx):
+    """bf16 operands against the oracle fed the same rounded values: what is left is fp32 accumulation."""
+    g = _bf16_sweep_geometries(14, seed=77)[idx]
+    print(f"case bf16 sweep {idx} geom {g}", flush=True)
+    x, w, dy = wl.lc_inputs(g, "halfnormal", seed=idx)
+    t = g.as_tuple()
+    G = lc.geom(*t)
+    bf = lambda a: torch.from_numpy(wl.to_bf16_round(a).view(np.int16)).cuda().view(torch.bfloat16)
+    rnd = lambda a: (wl.to_bf16_round(a).astype(np.uint32) << 16).view(np.float32)
+    y = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
+    dx = torch.full((g.B, g.H, g.W, g.C), float("nan"), device="cuda")
+    dw = torch.full((g.LH, g.LW, g.K, g.F), float("nan"), device="cuda")
+    lc.lc_forward(G, bf(x), bf(w), None, 1.0, y, lc.LC_BF16)
+    lc.lc_backward_data(G, bf(dy), bf(w), dx, lc.LC_BF16)
+    lc.lc_backward_weights(G, bf(x), bf(dy), 0.0, dw, lc.LC_BF16)
+    assert rel_fro(host(y), oracle.lc_forward(t, rnd(x), rnd(w))) <= TOL
+    assert rel_fro(host(dx), oracle.lc_backward_data(t, rnd(dy), rnd(w))) <= TOL
+    assert rel_fro(host(dw), oracle.lc_backward_weights(t, rnd(x), rnd(dy))) <= TOL
