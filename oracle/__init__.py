@@ -155,6 +155,32 @@ def lcn_bwd(x, mu, rstd, dy, ks=5, sigma=1.0):
     return dx
 
 
+LCN_PER_CHANNEL, LCN_ZERO_PAD, LCN_TWO_STAGE = 1, 2, 4
+
+
+def lcn_var_fwd(x, ks=5, sigma=1.0, eps=1e-4, flags=0):
+    """LCN variants (flags: 1 per-channel statistics, 2 zero-padded borders, 4 two stages)."""
+    x = _d(x)
+    B, H, W, Cc = x.shape
+    assert ks % 2 == 1 and ks <= 63 and 0 <= flags < 8
+    stat = (B, H, W, Cc) if flags & LCN_PER_CHANNEL else (B, H, W)
+    y, mu, rstd = np.empty_like(x), np.empty(stat), np.empty(stat)
+    _load().orc_lcn_var_fwd(C.c_int(B), C.c_int(H), C.c_int(W), C.c_int(Cc), C.c_int(ks), C.c_double(sigma),
+                            C.c_double(eps), C.c_uint(flags), _p(x), _p(y), _p(mu), _p(rstd))
+    return y, mu, rstd
+
+
+def lcn_var_bwd(x, mu, rstd, dy, ks=5, sigma=1.0, flags=0):
+    x, mu, rstd, dy = _d(x), _d(mu), _d(rstd), _d(dy)
+    B, H, W, Cc = x.shape
+    stat = (B, H, W, Cc) if flags & LCN_PER_CHANNEL else (B, H, W)
+    assert mu.shape == rstd.shape == stat and dy.shape == x.shape and 0 <= flags < 8
+    dx = np.empty_like(x)
+    _load().orc_lcn_var_bwd(C.c_int(B), C.c_int(H), C.c_int(W), C.c_int(Cc), C.c_int(ks), C.c_double(sigma),
+                            C.c_uint(flags), _p(x), _p(mu), _p(rstd), _p(dy), _p(dx))
+    return dx
+
+
 def sae_cost(g, x, w, b, alpha=1.0, lam=0.1, eps_s=1e-6):
     B, H, W, Cc, R, S, F = g
     LH, LW = n_loc(H, R, S), n_loc(W, R, S)

@@ -249,6 +249,157 @@ void orc_lcn_bwd(int B, int H, int W, int C, int ks, double sigma,
 }
 
 /*
+ * Variants of the local contrast normalisation of Sec. 3.1 (the paper names LCN without defining it, so the
+ * common published forms are provided beside orc_lcn_fwd).  flags:
+ *   1  statistics per channel (window over space only) instead of pooled over all channels;
+ *   2  zero-padded borders: pixels outside the image count as zeros and the window weights are NOT renormalised;
+ *   4  two stages: subtractive (v = x - local mean of x), then divisive (v / sqrt(local mean of v^2 + eps)),
+ *      where the local mean of v^2 uses every neighbour's own v.
+ * Without flag 4 this is the one-stage form of orc_lcn_fwd: var = max(mean(x^2) - mean(x)^2, 0).
+ * mu and rstd hold one value per pixel ([B,H,W]) when pooled, one per element ([B,H,W,C]) with flag 1.
+ */
+static double lcn_window_mean(int H, int W, int C, int ks, const double *g, int zero_pad, int per_channel,
+                              const double *f /* one image [H,W,C] */, int i, int j, int c) {
+    const int r = (ks - 1) / 2;
+    double Z = 0.0, s = 0.0;
+    for (int p = -r; p <= r; ++p)
+        for (int q = -r; q <= r; ++q) {
+            const int ii = i + p, jj = j + q;
+            if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
+            const double wt = g[p + r] * g[q + r];
+            Z += wt;
+            const double *fp = f + ((size_t)ii * W + jj) * C;
+            if (per_channel) s += wt * fp[c];
+            else for (int cc = 0; cc < C; ++cc) s += wt * fp[cc];
+        }
+    if (zero_pad) Z = 1.0;              /* taps sum to one over the full window */
+    return s / (per_channel ? Z : Z * C);
+}
+
+void orc_lcn_var_fwd(int B, int H, int W, int C, int ks, double sigma, double eps, unsigned flags,
+                     const double *x, double *y, double *mu, double *rstd) {
+    const int pc = (flags & 1u) != 0, zp = (flags & 2u) != 0, two = (flags & 4u) != 0;
+    const int CS = pc ? C : 1;
+    const size_t img = (size_t)H * W * C;
+    double g[64];
+    gauss_taps(ks, sigma, g);
+#pragma omp parallel for schedule(static)
+    for (int b = 0; b < B; ++b) {
+        const double *xb = x + b * img;
+        double *f = (double *)malloc(img * sizeof(double));   /* x^2 (one stage) or v^2 (two stages) */
+        double *mub = mu + (size_t)b * H * W * CS, *rsb = rstd + (size_t)b * H * W * CS;
+        for (int i = 0; i < H; ++i)
+            for (int j = 0; j < W; ++j)
+                for (int c = 0; c < CS; ++c)
+                    mub[((size_t)i * W + j) * CS + c] = lcn_window_mean(H, W, C, ks, g, zp, pc, xb, i, j, c);
+        for (size_t e = 0; e < img; ++e) {
+            const double m = mub[pc ? e : e / C];
+            f[e] = two ? (xb[e] - m) * (xb[e] - m) : xb[e] * xb[e];
+        }
+        for (int i = 0; i < H; ++i)
+            for (int j = 0; j < W; ++j)
+                for (int c = 0; c < CS; ++c) {
+                    const size_t s_ = ((size_t)i * W + j) * CS + c;
+                    double var = lcn_window_mean(H, W, C, ks, g, zp, pc, f, i, j, c);
+                    if (!two) { var -= mub[s_] * mub[s_]; if (var < 0.0) var = 0.0; }
+                    rsb[s_] = 1.0 / sqrt(var + eps);
+                }
+        for (size_t e = 0; e < img; ++e) {
+            const size_t s_ = pc ? e : e / C;
+            y[b * img + e] = (xb[e] - mub[s_]) * rsb[s_];
+        }
+        free(f);
+    }
+}
+
+/*
+ * Chain rule of orc_lcn_var_fwd (the clamp of the one-stage variance is taken as inactive).  Statistic s (a
+ * pixel, or a pixel and channel) owns the elements e(s) and draws on element q with weight a_s(q) = window
+ * weight / normaliser of s.
+ *   one stage:  b_s = sum_{e(s)} dy (x - mu_s);  dmu_s = -rstd_s sum_{e(s)} dy + rstd_s^3 mu_s b_s;
+ *               dm2_s = -rstd_s^3 b_s / 2;       dx[q] = dy[q] rstd + sum_s a_s(q) (dmu_s + 2 x[q] dm2_s).
+ *   two stages: dvar_s = -rstd_s^3 b_s / 2 with v in place of x - mu;
+ *               dv[q] = dy[q] rstd + 2 v[q] sum_s a_s(q) dvar_s;   dx[q] = dv[q] - sum_s a_s(q) sum_{e(s)} dv.
+ */
+void orc_lcn_var_bwd(int B, int H, int W, int C, int ks, double sigma, unsigned flags,
+                     const double *x, const double *mu, const double *rstd, const double *dy, double *dx) {
+    const int pc = (flags & 1u) != 0, zp = (flags & 2u) != 0, two = (flags & 4u) != 0;
+    const int CS = pc ? C : 1, CR = pc ? 1 : C, r = (ks - 1) / 2;
+    const size_t img = (size_t)H * W * C;
+    double g[64];
+    gauss_taps(ks, sigma, g);
+#pragma omp parallel for schedule(static)
+    for (int b = 0; b < B; ++b) {
+        const double *xb = x + b * img, *dyb = dy + b * img;
+        const double *mub = mu + (size_t)b * H * W * CS, *rsb = rstd + (size_t)b * H * W * CS;
+        double *dxb = dx + b * img;
+        double *dv = (double *)malloc(img * sizeof(double));
+        for (size_t e = 0; e < img; ++e) dv[e] = dyb[e] * rsb[pc ? e : e / C];
+        /* first sweep: every statistic scatters the gradient of its mean (one stage) and of its variance */
+        for (int i = 0; i < H; ++i)
+            for (int j = 0; j < W; ++j)
+                for (int c = 0; c < CS; ++c) {
+                    const size_t s_ = ((size_t)i * W + j) * CS + c;
+                    double Z = 0.0;
+                    for (int p = -r; p <= r; ++p)
+                        for (int q = -r; q <= r; ++q) {
+                            const int ii = i + p, jj = j + q;
+                            if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
+                            Z += g[p + r] * g[q + r];
+                        }
+                    if (zp) Z = 1.0;
+                    double t = 0.0, bs = 0.0;
+                    for (int cc = 0; cc < CR; ++cc) {
+                        const size_t e = s_ * CR + cc;
+                        t += dyb[e];
+                        bs += dyb[e] * (xb[e] - mub[s_]);
+                    }
+                    const double rs3 = rsb[s_] * rsb[s_] * rsb[s_];
+                    const double dvar = -0.5 * rs3 * bs;
+                    const double dmu = two ? 0.0 : -rsb[s_] * t + rs3 * mub[s_] * bs;
+                    for (int p = -r; p <= r; ++p)
+                        for (int q = -r; q <= r; ++q) {
+                            const int ii = i + p, jj = j + q;
+                            if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
+                            const double a = g[p + r] * g[q + r] / (Z * CR);
+                            for (int cc = 0; cc < CR; ++cc) {
+                                const size_t e = (((size_t)ii * W + jj) * CS + c) * CR + cc;
+                                const double base = two ? xb[e] - mub[((size_t)ii * W + jj) * CS + c] : xb[e];
+                                dv[e] += a * (dmu + 2.0 * base * dvar);
+                            }
+                        }
+                }
+        memcpy(dxb, dv, img * sizeof(double));
+        if (two) {
+            /* second sweep: v = x - mean(x), so each statistic takes the sum of dv over its elements back out */
+            for (int i = 0; i < H; ++i)
+                for (int j = 0; j < W; ++j)
+                    for (int c = 0; c < CS; ++c) {
+                        const size_t s_ = ((size_t)i * W + j) * CS + c;
+                        double Z = 0.0, t = 0.0;
+                        for (int p = -r; p <= r; ++p)
+                            for (int q = -r; q <= r; ++q) {
+                                const int ii = i + p, jj = j + q;
+                                if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
+                                Z += g[p + r] * g[q + r];
+                            }
+                        if (zp) Z = 1.0;
+                        for (int cc = 0; cc < CR; ++cc) t += dv[s_ * CR + cc];
+                        for (int p = -r; p <= r; ++p)
+                            for (int q = -r; q <= r; ++q) {
+                                const int ii = i + p, jj = j + q;
+                                if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
+                                const double a = g[p + r] * g[q + r] / (Z * CR);
+                                for (int cc = 0; cc < CR; ++cc)
+                                    dxb[(((size_t)ii * W + jj) * CS + c) * CR + cc] -= a * t;
+                            }
+                    }
+        }
+        free(dv);
+    }
+}
+
+/*
  * RICA cost of Eq. 1 for one stage, divided by the batch size:
  *   h = alpha W x,  xh = W^T h + b,  J = (1/B) [ sum (xh-x)^2 + lambda sum sqrt(h^2 + eps_s) ].
  * h (size B*L*F) and r = xh - x (size B*H*W*C) are returned for the gradient.

@@ -323,6 +323,120 @@ def test_lcn_bwd_by_finite_differences():
             assert abs(_fd_dir(f, x, d, 1e-6) - dx[idx]) <= 2e-7
 
 
+# ----------------------------------------------------------------- LCN variants
+def _lcn_var_by_library(x, ks, sigma, eps, flags):
+    """The variant's definition with scipy's zero-padded correlation as the window operator."""
+    from scipy import ndimage
+    k = _gauss2d(ks, sigma)[None, :, :, None]
+    corr = lambda f: ndimage.correlate(f, k, mode="constant", cval=0.0)
+    norm = 1.0 if flags & 2 else corr(np.ones_like(x))
+    pool = (lambda f: f) if flags & 1 else (lambda f: f.mean(axis=3, keepdims=True))
+    mean = lambda f: pool(corr(f) / norm)
+    m = mean(x)
+    var = mean((x - m) ** 2) if flags & 4 else np.maximum(mean(x * x) - m * m, 0.0)
+    rs = 1.0 / np.sqrt(var + eps)
+    sq = (lambda a: a) if flags & 1 else (lambda a: a[..., 0])
+    return (x - m) * rs, sq(m), sq(rs)
+
+
+@pytest.mark.parametrize("flags", range(8))
+def test_lcn_variants_match_library_correlation(flags):
+    r = rng(40 + flags)
+    for shape, ks, sigma in [((2, 9, 11, 3), 5, 1.0), ((1, 4, 3, 2), 7, 2.0), ((1, 6, 7, 1), 3, 0.7)]:
+        x = r.standard_normal(shape) + 0.3
+        y, mu, rstd = oracle.lcn_var_fwd(x, ks, sigma, 1e-3, flags)
+        ry, rmu, rrs = _lcn_var_by_library(x, ks, sigma, 1e-3, flags)
+        np.testing.assert_allclose(mu, rmu, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(rstd, rrs, rtol=1e-11)
+        np.testing.assert_allclose(y, ry, rtol=1e-11, atol=1e-12)
+
+
+def test_lcn_variant_without_flags_is_the_pooled_one_stage_form():
+    r = rng(48)
+    x, dy = r.standard_normal((2, 8, 7, 3)), r.standard_normal((2, 8, 7, 3))
+    y0, mu0, rs0 = oracle.lcn_fwd(x, 5, 1.0, 1e-3)
+    y1, mu1, rs1 = oracle.lcn_var_fwd(x, 5, 1.0, 1e-3, 0)
+    for a, b in [(y0, y1), (mu0, mu1), (rs0, rs1)]:
+        np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(oracle.lcn_var_bwd(x, mu0, rs0, dy, 5, 1.0, 0), oracle.lcn_bwd(x, mu0, rs0, dy, 5, 1.0),
+                               rtol=1e-12, atol=1e-13)
+
+
+def test_lcn_variants_closed_forms():
+    ks, sigma = 5, 1.0
+    g = _gauss2d(ks, sigma)
+    # constant image: renormalised borders see the constant everywhere, zero padding sees less of it at the rim
+    xc = np.full((1, 7, 8, 2), 2.5)
+    for flags in range(8):
+        y, mu, rstd = oracle.lcn_var_fwd(xc, ks, sigma, 1e-2, flags)
+        if not flags & 2:
+            assert np.allclose(mu, 2.5, rtol=1e-13) and np.all(np.abs(y) < 1e-12)
+            assert np.allclose(rstd, 10.0, rtol=1e-9)
+        else:
+            assert np.isclose(mu.reshape(7, 8, -1)[0, 0, 0], 2.5 * g[2:, 2:].sum(), rtol=1e-13)
+            assert np.isclose(mu.reshape(7, 8, -1)[3, 0, 0], 2.5 * g[:, 2:].sum(), rtol=1e-13)
+            assert np.isclose(mu.reshape(7, 8, -1)[3, 4, 0], 2.5, rtol=1e-13)
+    r = rng(49)
+    x = r.standard_normal((2, 8, 9, 3))
+    for flags in range(8):
+        y0 = oracle.lcn_var_fwd(x, ks, sigma, 0.0, flags)[0]
+        np.testing.assert_allclose(oracle.lcn_var_fwd(3.0 * x, ks, sigma, 0.0, flags)[0], y0, rtol=1e-10, atol=1e-11)
+        if not flags & 2:   # a shift is removed by the mean only when the window weights sum to one
+            np.testing.assert_allclose(oracle.lcn_var_fwd(x + 1.75, ks, sigma, 0.0, flags)[0], y0, rtol=1e-8, atol=1e-9)
+    # one channel: per-channel and pooled statistics are the same thing
+    x1 = r.standard_normal((2, 8, 9, 1))
+    for base in (0, 2, 4, 6):
+        a, b = oracle.lcn_var_fwd(x1, ks, sigma, 1e-3, base), oracle.lcn_var_fwd(x1, ks, sigma, 1e-3, base | 1)
+        np.testing.assert_allclose(a[0], b[0], rtol=1e-13, atol=1e-14)
+        np.testing.assert_allclose(a[1], b[1][..., 0], rtol=1e-13, atol=1e-14)
+    # identical channels: pooling over them changes nothing
+    xr = np.repeat(x1, 3, axis=3)
+    for base in (0, 2, 4, 6):
+        a, b = oracle.lcn_var_fwd(xr, ks, sigma, 1e-3, base), oracle.lcn_var_fwd(xr, ks, sigma, 1e-3, base | 1)
+        np.testing.assert_allclose(a[0], b[0], rtol=1e-12, atol=1e-13)
+
+
+def test_lcn_two_stage_unit_local_energy():
+    """Two stages, eps=0: around every pixel the window-weighted mean of (v * rstd_pixel)^2 over the neighbours'
+    own v is one, and v itself has zero window mean of x - mu only at the centre's statistics."""
+    r = rng(50)
+    B, H, W, C, ks = 1, 7, 8, 2, 5
+    x = r.standard_normal((B, H, W, C)) + 0.4
+    g2, rad = _gauss2d(ks, 1.0), 2
+    for flags in (4, 5):
+        _, mu, rstd = oracle.lcn_var_fwd(x, ks, 1.0, 0.0, flags)
+        v = x - (mu if flags & 1 else mu[..., None])
+        rs = rstd if flags & 1 else rstd[..., None]
+        for i in range(H):
+            for j in range(W):
+                acc, z = np.zeros(C if flags & 1 else 1), 0.0
+                for p in range(-rad, rad + 1):
+                    for q in range(-rad, rad + 1):
+                        if 0 <= i + p < H and 0 <= j + q < W:
+                            z += g2[p + rad, q + rad]
+                            e = v[0, i + p, j + q] ** 2
+                            acc += g2[p + rad, q + rad] * (e if flags & 1 else e.mean())
+                np.testing.assert_allclose(acc / z * rs[0, i, j] ** 2, 1.0, rtol=1e-10)
+
+
+@pytest.mark.parametrize("flags", range(8))
+def test_lcn_variant_bwd_by_finite_differences(flags):
+    r = rng(60 + flags)
+    for shape, ks in [((2, 7, 8, 3), 5), ((1, 4, 3, 2), 5), ((1, 6, 6, 1), 3)]:
+        x = r.standard_normal(shape)
+        y, mu, rstd = oracle.lcn_var_fwd(x, ks, 1.0, 1e-2, flags)
+        dy = r.standard_normal(shape)
+        dx = oracle.lcn_var_bwd(x, mu, rstd, dy, ks, 1.0, flags)
+        f = lambda xx: np.vdot(oracle.lcn_var_fwd(xx, ks, 1.0, 1e-2, flags)[0], dy)
+        for _ in range(4):
+            d = r.standard_normal(shape)
+            fd = _fd_dir(f, x, d, 1e-6)
+            assert abs(fd - np.vdot(dx, d)) <= 5e-7 * max(1.0, abs(fd))
+        for idx in [(0, 0, 0, 0), tuple(s - 1 for s in shape), (0, shape[1] // 2, shape[2] // 2, 0)]:
+            d = np.zeros(shape); d[idx] = 1.0
+            assert abs(_fd_dir(f, x, d, 1e-6) - dx[idx]) <= 5e-7
+
+
 # ------------------------------------------------------------ RICA cost / step
 SAE_G = wl.LCGeom(B=3, H=9, W=8, C=2, R=4, S=2, F=3)    # floor geometry: last column uncovered
 
