@@ -120,6 +120,27 @@ int lcn_fwd(const float *x, float *y, float *mu, float *rstd, int32_t B, int32_t
 int lcn_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B,
             int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma, void *hip_stream);
 
+/* Variants of lcn_fwd / lcn_bwd (Sec. 3.1 names LCN and gives no formula, so the common published forms are
+ * offered beside the default).  flags = 0 is lcn_fwd itself; the bits combine freely:
+ *   LCN_PER_CHANNEL  statistics per channel: the window runs over space only, and mu, rstd are [B,H,W,C];
+ *   LCN_ZERO_PAD     pixels outside the image count as zeros and the window weights keep their full-window
+ *                    normalisation (no renormalisation of the truncated window at the border);
+ *   LCN_TWO_STAGE    subtractive then divisive stage: v = x - mean_w(x), y = v / sqrt(mean_w(v^2) + eps), where
+ *                    mean_w is the Gaussian-window mean of lcn_fwd and mean_w(v^2) takes every neighbour's own v.
+ * mu, rstd ([B,H,W], or [B,H,W,C] with LCN_PER_CHANNEL) hold the subtracted mean and the factor y = (x - mu) rstd.
+ * lcn_variant_bwd overwrites dx [B,H,W,C] (which must not alias x or dy); with LCN_TWO_STAGE it needs
+ * lcn_variant_workspace_bytes() of scratch (LC_EWORKSPACE otherwise), 0 bytes for the one-stage forms.
+ * ksize odd, 1 <= ksize <= 15; unknown flag bits give LC_EINVAL. */
+#define LCN_PER_CHANNEL 1u
+#define LCN_ZERO_PAD 2u
+#define LCN_TWO_STAGE 4u
+size_t lcn_variant_workspace_bytes(int32_t B, int32_t H, int32_t W, int32_t C, uint32_t flags);
+int lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int32_t B, int32_t H, int32_t W, int32_t C,
+                    int32_t ksize, float gauss_sigma, float eps, uint32_t flags, void *hip_stream);
+int lcn_variant_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B,
+                    int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma, uint32_t flags, void *ws,
+                    size_t ws_bytes, void *hip_stream);
+
 /* One SGD step on the RICA cost of Eq. 1 for one layer (fp32):
  *   h = alpha W x;  xh = W^T h + b;  J = (1/B) [ sum (xh - x)^2 + lambda * sum sqrt(h^2 + eps_sparse) ]
  *   w -= lr dJ/dw (both uses of the tied weights);  b -= lr dJ/db;  alpha -= lr dJ/dalpha if LC_SAE_LEARN_ALPHA;

@@ -25,7 +25,8 @@ _STATUS = {0: "LC_OK", -1: "LC_EINVAL", -2: "LC_ENULL", -3: "LC_EALIGN", -4: "LC
            -5: "LC_EUNSUPPORTED", -6: "LC_EHIP"}
 
 EXPORTS = ("lc_geom_derive", "lc_workspace_bytes", "lc_forward", "lc_backward_data", "lc_backward_weights",
-           "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "sae_step", "lc_last_error")
+           "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
+           "lcn_variant_bwd", "sae_step", "lc_last_error")
 
 
 class LcGeom(C.Structure):
@@ -61,6 +62,10 @@ def lib() -> C.CDLL:
         L.l2pool_bwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
         L.lcn_fwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, vp]
         L.lcn_bwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp]
+        L.lcn_variant_workspace_bytes.argtypes = [i32, i32, i32, i32, C.c_uint32]
+        L.lcn_variant_workspace_bytes.restype = C.c_size_t
+        L.lcn_variant_fwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, C.c_uint32, vp]
+        L.lcn_variant_bwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, C.c_uint32, vp, C.c_size_t, vp]
         L.sae_step.argtypes = [G, vp, vp, vp, vp, f32, f32, f32, u32, vp, vp, vp, sz, vp]
         L.lc_last_error.restype = C.c_char_p
         for name in EXPORTS:
@@ -180,6 +185,33 @@ def lcn_bwd(x, mu, rstd, dy, dx, ksize: int, gauss_sigma: float) -> None:
         _dev(x, None, torch.float32, "x"), _dev(mu, (B, H, W), torch.float32, "mu"),
         _dev(rstd, (B, H, W), torch.float32, "rstd"), _dev(dy, x.shape, torch.float32, "dy"),
         _dev(dx, x.shape, torch.float32, "dx"), B, H, W, Cc, ksize, gauss_sigma, _stream()))
+
+
+LCN_PER_CHANNEL, LCN_ZERO_PAD, LCN_TWO_STAGE = 1, 2, 4
+
+
+def lcn_variant_workspace_bytes(shape, flags: int) -> int:
+    B, H, W, Cc = shape
+    return int(lib().lcn_variant_workspace_bytes(B, H, W, Cc, flags))
+
+
+def lcn_variant_fwd(x, y, mu, rstd, ksize: int, gauss_sigma: float, eps: float, flags: int) -> None:
+    B, H, W, Cc = x.shape
+    stat = (B, H, W, Cc) if flags & LCN_PER_CHANNEL else (B, H, W)
+    _check("lcn_variant_fwd", lib().lcn_variant_fwd(
+        _dev(x, None, torch.float32, "x"), _dev(y, x.shape, torch.float32, "y"),
+        _dev(mu, stat, torch.float32, "mu"), _dev(rstd, stat, torch.float32, "rstd"),
+        B, H, W, Cc, ksize, gauss_sigma, eps, flags, _stream()))
+
+
+def lcn_variant_bwd(x, mu, rstd, dy, dx, ksize: int, gauss_sigma: float, flags: int, ws=None) -> None:
+    B, H, W, Cc = x.shape
+    stat = (B, H, W, Cc) if flags & LCN_PER_CHANNEL else (B, H, W)
+    wp, wb = _ws(ws)
+    _check("lcn_variant_bwd", lib().lcn_variant_bwd(
+        _dev(x, None, torch.float32, "x"), _dev(mu, stat, torch.float32, "mu"),
+        _dev(rstd, stat, torch.float32, "rstd"), _dev(dy, x.shape, torch.float32, "dy"),
+        _dev(dx, x.shape, torch.float32, "dx"), B, H, W, Cc, ksize, gauss_sigma, flags, wp, wb, _stream()))
 
 
 def sae_step(g: LcGeom, x, w, b, alpha, lam: float, eps_sparse: float, lr: float, flags: int, h_out, cost_out,

@@ -153,6 +153,36 @@ int lcn_bwd(const float *x, const float *mu, const float *rstd, const float *dy,
                       0.f, (hipStream_t)hip_stream);
 }
 
+size_t lcn_variant_workspace_bytes(int32_t B, int32_t H, int32_t W, int32_t C, uint32_t flags) {
+    if (check_map(B, H, W, C) != LC_OK || (flags & ~7u)) return 0;
+    return lc::lcn_variant_scratch_bytes(B, H, W, C, flags);
+}
+
+int lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int32_t B, int32_t H, int32_t W, int32_t C,
+                    int32_t ksize, float gauss_sigma, float eps, uint32_t flags, void *hip_stream) {
+    if (check_map(B, H, W, C) != LC_OK || (flags & ~7u)) return LC_EINVAL;
+    if (ksize < 1 || ksize > 15 || (ksize & 1) == 0 || !(gauss_sigma > 0.f) || !(eps >= 0.f)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(y); LC_REQUIRE_PTR(mu); LC_REQUIRE_PTR(rstd);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(y); LC_REQUIRE_ALIGNED(mu); LC_REQUIRE_ALIGNED(rstd);
+    return launch_lcn_variant_fwd(x, y, mu, rstd, B, H, W, C, ksize, gauss_sigma, eps, flags, (hipStream_t)hip_stream);
+}
+
+int lcn_variant_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B,
+                    int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma, uint32_t flags, void *ws,
+                    size_t ws_bytes, void *hip_stream) {
+    if (check_map(B, H, W, C) != LC_OK || (flags & ~7u)) return LC_EINVAL;
+    if (ksize < 1 || ksize > 15 || (ksize & 1) == 0 || !(gauss_sigma > 0.f)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(mu); LC_REQUIRE_PTR(rstd); LC_REQUIRE_PTR(dy); LC_REQUIRE_PTR(dx);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(mu); LC_REQUIRE_ALIGNED(rstd); LC_REQUIRE_ALIGNED(dy); LC_REQUIRE_ALIGNED(dx);
+    if (dx == x || dx == dy) return LC_EINVAL;
+    if (flags & LCN_TWO_STAGE) {
+        if (ws == nullptr || ws_bytes < lc::lcn_variant_scratch_bytes(B, H, W, C, flags)) return LC_EWORKSPACE;
+        LC_REQUIRE_ALIGNED(ws);
+    }
+    return launch_lcn_variant_bwd(x, mu, rstd, dy, dx, B, H, W, C, ksize, gauss_sigma, flags, ws, ws_bytes,
+                                  (hipStream_t)hip_stream);
+}
+
 int sae_step(const lc_geom_t *g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
              float lr, uint32_t flags, float *h_out, float *cost_out, void *ws, size_t ws_bytes, void *hip_stream) {
     Geom q;

@@ -76,8 +76,15 @@ int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int 
 int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int B, int H, int W, int C, int ks,
                       int st, hipStream_t s);
 // mode 0: forward (out = y; mu, rstd written).  mode 1: backward (out = dx; mu, rstd read).
+// zero_pad: pixels outside the image count as zeros and the window keeps its full-window normalisation.
 int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
-               int C, int ks, float sigma, float eps, hipStream_t s);
+               int C, int ks, float sigma, float eps, hipStream_t s, int zero_pad = 0);
+// LCN variants (flags as in lc.h: per-channel statistics, zero-padded borders, two stages)
+size_t lcn_variant_scratch_bytes(int B, int H, int W, int C, unsigned flags);
+int launch_lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int B, int H, int W, int C, int ks,
+                           float sigma, float eps, unsigned flags, hipStream_t s);
+int launch_lcn_variant_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int B, int H,
+                           int W, int C, int ks, float sigma, unsigned flags, void *ws, size_t ws_bytes, hipStream_t s);
 // wide layers (128-filter blocks): workgroup-tiled forward; LC_EUNSUPPORTED outside forward_wide_supported()
 bool forward_wide_supported(const Geom &g);
 size_t forward_wide_workspace_bytes(const Geom &g);   // optional workspace: K-slices for layers with few fields

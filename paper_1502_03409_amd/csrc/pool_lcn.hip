@@ -267,7 +267,8 @@ __device__ __forceinline__ float group_sum(float v, int lpp) {
     return v;
 }
 
-// sum of the taps that stay inside [0,n) around position p
+// sum of the taps that stay inside [0,n) around position p (the normaliser of a window truncated at the border;
+// with zero padding, zpad, the taps keep their full-window normalisation instead)
 __device__ __forceinline__ float tap_norm(const GaussTaps &t, int p, int n, int r) {
     float z = 0.f;
     for (int d = -r; d <= r; ++d)
@@ -280,7 +281,7 @@ template <int VEC, int MODE>
 __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, const float *__restrict__ dy,
                                                   float *__restrict__ out, float *__restrict__ mu,
                                                   float *__restrict__ rstd, int H, int W, int C, int ks, float eps,
-                                                  GaussTaps taps, int lpp, int tiles_w, int tiles_per_img) {
+                                                  GaussTaps taps, int lpp, int tiles_w, int tiles_per_img, int zpad) {
     __shared__ float m1[kLcnHalo * kLcnHalo], m2[kLcnHalo * kLcnHalo];
     __shared__ float t1[kLcnTile * kLcnTile], t2[kLcnTile * kLcnTile];
     const int r = (ks - 1) / 2, halo = kLcnTile + 2 * r;
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
                 // transposed window sums need
                 float p1 = 0.f, p2 = 0.f;
                 if (in) {
-                    const float z = tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r) * (float)C;
+                    const float z = (zpad ? 1.f : tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r)) * (float)C;
                     const float bc = rsp * rsp * rsp * c2;
                     p1 = (bc * mp - rsp * a) / z;
                     p2 = bc / z;
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
                     s2 += wt * m2[hp];
                 }
             if (MODE == 0) {
-                const float z = tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r) * (float)C;
+                const float z = (zpad ? 1.f : tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r)) * (float)C;
                 const float m = s1 / z, q2 = s2 / z;
                 const float var = fmaxf(q2 - m * m, 0.f);
                 const float rs = 1.0f / sqrtf(var + eps);
@@ -422,7 +423,7 @@ template <int LPP>
 __global__ __launch_bounds__(256) void lcn_fwd_cached_kernel(const float *__restrict__ x, float *__restrict__ out,
                                                              float *__restrict__ mu, float *__restrict__ rstd, int H,
                                                              int W, int ks, float eps, GaussTaps taps, int tiles_w,
-                                                             int tiles_per_img) {
+                                                             int tiles_per_img, int zpad) {
     constexpr int C = 4 * LPP, NG = 256 / LPP, NI = LPP;   // NG pixel groups; NI passes cover the 256 tile pixels
     __shared__ float m1[kLcnHalo * kLcnHalo], m2[kLcnHalo * kLcnHalo];
     __shared__ float t1[kLcnTile * kLcnTile], t2[kLcnTile * kLcnTile];
@@ -482,7 +483,7 @@ __global__ __launch_bounds__(256) void lcn_fwd_cached_kernel(const float *__rest
                     s1 += wt * m1[hp];   // out-of-image halo entries are zero
                     s2 += wt * m2[hp];
                 }
-            const float z = tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r) * (float)C;
+            const float z = (zpad ? 1.f : tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r)) * (float)C;
             const float m = s1 / z, q2 = s2 / z;
             const float var = fmaxf(q2 - m * m, 0.f);
             const float rs = 1.0f / sqrtf(var + eps);
@@ -594,7 +595,7 @@ int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx
 }
 
 int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
-               int C, int ks, float sigma, float eps, hipStream_t s) {
+               int C, int ks, float sigma, float eps, hipStream_t s, int zero_pad) {
     GaussTaps taps;
     if (!make_taps(ks, sigma, &taps)) return LC_EINVAL;
     const int tiles_h = (H + kLcnTile - 1) / kLcnTile, tiles_w = (W + kLcnTile - 1) / kLcnTile;
@@ -605,10 +606,10 @@ int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu,
     dim3 grid((unsigned)nblk), block(256);
 #define LC_LCN(VEC_, MODE_)                                                                                       \
     hipLaunchKernelGGL((lcn_kernel<VEC_, MODE_>), grid, block, 0, s, x, dy, out, mu, rstd, H, W, C, ks, eps, taps, \
-                       lpp, tiles_w, tiles_h * tiles_w)
+                       lpp, tiles_w, tiles_h * tiles_w, zero_pad)
 #define LC_LCN_CACHED(LPP_)                                                                                    \
     hipLaunchKernelGGL((lcn_fwd_cached_kernel<LPP_>), grid, block, 0, s, x, out, mu, rstd, H, W, ks, eps, taps, \
-                       tiles_w, tiles_h * tiles_w)
+                       tiles_w, tiles_h * tiles_w, zero_pad)
     if (mode == 0 && C == 32) LC_LCN_CACHED(8);
     else if (mode == 0 && C == 16) LC_LCN_CACHED(4);
     else if (mode == 0 && C == 8) LC_LCN_CACHED(2);

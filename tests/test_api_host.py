@@ -82,6 +82,15 @@ def test_argument_validation_happens_before_any_launch():
     assert L.lcn_fwd(FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 5, 0.0, 1e-4, None) == B.LC_EINVAL     # sigma
     assert L.lcn_fwd(FAKE, FAKE, None, FAKE, 1, 8, 8, 4, 5, 1.0, 1e-4, None) == B.LC_ENULL
     assert L.lcn_bwd(FAKE, FAKE, FAKE, FAKE, None, 1, 8, 8, 4, 5, 1.0, None) == B.LC_ENULL
+    # LCN variants: unknown flag bits, the two-stage gradient without its scratch, aliased output
+    assert L.lcn_variant_fwd(FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 5, 1.0, 1e-4, 8, None) == B.LC_EINVAL
+    assert L.lcn_variant_fwd(FAKE, FAKE, FAKE, None, 1, 8, 8, 4, 5, 1.0, 1e-4, 7, None) == B.LC_ENULL
+    assert L.lcn_variant_bwd(FAKE, FAKE, FAKE, FAKE, FAKE + 16, 1, 8, 8, 4, 5, 1.0, 4, None, 0, None) == B.LC_EWORKSPACE
+    assert L.lcn_variant_bwd(FAKE, FAKE, FAKE, FAKE, FAKE + 16, 1, 8, 8, 4, 5, 1.0, 4, FAKE, 255, None) == B.LC_EWORKSPACE
+    assert L.lcn_variant_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 5, 1.0, 1, None, 0, None) == B.LC_EINVAL
+    assert L.lcn_variant_workspace_bytes(1, 8, 8, 4, 4) == 8 * 8 * 4
+    assert L.lcn_variant_workspace_bytes(1, 8, 8, 4, 5) == 8 * 8 * 4 * 4
+    assert L.lcn_variant_workspace_bytes(1, 8, 8, 4, 3) == 0
     need = lc.workspace_bytes(g, B.LC_OP_SAE_STEP)
     args = (gp, FAKE, FAKE, FAKE, FAKE, 0.1, 1e-6, 1e-3, 0, None, FAKE)
     assert L.sae_step(*args, None, 0, None) == B.LC_EWORKSPACE

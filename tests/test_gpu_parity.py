@@ -300,6 +300,37 @@ def test_lcn_matches_oracle(shape, ks):
     assert rel_fro(host(dx), oracle.lcn_bwd(x, ref_mu, ref_rstd, dy, ks, wl.LCN_SIGMA)) <= TOL
 
 
+LCN_VARIANT_SHAPES = [((2, 9, 10, 3), 5), ((3, 20, 37, 32), 5), ((1, 3, 2, 5), 5), ((2, 33, 17, 6), 7),
+                      ((1, 5, 40, 130), 3), ((2, 35, 18, 12), 15), ((8, 44, 44, 32), 5)]
+
+
+@pytest.mark.parametrize("flags", range(8))
+@pytest.mark.parametrize("shape,ks", LCN_VARIANT_SHAPES)
+def test_lcn_variants_match_oracle(shape, ks, flags):
+    """flags: 1 per-channel statistics, 2 zero-padded borders, 4 two stages (Sec. 3.1 leaves LCN undefined)."""
+    print(f"case lcn variant {shape} {ks} flags {flags}", flush=True)
+    x = wl.feature_maps(*shape, seed=3, signed=False)
+    ref_y, ref_mu, ref_rstd = oracle.lcn_var_fwd(x, ks, wl.LCN_SIGMA, wl.LCN_EPS, flags)
+    stat = shape if flags & lc.LCN_PER_CHANNEL else shape[:3]
+    xd = dev(x)
+    y = torch.full(shape, float("nan"), device="cuda")
+    mu = torch.full(stat, float("nan"), device="cuda")
+    rstd = torch.full(stat, float("nan"), device="cuda")
+    lc.lcn_variant_fwd(xd, y, mu, rstd, ks, wl.LCN_SIGMA, wl.LCN_EPS, flags)
+    assert rel_fro(host(mu), ref_mu) <= TOL
+    assert rel_fro(host(rstd), ref_rstd) <= TOL
+    assert rel_fro(host(y), ref_y) <= TOL
+    dy = wl.feature_maps(*shape, seed=4)
+    dx = torch.full(shape, float("nan"), device="cuda")
+    nws = lc.lcn_variant_workspace_bytes(shape, flags)
+    assert (nws > 0) == bool(flags & lc.LCN_TWO_STAGE)
+    ws = torch.full((nws // 4,), float("nan"), device="cuda") if nws else None
+    # backward from the oracle's saved statistics, so that only the gradient kernels are under test
+    lc.lcn_variant_bwd(xd, dev(ref_mu.astype(np.float32)), dev(ref_rstd.astype(np.float32)), dev(dy), dx, ks,
+                       wl.LCN_SIGMA, flags, ws)
+    assert rel_fro(host(dx), oracle.lcn_var_bwd(x, ref_mu, ref_rstd, dy, ks, wl.LCN_SIGMA, flags)) <= TOL
+
+
 def run_sae(g, x, w, b, alpha, lam, eps_s, lr, flags, with_h=True):
     G = lc.geom(*g.as_tuple())
     wd, bd = dev(w), dev(b)
