@@ -75,10 +75,12 @@ int launch_forward_f32(const Geom &g, const float *x, const float *w, const floa
 int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int ks, int st, float eps, hipStream_t s);
 int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int B, int H, int W, int C, int ks,
                       int st, hipStream_t s);
-// mode 0: forward (out = y; mu, rstd written).  mode 1: backward (out = dx; mu, rstd read).
+// Statistics pooled over the channels.  mode 0: forward (out = y; mu, rstd written).  mode 1: backward (out = dx;
+// mu, rstd read).  modes 2..5: the passes of the two-stage form (mean; divide; gradient up to dv and the field of
+// its channel sums; dx = dv - window sum of field), field = B*H*W floats of scratch for modes 4 and 5.
 // zero_pad: pixels outside the image count as zeros and the window keeps its full-window normalisation.
 int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
-               int C, int ks, float sigma, float eps, hipStream_t s, int zero_pad = 0);
+               int C, int ks, float sigma, float eps, hipStream_t s, int zero_pad = 0, float *field = nullptr);
 // LCN variants (flags as in lc.h: per-channel statistics, zero-padded borders, two stages)
 size_t lcn_variant_scratch_bytes(int B, int H, int W, int C, unsigned flags);
 int launch_lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int B, int H, int W, int C, int ks,

@@ -2,19 +2,19 @@
 // statistics per channel instead of pooled over the channels, zero-padded instead of renormalised borders, and
 // the two-stage form (subtract the local mean, then divide by the local root mean square of the result).
 //
-// One kernel template covers every pass.  A "statistic" is a pixel (pooled: it owns the pixel's CR = C channels)
-// or a pixel and channel (per channel: CR = 1).  A workgroup takes a 16x16 pixel tile and up to SC statistics per
-// pixel; it reduces a per-statistic quantity over the tile and its halo into LDS, forms the Gaussian window sums,
-// and finishes with the elementwise pass over the elements its statistics own.  Bandwidth-bound: the tile is
-// read once or twice, the halo ring comes from L2.
+// Pooled statistics run in the channel-reduction kernels of the default form (pool_lcn.hip).  This file holds the
+// per-channel kernel: every element has its own statistics, so a workgroup stages an 8x16 pixel tile, its halo and
+// up to 32 channels of the quantity under the window in LDS (as float4 where C % 4 == 0), and each thread forms
+// the Gaussian window sums for one pixel and four channels at a time.  Bandwidth-bound: the forward passes read
+// the tile once (the centre value is taken from LDS), the halo ring comes from L2.
 #include "lc_common.hpp"
 
 namespace lc {
 namespace {
 
-constexpr int kTile = 16;
+constexpr int kTileH = 8, kTileW = 16;
 constexpr int kMaxK = 15;
-constexpr int kMaxStatsPerBlock = 8;
+constexpr int kLdsTarget = 32 * 1024;   // per workgroup: several workgroups per compute unit hide the load latency
 
 struct Taps { float g[kMaxK]; };
 
@@ -23,14 +23,14 @@ enum : int {
     kMean,      // x -> mu
     kDivide,    // x, mu -> rstd, y = (x - mu) rstd with the window mean of the neighbours' own (x - mu)^2
     kBwdOne,    // one-stage gradient
-    kBwdTwoA,   // two-stage gradient up to dv (written to dx) and the per-statistic sums of dv / normaliser
-    kBwdTwoB    // dx = dv - window sum of those sums
+    kBwdTwoA,   // two-stage gradient up to dv (written to dx) and field = dv / normaliser
+    kBwdTwoB    // dx = dv - window sum of field
 };
 
 struct Args {
     const float *x, *dy, *mu_in, *rstd_in;
     float *out, *mu_out, *rstd_out, *field;
-    int H, W, CS, CR, SC, ks, zpad, tiles_w, tiles_per_img, nchunk;
+    int H, W, C, CB, ks, zpad, tiles_w, tiles_per_img, nchunk;
     float eps;
     Taps taps;
 };
@@ -42,140 +42,161 @@ __device__ __forceinline__ float taps_inside(const Taps &t, int p, int n, int r)
     return z;
 }
 
-template <int OP>
-__global__ __launch_bounds__(256) void lcn_variant_kernel(Args a) {
-    extern __shared__ float lds[];
-    constexpr bool kTwoMaps = OP == kFwdOne || OP == kBwdOne;
-    const int r = (a.ks - 1) / 2, halo = kTile + 2 * r, SC = a.SC, CR = a.CR, CS = a.CS, H = a.H, W = a.W;
-    float *m1 = lds, *m2 = lds + halo * halo * SC;
+template <int V> struct Pack { float v[V]; };
+
+template <int V> __device__ __forceinline__ Pack<V> load(const float *p) {
+    Pack<V> r;
+    if constexpr (V == 4) {
+        const float4 t = *(const float4 *)p;
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else {
+        r.v[0] = *p;
+    }
+    return r;
+}
+
+template <int V> __device__ __forceinline__ void store(float *p, const Pack<V> &r) {
+    if constexpr (V == 4) *(float4 *)p = make_float4(r.v[0], r.v[1], r.v[2], r.v[3]);
+    else *p = r.v[0];
+}
+
+// V channels per work item (4 where C % 4 == 0); a.CB channels per workgroup, a multiple of V.
+template <int OP, int V>
+__global__ __launch_bounds__(256) void lcn_channel_kernel(Args a) {
+    extern __shared__ __align__(16) float lds[];
+    constexpr bool kTwoMaps = OP == kBwdOne;
+    const int r = (a.ks - 1) / 2, hh = kTileH + 2 * r, hw = kTileW + 2 * r, H = a.H, W = a.W, C = a.C;
+    const int CBV = a.CB / V;
+    float *m1 = lds, *m2 = lds + hh * hw * a.CB;
     const int tid = threadIdx.x;
     int blk = blockIdx.x;
     const int chunk = blk % a.nchunk;
     blk /= a.nchunk;
     const int b = blk / a.tiles_per_img, tile = blk - b * a.tiles_per_img;
-    const int ti = (tile / a.tiles_w) * kTile, tj = (tile % a.tiles_w) * kTile;
-    const int sc0 = chunk * SC, nsc = min(SC, CS - sc0);
+    const int ti = (tile / a.tiles_w) * kTileH, tj = (tile % a.tiles_w) * kTileW;
+    const int c0 = chunk * a.CB, ncv = min(CBV, (C - c0) / V);
     const size_t img = (size_t)b * H * W;
-    const float zc = (float)CR;
+    // window normalisers of the staged rows and columns, once per workgroup (an element's is their product)
+    __shared__ float zr[kTileH + kMaxK - 1], zc[kTileW + kMaxK - 1];
+    if (tid < hh) zr[tid] = a.zpad ? 1.f : taps_inside(a.taps, ti - r + tid, H, r);
+    else if (tid >= 64 && tid < 64 + hw) zc[tid - 64] = a.zpad ? 1.f : taps_inside(a.taps, tj - r + tid - 64, W, r);
+    if (OP == kBwdOne || OP == kBwdTwoA) __syncthreads();   // the other passes first use them after phase 1's barrier
+    auto norm_at = [&](int row, int col) { return zr[row - ti + r] * zc[col - tj + r]; };
 
-    // the normaliser of the statistic centred on (row, col)
-    auto norm_at = [&](int row, int col) {
-        return (a.zpad ? 1.f : taps_inside(a.taps, row, H, r) * taps_inside(a.taps, col, W, r)) * zc;
-    };
-
-    // phase 1: one quantity (or two) per statistic of the tile and its halo; zeros outside the image
-    for (int idx = tid; idx < halo * halo * SC; idx += 256) {
-        const int hp = idx / SC, sc = idx - hp * SC;
-        const int hi = hp / halo, hj = hp - hi * halo;
+    // phase 1: the quantity under the window for the tile and its halo; zeros outside the image
+    for (int idx = tid; idx < hh * hw * CBV; idx += 256) {
+        const int hp = idx / CBV, cv = idx - hp * CBV;
+        const int hi = hp / hw, hj = hp - hi * hw;
         const int row = ti - r + hi, col = tj - r + hj;
-        float p1 = 0.f, p2 = 0.f;
-        if (sc < nsc && row >= 0 && row < H && col >= 0 && col < W) {
-            const size_t st = (img + (size_t)row * W + col) * CS + sc0 + sc;
-            const size_t e0 = st * CR;
+        Pack<V> p1, p2;
+#pragma unroll
+        for (int k = 0; k < V; ++k) p1.v[k] = p2.v[k] = 0.f;
+        if (cv < ncv && row >= 0 && row < H && col >= 0 && col < W) {
+            const size_t e = (img + (size_t)row * W + col) * C + c0 + cv * V;
             if (OP == kBwdTwoB) {
-                p1 = a.field[st];
+                p1 = load<V>(a.field + e);
+            } else if (OP == kFwdOne || OP == kMean) {
+                p1 = load<V>(a.x + e);
+            } else if (OP == kDivide) {
+                const Pack<V> xv = load<V>(a.x + e), m = load<V>(a.mu_in + e);
+#pragma unroll
+                for (int k = 0; k < V; ++k) p1.v[k] = xv.v[k] - m.v[k];
             } else {
-                float m = 0.f, rs = 0.f;
-                if (OP == kDivide || OP == kBwdOne || OP == kBwdTwoA) m = a.mu_in[st];
-                if (OP == kBwdOne || OP == kBwdTwoA) rs = a.rstd_in[st];
-                float s1 = 0.f, s2 = 0.f;
-                auto take = [&](float xv, float dv) {
-                    if (OP == kFwdOne) { s1 += xv; s2 += xv * xv; }
-                    if (OP == kMean) s1 += xv;
-                    if (OP == kDivide) s1 += (xv - m) * (xv - m);
-                    if (OP == kBwdOne) { s1 += dv; s2 += dv * (xv - m); }
-                    if (OP == kBwdTwoA) s2 += dv * (xv - m);
-                };
-                constexpr bool kNeedDy = OP == kBwdOne || OP == kBwdTwoA;
-                if ((CR & 3) == 0) {
-                    for (int c = 0; c < CR; c += 4) {
-                        const float4 xv = *(const float4 *)(a.x + e0 + c);
-                        float4 dv = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (kNeedDy) dv = *(const float4 *)(a.dy + e0 + c);
-                        take(xv.x, dv.x); take(xv.y, dv.y); take(xv.z, dv.z); take(xv.w, dv.w);
+                const Pack<V> xv = load<V>(a.x + e), dv = load<V>(a.dy + e), m = load<V>(a.mu_in + e),
+                              rs = load<V>(a.rstd_in + e);
+                const float iz = 1.f / norm_at(row, col);
+#pragma unroll
+                for (int k = 0; k < V; ++k) {
+                    // gradients of this element's window mean and second moment (or variance), over its normaliser
+                    const float bc = rs.v[k] * rs.v[k] * rs.v[k] * dv.v[k] * (xv.v[k] - m.v[k]);
+                    if (OP == kBwdOne) {
+                        p1.v[k] = (bc * m.v[k] - rs.v[k] * dv.v[k]) * iz;
+                        p2.v[k] = bc * iz;
+                    } else {
+                        p1.v[k] = -0.5f * bc * iz;
                     }
-                } else {
-                    for (int c = 0; c < CR; ++c) take(a.x[e0 + c], kNeedDy ? a.dy[e0 + c] : 0.f);
                 }
-                if (OP == kFwdOne) { p1 = s1; p2 = s2; }
-                if (OP == kMean || OP == kDivide) p1 = s1;
-                if (OP == kBwdOne) {
-                    // gradients of this statistic's mean and second moment, already divided by its normaliser
-                    const float z = norm_at(row, col), bc = rs * rs * rs * s2;
-                    p1 = (bc * m - rs * s1) / z;
-                    p2 = bc / z;
-                }
-                if (OP == kBwdTwoA) p1 = -0.5f * rs * rs * rs * s2 / norm_at(row, col);
             }
         }
-        m1[idx] = p1;
-        if (kTwoMaps) m2[idx] = p2;
+        store<V>(m1 + (size_t)idx * V, p1);
+        if (kTwoMaps) store<V>(m2 + (size_t)idx * V, p2);
     }
     __syncthreads();
 
-    // phase 2: window sums for the tile's statistics, then the elementwise pass over what each one owns
-    for (int idx = tid; idx < kTile * kTile * SC; idx += 256) {
-        const int op = idx / SC, sc = idx - op * SC;
-        const int oi = op / kTile, oj = op - oi * kTile;
+    // phase 2: window sums for one pixel and V channels, then that element's output
+    for (int idx = tid; idx < kTileH * kTileW * CBV; idx += 256) {
+        const int op = idx / CBV, cv = idx - op * CBV;
+        const int oi = op / kTileW, oj = op - oi * kTileW;
         const int row = ti + oi, col = tj + oj;
-        if (sc >= nsc || row >= H || col >= W) continue;
-        float s1 = 0.f, s2 = 0.f;
+        if (cv >= ncv || row >= H || col >= W) continue;
+        float s1[V], s2[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) s1[k] = s2[k] = 0.f;
         for (int p = 0; p < a.ks; ++p)
             for (int q = 0; q < a.ks; ++q) {
                 const float wt = a.taps.g[p] * a.taps.g[q];
-                const int h = ((oi + p) * halo + oj + q) * SC + sc;
-                s1 += wt * m1[h];
-                if (kTwoMaps) s2 += wt * m2[h];
+                const int h = (((oi + p) * hw + oj + q) * CBV + cv) * V;
+                const Pack<V> t = load<V>(m1 + h);
+                if (OP == kBwdOne) {
+                    const Pack<V> t2 = load<V>(m2 + h);
+#pragma unroll
+                    for (int k = 0; k < V; ++k) { s1[k] += wt * t.v[k]; s2[k] += wt * t2.v[k]; }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < V; ++k) {
+                        if (OP == kDivide) s1[k] += wt * t.v[k] * t.v[k];
+                        else s1[k] += wt * t.v[k];
+                        if (OP == kFwdOne) s2[k] += wt * t.v[k] * t.v[k];
+                    }
+                }
             }
-        const size_t st = (img + (size_t)row * W + col) * CS + sc0 + sc;
-        const size_t e0 = st * CR;
-        float u = 0.f, v = 0.f;   // the two per-statistic factors of the elementwise pass
-        if (OP == kFwdOne) {
-            const float z = norm_at(row, col);
-            u = s1 / z;
-            v = 1.0f / sqrtf(fmaxf(s2 / z - u * u, 0.f) + a.eps);
-            a.mu_out[st] = u;
-            a.rstd_out[st] = v;
-        }
-        if (OP == kMean) {
-            a.mu_out[st] = s1 / norm_at(row, col);
-            continue;
-        }
-        if (OP == kDivide) {
-            u = a.mu_in[st];
-            v = 1.0f / sqrtf(s1 / norm_at(row, col) + a.eps);
-            a.rstd_out[st] = v;
-        }
-        if (OP == kBwdOne) { u = s1; v = s2; }
-        if (OP == kBwdTwoA || OP == kBwdTwoB) u = s1;
-        float rs = 0.f, m = 0.f, acc = 0.f;
-        if (OP == kBwdOne || OP == kBwdTwoA) rs = a.rstd_in[st];
-        if (OP == kBwdTwoA) m = a.mu_in[st];
-        auto each = [&](float xv, float dv, float ov) -> float {
-            if (OP == kFwdOne || OP == kDivide) return (xv - u) * v;
-            if (OP == kBwdOne) return dv * rs + u - xv * v;
-            if (OP == kBwdTwoA) {
-                const float g = dv * rs + 2.f * (xv - m) * u;
-                acc += g;
-                return g;
+        const size_t e = (img + (size_t)row * W + col) * C + c0 + cv * V;
+        const float z = norm_at(row, col);
+        Pack<V> o;
+        if (OP == kFwdOne || OP == kDivide) {
+            // the element's own x (or x - mu) is still in LDS
+            const Pack<V> ctr = load<V>(m1 + (((oi + r) * hw + oj + r) * CBV + cv) * V);
+            Pack<V> m, rs;
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                if (OP == kFwdOne) {
+                    m.v[k] = s1[k] / z;
+                    rs.v[k] = 1.0f / sqrtf(fmaxf(s2[k] / z - m.v[k] * m.v[k], 0.f) + a.eps);
+                    o.v[k] = (ctr.v[k] - m.v[k]) * rs.v[k];
+                } else {
+                    rs.v[k] = 1.0f / sqrtf(s1[k] / z + a.eps);
+                    o.v[k] = ctr.v[k] * rs.v[k];
+                }
             }
-            return ov - u;   // kBwdTwoB
-        };
-        constexpr bool kNeedX = OP != kBwdTwoB, kNeedDy = OP == kBwdOne || OP == kBwdTwoA, kNeedOut = OP == kBwdTwoB;
-        if ((CR & 3) == 0) {
-            const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int c = 0; c < CR; c += 4) {
-                const float4 xv = kNeedX ? *(const float4 *)(a.x + e0 + c) : zero;
-                const float4 dv = kNeedDy ? *(const float4 *)(a.dy + e0 + c) : zero;
-                const float4 ov = kNeedOut ? *(const float4 *)(a.out + e0 + c) : zero;
-                *(float4 *)(a.out + e0 + c) =
-                    make_float4(each(xv.x, dv.x, ov.x), each(xv.y, dv.y, ov.y), each(xv.z, dv.z, ov.z), each(xv.w, dv.w, ov.w));
+            if (OP == kFwdOne) store<V>(a.mu_out + e, m);
+            store<V>(a.rstd_out + e, rs);
+            store<V>(a.out + e, o);
+        } else if (OP == kMean) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) o.v[k] = s1[k] / z;
+            store<V>(a.mu_out + e, o);
+        } else if (OP == kBwdOne) {
+            const Pack<V> xv = load<V>(a.x + e), dv = load<V>(a.dy + e), rs = load<V>(a.rstd_in + e);
+#pragma unroll
+            for (int k = 0; k < V; ++k) o.v[k] = dv.v[k] * rs.v[k] + s1[k] - xv.v[k] * s2[k];
+            store<V>(a.out + e, o);
+        } else if (OP == kBwdTwoA) {
+            const Pack<V> xv = load<V>(a.x + e), dv = load<V>(a.dy + e), m = load<V>(a.mu_in + e),
+                          rs = load<V>(a.rstd_in + e);
+            Pack<V> f;
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                o.v[k] = dv.v[k] * rs.v[k] + 2.f * (xv.v[k] - m.v[k]) * s1[k];
+                f.v[k] = o.v[k] / z;
             }
-        } else {
-            for (int c = 0; c < CR; ++c)
-                a.out[e0 + c] = each(kNeedX ? a.x[e0 + c] : 0.f, kNeedDy ? a.dy[e0 + c] : 0.f, kNeedOut ? a.out[e0 + c] : 0.f);
+            store<V>(a.out + e, o);
+            store<V>(a.field + e, f);
+        } else {   // kBwdTwoB
+            const Pack<V> dv = load<V>(a.out + e);
+#pragma unroll
+            for (int k = 0; k < V; ++k) o.v[k] = dv.v[k] - s1[k];
+            store<V>(a.out + e, o);
         }
-        if (OP == kBwdTwoA) a.field[st] = acc / norm_at(row, col);
     }
 }
 
@@ -191,23 +212,30 @@ bool make_taps(int ks, float sigma, Taps *t) {
     return true;
 }
 
-template <int OP>
-int launch_pass(Args a, int B, hipStream_t s, const char *where) {
-    const int tiles_h = (a.H + kTile - 1) / kTile;
-    a.tiles_w = (a.W + kTile - 1) / kTile;
+template <int OP, int V>
+int launch_pass_v(Args a, int B, hipStream_t s, const char *where) {
+    const int tiles_h = (a.H + kTileH - 1) / kTileH;
+    a.tiles_w = (a.W + kTileW - 1) / kTileW;
     a.tiles_per_img = tiles_h * a.tiles_w;
-    a.SC = a.CS < kMaxStatsPerBlock ? a.CS : kMaxStatsPerBlock;
-    a.nchunk = (a.CS + a.SC - 1) / a.SC;
+    const int maps = OP == kBwdOne ? 2 : 1;
+    const size_t per_channel = (size_t)(kTileH + a.ks - 1) * (kTileW + a.ks - 1) * maps * sizeof(float);
+    // whole 128-byte lines of a pixel where LDS allows; never fewer than V channels (at most 10.6 KB then)
+    a.CB = a.C < 32 ? a.C : 32;
+    while (a.CB > V && a.CB * per_channel > (size_t)kLdsTarget) a.CB = (a.CB / 2 + V - 1) / V * V;
+    a.nchunk = (a.C + a.CB - 1) / a.CB;
     const long long nblk = (long long)B * a.tiles_per_img * a.nchunk;
     if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
-    const int halo = kTile + a.ks - 1;
-    const bool two_maps = OP == kFwdOne || OP == kBwdOne;
-    const size_t lds = (size_t)halo * halo * a.SC * sizeof(float) * (two_maps ? 2 : 1);   // at most 57.6 KB
-    auto kern = lcn_variant_kernel<OP>;
+    const size_t lds = a.CB * per_channel;
+    auto kern = lcn_channel_kernel<OP, V>;
     if (int rc = allow_dynamic_lds((const void *)kern, lds, where)) return rc;
     hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), lds, s, a);
     LC_HIP_LAUNCH_CHECK(where);
     return LC_OK;
+}
+
+template <int OP>
+int launch_pass(const Args &a, int B, hipStream_t s, const char *where) {
+    return a.C % 4 == 0 ? launch_pass_v<OP, 4>(a, B, s, where) : launch_pass_v<OP, 1>(a, B, s, where);
 }
 
 }  // namespace
@@ -220,12 +248,15 @@ size_t lcn_variant_scratch_bytes(int B, int H, int W, int C, unsigned flags) {
 int launch_lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int B, int H, int W, int C, int ks,
                            float sigma, float eps, unsigned flags, hipStream_t s) {
     const bool pc = flags & LCN_PER_CHANNEL, zp = flags & LCN_ZERO_PAD, two = flags & LCN_TWO_STAGE;
-    // pooled one-stage statistics: the wavefront-reduction kernels of the default form
-    if (!pc && !two) return launch_lcn(0, x, nullptr, y, mu, rstd, B, H, W, C, ks, sigma, eps, s, zp);
+    if (!pc) {
+        if (!two) return launch_lcn(0, x, nullptr, y, mu, rstd, B, H, W, C, ks, sigma, eps, s, zp);
+        if (int rc = launch_lcn(2, x, nullptr, y, mu, rstd, B, H, W, C, ks, sigma, eps, s, zp)) return rc;
+        return launch_lcn(3, x, nullptr, y, mu, rstd, B, H, W, C, ks, sigma, eps, s, zp);
+    }
     Args a{};
     if (!make_taps(ks, sigma, &a.taps)) return LC_EINVAL;
     a.x = x; a.out = y; a.mu_out = mu; a.rstd_out = rstd; a.mu_in = mu;
-    a.H = H; a.W = W; a.CS = pc ? C : 1; a.CR = pc ? 1 : C; a.ks = ks; a.zpad = zp; a.eps = eps;
+    a.H = H; a.W = W; a.C = C; a.ks = ks; a.zpad = zp; a.eps = eps;
     if (!two) return launch_pass<kFwdOne>(a, B, s, "lcn_variant_fwd");
     if (int rc = launch_pass<kMean>(a, B, s, "lcn_variant_fwd (mean)")) return rc;
     return launch_pass<kDivide>(a, B, s, "lcn_variant_fwd (divide)");
@@ -234,16 +265,18 @@ int launch_lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int
 int launch_lcn_variant_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int B, int H,
                            int W, int C, int ks, float sigma, unsigned flags, void *ws, size_t ws_bytes, hipStream_t s) {
     const bool pc = flags & LCN_PER_CHANNEL, zp = flags & LCN_ZERO_PAD, two = flags & LCN_TWO_STAGE;
-    if (!pc && !two)
-        return launch_lcn(1, x, dy, dx, const_cast<float *>(mu), const_cast<float *>(rstd), B, H, W, C, ks, sigma, 0.f, s,
-                          zp);
+    if (two && (ws == nullptr || ws_bytes < lcn_variant_scratch_bytes(B, H, W, C, flags))) return LC_EWORKSPACE;
+    float *mu_ = const_cast<float *>(mu), *rstd_ = const_cast<float *>(rstd);   // read only in these modes
+    if (!pc) {
+        if (!two) return launch_lcn(1, x, dy, dx, mu_, rstd_, B, H, W, C, ks, sigma, 0.f, s, zp);
+        if (int rc = launch_lcn(4, x, dy, dx, mu_, rstd_, B, H, W, C, ks, sigma, 0.f, s, zp, (float *)ws)) return rc;
+        return launch_lcn(5, x, dy, dx, mu_, rstd_, B, H, W, C, ks, sigma, 0.f, s, zp, (float *)ws);
+    }
     Args a{};
     if (!make_taps(ks, sigma, &a.taps)) return LC_EINVAL;
-    a.x = x; a.dy = dy; a.mu_in = mu; a.rstd_in = rstd; a.out = dx;
-    a.H = H; a.W = W; a.CS = pc ? C : 1; a.CR = pc ? 1 : C; a.ks = ks; a.zpad = zp;
+    a.x = x; a.dy = dy; a.mu_in = mu; a.rstd_in = rstd; a.out = dx; a.field = (float *)ws;
+    a.H = H; a.W = W; a.C = C; a.ks = ks; a.zpad = zp;
     if (!two) return launch_pass<kBwdOne>(a, B, s, "lcn_variant_bwd");
-    if (ws == nullptr || ws_bytes < lcn_variant_scratch_bytes(B, H, W, C, flags)) return LC_EWORKSPACE;
-    a.field = (float *)ws;
     if (int rc = launch_pass<kBwdTwoA>(a, B, s, "lcn_variant_bwd (dv)")) return rc;
     return launch_pass<kBwdTwoB>(a, B, s, "lcn_variant_bwd (mean)");
 }

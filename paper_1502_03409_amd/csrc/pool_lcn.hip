@@ -276,13 +276,20 @@ __device__ __forceinline__ float tap_norm(const GaussTaps &t, int p, int n, int 
     return z;
 }
 
-// MODE 0: forward.  MODE 1: backward (x, mu, rstd, dy -> dx).
+// Statistics pooled over the channels.  One-stage form: MODE 0 forward, MODE 1 backward (x, mu, rstd, dy -> dx).
+// Two-stage form (subtract the window mean, divide by the root of the window mean of the neighbours' own squared
+// differences) as two passes each way:
+//   MODE 2  x -> mu;                          MODE 3  x, mu -> rstd, y = (x - mu) rstd;
+//   MODE 4  x, mu, rstd, dy -> dv (into out) and field[p] = sum_c dv[p,c] / normaliser(p);
+//   MODE 5  out = dv - window sum of field (in place).
 template <int VEC, int MODE>
 __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, const float *__restrict__ dy,
                                                   float *__restrict__ out, float *__restrict__ mu,
-                                                  float *__restrict__ rstd, int H, int W, int C, int ks, float eps,
-                                                  GaussTaps taps, int lpp, int tiles_w, int tiles_per_img, int zpad) {
-    __shared__ float m1[kLcnHalo * kLcnHalo], m2[kLcnHalo * kLcnHalo];
+                                                  float *__restrict__ rstd, float *__restrict__ field, int H, int W,
+                                                  int C, int ks, float eps, GaussTaps taps, int lpp, int tiles_w,
+                                                  int tiles_per_img, int zpad) {
+    constexpr bool kTwoMaps = MODE == 0 || MODE == 1;
+    __shared__ float m1[kLcnHalo * kLcnHalo], m2[kTwoMaps ? kLcnHalo * kLcnHalo : 1];
     __shared__ float t1[kLcnTile * kLcnTile], t2[kLcnTile * kLcnTile];
     const int r = (ks - 1) / 2, halo = kLcnTile + 2 * r;
     const int tid = threadIdx.x;
@@ -290,6 +297,12 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
     const int ti = (tile / tiles_w) * kLcnTile, tj = (tile % tiles_w) * kLcnTile;
     const int CV = C / VEC;
     const size_t img = (size_t)b * H * W;
+    // window normalisers of the staged rows and columns, once per workgroup (a pixel's is their product times C)
+    __shared__ float zr[kLcnHalo], zc[kLcnHalo];
+    if (tid < halo) zr[tid] = zpad ? 1.f : tap_norm(taps, ti - r + tid, H, r);
+    else if (tid >= 64 && tid < 64 + halo) zc[tid - 64] = zpad ? 1.f : tap_norm(taps, tj - r + tid - 64, W, r);
+    if (MODE == 1 || MODE == 4) __syncthreads();   // the other modes first use them after phase 1's barrier
+    auto norm_at = [&](int row, int col) { return zr[row - ti + r] * zc[col - tj + r] * (float)C; };
 
     // phase 1: per-pixel channel sums over the tile and its halo; lpp lanes share a pixel
     const int grp = tid / lpp, gl = tid % lpp, ngrp = 256 / lpp;
@@ -298,24 +311,27 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
         const int row = ti - r + hi, col = tj - r + hj;
         float a = 0.f, c2 = 0.f;
         const bool in = row >= 0 && row < H && col >= 0 && col < W;
-        // backward: the pixel's own statistics are fetched with its values, not after the reduction
+        // the pixel's own statistics are fetched with its values, not after the reduction
         float mp = 0.f, rsp = 0.f;
-        if (MODE == 1 && in) {
-            mp = mu[img + (size_t)row * W + col];
-            rsp = rstd[img + (size_t)row * W + col];
-        }
-        if (in) {
+        if ((MODE == 1 || MODE == 3 || MODE == 4) && in) mp = mu[img + (size_t)row * W + col];
+        if ((MODE == 1 || MODE == 4) && in) rsp = rstd[img + (size_t)row * W + col];
+        if (MODE == 5) {
+            if (in) a = field[img + (size_t)row * W + col];
+        } else if (in) {
             const size_t pix = img + (size_t)row * W + col;
             const float *xp = x + pix * C;
-            if (MODE == 0) {
+            if (MODE == 0 || MODE == 2 || MODE == 3) {
                 for (int cv = gl; cv < CV; cv += lpp) {
-                    if (VEC == 4) {
-                        const float4 v = *(const float4 *)(xp + cv * 4);
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (VEC == 4) v = *(const float4 *)(xp + cv * 4);
+                    else v.x = xp[cv];
+                    if (MODE == 3) {   // squared differences from the pixel's own mean (unused lanes of v stay out)
+                        v.x -= mp;
+                        if (VEC == 4) { v.y -= mp; v.z -= mp; v.w -= mp; }
+                        a += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+                    } else {
                         a += (v.x + v.y) + (v.z + v.w);
                         c2 += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
-                    } else {
-                        a += xp[cv];
-                        c2 += xp[cv] * xp[cv];
                     }
                 }
             } else {
@@ -332,24 +348,29 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
                 }
             }
         }
-        a = group_sum(a, lpp);
-        c2 = group_sum(c2, lpp);
+        if (MODE != 5) a = group_sum(a, lpp);
+        if (MODE == 0 || MODE == 1 || MODE == 4) c2 = group_sum(c2, lpp);
         if (gl == 0) {
             if (MODE == 0) {
                 m1[hp] = a;
                 m2[hp] = c2;
-            } else {
+            } else if (MODE == 1) {
                 // backward: fold this pixel's own normaliser and statistics into the two maps the
                 // transposed window sums need
                 float p1 = 0.f, p2 = 0.f;
                 if (in) {
-                    const float z = (zpad ? 1.f : tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r)) * (float)C;
+                    const float z = norm_at(row, col);
                     const float bc = rsp * rsp * rsp * c2;
                     p1 = (bc * mp - rsp * a) / z;
                     p2 = bc / z;
                 }
                 m1[hp] = p1;
                 m2[hp] = p2;
+            } else if (MODE == 4) {
+                // gradient of this pixel's variance, divided by its normaliser
+                m1[hp] = in ? -0.5f * rsp * rsp * rsp * c2 / norm_at(row, col) : 0.f;
+            } else {
+                m1[hp] = a;
             }
         }
     }
@@ -366,17 +387,24 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
                     const float wt = taps.g[p] * taps.g[q];
                     const int hp = (oi + p) * halo + oj + q;
                     s1 += wt * m1[hp];   // out-of-image halo entries are zero
-                    s2 += wt * m2[hp];
+                    if (kTwoMaps) s2 += wt * m2[hp];
                 }
+            const size_t pix = img + (size_t)row * W + col;
             if (MODE == 0) {
-                const float z = (zpad ? 1.f : tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r)) * (float)C;
+                const float z = norm_at(row, col);
                 const float m = s1 / z, q2 = s2 / z;
                 const float var = fmaxf(q2 - m * m, 0.f);
                 const float rs = 1.0f / sqrtf(var + eps);
-                const size_t pix = img + (size_t)row * W + col;
                 mu[pix] = m;
                 rstd[pix] = rs;
                 t1[tid] = m;
+                t2[tid] = rs;
+            } else if (MODE == 2) {
+                mu[pix] = s1 / norm_at(row, col);
+            } else if (MODE == 3) {
+                const float rs = 1.0f / sqrtf(s1 / norm_at(row, col) + eps);
+                rstd[pix] = rs;
+                t1[tid] = mu[pix];
                 t2[tid] = rs;
             } else {
                 t1[tid] = s1;
@@ -384,7 +412,37 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
             }
         }
     }
+    if (MODE == 2) return;
     __syncthreads();
+
+    if (MODE == 4) {
+        // phase 3 of the two-stage gradient: a pixel's lanes write dv and reduce it over the channels
+        for (int op = grp; op < kLcnTile * kLcnTile; op += ngrp) {
+            const int oi = op / kLcnTile, oj = op % kLcnTile;
+            const int row = ti + oi, col = tj + oj;
+            if (row >= H || col >= W) continue;   // uniform over the group
+            const size_t pix = img + (size_t)row * W + col;
+            const float rs = rstd[pix], m = mu[pix], gs = 2.f * t1[op];
+            float acc = 0.f;
+            for (int cv = gl; cv < CV; cv += lpp) {
+                const size_t o = pix * C + cv * VEC;
+                if (VEC == 4) {
+                    const float4 xv = *(const float4 *)(x + o), d = *(const float4 *)(dy + o);
+                    const float4 g = make_float4(d.x * rs + (xv.x - m) * gs, d.y * rs + (xv.y - m) * gs,
+                                                 d.z * rs + (xv.z - m) * gs, d.w * rs + (xv.w - m) * gs);
+                    *(float4 *)(out + o) = g;
+                    acc += (g.x + g.y) + (g.z + g.w);
+                } else {
+                    const float g = dy[o] * rs + (x[o] - m) * gs;
+                    out[o] = g;
+                    acc += g;
+                }
+            }
+            acc = group_sum(acc, lpp);
+            if (gl == 0) field[pix] = acc / norm_at(row, col);
+        }
+        return;
+    }
 
     // phase 3: elementwise pass over the tile
     for (int e = tid; e < kLcnTile * kLcnTile * CV; e += 256) {
@@ -395,14 +453,14 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
         const size_t pix = img + (size_t)row * W + col;
         const size_t o = pix * C + cv * VEC;
         const float u = t1[op], v = t2[op];
-        if (MODE == 0) {
+        if (MODE == 0 || MODE == 3) {
             if (VEC == 4) {
                 const float4 xv = *(const float4 *)(x + o);
                 *(float4 *)(out + o) = make_float4((xv.x - u) * v, (xv.y - u) * v, (xv.z - u) * v, (xv.w - u) * v);
             } else {
                 out[o] = (x[o] - u) * v;
             }
-        } else {
+        } else if (MODE == 1) {
             const float rs = rstd[pix];
             if (VEC == 4) {
                 const float4 xv = *(const float4 *)(x + o), d = *(const float4 *)(dy + o);
@@ -410,6 +468,13 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
                                                    d.z * rs + u - xv.z * v, d.w * rs + u - xv.w * v);
             } else {
                 out[o] = dy[o] * rs + u - x[o] * v;
+            }
+        } else {   // MODE 5
+            if (VEC == 4) {
+                const float4 d = *(const float4 *)(out + o);
+                *(float4 *)(out + o) = make_float4(d.x - u, d.y - u, d.z - u, d.w - u);
+            } else {
+                out[o] -= u;
             }
         }
     }
@@ -432,6 +497,10 @@ __global__ __launch_bounds__(256) void lcn_fwd_cached_kernel(const float *__rest
     const int b = blockIdx.x / tiles_per_img, tile = blockIdx.x - b * tiles_per_img;
     const int ti = (tile / tiles_w) * kLcnTile, tj = (tile % tiles_w) * kLcnTile;
     const size_t img = (size_t)b * H * W;
+    // window normalisers of the tile's rows and columns (read after phase 1's barrier)
+    __shared__ float zr[kLcnTile], zc[kLcnTile];
+    if (tid < kLcnTile) zr[tid] = zpad ? 1.f : tap_norm(taps, ti + tid, H, r);
+    else if (tid >= 64 && tid < 64 + kLcnTile) zc[tid - 64] = zpad ? 1.f : tap_norm(taps, tj + tid - 64, W, r);
 
     // one halo pixel's channel sums -> the two maps of phase 2 (lane 0 of the group writes)
     auto put = [&](int hp, const float4 &v) {
@@ -483,7 +552,7 @@ __global__ __launch_bounds__(256) void lcn_fwd_cached_kernel(const float *__rest
                     s1 += wt * m1[hp];   // out-of-image halo entries are zero
                     s2 += wt * m2[hp];
                 }
-            const float z = (zpad ? 1.f : tap_norm(taps, row, H, r) * tap_norm(taps, col, W, r)) * (float)C;
+            const float z = zr[oi] * zc[oj] * (float)C;
             const float m = s1 / z, q2 = s2 / z;
             const float var = fmaxf(q2 - m * m, 0.f);
             const float rs = 1.0f / sqrtf(var + eps);
@@ -595,27 +664,34 @@ int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx
 }
 
 int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
-               int C, int ks, float sigma, float eps, hipStream_t s, int zero_pad) {
+               int C, int ks, float sigma, float eps, hipStream_t s, int zero_pad, float *field) {
     GaussTaps taps;
     if (!make_taps(ks, sigma, &taps)) return LC_EINVAL;
+    if (mode < 0 || mode > 5 || ((mode == 4 || mode == 5) && field == nullptr)) return LC_EINVAL;
     const int tiles_h = (H + kLcnTile - 1) / kLcnTile, tiles_w = (W + kLcnTile - 1) / kLcnTile;
     const long long nblk = (long long)B * tiles_h * tiles_w;
     if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
     const int vec = (C % 4 == 0) ? 4 : 1;
     const int lpp = lanes_per_pixel(C / vec);
     dim3 grid((unsigned)nblk), block(256);
-#define LC_LCN(VEC_, MODE_)                                                                                       \
-    hipLaunchKernelGGL((lcn_kernel<VEC_, MODE_>), grid, block, 0, s, x, dy, out, mu, rstd, H, W, C, ks, eps, taps, \
-                       lpp, tiles_w, tiles_h * tiles_w, zero_pad)
+#define LC_LCN(VEC_, MODE_)                                                                                      \
+    hipLaunchKernelGGL((lcn_kernel<VEC_, MODE_>), grid, block, 0, s, x, dy, out, mu, rstd, field, H, W, C, ks, eps, \
+                       taps, lpp, tiles_w, tiles_h * tiles_w, zero_pad)
+#define LC_LCN_MODE(MODE_) do { if (vec == 4) LC_LCN(4, MODE_); else LC_LCN(1, MODE_); } while (0)
 #define LC_LCN_CACHED(LPP_)                                                                                    \
     hipLaunchKernelGGL((lcn_fwd_cached_kernel<LPP_>), grid, block, 0, s, x, out, mu, rstd, H, W, ks, eps, taps, \
                        tiles_w, tiles_h * tiles_w, zero_pad)
     if (mode == 0 && C == 32) LC_LCN_CACHED(8);
     else if (mode == 0 && C == 16) LC_LCN_CACHED(4);
     else if (mode == 0 && C == 8) LC_LCN_CACHED(2);
-    else if (mode == 0) { if (vec == 4) LC_LCN(4, 0); else LC_LCN(1, 0); }
-    else                { if (vec == 4) LC_LCN(4, 1); else LC_LCN(1, 1); }
+    else if (mode == 0) LC_LCN_MODE(0);
+    else if (mode == 1) LC_LCN_MODE(1);
+    else if (mode == 2) LC_LCN_MODE(2);
+    else if (mode == 3) LC_LCN_MODE(3);
+    else if (mode == 4) LC_LCN_MODE(4);
+    else LC_LCN_MODE(5);
 #undef LC_LCN_CACHED
+#undef LC_LCN_MODE
 #undef LC_LCN
     LC_HIP_LAUNCH_CHECK("lcn launch");
     return LC_OK;
