@@ -358,6 +358,36 @@ def bench_others(lc, wl, torch, iters):
                                     "shape": dict(zip("BHWCRSF", g.as_tuple()))}
     del x, w, b, h, ws
     torch.cuda.empty_cache()
+
+    # the LCN variants at cfg3's shape (flags: 1 per-channel statistics, 2 zero-padded borders, 4 two stages)
+    g = wl.CONFIG_GEOM["cfg3"]
+    shape = (g.B, (g.LH - wl.POOL_KSIZE) // wl.POOL_STRIDE + 1, (g.LW - wl.POOL_KSIZE) // wl.POOL_STRIDE + 1, g.F)
+    x, dy = torch.randn(shape, device="cuda"), torch.randn(shape, device="cuda")
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    entry = {"shape": list(shape), "ksize": wl.LCN_KSIZE}
+    for flags in range(8):
+        stat = shape if flags & lc.LCN_PER_CHANNEL else shape[:3]
+        mu, rstd = torch.empty(stat, device="cuda"), torch.empty(stat, device="cuda")
+        nws = lc.lcn_variant_workspace_bytes(shape, flags)
+        ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+        fns = {"fwd": (lambda: lc.lcn_variant_fwd(x, y, mu, rstd, wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS, flags),
+                       4 * (2 * x.numel() + 2 * mu.numel())),
+               "bwd": (lambda: lc.lcn_variant_bwd(x, mu, rstd, dy, dx, wl.LCN_KSIZE, wl.LCN_SIGMA, flags, ws),
+                       4 * (3 * x.numel() + 2 * mu.numel()))}
+        e = {}
+        for kn, (f, nbytes) in fns.items():
+            for _ in range(2):
+                f()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(iters):
+                f()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / iters
+            e[kn] = {"us": round(ms * 1e3, 1), "frac_hbm_roof": round(nbytes / (HBM_PEAK_GBS * 1e9) / (ms * 1e-3), 4)}
+        entry[f"flags{flags}"] = e
+    res["lcn_variants_cfg3"] = entry
     return res
 
 
