@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sae", action="store_true")
     ap.add_argument("--no-others", action="store_true",
@@ -181,7 +181,7 @@ def main() -> int:
 
     # ---------------------------------------------------------------- the three contractions on the other shapes
     if not args.no_others:
-        out["other_workloads"] = bench_others(lc, wl, torch, max(3, args.steps // 4))
+        out["other_workloads"] = bench_others(lc, wl, torch, min(50, max(3, args.steps // 4)))
 
     # ---------------------------------------------------------------- CPU oracle, as a scale reference
     if not args.no_cpu_baseline:
@@ -283,6 +283,25 @@ def bench_sae(lc, wl, np, torch, dev, steps, warmup):
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 
 
+def timed_ms(torch, stream, f, iters, warm_ms=60.0):
+    """Average duration of f() in ms between two HIP events on `stream`, after at least warm_ms of the same work:
+    the GPU's clocks take some tens of milliseconds of load to settle, and the first calls run up to 15 % slower."""
+    f()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < warm_ms:
+        for _ in range(4):
+            f()
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(iters):
+        f()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
 def bench_others(lc, wl, torch, iters):
     """lc_forward / lc_backward_data / lc_backward_weights alone on the other workloads (random device
     tensors of the workload's shape; parity at these shapes is the tests' business), HIP events on the
@@ -313,15 +332,7 @@ def bench_others(lc, wl, torch, iters):
         peak = BF16_MFMA_PEAK_TFLOPS if dt == "bf16" else FP32_MFMA_PEAK_TFLOPS
         entry, total = {}, 0.0
         for kn, f in fns.items():
-            for _ in range(2):
-                f()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(iters):
-                f()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / iters
+            ms = timed_ms(torch, stream, f, iters)
             total += ms
             tf = g.flop_per_pass / (ms * 1e-3) / 1e12
             entry[kn] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1), "frac_mfma_peak": round(tf / peak, 4),
@@ -343,15 +354,7 @@ def bench_others(lc, wl, torch, iters):
     h = torch.empty((g.B, g.LH, g.LW, g.F), device="cuda")
     ws = torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda")
     f = lambda: lc.sae_step(G, x, w, b, a, wl.SAE_LAMBDA, wl.SAE_EPS, wl.SAE_LR, 0, h, cost, ws)
-    for _ in range(2):
-        f()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(iters):
-        f()
-    e1.record(stream)
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / iters
+    ms = timed_ms(torch, stream, f, iters)
     tf = 5 * g.flop_per_pass / (ms * 1e-3) / 1e12
     res["paper_layer1_sae_step"] = {"ms": round(ms, 3), "images_per_s": round(g.B / (ms * 1e-3), 1),
                                     "TFLOP/s": round(tf, 1), "frac_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4),
@@ -376,15 +379,7 @@ def bench_others(lc, wl, torch, iters):
                        4 * (3 * x.numel() + 2 * mu.numel()))}
         e = {}
         for kn, (f, nbytes) in fns.items():
-            for _ in range(2):
-                f()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(iters):
-                f()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / iters
+            ms = timed_ms(torch, stream, f, iters)
             e[kn] = {"us": round(ms * 1e3, 1), "frac_hbm_roof": round(nbytes / (HBM_PEAK_GBS * 1e9) / (ms * 1e-3), 4)}
         entry[f"flags{flags}"] = e
     res["lcn_variants_cfg3"] = entry

@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
 template <int MT, int NT, int NCELL, int AP, int NW = 4>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_kernel(
     Geom g, const float *__restrict__ dy, const float *__restrict__ w, float *__restrict__ dx, int strips_per_row,
-    int RS, int work_offset, int nbt) {
+    int RS, int nbt) {
     typedef const __attribute__((address_space(1))) f32x4 *g4_ptr;
     typedef const __attribute__((address_space(1))) float *gf_ptr;
     typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -171,11 +171,30 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, kk = lane >> 4;
     const int SC = g.S * g.C, NCV = g.S * SC;
-    // batch tiles of one strip are neighbours in dispatch order on the same XCD: the second one finds
-    // the strip's weights in that XCD's L2
-    const int t_id = remap_xcd(blockIdx.x, gridDim.x);
-    const int work = work_offset + t_id / nbt;
-    const int ri = work / strips_per_row, wi0 = (work - ri * strips_per_row) * NCELL;
+    // Work order.  Cell rows that all AP field rows cover cost the same and come first: each XCD walks a
+    // contiguous range of them, and the batch tiles of one strip are neighbours in that order, so the second
+    // one finds the strip's weights in that XCD's L2.  The rows at the top and bottom edge, covered by fewer
+    // field rows and cheaper in proportion, come last in plain hardware order, which deals them out evenly:
+    // in one contiguous walk the XCDs holding the edge rows would run dry while the others still work.
+#ifdef LC_ABL_PLAIN_ORDER
+    const int r_lo = 0, n_in = 0;
+#else
+    const int r_lo = AP - 1, n_in = g.LH > r_lo ? g.LH - r_lo : 0;   // interior cell rows [r_lo, LH)
+#endif
+    const int per_row = strips_per_row * nbt, n_first = n_in * per_row;
+    int ri, t_id;
+    if ((int)blockIdx.x < n_first) {
+        t_id = remap_xcd(blockIdx.x, n_first);
+        ri = r_lo + t_id / per_row;
+    } else if (n_in > 0) {
+        t_id = blockIdx.x - n_first;
+        const int rb = t_id / per_row;
+        ri = rb < r_lo ? rb : g.LH + (rb - r_lo);
+    } else {
+        t_id = remap_xcd(blockIdx.x, gridDim.x);
+        ri = t_id / per_row;
+    }
+    const int wi0 = ((t_id / nbt) % strips_per_row) * NCELL;
     const int b0 = (t_id % nbt) * BT;
     const int wc = wave % NCELL;
     const int wi = wi0 + wc;
@@ -373,7 +392,7 @@ int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipSt
     const int nblk = (NW / NCELL) * NT * 16;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(strips * CH * nbt, (NCV + nblk - 1) / nblk);
-    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, g, dy, w, dx, strips, RS, 0, nbt);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, g, dy, w, dx, strips, RS, nbt);
     LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
     return LC_OK;
 }
