@@ -76,6 +76,7 @@ SMALL = {
     "wide_bd_c64": (wl.LCGeom(B=80, H=11, W=13, C=64, R=4, S=2, F=64), "halfnormal"),  # workgroup-tiled backward data, uncovered edge
     "bd_ap4_n48": (wl.LCGeom(B=72, H=28, W=32, C=3, R=16, S=4, F=32), "pink"),       # 4x4 covering fields, 48-value cells
     "bd_ap3_n48": (wl.LCGeom(B=72, H=20, W=24, C=3, R=12, S=4, F=16), "pink"),       # 3x3 covering fields
+    "bd_ap4_wide": (wl.LCGeom(B=72, H=24, W=262, C=3, R=16, S=4, F=16), "pink"),     # 66 cells per row: eight cells per workgroup, ragged last strip
     "dense_small": (wl.LCGeom(B=80, H=24, W=24, C=8, R=24, S=1, F=128), "halfnormal"),  # one field: contraction cut into slices
     "dense_k16": (wl.LCGeom(B=72, H=12, W=12, C=4, R=12, S=1, F=128), "halfnormal"),    # one field, 16-value chunks
     "wide_k16": (wl.LCGeom(B=72, H=14, W=16, C=4, R=4, S=2, F=128), "halfnormal"),      # 16-value chunks, many fields
