@@ -157,14 +157,15 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
 // of image m from LDS, so component t of both vectors is contraction index 4kk+t of MFMA number t.
 // Fields outside the grid are staged as zeros (their weights are read from a clamped, valid address),
 // so the inner loop has no branches.
-template <int MT, int NT, int NCELL, int AP, int NW = 4>
+template <int MT, int NT, int NCELL, int AP, int NW = 4, typename T = float>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_kernel(
-    Geom g, const float *__restrict__ dy, const float *__restrict__ w, float *__restrict__ dx, int strips_per_row,
+    Geom g, const T *__restrict__ dy, const T *__restrict__ w, float *__restrict__ dx, int strips_per_row,
     int RS, int nbt) {
-    typedef const __attribute__((address_space(1))) f32x4 *g4_ptr;
-    typedef const __attribute__((address_space(1))) float *gf_ptr;
+    typedef typename RawVec<T, 4>::V XV;      // four consecutive dy or w values as loaded (fp32, or bf16 bit patterns)
+    typedef const __attribute__((address_space(1))) XV *g4_ptr;
+    typedef const __attribute__((address_space(1))) T *gf_ptr;
     typedef float f32x2 __attribute__((ext_vector_type(2)));
-    constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 4;   // R4: dwordx4 per image and chunk
+    constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 4;   // R4: 4-element vectors per image and chunk
     constexpr int NTHR = 64 * NW;                                   // NW waves: NCELL cells x NW/NCELL value blocks
     constexpr int NSLOT = (BT * R4 + NTHR - 1) / NTHR;
     extern __shared__ __attribute__((aligned(16))) float dys[];
@@ -225,15 +226,15 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
 
     const int v0 = tid % R4, bq0 = tid / R4;
     constexpr int DV = NTHR % R4, DB = NTHR / R4;
-    f32x4 st[NSLOT];
+    XV st[NSLOT];
     auto stage_load = [&](int c) {
         const int a = a_lo + c / nfh, fh = c - (c / nfh) * nfh;
-        const float *base = dy + (size_t)b0 * dyimg + (size_t)((ri - a) * g.LW) * g.F + fh * 16;
+        const T *base = dy + (size_t)b0 * dyimg + (size_t)((ri - a) * g.LW) * g.F + fh * 16;
         int v = v0, b = bq0;
 #pragma unroll
         for (int q = 0; q < NSLOT; ++q) {
             const int j = jlo + (v >> 2);
-            f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
+            XV t = XV{};
             if (b < BT && b0 + b < g.B && j >= 0 && j < g.LW)
                 t = *(g4_ptr)(base + (size_t)b * dyimg + j * g.F + (v & 3) * 4);
             st[q] = t;
@@ -248,8 +249,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
             if (b < BT) {
                 // two 8-byte stores: 16-byte LDS stores of a row-major tile run into bank conflicts
                 float *dst = dys + buf * BT * RS + b * RS + v * 4;
-                *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
-                *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
+                const f32x4 f = raw_widen4<T>(st[q]);
+                *(f32x2 *)dst = (f32x2){f[0], f[1]};
+                *(f32x2 *)(dst + 2) = (f32x2){f[2], f[3]};
             }
             v += DV; b += DB;
             if (v >= R4) { v -= R4; ++b; }
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     if (nchunks > 0) {
         // weight ring: slot a' holds the weights of step a' of the current chunk and is refilled, right
         // after its use, with step a' of the next chunk: loads run one whole chunk ahead of the MFMAs
-        f32x4 wb[AP][NT];
+        XV wb[AP][NT];
 #pragma unroll
         for (int ap = 0; ap < AP; ++ap) {
             gf_ptr p0 = wbase(0, ap);
@@ -296,7 +298,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
                         for (int t = 0; t < 4; ++t)
 #pragma unroll
                             for (int nt = 0; nt < NT; ++nt)
-                                acc[mt][nt] = mfma16(av[t], wb[ap][nt][t], acc[mt][nt]);
+                                acc[mt][nt] = mfma16(av[t], raw_get<T, 4>(wb[ap][nt], t), acc[mt][nt]);
                     }
                 }
                 gf_ptr pn = wbase(cn, ap);
@@ -379,14 +381,14 @@ int launch_mt(const Geom &g, const float *dy, const float *w, float *dx, hipStre
 
 namespace {
 
-template <int MT, int NT, int NCELL, int AP, int NW = 4>
-int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+template <int MT, int NT, int NCELL, int AP, int NW = 4, typename T>
+int launch_fast(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s) {
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int NCV = g.S * g.S * g.C;
     const int RS = ((JW * 16 + 31) / 32) * 32 + 4;
     const size_t lds = (size_t)2 * BT * RS * sizeof(float);      // two buffers
-    auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP, NW>;
+    auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP, NW, T>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
     const int strips = (CW + NCELL - 1) / NCELL;
     const int nblk = (NW / NCELL) * NT * 16;
@@ -397,16 +399,15 @@ int launch_fast(const Geom &g, const float *dy, const float *w, float *dx, hipSt
     return LC_OK;
 }
 
-}  // namespace
-
-int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
-    // cells of 128-value blocks: one cell per workgroup, dy through LDS, 128 x 128 output tiles
-    if (backward_data_wide_supported(g) || backward_data_dense_supported(g))
-        return launch_backward_data_wide_f32(g, dy, w, dx, s);
+// The pipelined kernel for filters in blocks of 16 and fields that tile the cells exactly; *done tells whether a
+// kernel was launched.  T = float or bf16_t (bf16 storage widened on the way in).
+template <typename T>
+int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s, bool *done) {
+    *done = false;
     // pipelined kernel: filters in blocks of 16, fields that tile the cells exactly, a batch tile of 64 images
     if (g.F % 16 == 0 && g.R % g.S == 0 && g.B > 32) {
         const int ap = g.R / g.S, ntt = (g.S * g.S * g.C + 15) / 16;   // steps per chunk, tiles of 16 cell values
-#define LC_BD(AP_, NT_, NCELL_) return launch_fast<4, NT_, NCELL_, AP_>(g, dy, w, dx, s)
+#define LC_BD(AP_, NT_, NCELL_) do { *done = true; return launch_fast<4, NT_, NCELL_, AP_>(g, dy, w, dx, s); } while (0)
         if (ap == 2) {
             if (ntt <= 3) LC_BD(2, 3, 4);
             if (ntt == 4) LC_BD(2, 4, 4);
@@ -419,7 +420,7 @@ int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, flo
         } else if (ap == 4) {
             // wide images: eight cells per workgroup stage 11 field columns instead of 2 x 7 (the paper's first
             // layer: 6.04 -> 5.89 ms); with 5 x 5 covering fields and 50 cells per row (cfg3) the same loses
-            if (ntt == 3 && (g.W + g.S - 1) / g.S >= 64) return launch_fast<4, 3, 8, 4, 8>(g, dy, w, dx, s);
+            if (ntt == 3 && (g.W + g.S - 1) / g.S >= 64) { *done = true; return launch_fast<4, 3, 8, 4, 8>(g, dy, w, dx, s); }
             if (ntt <= 2) LC_BD(4, 2, 4);
             if (ntt == 3) LC_BD(4, 3, 4);
             if (ntt == 4) LC_BD(4, 4, 4);
@@ -429,14 +430,34 @@ int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, flo
             if (ntt == 4) LC_BD(5, 4, 4);
         } else if (ap == 8) {
             // one tile of cell values per wave: eight cells per workgroup share the staged fields
-            if (ntt == 1) return launch_fast<4, 1, 8, 8, 8>(g, dy, w, dx, s);
+            if (ntt == 1) { *done = true; return launch_fast<4, 1, 8, 8, 8>(g, dy, w, dx, s); }
         }
 #undef LC_BD
+    }
+    return LC_OK;
+}
+
+}  // namespace
+
+int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    // cells of 128-value blocks: one cell per workgroup, dy through LDS, 128 x 128 output tiles
+    if (backward_data_wide_supported(g) || backward_data_dense_supported(g))
+        return launch_backward_data_wide_f32(g, dy, w, dx, s);
+    {
+        bool done = false;
+        const int rc = launch_backward_data_fast_path(g, dy, w, dx, s, &done);
+        if (done) return rc;
     }
     if (g.B > 64) return launch_mt<8>(g, dy, w, dx, s);
     if (g.B > 32) return launch_mt<4>(g, dy, w, dx, s);
     if (g.B > 16) return launch_mt<2>(g, dy, w, dx, s);
     return launch_mt<1>(g, dy, w, dx, s);
+}
+
+int launch_backward_data_bf16_storage(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
+    bool done = false;
+    const int rc = launch_backward_data_fast_path(g, (const bf16_t *)dy, (const bf16_t *)w, dx, s, &done);
+    return done ? rc : LC_EUNSUPPORTED;
 }
 
 }  // namespace lc

@@ -122,20 +122,21 @@ __device__ __forceinline__ float vget(const typename VecT<N>::T &v, int i) {
     if constexpr (N == 1) return v; else return v[i];
 }
 
-template <int G, int VA, int NT, int PF>
-__global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const float *__restrict__ x1,
-                                                                  const float *__restrict__ dy1,
-                                                                  const float *__restrict__ x2,
-                                                                  const float *__restrict__ dy2, float beta,
+template <int G, int VA, int NT, int PF, typename T = float>
+__global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const T *__restrict__ x1,
+                                                                  const T *__restrict__ dy1,
+                                                                  const T *__restrict__ x2,
+                                                                  const T *__restrict__ dy2, float beta,
                                                                   float gamma, float *__restrict__ out, int kblocks,
                                                                   int ntasks) {
-    typedef typename VecT<VA>::T AV;
-    typedef typename VecT<NT>::T BV;
-    // global address space: plain global_load, not flat.  The patch vectors are only float-aligned in general
-    // (a field starts every S*C floats): the declared alignment says so, and the vector load stays one instruction
-    typedef __attribute__((address_space(1), aligned(4))) AV GAV;
-    typedef __attribute__((address_space(1))) BV GBV;
-    typedef const __attribute__((address_space(1))) float *gfloat_ptr;
+    typedef typename RawVec<T, VA>::V AV;     // VA consecutive patch elements as loaded (fp32, or bf16 bit patterns)
+    typedef typename RawVec<T, NT>::V BR;     // NT consecutive dy values as loaded
+    typedef typename VecT<NT>::T BV;          // NT consecutive outputs
+    // global address space: plain global_load, not flat.  The patch vectors are only element-aligned in general
+    // (a field starts every S*C elements): the declared alignment says so, and the vector load stays one instruction
+    typedef __attribute__((address_space(1), aligned(sizeof(T)))) AV GAV;
+    typedef __attribute__((address_space(1))) BR GBV;
+    typedef const __attribute__((address_space(1))) T *gfloat_ptr;
     constexpr int KB = G * VA * 16;  // patch elements per task
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, kk = lane >> 4;
@@ -168,15 +169,15 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const 
     const int nsteps = g.B >> 2;                 // B % (4*PF) == 0 on this path
     const size_t xstep = 4 * img, dstep = (size_t)4 * g.L * g.F;
     for (int p = 0; p < 2; ++p) {
-        const float *x = p ? x2 : x1;
-        const float *dy = p ? dy2 : dy1;
+        const T *x = p ? x2 : x1;
+        const T *dy = p ? dy2 : dy1;
         if (!x) break;
         gfloat_ptr xa[G];
 #pragma unroll
         for (int gg = 0; gg < G; ++gg) xa[gg] = (gfloat_ptr)x + ((size_t)kk * img + off[gg]);
         gfloat_ptr da = (gfloat_ptr)dy + (((size_t)kk * g.L + loc) * g.F + f0 + NT * m);
         AV a[PF][G];
-        BV bv[PF];
+        BR bv[PF];
         // ring prologue: steps 0 .. PF-1
 #pragma unroll
         for (int ss = 0; ss < PF; ++ss) {
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const 
                     for (int t = 0; t < VA; ++t)
 #pragma unroll
                         for (int u = 0; u < NT; ++u)
-                            acc[gg][t][u] = mfma16(vget<VA>(a[ss][gg], t), vget<NT>(bv[ss], u), acc[gg][t][u]);
+                            acc[gg][t][u] = mfma16(raw_get<T, VA>(a[ss][gg], t), raw_get<T, NT>(bv[ss], u), acc[gg][t][u]);
 #pragma unroll
                 for (int gg = 0; gg < G; ++gg) { a[ss][gg] = *(const GAV *)xa[gg]; xa[gg] += xstep; }
                 bv[ss] = *(const GBV *)da; da += dstep;
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const 
                 for (int t = 0; t < VA; ++t)
 #pragma unroll
                     for (int u = 0; u < NT; ++u)
-                        acc[gg][t][u] = mfma16(vget<VA>(a[ss][gg], t), vget<NT>(bv[ss], u), acc[gg][t][u]);
+                        acc[gg][t][u] = mfma16(raw_get<T, VA>(a[ss][gg], t), raw_get<T, NT>(bv[ss], u), acc[gg][t][u]);
     }
 
     float *ol = out + (size_t)loc * g.K * g.F + f0 + NT * m;
@@ -276,15 +277,15 @@ int launch_nt(const Geom &g, const float *x1, const float *dy1, const float *x2,
 
 namespace {
 
-template <int G, int VA, int NT, int PF>
-int launch_fast(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2, float beta,
+template <int G, int VA, int NT, int PF, typename T>
+int launch_fast(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
                 float gamma, float *out, hipStream_t s) {
     constexpr int KB = G * VA * 16;
     const int kblocks = (g.K + KB - 1) / KB;
     const long long ntasks = (long long)g.L * kblocks;
     if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
     dim3 grid((unsigned)((ntasks + 3) / 4), g.F / (NT * 16));
-    hipLaunchKernelGGL((lc_bwd_weights_fast_kernel<G, VA, NT, PF>), grid, dim3(256), 0, s, g, x1, dy1, x2, dy2, beta,
+    hipLaunchKernelGGL((lc_bwd_weights_fast_kernel<G, VA, NT, PF, T>), grid, dim3(256), 0, s, g, x1, dy1, x2, dy2, beta,
                        gamma, out, kblocks, (int)ntasks);
     LC_HIP_LAUNCH_CHECK("lc_backward_weights launch");
     return LC_OK;
@@ -297,32 +298,53 @@ int patch_vector_width(const Geom &g) {
     return 1;
 }
 
-template <int G, int VA, int NT>
-int launch_fast_pf(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2, float beta,
+template <int G, int VA, int NT, typename T>
+int launch_fast_pf(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
                    float gamma, float *out, hipStream_t s) {
     if (g.B % 16 == 0) return launch_fast<G, VA, NT, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
     if (g.B % 8 == 0) return launch_fast<G, VA, NT, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
     return launch_fast<G, VA, NT, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
 }
 
+// The whole-line kernel for aligned shapes; *done tells whether a kernel was launched.  T = float or bf16_t.
+template <typename T>
+int launch_backward_weights_fast_path(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
+                                      float gamma, float *out, hipStream_t s, bool *done) {
+    *done = false;
+    const int va = patch_vector_width(g);
+    if ((g.B & 3) == 0 && va == 4) {
+        if (g.F % 64 == 0) { *done = true; return launch_fast_pf<1, 4, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+        if (g.F % 32 == 0) { *done = true; return launch_fast_pf<2, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+        if (g.F % 16 == 0) { *done = true; return launch_fast_pf<2, 4, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+    }
+    if ((g.B & 3) == 0 && va == 2) {
+        if (g.F % 64 == 0) { *done = true; return launch_fast_pf<2, 2, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+        if (g.F % 32 == 0) { *done = true; return launch_fast_pf<4, 2, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+        if (g.F % 16 == 0) { *done = true; return launch_fast_pf<4, 2, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+    }
+    return LC_OK;
+}
+
 }  // namespace
 
 int launch_backward_weights_f32(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2,
                                 float beta, float gamma, float *out, hipStream_t s) {
-    const int va = patch_vector_width(g);
-    if ((g.B & 3) == 0 && va == 4) {
-        if (g.F % 64 == 0) return launch_fast_pf<1, 4, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-        if (g.F % 32 == 0) return launch_fast_pf<2, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-        if (g.F % 16 == 0) return launch_fast_pf<2, 4, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-    }
-    if ((g.B & 3) == 0 && va == 2) {
-        if (g.F % 64 == 0) return launch_fast_pf<2, 2, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-        if (g.F % 32 == 0) return launch_fast_pf<4, 2, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-        if (g.F % 16 == 0) return launch_fast_pf<4, 2, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+    {
+        bool done = false;
+        const int rc = launch_backward_weights_fast_path(g, x1, dy1, x2, dy2, beta, gamma, out, s, &done);
+        if (done) return rc;
     }
     if (g.F <= 16) return launch_nt<1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
     if (g.F <= 32) return launch_nt<2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
     return launch_nt<4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+}
+
+int launch_backward_weights_bf16_storage(const Geom &g, const void *x, const void *dy, float beta, float *dw,
+                                         hipStream_t s) {
+    bool done = false;
+    const int rc = launch_backward_weights_fast_path(g, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)nullptr,
+                                                     (const bf16_t *)nullptr, beta, 1.f, dw, s, &done);
+    return done ? rc : LC_EUNSUPPORTED;
 }
 
 }  // namespace lc

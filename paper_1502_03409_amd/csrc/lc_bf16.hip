@@ -247,7 +247,8 @@ bool bf16_shape_supported(const Geom &g) {
 
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s) {
-    if (!bf16_shape_supported(g)) return LC_EUNSUPPORTED;
+    // other shapes: the fp32 pipelined kernel reading bf16 storage (same MFMAs, half the bytes), where it applies
+    if (!bf16_shape_supported(g)) return launch_forward_bf16_storage(g, x, w, bias, alpha, y, s);
     if (bf16_tiled_forward_supported(g)) return launch_forward_bf16_tiled(g, x, w, bias, alpha, y, s);
     const int fblocks = g.F / 64;
     auto go = [&](auto kern, int MT) {
@@ -263,7 +264,7 @@ int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float
 }
 
 int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
-    if (!bf16_shape_supported(g)) return LC_EUNSUPPORTED;
+    if (!bf16_shape_supported(g)) return launch_backward_data_bf16_storage(g, dy, w, dx, s);
     if (bf16_tiled_backward_data_supported(g)) return launch_backward_data_bf16_tiled(g, dy, w, dx, s);
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int nblocks = (g.S * g.S * g.C + 63) / 64;
@@ -282,7 +283,7 @@ int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, floa
 
 int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, float beta, float *dw,
                                  hipStream_t s) {
-    if (!bf16_shape_supported(g)) return LC_EUNSUPPORTED;
+    if (!bf16_shape_supported(g)) return launch_backward_weights_bf16_storage(g, x, dy, beta, dw, s);
     if (bf16_tiled_backward_weights_supported(g)) return launch_backward_weights_bf16_tiled(g, x, dy, beta, dw, s);
     const int kblocks = (g.K + 127) / 128;
     const long long ntasks = (long long)g.L * kblocks;

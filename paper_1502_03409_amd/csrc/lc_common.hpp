@@ -55,6 +55,46 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
+// N consecutive fp32 values as one vector register group
+template <int N> struct FVec;
+template <> struct FVec<1> { typedef float T; };
+template <> struct FVec<2> { typedef float T __attribute__((ext_vector_type(2))); };
+template <> struct FVec<4> { typedef float T __attribute__((ext_vector_type(4))); };
+template <int N>
+__device__ __forceinline__ float fget(const typename FVec<N>::T &v, int i) {
+    if constexpr (N == 1) return v; else return v[i];
+}
+
+
+// Operand storage.  T = float, or bf16_t: bf16 bit patterns that are widened to fp32 (exactly) on their way to
+// LDS or to the B operand, so the same fp32 MFMAs serve both; bf16 storage halves the bytes fetched.
+typedef unsigned short bf16_t;
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+template <typename T, int N> struct RawVec { typedef typename FVec<N>::T V; };            // N consecutive elements as loaded
+template <> struct RawVec<bf16_t, 1> { typedef unsigned short V; };
+template <> struct RawVec<bf16_t, 2> { typedef unsigned int V; };
+template <> struct RawVec<bf16_t, 4> { typedef u32x2 V; };
+__device__ __forceinline__ float bf16_lo(unsigned int v) { return __builtin_bit_cast(float, v << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned int v) { return __builtin_bit_cast(float, v & 0xffff0000u); }
+// element i of a raw vector of N, as fp32
+template <typename T, int N>
+__device__ __forceinline__ float raw_get(const typename RawVec<T, N>::V &v, int i) {
+    if constexpr (sizeof(T) == 4) {
+        return fget<N>(v, i);
+    } else if constexpr (N == 1) {
+        return bf16_lo(v);
+    } else if constexpr (N == 2) {
+        return (i & 1) ? bf16_hi(v) : bf16_lo(v);
+    } else {
+        return (i & 1) ? bf16_hi(v[i >> 1]) : bf16_lo(v[i >> 1]);
+    }
+}
+template <typename T>
+__device__ __forceinline__ f32x4 raw_widen4(const typename RawVec<T, 4>::V &v) {
+    if constexpr (sizeof(T) == 4) return v;
+    else return (f32x4){bf16_lo(v[0]), bf16_hi(v[0]), bf16_lo(v[1]), bf16_hi(v[1])};
+}
+
 void set_hip_error(hipError_t e, const char *where);
 // raises a kernel's dynamic LDS limit when `bytes` needs it (once per kernel and device); LC_OK or LC_EHIP
 int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where);
@@ -100,6 +140,13 @@ int launch_backward_data_wide_f32(const Geom &g, const float *dy, const float *w
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s);
 int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s);
+// bf16 storage through the fp32 pipelined kernels (operands widened on the way in, fp32 MFMAs): the aligned shapes
+// of those kernels; LC_EUNSUPPORTED otherwise
+int launch_forward_bf16_storage(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
+                                hipStream_t s);
+int launch_backward_data_bf16_storage(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s);
+int launch_backward_weights_bf16_storage(const Geom &g, const void *x, const void *dy, float beta, float *dw,
+                                         hipStream_t s);
 // workgroup-tiled bf16 forward for wide layers; LC_EUNSUPPORTED outside bf16_tiled_forward_supported()
 bool bf16_tiled_forward_supported(const Geom &g);
 int launch_forward_bf16_tiled(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,

@@ -131,29 +131,23 @@ __global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const float *__
 //     of NT different N-tiles: 16 lanes cover a whole run of w, and the epilogue stores NT filters
 //     of one image as one vector.
 // Rows of A are images and are never masked (images beyond B are staged as zeros).
-template <int N> struct FVec;
-template <> struct FVec<1> { typedef float T; };
-template <> struct FVec<2> { typedef float T __attribute__((ext_vector_type(2))); };
-template <> struct FVec<4> { typedef float T __attribute__((ext_vector_type(4))); };
-template <int N>
-__device__ __forceinline__ float fget(const typename FVec<N>::T &v, int i) {
-    if constexpr (N == 1) return v; else return v[i];
-}
-
 constexpr int kFwdStageSlotsWide = 6;   // eight-wave workgroups: half the registers per lane
 constexpr int kFwdStageSlots = 12;  // dwordx4 staging registers per lane: chunk <= 12*256*16 B = 48 KB
 
-template <int MT, int NT, int NLOC, int UNR, int NW = 4>
-__global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kernel(Geom g, const float *__restrict__ x,
-                                                              const float *__restrict__ w,
+template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T = float>
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kernel(Geom g, const T *__restrict__ x,
+                                                              const T *__restrict__ w,
                                                               const float *__restrict__ bias, float alpha,
                                                               const float *__restrict__ alpha_dev,
                                                               float *__restrict__ y, int strips_per_row, int CQ,
                                                               int sq4, int RS, int NR, int work_offset, int nbt) {
-    typedef typename FVec<NT>::T WV;
+    typedef typename RawVec<T, NT>::V WV;     // NT consecutive weights as loaded
+    typedef typename RawVec<T, 4>::V XV;      // four consecutive x values as loaded
+    typedef typename FVec<NT>::T OV;          // NT consecutive outputs
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     typedef const __attribute__((address_space(1))) WV *gw_ptr;
-    typedef const __attribute__((address_space(1))) f32x4 *gx4_ptr;
+    typedef const __attribute__((address_space(1))) XV *gx4_ptr;
+    typedef const __attribute__((address_space(1))) T *gt_ptr;
     constexpr int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW;   // NW waves: NLOC fields x NFW filter blocks
     constexpr int SLOTS = NW == 8 ? kFwdStageSlotsWide : kFwdStageSlots;
     extern __shared__ __attribute__((aligned(16))) float xs[];
@@ -199,15 +193,15 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
         }
     }
     const int col0 = j0 * SC;
-    f32x4 st[SLOTS];
+    XV st[SLOTS];
     auto stage_load = [&](int kh, int sc) {
-        const float *row = x + (size_t)b0 * img + (size_t)(i * g.S + kh) * WC + col0 + sc * CQ;
+        const T *row = x + (size_t)b0 * img + (size_t)(i * g.S + kh) * WC + col0 + sc * CQ;
         const int lim = WC - col0 - sc * CQ;          // floats of this image row that exist from the chunk start on
 #pragma unroll
         for (int q = 0; q < SLOTS; ++q) {
             if (q < nslots) {
                 const int b = (sb[q] >> 16) & 0x3fff, r = (sb[q] >> 12) & 15, v = sb[q] & 0xfff;
-                f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
+                XV t = XV{};
                 if ((sb[q] & 0xc0000000) == 0 && v < lim) t = *(gx4_ptr)(row + (size_t)b * img + r * WC + v);
                 st[q] = t;
             }
@@ -220,8 +214,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
                 const int b = (sb[q] >> 16) & 0x3fff, r = (sb[q] >> 12) & 15, v = sb[q] & 0xfff;
                 // rows of images 8..15 (mod 16) sit 2 floats to the right (see xwin below)
                 float *dst = xs + b * RS + r * sqc + ((b >> 2) & 2) + v;
-                *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
-                *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
+                const f32x4 f = raw_widen4<T>(st[q]);
+                *(f32x2 *)dst = (f32x2){f[0], f[1]};
+                *(f32x2 *)(dst + 2) = (f32x2){f[2], f[3]};
             }
         }
     };
@@ -236,7 +231,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
     for (int s = 0; s < UNR; ++s) {
         wr[s] = *wp;
         --wleft;
-        wp = (gw_ptr)((const __attribute__((address_space(1))) float *)wp + (wleft > 0 ? 4 * wstep : 0));
+        wp = (gw_ptr)((gt_ptr)wp + (wleft > 0 ? 4 * wstep : 0));
     }
 
     // LDS bank layout: RS == 4 (mod 32) puts images m and m+8 of an A operand on the same banks; shifting
@@ -267,10 +262,10 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
                         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                             for (int u = 0; u < NT; ++u)
-                                acc[mt][u] = mfma16(a[mt], fget<NT>(wr[ss], u), acc[mt][u]);
+                                acc[mt][u] = mfma16(a[mt], raw_get<T, NT>(wr[ss], u), acc[mt][u]);
                         wr[ss] = *wp;
                         --wleft;
-                        wp = (gw_ptr)((const __attribute__((address_space(1))) float *)wp + (wleft > 0 ? 4 * wstep : 0));
+                        wp = (gw_ptr)((gt_ptr)wp + (wleft > 0 ? 4 * wstep : 0));
                         // MFMAs and global loads keep their order (LDS reads and address arithmetic may move across)
                         __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
                     }
@@ -281,23 +276,23 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
 
     if (!active) return;
     if (alpha_dev) alpha = *alpha_dev;
-    WV bv;
-    if constexpr (NT == 1) bv = 0.f; else bv = (WV)(0.f);
-    if (bias) bv = *(const WV *)(bias + (size_t)loc * g.F + f0 + NT * n);
+    OV bv;
+    if constexpr (NT == 1) bv = 0.f; else bv = (OV)(0.f);
+    if (bias) bv = *(const OV *)(bias + (size_t)loc * g.F + f0 + NT * n);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int b = b0 + mt * 16 + 4 * kk + r;
             if (b >= g.B) continue;
-            WV o;
+            OV o;
             if constexpr (NT == 1) {
                 o = alpha * acc[mt][0][r] + bv;
             } else {
 #pragma unroll
                 for (int u = 0; u < NT; ++u) o[u] = alpha * acc[mt][u][r] + bv[u];
             }
-            *(WV *)(y + ((size_t)b * g.L + loc) * g.F + f0 + NT * n) = o;
+            *(OV *)(y + ((size_t)b * g.L + loc) * g.F + f0 + NT * n) = o;
         }
 }
 
@@ -341,14 +336,14 @@ int fast_row_stride(int sqc) {
     return ((sqc + 31) / 32) * 32 + 4;
 }
 
-template <int MT, int NT, int NLOC, int UNR, int NW = 4>
-int launch_fast(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T>
+int launch_fast(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                 const float *alpha_dev, float *y, int CQ, int NR, int work_first, int work_count, hipStream_t s) {
     constexpr int BT = 16 * MT, NFW = NW / NLOC;
     const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;   // staged floats per image and patch row
     const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
-    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW>;
+    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW, T>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward: hipFuncSetAttribute")) return rc_lds;
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int nbt = (g.B + BT - 1) / BT;
@@ -365,8 +360,8 @@ int launch_fast(const Geom &g, const float *x, const float *w, const float *bias
 // workgroups take a quarter of the batch tile each: four times as many, a quarter as long.
 constexpr int kComputeUnits = 256, kBigTilesPerCu = 2;
 
-template <int MT, int NT, int NLOC, int UNR>
-int launch_fast_tiered(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+template <int MT, int NT, int NLOC, int UNR, typename T>
+int launch_fast_tiered(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                        const float *alpha_dev, float *y, int CQ, hipStream_t s) {
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int ntask = strips * g.LH, slots = kComputeUnits * kBigTilesPerCu;
@@ -424,8 +419,8 @@ int pick_chunk(const Geom &g, int BT, int NLOC, int UNR, size_t lds_budget, int 
     return 0;
 }
 
-template <int MT, int NT, int NLOC>
-int launch_fast_unr(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+template <int MT, int NT, int NLOC, typename T>
+int launch_fast_unr(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                     const float *alpha_dev, float *y, hipStream_t s, bool *done) {
     const size_t budget = 52 * 1024;  // three workgroups per compute unit
     *done = true;
@@ -444,7 +439,8 @@ int launch_fast_unr(const Geom &g, const float *x, const float *w, const float *
 // Layers with 16 filters per field give a wave one filter tile, so a staged strip feeds few MFMAs.  Eight
 // waves (eight fields) per workgroup share a strip that is only about a third longer than the one four
 // fields need, and with so few accumulators two such workgroups still fit a compute unit.
-int launch_fast_wide(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+template <typename T>
+int launch_fast_wide(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                      const float *alpha_dev, float *y, hipStream_t s, bool *done) {
     const size_t budget = 78 * 1024;
     const int spr = g.RC / 4, ntask = ((g.LW + 7) / 8) * g.LH;
@@ -461,8 +457,8 @@ int launch_fast_wide(const Geom &g, const float *x, const float *w, const float 
 }
 
 // filters per wave / fields per workgroup by F (at most nt_cap tiles of 16 filters per wave)
-template <int MT>
-int launch_fast_mt(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+template <int MT, typename T>
+int launch_fast_mt(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                    const float *alpha_dev, float *y, hipStream_t s, bool *done, int nt_cap) {
     *done = false;
     if (g.F % 128 == 0 && nt_cap >= 4) return launch_fast_unr<MT, 4, 2>(g, x, w, bias, alpha, alpha_dev, y, s, done);
@@ -480,14 +476,13 @@ long long fast_workgroups(const Geom &g, int mt, int nt) {
     return strips * g.LH * ((g.B + 16 * mt - 1) / (16 * mt)) * (g.F / ((4 / nloc) * ntf * 16));
 }
 
-}  // namespace
-
-int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
-                       const float *alpha_dev, float *y, hipStream_t s, void *ws, size_t ws_bytes) {
-    // aligned shapes take the pipelined kernel: patch rows that are whole dwordx4 runs, strips that start on a
-    // 16-byte boundary (4 fields x S x C floats, or 2 when 128 filters are split over the waves)
-    // layers with 128-filter blocks: one field per workgroup, patches through LDS, 128 x 128 output tiles
-    if (forward_wide_supported(g)) return launch_forward_wide_f32(g, x, w, bias, alpha, alpha_dev, y, ws, ws_bytes, s);
+// The pipelined kernel for aligned shapes: patch rows that are whole 4-element runs, strips that start on a
+// 4-element boundary (4 fields x S x C elements, or 2 when 128 filters are split over the waves).  *done_out tells
+// whether a kernel was launched.
+template <typename T>
+int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
+                             const float *alpha_dev, float *y, hipStream_t s, bool *done_out) {
+    *done_out = false;
     const int nloc = g.F % 128 == 0 ? 2 : 4;
     const bool aligned = g.RC % 4 == 0 && (nloc * g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0 && g.K / 4 >= 16;
     if (aligned && g.B > 16) {
@@ -511,6 +506,23 @@ int launch_forward_f32(const Geom &g, const float *x, const float *w, const floa
         if (!done && mt == 8) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
         if (!done && mt >= 4 && g.B > 32) rc = launch_fast_mt<4>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
         if (!done) rc = launch_fast_mt<2>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
+        *done_out = done;
+        return rc;
+    }
+    return LC_OK;
+}
+
+}  // namespace
+
+int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                       const float *alpha_dev, float *y, hipStream_t s, void *ws, size_t ws_bytes) {
+    // aligned shapes take the pipelined kernel: patch rows that are whole dwordx4 runs, strips that start on a
+    // 16-byte boundary (4 fields x S x C floats, or 2 when 128 filters are split over the waves)
+    // layers with 128-filter blocks: one field per workgroup, patches through LDS, 128 x 128 output tiles
+    if (forward_wide_supported(g)) return launch_forward_wide_f32(g, x, w, bias, alpha, alpha_dev, y, ws, ws_bytes, s);
+    {
+        bool done = false;
+        const int rc = launch_forward_fast_path(g, x, w, bias, alpha, alpha_dev, y, s, &done);
         if (done) return rc;
     }
     // Pick the tile: as many images per wave as the batch offers (weights are re-read once per batch
@@ -545,6 +557,13 @@ int launch_forward_f32(const Geom &g, const float *x, const float *w, const floa
     if (ft <= 2 && strip_bytes(4, 1) <= kLdsTarget) LC_TRY(1, 2, 4);
     LC_TRY(1, 4, 1);
 #undef LC_TRY
+}
+
+int launch_forward_bf16_storage(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
+                                hipStream_t s) {
+    bool done = false;
+    const int rc = launch_forward_fast_path(g, (const bf16_t *)x, (const bf16_t *)w, bias, alpha, nullptr, y, s, &done);
+    return done ? rc : LC_EUNSUPPORTED;
 }
 
 }  // namespace lc

@@ -164,6 +164,11 @@ BF16_CASES = {
     "tiled_b80": (wl.LCGeom(B=80, H=12, W=14, C=16, R=4, S=2, F=128), "halfnormal"),   # 128-image tiles, ragged
     "tiled_bd_c64": (wl.LCGeom(B=80, H=11, W=13, C=64, R=4, S=2, F=64), "halfnormal"),  # two cell blocks, uncovered edge
     "tiled_f256": (wl.LCGeom(B=272, H=10, W=10, C=16, R=4, S=2, F=256), "halfnormal"), # two filter blocks, two batch tiles
+    # shapes outside the bf16 MFMA kernels: the fp32 pipelined kernels reading bf16 storage
+    "storage_cfg3_like": (wl.LCGeom(B=72, H=44, W=48, C=3, R=20, S=4, F=32), "pink"),       # 60-value patch rows, 5x5 covering fields
+    "storage_cfg5s1_like": (wl.LCGeom(B=132, H=30, W=36, C=3, R=16, S=2, F=16), "pink"),    # 16 filters: eight-wave workgroups
+    "storage_f48": (wl.LCGeom(B=72, H=28, W=32, C=3, R=16, S=4, F=48), "pink"),             # one filter tile per wave
+    "storage_c16": (wl.LCGeom(B=40, H=15, W=17, C=16, R=6, S=2, F=32), "halfnormal"),       # uncovered last column
 }
 
 
@@ -198,12 +203,14 @@ def test_lc_primitives_bf16_match_oracle(name):
     assert rel_fro(host(dw1), ref_dw + prev) <= 2e-2
 
 
-def test_cfg4_bf16_full_size_sampled():
-    """Workload cfg4 with bf16 operands at full size: sampled outputs against the oracle's single-output
-    evaluators on the unrounded fp32 inputs (bar 2e-2), and the adjoint identities on the device results."""
-    g = wl.CONFIG_GEOM["cfg4"]
-    print(f"case cfg4 bf16 geom {g}", flush=True)
-    x, w, dy = wl.lc_inputs(g, wl.CONFIG_IMAGE_KIND["cfg4"], seed=0)
+@pytest.mark.parametrize("cfg", ["cfg4", "cfg3"])
+def test_bf16_full_size_sampled(cfg):
+    """Workloads cfg4 (bf16 MFMA kernels) and cfg3 (bf16 storage through the fp32 kernels) with bf16 operands at
+    full size: sampled outputs against the oracle's single-output evaluators on the unrounded fp32 inputs (bar
+    2e-2), and the adjoint identities on the device results."""
+    g = wl.CONFIG_GEOM[cfg]
+    print(f"case {cfg} bf16 geom {g}", flush=True)
+    x, w, dy = wl.lc_inputs(g, wl.CONFIG_IMAGE_KIND[cfg], seed=0)
     t = g.as_tuple()
     G = lc.geom(*t)
     bf = lambda a: torch.from_numpy(wl.to_bf16_round(a).view(np.int16)).cuda().view(torch.bfloat16)
