@@ -168,7 +168,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 4;   // R4: 4-element vectors per image and chunk
     constexpr int NTHR = 64 * NW;                                   // NW waves: NCELL cells x NW/NCELL value blocks
     constexpr int NSLOT = (BT * R4 + NTHR - 1) / NTHR;
-    extern __shared__ __attribute__((aligned(16))) float dys[];
+    extern __shared__ __attribute__((aligned(16))) float dys_f32[];
+    T *dys = (T *)dys_f32;                    // staged dy in the operands' own storage type; RS counts elements
+    constexpr bool kHalf = sizeof(T) == 2;    // bf16: one 16x16x16 bf16 MFMA takes the place of four fp32 steps
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, kk = lane >> 4;
     const int SC = g.S * g.C, NCV = g.S * SC;
@@ -248,10 +250,13 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
         for (int q = 0; q < NSLOT; ++q) {
             if (b < BT) {
                 // two 8-byte stores: 16-byte LDS stores of a row-major tile run into bank conflicts
-                float *dst = dys + buf * BT * RS + b * RS + v * 4;
-                const f32x4 f = raw_widen4<T>(st[q]);
-                *(f32x2 *)dst = (f32x2){f[0], f[1]};
-                *(f32x2 *)(dst + 2) = (f32x2){f[2], f[3]};
+                T *dst = dys + buf * BT * RS + b * RS + v * 4;
+                if constexpr (kHalf) {
+                    *(XV *)dst = st[q];
+                } else {
+                    *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
+                    *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
+                }
             }
             v += DV; b += DB;
             if (v >= R4) { v -= R4; ++b; }
@@ -284,7 +289,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
         if (nchunks > 1) stage_load(1);
         __syncthreads();
         for (int c = 0; c < nchunks; ++c) {
-            const float *arow = dys + (c & 1) * BUF + m * RS + 4 * kk;
+            const T *arow = dys + (c & 1) * BUF + m * RS + 4 * kk;
             const int cn = c + 1 < nchunks ? c + 1 : c;
 #pragma unroll
             for (int ap = 0; ap < AP; ++ap) {
@@ -293,12 +298,18 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
                 if (wi - ap >= 0 && wi - ap < g.LW) {
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        const f32x4 av = *(const f32x4 *)(arow + mt * 16 * RS + js * 16);
+                        const XV av = *(const XV *)(arow + mt * 16 * RS + js * 16);
+                        if constexpr (kHalf) {
+                            // the vectors already are the operands: four consecutive f of image m / of cell value n
 #pragma unroll
-                        for (int t = 0; t < 4; ++t)
+                            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16_bf16(av, wb[ap][nt], acc[mt][nt]);
+                        } else {
 #pragma unroll
-                            for (int nt = 0; nt < NT; ++nt)
-                                acc[mt][nt] = mfma16(av[t], raw_get<T, 4>(wb[ap][nt], t), acc[mt][nt]);
+                            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                                for (int nt = 0; nt < NT; ++nt)
+                                    acc[mt][nt] = mfma16(av[t], wb[ap][nt][t], acc[mt][nt]);
+                        }
                     }
                 }
                 gf_ptr pn = wbase(cn, ap);
@@ -386,8 +397,10 @@ int launch_fast(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int NCV = g.S * g.S * g.C;
-    const int RS = ((JW * 16 + 31) / 32) * 32 + 4;
-    const size_t lds = (size_t)2 * BT * RS * sizeof(float);      // two buffers
+    // row stride: 16 bytes past a multiple of 128 bytes, so that the 16 image rows a wave reads at once start
+    // four banks apart (fp32: 16-byte reads of 4 f; bf16: 8-byte reads)
+    const int RS = sizeof(T) == 2 ? ((JW * 16 + 63) / 64) * 64 + 8 : ((JW * 16 + 31) / 32) * 32 + 4;
+    const size_t lds = (size_t)2 * BT * RS * sizeof(T);          // two buffers
     auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP, NW, T>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
     const int strips = (CW + NCELL - 1) / NCELL;

@@ -12,15 +12,8 @@
 
 namespace lc {
 
-typedef short bf16x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef const __attribute__((address_space(1))) u32x2 *g2_ptr;
 typedef const __attribute__((address_space(1))) unsigned short *gh_ptr;
-
-__device__ __forceinline__ f32x4 mfma16_bf16(u32x2 a, u32x2 b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, a), __builtin_bit_cast(bf16x4, b), c,
-                                                     0, 0, 0);
-}
 
 // r[t] = four bf16 (e0..e3) of row t.  o[u] = (r[0].e_u, r[1].e_u, r[2].e_u, r[3].e_u).
 __device__ __forceinline__ void transpose4x4_bf16(const u32x2 (&r)[4], u32x2 (&o)[4]) {

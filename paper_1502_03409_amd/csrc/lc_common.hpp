@@ -95,6 +95,14 @@ __device__ __forceinline__ f32x4 raw_widen4(const typename RawVec<T, 4>::V &v) {
     else return (f32x4){bf16_lo(v[0]), bf16_hi(v[0]), bf16_lo(v[1]), bf16_hi(v[1])};
 }
 
+// v_mfma_f32_16x16x16_bf16: D[16x16] += A[16x16] * B[16x16] with bf16 operands.  Lane l supplies the four
+// consecutive contraction indices 4*(l/16) .. +3 of row (A) or column (B) l%16, packed two per register; D as above.
+typedef short bf16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4 mfma16_bf16(u32x2 a, u32x2 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4, a), __builtin_bit_cast(bf16x4, b), c,
+                                                     0, 0, 0);
+}
+
 void set_hip_error(hipError_t e, const char *where);
 // raises a kernel's dynamic LDS limit when `bytes` needs it (once per kernel and device); LC_OK or LC_EHIP
 int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where);
