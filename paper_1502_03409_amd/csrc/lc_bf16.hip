@@ -241,7 +241,10 @@ bool bf16_shape_supported(const Geom &g) {
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s) {
     // other shapes: the fp32 pipelined kernel reading bf16 storage (same MFMAs, half the bytes), where it applies
-    if (!bf16_shape_supported(g)) return launch_forward_bf16_storage(g, x, w, bias, alpha, y, s);
+    if (!bf16_shape_supported(g)) {
+        if (bf16_strip_forward_supported(g)) return launch_forward_bf16_strip(g, x, w, bias, alpha, y, s);
+        return launch_forward_bf16_storage(g, x, w, bias, alpha, y, s);
+    }
     if (bf16_tiled_forward_supported(g)) return launch_forward_bf16_tiled(g, x, w, bias, alpha, y, s);
     const int fblocks = g.F / 64;
     auto go = [&](auto kern, int MT) {

@@ -1,0 +1,275 @@
+// bf16 operands on the layers whose patch rows are not multiples of 16 values or whose filters come in blocks of 16
+// or 32 (workloads cfg3 and cfg5): lc_forward with the strip-sharing decomposition of the fp32 pipelined kernel
+// (Sec. 3.1's untied fields overlap by R-S pixels, so a strip of adjacent fields shares the image rows it reads) and
+// v_mfma_f32_16x16x16_bf16 in place of the fp32 matrix instruction.
+//
+// Workgroup = NLOC adjacent fields of one field row x a batch tile of 16*MT images x NW/NLOC blocks of 16*NT filters.
+// A chunk is CQ values of one patch row for all fields of the strip, staged in LDS as bf16 (8-byte stores and reads);
+// the next chunk's strip travels through registers meanwhile.  The contraction runs in blocks of 16 patch values:
+// lane (m,kk) reads the four values 16 blk + 4 kk .. +3 of image m from LDS; lane (n,kk) loads the NT filters
+// f0 + NT n .. of the four weight rows 16 blk + 4 kk .. +3 (the filters are the fast index of w, the patch values the
+// slow one) and transposes them in registers into NT operands of four consecutive patch values each.  A patch row
+// that is not a multiple of 16 ends in a partial block: its lanes beyond the row feed zeros as weights (the LDS
+// holds the neighbouring field's pixels there).  The weights of a whole chunk are in flight ahead of their use.
+#include "lc_common.hpp"
+
+namespace lc {
+namespace {
+
+constexpr int kStripSlots = 8;    // 8-byte staging registers per lane: chunk <= 8 * 256 * 8 B = 16 KB
+
+// o[u] = (r[0].e_u, r[1].e_u, r[2].e_u, r[3].e_u): four rows of NT bf16 each -> NT operands of four rows
+template <int NT>
+__device__ __forceinline__ void rows_to_operands(const typename RawVec<bf16_t, NT>::V (&r)[4], u32x2 (&o)[NT]) {
+    constexpr unsigned LO = 0x05040100u, HI = 0x07060302u;   // low / high halves of {src0:src1}
+    if constexpr (NT == 1) {
+        o[0] = (u32x2){(unsigned)r[0] | ((unsigned)r[1] << 16), (unsigned)r[2] | ((unsigned)r[3] << 16)};
+    } else if constexpr (NT == 2) {
+        o[0] = (u32x2){__builtin_amdgcn_perm(r[1], r[0], LO), __builtin_amdgcn_perm(r[3], r[2], LO)};
+        o[1] = (u32x2){__builtin_amdgcn_perm(r[1], r[0], HI), __builtin_amdgcn_perm(r[3], r[2], HI)};
+    } else {
+        o[0] = (u32x2){__builtin_amdgcn_perm(r[1][0], r[0][0], LO), __builtin_amdgcn_perm(r[3][0], r[2][0], LO)};
+        o[1] = (u32x2){__builtin_amdgcn_perm(r[1][0], r[0][0], HI), __builtin_amdgcn_perm(r[3][0], r[2][0], HI)};
+        o[2] = (u32x2){__builtin_amdgcn_perm(r[1][1], r[0][1], LO), __builtin_amdgcn_perm(r[3][1], r[2][1], LO)};
+        o[3] = (u32x2){__builtin_amdgcn_perm(r[1][1], r[0][1], HI), __builtin_amdgcn_perm(r[3][1], r[2][1], HI)};
+    }
+}
+
+template <int MT, int NT, int NLOC, int NB, int NW>
+__global__ __launch_bounds__(64 * NW, NT == 4 ? 2 : 3) void lc_forward_bf16_strip_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                                            const bf16_t *__restrict__ w,
+                                                                            const float *__restrict__ bias, float alpha,
+                                                                            float *__restrict__ y, int strips_per_row,
+                                                                            int CQ, int sq4, int RS, int nbt,
+                                                                            int work_first) {
+    typedef typename RawVec<bf16_t, NT>::V WV;    // NT consecutive filters of one weight row
+    typedef typename FVec<NT>::T OV;              // NT consecutive outputs
+    typedef const __attribute__((address_space(1))) WV *gw_ptr;
+    typedef const __attribute__((address_space(1))) u32x2 *gx4_ptr;
+    typedef const __attribute__((address_space(1))) bf16_t *gt_ptr;
+    constexpr int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW;
+    extern __shared__ __attribute__((aligned(16))) bf16_t xh[];      // [BT][RS]: the staged strip of one chunk
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, kk = lane >> 4;
+    // batch tiles of one strip are neighbours in dispatch order on the same XCD
+    const int t_id = remap_xcd(blockIdx.x, gridDim.x);
+    const int work = work_first + t_id / nbt;
+    const int i = work / strips_per_row, j0 = (work - i * strips_per_row) * NLOC;
+    const int b0 = (t_id % nbt) * BT;
+    const int wl = wave % NLOC, wf = wave / NLOC;
+    const int j = j0 + wl;
+    const int f0 = (blockIdx.y * NFW + wf) * NT * 16;
+    const bool active = j < g.LW;
+    const int loc = i * g.LW + (active ? j : g.LW - 1);   // idle waves shadow the last field of the row
+    const int SC = g.S * g.C, WC = g.W * g.C;
+    const size_t img = (size_t)g.H * WC;
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) acc[mt][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // staging map: slot q of this thread copies 4-value vector number e = tid + NTHR*q of the [BT][sq4] chunk.
+    // sb[q] = image << 16 | value offset in the row; bit 31: past the end of the chunk, bit 30: image beyond B.
+    const int sqc = sq4 * 4;
+    const int nslots = (BT * sq4 + NTHR - 1) / NTHR;
+    int sb[kStripSlots];
+    {
+        int vv = tid % sq4, b = tid / sq4;
+        const int dv = NTHR % sq4, db = NTHR / sq4;
+#pragma unroll
+        for (int q = 0; q < kStripSlots; ++q) {
+            sb[q] = (b << 16) | (vv * 4);
+            if (b >= BT) sb[q] = (int)0x80000000;
+            else if (b0 + b >= g.B) sb[q] |= 0x40000000;
+            vv += dv; b += db;
+            if (vv >= sq4) { vv -= sq4; ++b; }
+        }
+    }
+    // a partial last block reads up to 12 values past the staged row: those lanes' weights are zeros, and the LDS
+    // there is cleared once so that no stale bit pattern (a NaN) meets them
+    for (int e = tid; e < BT * 4; e += NTHR) *(u32x2 *)(xh + (e >> 2) * RS + sqc + 4 * (e & 3)) = (u32x2){0u, 0u};
+    const int col0 = j0 * SC;
+    u32x2 st[kStripSlots];
+    auto stage_load = [&](int kh, int sc) {
+        const bf16_t *row = x + (size_t)b0 * img + (size_t)(i * g.S + kh) * WC + col0 + sc * CQ;
+        const int lim = WC - col0 - sc * CQ;          // values of this image row that exist from the chunk start on
+#pragma unroll
+        for (int q = 0; q < kStripSlots; ++q) {
+            if (q < nslots) {
+                const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xffff;
+                u32x2 t = (u32x2){0u, 0u};
+                if ((sb[q] & 0xc0000000) == 0 && v < lim) t = *(gx4_ptr)(row + (size_t)b * img + v);
+                st[q] = t;
+            }
+        }
+    };
+    auto stage_store = [&]() {
+#pragma unroll
+        for (int q = 0; q < kStripSlots; ++q) {
+            if (q < nslots && sb[q] >= 0) {
+                const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xffff;
+                *(u32x2 *)(xh + b * RS + v) = st[q];
+            }
+        }
+    };
+
+    // weights of block blk of the chunk that starts at patch value kbase: rows kbase + 16 blk + 4 kk + jj, clamped
+    // into the field's matrix (rows beyond the patch row are multiplied by zeros or zeroed below)
+    gt_ptr wfield = (gt_ptr)w + (size_t)loc * g.K * g.F + f0 + NT * n;
+    WV wr[NB][4];
+    auto load_block = [&](int kbase, int blk) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            int k = kbase + 16 * blk + 4 * kk + jj;
+            k = k < g.K ? k : g.K - 1;
+            wr[blk][jj] = *(gw_ptr)(wfield + (size_t)k * g.F);
+        }
+    };
+
+    const bf16_t *xwin = xh + (size_t)(lane & 15) * RS + wl * SC + 4 * kk;
+    const int nsub = g.RC / CQ, nchunks = g.R * nsub;
+#pragma unroll
+    for (int blk = 0; blk < NB; ++blk)
+        if (16 * blk < CQ) load_block(0, blk);
+    stage_load(0, 0);
+    for (int c = 0; c < nchunks; ++c) {
+        __syncthreads();                    // all waves are done reading the previous chunk
+        stage_store();
+        __syncthreads();
+        const int cn = c + 1 < nchunks ? c + 1 : c;
+        {
+            const int kh = cn / nsub, sc = cn - kh * nsub;
+            if (c + 1 < nchunks) stage_load(kh, sc);
+        }
+        const int knext = (cn / nsub) * g.RC + (cn % nsub) * CQ;
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk) {
+            if (16 * blk < CQ) {            // uniform
+                u32x2 a[MT], bo[NT];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) a[mt] = *(const u32x2 *)(xwin + mt * 16 * RS + 16 * blk);
+                rows_to_operands<NT>(wr[blk], bo);
+                if (16 * blk + 4 * kk >= CQ) {   // lanes past the end of the patch row chunk
+#pragma unroll
+                    for (int u = 0; u < NT; ++u) bo[u] = (u32x2){0u, 0u};
+                }
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int u = 0; u < NT; ++u) acc[mt][u] = mfma16_bf16(a[mt], bo[u], acc[mt][u]);
+                load_block(knext, blk);
+                // MFMAs and global loads keep their order (LDS reads and address arithmetic may move across)
+                __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
+            }
+        }
+    }
+
+    if (!active) return;
+    OV bv;
+    if constexpr (NT == 1) bv = 0.f; else bv = (OV)(0.f);
+    if (bias) bv = *(const OV *)(bias + (size_t)loc * g.F + f0 + NT * n);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int b = b0 + mt * 16 + 4 * kk + r;
+            if (b >= g.B) continue;
+            OV o;
+            if constexpr (NT == 1) {
+                o = alpha * acc[mt][0][r] + bv;
+            } else {
+#pragma unroll
+                for (int u = 0; u < NT; ++u) o[u] = alpha * acc[mt][u][r] + bv[u];
+            }
+            *(OV *)(y + ((size_t)b * g.L + loc) * g.F + f0 + NT * n) = o;
+        }
+}
+
+// row stride in bf16 values: 16 bytes past a multiple of 128 bytes, so that the 16 image rows a wave reads at once
+// start four banks apart; the row keeps 16 values of padding behind the staged strip
+int strip_row_stride(int sqc) { return ((sqc + 8 + 63) / 64) * 64 + 8; }   // at least 16 values of padding
+
+template <int MT, int NT, int NB>
+int launch_strip(const Geom &g, const bf16_t *x, const bf16_t *w, const float *bias, float alpha, float *y, int CQ,
+                 int work_first, int work_count, hipStream_t s) {
+    constexpr int NLOC = 4, NW = 4, BT = 16 * MT;
+    const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;
+    const int RS = strip_row_stride(sqc);
+    const size_t lds = (size_t)BT * RS * sizeof(bf16_t);
+    auto kern = lc_forward_bf16_strip_kernel<MT, NT, NLOC, NB, NW>;
+    if (int rc = allow_dynamic_lds((const void *)kern, lds, "lc_forward (bf16 strip): hipFuncSetAttribute")) return rc;
+    const int strips = (g.LW + NLOC - 1) / NLOC, nbt = (g.B + BT - 1) / BT;
+    const long long nwg = (long long)work_count * nbt;
+    if (nwg > 0x7fffffffLL) return LC_EUNSUPPORTED;
+    dim3 grid((unsigned)nwg, g.F / (NT * 16));
+    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, g, x, w, bias, alpha, y, strips, CQ, sqc / 4, RS, nbt,
+                       work_first);
+    LC_HIP_LAUNCH_CHECK("lc_forward (bf16 strip) launch");
+    return LC_OK;
+}
+
+// the chunk: the largest divisor of a patch row (in whole 4-value vectors, at most 128 values) whose strip fits the
+// staging registers and 48 KB of LDS; 0 if none does
+int strip_chunk(const Geom &g, int BT) {
+    const int SC = g.S * g.C;
+    for (int nsub = 1; nsub <= g.RC / 4; ++nsub) {
+        if (g.RC % nsub) continue;
+        const int CQ = g.RC / nsub;
+        if (CQ % 4 || CQ > 128) continue;
+        const int sqc = (CQ + 3 * SC + 3) & ~3;
+        if ((size_t)BT * (sqc / 4) > (size_t)kStripSlots * 256) continue;
+        if ((size_t)BT * strip_row_stride(sqc) * sizeof(bf16_t) > 48 * 1024) continue;
+        if (sqc > 0xffff) continue;
+        return CQ;
+    }
+    return 0;
+}
+
+template <int MT, int NT>
+int launch_strip_nb(const Geom &g, const bf16_t *x, const bf16_t *w, const float *bias, float alpha, float *y, int CQ,
+                    int first, int count, hipStream_t s) {
+    switch ((CQ + 15) / 16) {
+        case 1: return launch_strip<MT, NT, 1>(g, x, w, bias, alpha, y, CQ, first, count, s);
+        case 2: return launch_strip<MT, NT, 2>(g, x, w, bias, alpha, y, CQ, first, count, s);
+        case 3: return launch_strip<MT, NT, 3>(g, x, w, bias, alpha, y, CQ, first, count, s);
+        case 4: return launch_strip<MT, NT, 4>(g, x, w, bias, alpha, y, CQ, first, count, s);
+        case 5: return launch_strip<MT, NT, 5>(g, x, w, bias, alpha, y, CQ, first, count, s);
+        case 6: return launch_strip<MT, NT, 6>(g, x, w, bias, alpha, y, CQ, first, count, s);
+        case 7: return launch_strip<MT, NT, 7>(g, x, w, bias, alpha, y, CQ, first, count, s);
+        default: return launch_strip<MT, NT, 8>(g, x, w, bias, alpha, y, CQ, first, count, s);
+    }
+}
+
+// Batch tiles of 64 images: three workgroups fit a compute unit and the second tile of a strip finds the weights in
+// L2.  128-image tiles (two per compute unit, one round of 512 plus a remainder launch for cfg3's 552 strips)
+// measured slower: 114 against 106 us.
+template <int NT>
+int launch_strip_mt(const Geom &g, const bf16_t *x, const bf16_t *w, const float *bias, float alpha, float *y, int CQ,
+                    hipStream_t s) {
+    const int ntask = ((g.LW + 3) / 4) * g.LH;
+    if (g.B > 32) return launch_strip_nb<4, NT>(g, x, w, bias, alpha, y, CQ, 0, ntask, s);
+    return launch_strip_nb<2, NT>(g, x, w, bias, alpha, y, CQ, 0, ntask, s);
+}
+
+}  // namespace
+
+// Shapes: patch rows, field offsets and image rows in whole 4-value vectors (8-byte accesses), filters in blocks of 16.
+bool bf16_strip_forward_supported(const Geom &g) {
+    const int SC = g.S * g.C;
+    if (g.RC % 4 || SC % 4 || (g.W * g.C) % 4 || g.F % 16 || g.B <= 16) return false;
+    return strip_chunk(g, g.B > 32 ? 64 : 32) != 0;
+}
+
+int launch_forward_bf16_strip(const Geom &g, const void *xv, const void *wv, const float *bias, float alpha, float *y,
+                              hipStream_t s) {
+    if (!bf16_strip_forward_supported(g)) return LC_EUNSUPPORTED;
+    const bf16_t *x = (const bf16_t *)xv, *w = (const bf16_t *)wv;
+    const int CQ = strip_chunk(g, g.B > 32 ? 64 : 32);
+    if (g.F % 64 == 0) return launch_strip_mt<4>(g, x, w, bias, alpha, y, CQ, s);
+    if (g.F % 32 == 0) return launch_strip_mt<2>(g, x, w, bias, alpha, y, CQ, s);
+    return launch_strip_mt<1>(g, x, w, bias, alpha, y, CQ, s);
+}
+
+}  // namespace lc

@@ -155,6 +155,10 @@ int launch_forward_bf16_storage(const Geom &g, const void *x, const void *w, con
 int launch_backward_data_bf16_storage(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s);
 int launch_backward_weights_bf16_storage(const Geom &g, const void *x, const void *dy, float beta, float *dw,
                                          hipStream_t s);
+// strip-sharing bf16 forward for patch rows that are not multiples of 16 values and filters in blocks of 16 or 32
+bool bf16_strip_forward_supported(const Geom &g);
+int launch_forward_bf16_strip(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
+                              hipStream_t s);
 // workgroup-tiled bf16 forward for wide layers; LC_EUNSUPPORTED outside bf16_tiled_forward_supported()
 bool bf16_tiled_forward_supported(const Geom &g);
 int launch_forward_bf16_tiled(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,

@@ -169,6 +169,10 @@ BF16_CASES = {
     "storage_cfg5s1_like": (wl.LCGeom(B=132, H=30, W=36, C=3, R=16, S=2, F=16), "pink"),    # 16 filters: eight-wave workgroups
     "storage_f48": (wl.LCGeom(B=72, H=28, W=32, C=3, R=16, S=4, F=48), "pink"),             # one filter tile per wave
     "storage_c16": (wl.LCGeom(B=40, H=15, W=17, C=16, R=6, S=2, F=32), "halfnormal"),       # uncovered last column
+    # forward through the strip-sharing bf16 kernel: partial 16-value blocks, 64 / 16 filters, patch rows cut in two
+    "strip_f64": (wl.LCGeom(B=48, H=24, W=28, C=3, R=20, S=4, F=64), "pink"),
+    "strip_f16": (wl.LCGeom(B=36, H=12, W=14, C=2, R=6, S=2, F=16), "pink"),
+    "strip_sub": (wl.LCGeom(B=40, H=14, W=16, C=16, R=10, S=2, F=32), "halfnormal"),
 }
 
 
@@ -239,6 +243,19 @@ def test_bf16_full_size_sampled(cfg):
     assert rel_fro(gy, ry) <= 2e-2
     assert rel_fro(gx, rx) <= 2e-2
     assert rel_fro(gw, rw) <= 2e-2
+
+
+def test_bf16_forward_small_batch_tile():
+    """32-image tiles of the strip-sharing bf16 forward kernel (the backward passes need more than 32 images)."""
+    g = wl.LCGeom(B=24, H=16, W=20, C=4, R=8, S=2, F=32)
+    print(f"case bf16 strip small batch geom {g}", flush=True)
+    x, w, _, bias = wl.lc_inputs(g, "pink", seed=3, with_bias=True)
+    t = g.as_tuple()
+    bf = lambda a: torch.from_numpy(wl.to_bf16_round(a).view(np.int16)).cuda().view(torch.bfloat16)
+    rnd = lambda a: (wl.to_bf16_round(a).astype(np.uint32) << 16).view(np.float32)
+    y = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
+    lc.lc_forward(lc.geom(*t), bf(x), bf(w), dev(bias), 1.25, y, lc.LC_BF16)
+    assert rel_fro(host(y), oracle.lc_forward(t, rnd(x), rnd(w), bias, 1.25)) <= 1e-4
 
 
 def test_bf16_unsupported_shape_is_reported():
