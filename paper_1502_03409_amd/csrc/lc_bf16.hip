@@ -279,7 +279,10 @@ int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, floa
 
 int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, float beta, float *dw,
                                  hipStream_t s) {
-    if (!bf16_shape_supported(g)) return launch_backward_weights_bf16_storage(g, x, dy, beta, dw, s);
+    if (!bf16_shape_supported(g)) {
+        if (bf16_rows_backward_weights_supported(g)) return launch_backward_weights_bf16_rows(g, x, dy, beta, dw, s);
+        return launch_backward_weights_bf16_storage(g, x, dy, beta, dw, s);
+    }
     if (bf16_tiled_backward_weights_supported(g)) return launch_backward_weights_bf16_tiled(g, x, dy, beta, dw, s);
     const int kblocks = (g.K + 127) / 128;
     const long long ntasks = (long long)g.L * kblocks;

@@ -253,7 +253,150 @@ int launch_strip_mt(const Geom &g, const bf16_t *x, const bf16_t *w, const float
     return launch_strip_nb<2, NT>(g, x, w, bias, alpha, y, CQ, 0, ntask, s);
 }
 
+// ------------------------------------------------------------------------------ backward weights
+// dw[l,k,f] = beta dw + sum_b x[b, patch k of l] dy[b,l,f] with bf16 operands (the weight gradient of Eq. 1's terms).
+// The decomposition of the fp32 kernel: a wave owns one location, G*64 patch elements and 16*NT filters, both
+// operands come straight from global memory with lanes along the contiguous axis (4 patch elements of an image row,
+// NT filters).  The contraction runs over the batch, 16 images per bf16 MFMA: lane (m,kk) loads its vectors for the
+// four images 4 kk .. +3 of a step and transposes them in registers, so that operand t holds patch element
+// kg + 4 m + t (operand u: filter f0 + NT m + u) of those four images.  Loads run PF steps ahead in a register ring.
+template <int G, int NT, int PF>
+__global__ __launch_bounds__(256, 3) void lc_bwd_weights_bf16_rows_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                                       const bf16_t *__restrict__ dy, float beta,
+                                                                       float *__restrict__ out, int kblocks,
+                                                                       int ntasks) {
+    typedef typename RawVec<bf16_t, NT>::V BR;     // NT consecutive dy values as loaded
+    typedef typename FVec<NT>::T BV;               // NT consecutive outputs
+    // the patch vectors are only element-aligned in general (a field starts every S*C elements)
+    typedef __attribute__((address_space(1), aligned(2))) u32x2 GAV;
+    typedef __attribute__((address_space(1))) BR GBV;
+    typedef const __attribute__((address_space(1))) bf16_t *gt_ptr;
+    constexpr int KB = G * 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, kk = lane >> 4;
+    const int task = remap_xcd(blockIdx.x, gridDim.x) * 4 + wave;
+    if (task >= ntasks) return;
+    const int loc = task / kblocks, k0 = (task - loc * kblocks) * KB;
+    const int i = loc / g.LW, j = loc - i * g.LW;
+    const int f0 = blockIdx.y * NT * 16;
+    const size_t img = (size_t)g.H * g.W * g.C, dyimg = (size_t)g.L * g.F;
+
+    // rows of the A tiles beyond K are loaded from a valid address (element 0 of the patch) and never stored
+    gt_ptr xa[G];
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) {
+        const int k = k0 + gg * 64 + 4 * m;
+        const int kc = k < g.K ? k : 0;
+        const int kh = kc / g.RC, rem = kc - kh * g.RC;
+        xa[gg] = (gt_ptr)x + (size_t)(4 * kk) * img + ((i * g.S + kh) * g.W + j * g.S) * g.C + rem;
+    }
+    gt_ptr da = (gt_ptr)dy + (size_t)(4 * kk) * dyimg + (size_t)loc * g.F + f0 + NT * m;
+
+    f32x4 acc[G][4][NT];
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int u = 0; u < NT; ++u) acc[gg][t][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    u32x2 a[PF][G][4];
+    BR bv[PF][4];
+    auto load_step = [&](int ss) {      // one step = 16 images: this lane's four, then on to the next step
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+#pragma unroll
+            for (int gg = 0; gg < G; ++gg) a[ss][gg][jj] = *(const GAV *)(xa[gg] + (size_t)jj * img);
+            bv[ss][jj] = *(const GBV *)(da + (size_t)jj * dyimg);
+        }
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) xa[gg] += 16 * img;
+        da += 16 * dyimg;
+    };
+    auto mul_step = [&](int ss) {
+        u32x2 bo[NT];
+        rows_to_operands<NT>(bv[ss], bo);
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) {
+            u32x2 ao[4];
+            rows_to_operands<4>(a[ss][gg], ao);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int u = 0; u < NT; ++u) acc[gg][t][u] = mfma16_bf16(ao[t], bo[u], acc[gg][t][u]);
+        }
+    };
+    const int nsteps = g.B >> 4;             // B % (16*PF) == 0 on this path
+#pragma unroll
+    for (int ss = 0; ss < PF; ++ss) load_step(ss);
+    for (int s0 = PF; s0 < nsteps; s0 += PF) {
+#pragma unroll
+        for (int ss = 0; ss < PF; ++ss) {
+            mul_step(ss);
+            load_step(ss);
+            // the refill of slot ss stays right behind the MFMAs that consumed it
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int ss = 0; ss < PF; ++ss) mul_step(ss);
+
+    float *ol = out + (size_t)loc * g.K * g.F + f0 + NT * m;
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int k = k0 + gg * 64 + 4 * (4 * kk + r) + t;
+                if (k >= g.K) continue;
+                BV *o = (BV *)(ol + (size_t)k * g.F);
+                BV v;
+                if constexpr (NT == 1) {
+                    v = acc[gg][t][0][r];
+                } else {
+#pragma unroll
+                    for (int u = 0; u < NT; ++u) v[u] = acc[gg][t][u][r];
+                }
+                if (beta != 0.f) v += beta * *o;
+                *o = v;
+            }
+}
+
+template <int G, int NT, int PF>
+int launch_rows(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, float *out, hipStream_t s) {
+    constexpr int KB = G * 64;
+    const int kblocks = (g.K + KB - 1) / KB;
+    const long long ntasks = (long long)g.L * kblocks;
+    if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
+    dim3 grid((unsigned)((ntasks + 3) / 4), g.F / (NT * 16));
+    hipLaunchKernelGGL((lc_bwd_weights_bf16_rows_kernel<G, NT, PF>), grid, dim3(256), 0, s, g, x, dy, beta, out, kblocks,
+                       (int)ntasks);
+    LC_HIP_LAUNCH_CHECK("lc_backward_weights (bf16 rows) launch");
+    return LC_OK;
+}
+
+template <int G, int NT>
+int launch_rows_pf(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, float *out, hipStream_t s) {
+    if (g.B % 32 == 0) return launch_rows<G, NT, 2>(g, x, dy, beta, out, s);
+    return launch_rows<G, NT, 1>(g, x, dy, beta, out, s);
+}
+
 }  // namespace
+
+// Shapes: patch rows in whole 4-value vectors, filters in blocks of 16, batches in steps of 16 images.
+bool bf16_rows_backward_weights_supported(const Geom &g) {
+    return g.RC % 4 == 0 && g.F % 16 == 0 && g.B % 16 == 0;
+}
+
+int launch_backward_weights_bf16_rows(const Geom &g, const void *xv, const void *dyv, float beta, float *dw,
+                                      hipStream_t s) {
+    if (!bf16_rows_backward_weights_supported(g)) return LC_EUNSUPPORTED;
+    const bf16_t *x = (const bf16_t *)xv, *dy = (const bf16_t *)dyv;
+    if (g.F % 64 == 0) return launch_rows_pf<1, 4>(g, x, dy, beta, dw, s);
+    if (g.F % 32 == 0) return launch_rows_pf<2, 2>(g, x, dy, beta, dw, s);
+    return launch_rows_pf<2, 1>(g, x, dy, beta, dw, s);
+}
 
 // Shapes: patch rows, field offsets and image rows in whole 4-value vectors (8-byte accesses), filters in blocks of 16.
 bool bf16_strip_forward_supported(const Geom &g) {

@@ -159,6 +159,10 @@ int launch_backward_weights_bf16_storage(const Geom &g, const void *x, const voi
 bool bf16_strip_forward_supported(const Geom &g);
 int launch_forward_bf16_strip(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                               hipStream_t s);
+// bf16 weight gradient for patch rows in whole 4-value vectors and filters in blocks of 16 (batches in steps of 16)
+bool bf16_rows_backward_weights_supported(const Geom &g);
+int launch_backward_weights_bf16_rows(const Geom &g, const void *x, const void *dy, float beta, float *dw,
+                                      hipStream_t s);
 // workgroup-tiled bf16 forward for wide layers; LC_EUNSUPPORTED outside bf16_tiled_forward_supported()
 bool bf16_tiled_forward_supported(const Geom &g);
 int launch_forward_bf16_tiled(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,

@@ -173,6 +173,11 @@ BF16_CASES = {
     "strip_f64": (wl.LCGeom(B=48, H=24, W=28, C=3, R=20, S=4, F=64), "pink"),
     "strip_f16": (wl.LCGeom(B=36, H=12, W=14, C=2, R=6, S=2, F=16), "pink"),
     "strip_sub": (wl.LCGeom(B=40, H=14, W=16, C=16, R=10, S=2, F=32), "halfnormal"),
+    # batches in steps of 16 images: the weight gradient through the bf16 kernel with in-register transposes
+    "rows_cfg3_like": (wl.LCGeom(B=80, H=44, W=48, C=3, R=20, S=4, F=32), "pink"),          # one step in flight
+    "rows_f16": (wl.LCGeom(B=144, H=30, W=36, C=3, R=16, S=2, F=16), "pink"),
+    "rows_f64": (wl.LCGeom(B=64, H=24, W=28, C=3, R=20, S=4, F=64), "pink"),                # two steps in flight
+    "rows_f48": (wl.LCGeom(B=64, H=28, W=32, C=3, R=16, S=4, F=48), "pink"),                # three filter blocks
 }
 
 
