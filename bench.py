@@ -346,9 +346,7 @@ def bench_others(lc, wl, torch, iters):
         min_bytes = {"lc_forward": esz * (w.numel() + x.numel()) + 4 * y.numel(),
                      "lc_backward_data": esz * (w.numel() + dy.numel()) + 4 * dx.numel(),
                      "lc_backward_weights": esz * (x.numel() + dy.numel()) + 4 * dw.numel()}
-        # cfg3's shape is outside the bf16 matrix kernels: bf16 storage, fp32 matrix instructions, fp32 peak
-        widened = dt == "bf16" and name == "cfg3"
-        peak = BF16_MFMA_PEAK_TFLOPS if dt == "bf16" and not widened else FP32_MFMA_PEAK_TFLOPS
+        peak = BF16_MFMA_PEAK_TFLOPS if dt == "bf16" else FP32_MFMA_PEAK_TFLOPS
         entry, total = {}, 0.0
         for kn, f in fns.items():
             ms = timed_ms(torch, stream, f, iters)
@@ -359,8 +357,6 @@ def bench_others(lc, wl, torch, iters):
         tf = 3 * g.flop_per_pass / (total * 1e-3) / 1e12
         entry["fwd_bwd"] = {"ms": round(total, 4), "TFLOP/s": round(tf, 1), "frac_mfma_peak": round(tf / peak, 4)}
         entry["shape"] = dict(zip("BHWCRSF", g.as_tuple()))
-        if widened:
-            entry["note"] = "bf16 operands widened on the way in, fp32 MFMA; fractions are of the fp32 peak"
         res[f"{name}_{dt}"] = entry
         del x, w, dy, y, dx, dw
         torch.cuda.empty_cache()

@@ -18,13 +18,15 @@
  *    rows/columns that no field covers are ignored by the forward pass and receive zero
  *    from lc_backward_data).
  *  - `dtype` names the storage type of the x / w / dy operands: LC_F32, or LC_BF16 (bf16
- *    operands, fp32 accumulation).  Outputs are always fp32.  LC_BF16 runs bf16 matrix
- *    instructions on the aligned shapes R*C % 16 == 0, S*C % 4 == 0, W*C % 4 == 0,
- *    F % 64 == 0, B % 16 == 0, R % S == 0; on the other shapes that the pipelined fp32
- *    kernels cover (F % 16 == 0, R*C % 4 == 0, 4*S*C % 4 == 0, W*C % 4 == 0, B > 32 and
- *    B % 4 == 0, R % S == 0 with R/S in 2..5 or 8) the bf16 values are widened on their way
- *    in and multiplied by the fp32 matrix instructions: same results, half the memory, fp32
- *    speed.  LC_EUNSUPPORTED otherwise, returned before anything is launched.
+ *    operands, fp32 accumulation).  Outputs are always fp32.  LC_BF16 covers at least
+ *    F % 16 == 0, R*C % 4 == 0, S*C % 2 == 0, W*C % 4 == 0, R*R*C >= 64, B > 32 and
+ *    B % 4 == 0, R % S == 0 with R/S in 2..5 or 8, and every shape with
+ *    R*C % 16 == 0, S*C % 4 == 0, W*C % 4 == 0, F % 64 == 0, B % 16 == 0, R % S == 0.
+ *    Inside that set the kernels pick bf16 matrix instructions wherever the layout allows
+ *    (always for lc_backward_data; for lc_forward if S*C % 4 == 0; for lc_backward_weights
+ *    if B % 16 == 0) and otherwise widen the bf16 values on their way in and multiply with
+ *    the fp32 matrix instruction: the same results either way.  LC_EUNSUPPORTED outside,
+ *    returned before anything is launched.
  *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    only enqueue work; none synchronises.  Arguments are validated on the host before
  *    anything is launched, so every error except LC_EHIP is returned without touching
