@@ -441,9 +441,11 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
         } else if (ap == 5) {
             if (ntt <= 3) LC_BD(5, 3, 4);
             if (ntt == 4) LC_BD(5, 4, 4);
+            LC_BD(5, 4, 2);
         } else if (ap == 8) {
             // one tile of cell values per wave: eight cells per workgroup share the staged fields
             if (ntt == 1) { *done = true; return launch_fast<4, 1, 8, 8, 8>(g, dy, w, dx, s); }
+            LC_BD(8, 2, 2);
         }
 #undef LC_BD
     }

@@ -16,7 +16,7 @@
 namespace lc {
 namespace {
 
-constexpr int kStripSlots = 8;    // 8-byte staging registers per lane: chunk <= 8 * 256 * 8 B = 16 KB
+constexpr int kStripSlots = 12;   // 8-byte staging registers per lane: chunk <= 12 * 256 * 8 B = 24 KB
 
 // o[u] = (r[0].e_u, r[1].e_u, r[2].e_u, r[3].e_u): four rows of NT bf16 each -> NT operands of four rows
 template <int NT>

@@ -77,6 +77,8 @@ SMALL = {
     "bd_ap4_n48": (wl.LCGeom(B=72, H=28, W=32, C=3, R=16, S=4, F=32), "pink"),       # 4x4 covering fields, 48-value cells
     "bd_ap3_n48": (wl.LCGeom(B=72, H=20, W=24, C=3, R=12, S=4, F=16), "pink"),       # 3x3 covering fields
     "bd_ap4_wide": (wl.LCGeom(B=72, H=24, W=262, C=3, R=16, S=4, F=16), "pink"),     # 66 cells per row: eight cells per workgroup, ragged last strip
+    "bd_ap5_n72": (wl.LCGeom(B=72, H=28, W=15, C=8, R=15, S=3, F=80), "halfnormal"),  # 5x5 covering fields, 72-value cells: two cells per workgroup
+    "bd_ap8_n24": (wl.LCGeom(B=88, H=25, W=24, C=6, R=16, S=2, F=48), "halfnormal"),  # 8x8 covering fields, 24-value cells
     "dense_small": (wl.LCGeom(B=80, H=24, W=24, C=8, R=24, S=1, F=128), "halfnormal"),  # one field: contraction cut into slices
     "dense_k16": (wl.LCGeom(B=72, H=12, W=12, C=4, R=12, S=1, F=128), "halfnormal"),    # one field, 16-value chunks
     "wide_k16": (wl.LCGeom(B=72, H=14, W=16, C=4, R=4, S=2, F=128), "halfnormal"),      # 16-value chunks, many fields
@@ -178,6 +180,8 @@ BF16_CASES = {
     "rows_f16": (wl.LCGeom(B=144, H=30, W=36, C=3, R=16, S=2, F=16), "pink"),
     "rows_f64": (wl.LCGeom(B=64, H=24, W=28, C=3, R=20, S=4, F=64), "pink"),                # two steps in flight
     "rows_f48": (wl.LCGeom(B=64, H=28, W=32, C=3, R=16, S=4, F=48), "pink"),                # three filter blocks
+    "bd_ap5_n72": (wl.LCGeom(B=72, H=28, W=15, C=8, R=15, S=3, F=80), "halfnormal"),        # backward data: two cells per workgroup
+    "bd_ap8_n24": (wl.LCGeom(B=88, H=25, W=24, C=6, R=16, S=2, F=48), "halfnormal"),
 }
 
 
