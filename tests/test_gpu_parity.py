@@ -536,3 +536,43 @@ def test_lc_primitives_bf16_geometry_sweep(idx):
     assert rel_fro(host(y), oracle.lc_forward(t, rnd(x), rnd(w))) <= TOL
     assert rel_fro(host(dx), oracle.lc_backward_data(t, rnd(dy), rnd(w))) <= TOL
     assert rel_fro(host(dw), oracle.lc_backward_weights(t, rnd(x), rnd(dy))) <= TOL
+
+
+def _bf16_narrow_geometries(n, seed):
+    """Seeded random geometries of the narrow layers: patch rows in whole 4-value vectors only, filters in blocks
+    of 16, any batch that is a multiple of 4 above 32."""
+    r = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        S = int(r.choice([1, 2, 4]))
+        R = S * int(r.choice([2, 3, 4, 5, 8]))
+        C = int(r.choice([1, 2, 3, 4, 6, 8, 12]))
+        F = 16 * int(r.integers(1, 6))
+        B = 4 * int(r.integers(9, 40))
+        H, W = R + int(r.integers(0, 14)), R + int(r.integers(0, 14))
+        g = wl.LCGeom(B=B, H=H, W=W, C=C, R=R, S=S, F=F)
+        if R > 24 or (S * C) % 4 or S * C > 60 or (W * C) % 4 or g.K < 64 or g.flop_per_pass > 1e9 or g.params > 8e6:
+            continue
+        out.append(g)
+    return out
+
+
+@pytest.mark.parametrize("idx", range(14))
+def test_lc_primitives_bf16_narrow_sweep(idx):
+    """The bf16 kernels of the narrow layers against the oracle fed the same rounded values."""
+    g = _bf16_narrow_geometries(14, seed=91)[idx]
+    print(f"case bf16 narrow sweep {idx} geom {g}", flush=True)
+    x, w, dy = wl.lc_inputs(g, "pink", seed=idx)
+    t = g.as_tuple()
+    G = lc.geom(*t)
+    bf = lambda a: torch.from_numpy(wl.to_bf16_round(a).view(np.int16)).cuda().view(torch.bfloat16)
+    rnd = lambda a: (wl.to_bf16_round(a).astype(np.uint32) << 16).view(np.float32)
+    y = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
+    dx = torch.full((g.B, g.H, g.W, g.C), float("nan"), device="cuda")
+    dw = torch.full((g.LH, g.LW, g.K, g.F), float("nan"), device="cuda")
+    lc.lc_forward(G, bf(x), bf(w), None, 1.0, y, lc.LC_BF16)
+    lc.lc_backward_data(G, bf(dy), bf(w), dx, lc.LC_BF16)
+    lc.lc_backward_weights(G, bf(x), bf(dy), 0.0, dw, lc.LC_BF16)
+    assert rel_fro(host(y), oracle.lc_forward(t, rnd(x), rnd(w))) <= TOL
+    assert rel_fro(host(dx), oracle.lc_backward_data(t, rnd(dy), rnd(w))) <= TOL
+    assert rel_fro(host(dw), oracle.lc_backward_weights(t, rnd(x), rnd(dy))) <= TOL
