@@ -179,11 +179,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     // one finds the strip's weights in that XCD's L2.  The rows at the top and bottom edge, covered by fewer
     // field rows and cheaper in proportion, come last in plain hardware order, which deals them out evenly:
     // in one contiguous walk the XCDs holding the edge rows would run dry while the others still work.
-#ifdef LC_ABL_PLAIN_ORDER
-    const int r_lo = 0, n_in = 0;
-#else
     const int r_lo = AP - 1, n_in = g.LH > r_lo ? g.LH - r_lo : 0;   // interior cell rows [r_lo, LH)
-#endif
     const int per_row = strips_per_row * nbt, n_first = n_in * per_row;
     int ri, t_id;
     if ((int)blockIdx.x < n_first) {

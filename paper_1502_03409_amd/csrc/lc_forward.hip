@@ -493,13 +493,9 @@ int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float 
         // strip finds the weights in L2).  A layer too small to fill one round of two workgroups per CU at that
         // tile size steps down to smaller wave tiles until it does: finer workgroups spread evenly over the CUs.
         int mt = g.B > 64 && g.F % 64 != 0 ? 8 : g.B > 32 ? 4 : 2, nt = 4;
-#if defined(LC_FWD_FORCE_MT)
-        mt = LC_FWD_FORCE_MT; nt = LC_FWD_FORCE_NT;
-#else
         while (fast_workgroups(g, mt, nt) < kComputeUnits * kBigTilesPerCu && (mt > 2 || nt > 1)) {
             if (nt > 1 && (nt >= mt || mt == 2)) nt >>= 1; else mt >>= 1;
         }
-#endif
         const bool one_tile = g.F % 32 != 0 || nt == 1;
         if (mt == 8 && one_tile && g.LW >= 8 && (8 * g.S * g.C) % 4 == 0)
             rc = launch_fast_wide(g, x, w, bias, alpha, alpha_dev, y, s, &done);
