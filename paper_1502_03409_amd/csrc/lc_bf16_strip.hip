@@ -382,6 +382,188 @@ int launch_rows_pf(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta,
     return launch_rows<G, NT, 1>(g, x, dy, beta, out, s);
 }
 
+// The weight gradient with the patches shared through LDS.  In the kernel above every wave fetches its own
+// 1200 x 128 patch, and those 8-byte loads are what binds it (cfg3: 152 us, 88 us with the patch loads compiled out).
+// Here a workgroup takes four adjacent fields and stages, per patch row, the image-row strip they share (as the
+// forward kernel does; 2.5x fewer patch bytes in cfg3, fetched once); wave = field.  Per patch row a wave contracts
+// over the whole batch: lane (m,kk) reads the patch values 64 blk + 4 m .. +3 of the four images 16 s + 4 kk .. +3
+// from LDS and transposes them in registers into four operands; the dy operands of all steps sit in registers for
+// the whole kernel (batches up to 128 images).  The 64 x 16 NT tile of a patch row is stored as soon as it is
+// complete.  Rows of a block beyond the patch row read the neighbour's pixels: they only reach output rows that
+// are not stored.  The patch rows are split over grid.z so that small layers still fill the chip.
+template <int NT, int NBK>
+__global__ __launch_bounds__(256, 3) void lc_bwd_weights_bf16_strip_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                                         const bf16_t *__restrict__ dy, float beta,
+                                                                         float *__restrict__ out, int strips_per_row,
+                                                                         int sq4, int RS, int rows_per_wg) {
+    typedef typename RawVec<bf16_t, NT>::V BR;     // NT consecutive dy values as loaded
+    typedef typename FVec<NT>::T BV;               // NT consecutive outputs
+    typedef const __attribute__((address_space(1))) BR *gb_ptr;
+    typedef const __attribute__((address_space(1))) u32x2 *gx4_ptr;
+    constexpr int BT = 128, NSTEP = BT / 16, NLOC = 4, NTHR = 256;
+    extern __shared__ __attribute__((aligned(16))) bf16_t xh[];      // [BT][RS] (+ 64 values of slack)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, kk = lane >> 4;
+    const int work = remap_xcd(blockIdx.x, gridDim.x);
+    const int i = work / strips_per_row, j0 = (work - i * strips_per_row) * NLOC;
+    const int j = j0 + wave;
+    const bool active = j < g.LW;
+    const int loc = i * g.LW + (active ? j : g.LW - 1);   // idle waves shadow the last field of the row
+    const int f0 = blockIdx.y * NT * 16;
+    const int kh_lo = blockIdx.z * rows_per_wg, kh_hi = min(g.R, kh_lo + rows_per_wg);
+    const int SC = g.S * g.C, WC = g.W * g.C;
+    const size_t img = (size_t)g.H * WC, dyimg = (size_t)g.L * g.F;
+
+    // dy operands of every step: images 16 s + 4 kk .. +3, filters f0 + NT m .. (zeros beyond the batch)
+    u32x2 bo[NSTEP][NT];
+#pragma unroll
+    for (int st = 0; st < NSTEP; ++st) {
+        BR r[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int b = 16 * st + 4 * kk + jj;
+            r[jj] = BR{};
+            if (b < g.B) r[jj] = *(gb_ptr)(dy + (size_t)b * dyimg + (size_t)loc * g.F + f0 + NT * m);
+        }
+        rows_to_operands<NT>(r, bo[st]);
+    }
+
+    // staging map as in the forward kernel: slot q copies 4-value vector number tid + 256 q of the [BT][sq4] chunk
+    const int sqc = sq4 * 4;
+    const int nslots = (BT * sq4 + NTHR - 1) / NTHR;
+    int sb[kStripSlots];
+    {
+        int vv = tid % sq4, b = tid / sq4;
+        const int dv = NTHR % sq4, db = NTHR / sq4;
+#pragma unroll
+        for (int q = 0; q < kStripSlots; ++q) {
+            sb[q] = (b << 16) | (vv * 4);
+            if (b >= BT) sb[q] = (int)0x80000000;
+            else if (b >= g.B) sb[q] |= 0x40000000;
+            vv += dv; b += db;
+            if (vv >= sq4) { vv -= sq4; ++b; }
+        }
+    }
+    const int col0 = j0 * SC;
+    u32x2 st[kStripSlots];
+    auto stage_load = [&](int kh) {
+        const bf16_t *row = x + (size_t)(i * g.S + kh) * WC + col0;
+        const int lim = WC - col0;
+#pragma unroll
+        for (int q = 0; q < kStripSlots; ++q) {
+            if (q < nslots) {
+                const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xffff;
+                u32x2 t = (u32x2){0u, 0u};
+                if ((sb[q] & 0xc0000000) == 0 && v < lim) t = *(gx4_ptr)(row + (size_t)b * img + v);
+                st[q] = t;
+            }
+        }
+    };
+    auto stage_store = [&]() {
+#pragma unroll
+        for (int q = 0; q < kStripSlots; ++q) {
+            if (q < nslots && sb[q] >= 0) {
+                const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xffff;
+                *(u32x2 *)(xh + b * RS + v) = st[q];
+            }
+        }
+    };
+
+    const bf16_t *xwin = xh + (size_t)(4 * kk) * RS + wave * SC + 4 * m;
+    float *ol = out + (size_t)loc * g.K * g.F + f0 + NT * m;
+    const int nsteps = (g.B + 15) >> 4;
+    if (kh_lo < kh_hi) stage_load(kh_lo);
+    for (int kh = kh_lo; kh < kh_hi; ++kh) {
+        __syncthreads();                    // all waves are done reading the previous patch row
+        stage_store();
+        __syncthreads();
+        if (kh + 1 < kh_hi) stage_load(kh + 1);
+#pragma unroll
+        for (int blk = 0; blk < NBK; ++blk) {
+            if (64 * blk >= g.RC) break;    // uniform
+            f32x4 acc[4][NT];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int u = 0; u < NT; ++u) acc[t][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sp = 0; sp < NSTEP; ++sp) {
+                if (sp < nsteps) {          // uniform
+                    u32x2 r[4], ao[4];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) r[jj] = *(const u32x2 *)(xwin + (size_t)(16 * sp + jj) * RS + 64 * blk);
+                    rows_to_operands<4>(r, ao);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int u = 0; u < NT; ++u) acc[t][u] = mfma16_bf16(ao[t], bo[sp][u], acc[t][u]);
+                }
+            }
+            if (active) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int kl = 64 * blk + 4 * (4 * kk + r) + t;
+                        if (kl >= g.RC) continue;
+                        BV *o = (BV *)(ol + (size_t)(kh * g.RC + kl) * g.F);
+                        BV v;
+                        if constexpr (NT == 1) {
+                            v = acc[t][0][r];
+                        } else {
+#pragma unroll
+                            for (int u = 0; u < NT; ++u) v[u] = acc[t][u][r];
+                        }
+                        if (beta != 0.f) v += beta * *o;
+                        *o = v;
+                    }
+            }
+        }
+    }
+}
+
+// row stride: 16 bytes past a multiple of 128 bytes, wide enough for the staged strip and for the 64-value blocks of
+// the last field (which read past its patch row)
+int wstrip_row_stride(const Geom &g, int sqc) {
+    const int nbk = (g.RC + 63) / 64, need = std::max(sqc, 3 * g.S * g.C + 64 * nbk);
+    return ((need - 8 + 63) / 64) * 64 + 8;
+}
+
+template <int NT, int NBK>
+int launch_wstrip(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, float *out, hipStream_t s) {
+    const int sqc = (g.RC + 3 * g.S * g.C + 3) & ~3;
+    const int RS = wstrip_row_stride(g, sqc);
+    const size_t lds = ((size_t)128 * RS + 64) * sizeof(bf16_t);
+    auto kern = lc_bwd_weights_bf16_strip_kernel<NT, NBK>;
+    if (int rc = allow_dynamic_lds((const void *)kern, lds, "lc_backward_weights (bf16 strip): hipFuncSetAttribute"))
+        return rc;
+    const int strips = (g.LW + 3) / 4;
+    const long long nwork = (long long)strips * g.LH;
+    if (nwork > 0x7fffffffLL) return LC_EUNSUPPORTED;
+    // split the patch rows over grid.z until there are about four workgroups per compute unit
+    int zsplit = 1;
+    while (zsplit < g.R && nwork * (g.F / (NT * 16)) * zsplit < 4 * 256) ++zsplit;
+    const int rows_per_wg = (g.R + zsplit - 1) / zsplit;
+    dim3 grid((unsigned)nwork, g.F / (NT * 16), (g.R + rows_per_wg - 1) / rows_per_wg);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, dy, beta, out, strips, sqc / 4, RS, rows_per_wg);
+    LC_HIP_LAUNCH_CHECK("lc_backward_weights (bf16 strip) launch");
+    return LC_OK;
+}
+
+bool wstrip_supported(const Geom &g) {
+    const int SC = g.S * g.C;
+    if (g.RC % 4 || SC % 4 || (g.W * g.C) % 4 || g.F % 16 || g.B > 128 || g.RC > 128) return false;
+    const int sqc = (g.RC + 3 * SC + 3) & ~3;
+    if ((size_t)128 * (sqc / 4) > (size_t)kStripSlots * 256) return false;
+    return ((size_t)128 * wstrip_row_stride(g, sqc) + 64) * sizeof(bf16_t) <= 48 * 1024 && sqc <= 0xffff;
+}
+
+template <int NT>
+int launch_wstrip_nbk(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, float *out, hipStream_t s) {
+    if (g.RC <= 64) return launch_wstrip<NT, 1>(g, x, dy, beta, out, s);
+    return launch_wstrip<NT, 2>(g, x, dy, beta, out, s);
+}
+
 }  // namespace
 
 // Shapes: patch rows in whole 4-value vectors, filters in blocks of 16, batches in steps of 16 images.
@@ -393,6 +575,10 @@ int launch_backward_weights_bf16_rows(const Geom &g, const void *xv, const void 
                                       hipStream_t s) {
     if (!bf16_rows_backward_weights_supported(g)) return LC_EUNSUPPORTED;
     const bf16_t *x = (const bf16_t *)xv, *dy = (const bf16_t *)dyv;
+    if (wstrip_supported(g)) {
+        if (g.F % 32 == 0) return launch_wstrip_nbk<2>(g, x, dy, beta, dw, s);
+        return launch_wstrip_nbk<1>(g, x, dy, beta, dw, s);
+    }
     if (g.F % 64 == 0) return launch_rows_pf<1, 4>(g, x, dy, beta, dw, s);
     if (g.F % 32 == 0) return launch_rows_pf<2, 2>(g, x, dy, beta, dw, s);
     return launch_rows_pf<2, 1>(g, x, dy, beta, dw, s);

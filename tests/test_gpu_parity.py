@@ -180,6 +180,8 @@ BF16_CASES = {
     "rows_f16": (wl.LCGeom(B=144, H=30, W=36, C=3, R=16, S=2, F=16), "pink"),
     "rows_f64": (wl.LCGeom(B=64, H=24, W=28, C=3, R=20, S=4, F=64), "pink"),                # two steps in flight
     "rows_f48": (wl.LCGeom(B=64, H=28, W=32, C=3, R=16, S=4, F=48), "pink"),                # three filter blocks
+    "wstrip_rc96": (wl.LCGeom(B=48, H=15, W=17, C=16, R=6, S=2, F=32), "halfnormal"),       # weight gradient through LDS: two 64-value blocks per patch row, uncovered column
+    "wstrip_b112": (wl.LCGeom(B=112, H=26, W=32, C=3, R=20, S=4, F=16), "pink"),            # batch short of the 128 staged rows, one filter tile
     "bd_ap5_n72": (wl.LCGeom(B=72, H=28, W=15, C=8, R=15, S=3, F=80), "halfnormal"),        # backward data: two cells per workgroup
     "bd_ap8_n24": (wl.LCGeom(B=88, H=25, W=24, C=6, R=16, S=2, F=48), "halfnormal"),
 }
