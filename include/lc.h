@@ -30,8 +30,9 @@
  *    (The call itself is the test: a shape outside returns LC_EUNSUPPORTED.)
  *    Inside that set the kernels use bf16 matrix instructions wherever the layout allows
  *    (always for lc_backward_data; for lc_forward if S*C % 4 == 0; for lc_backward_weights
- *    if R*C % 4 == 0 and B % 16 == 0) and otherwise widen the bf16 values on their way in
- *    and multiply with the fp32 matrix instruction: the same results either way.
+ *    if R*C % 4 == 0 and either B % 16 == 0 or B <= 128 with S*C % 4 == 0) and otherwise
+ *    widen the bf16 values on their way in and multiply with the fp32 matrix instruction:
+ *    the same results either way.
  *    LC_EUNSUPPORTED is returned before anything is launched.
  *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    only enqueue work; none synchronises.  Arguments are validated on the host before

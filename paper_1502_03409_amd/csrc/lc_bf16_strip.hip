@@ -566,9 +566,10 @@ int launch_wstrip_nbk(const Geom &g, const bf16_t *x, const bf16_t *dy, float be
 
 }  // namespace
 
-// Shapes: patch rows in whole 4-value vectors, filters in blocks of 16, batches in steps of 16 images.
+// Shapes: patch rows in whole 4-value vectors, filters in blocks of 16, and either batches in steps of 16 images or
+// a shape the strip-sharing kernel takes (any batch up to 128: it stages the missing images as zeros).
 bool bf16_rows_backward_weights_supported(const Geom &g) {
-    return g.RC % 4 == 0 && g.F % 16 == 0 && g.B % 16 == 0;
+    return g.RC % 4 == 0 && g.F % 16 == 0 && (g.B % 16 == 0 || wstrip_supported(g));
 }
 
 int launch_backward_weights_bf16_rows(const Geom &g, const void *xv, const void *dyv, float beta, float *dw,
