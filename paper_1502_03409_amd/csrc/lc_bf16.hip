@@ -238,14 +238,15 @@ bool bf16_shape_supported(const Geom &g) {
            g.R % g.S == 0;
 }
 
+// Order of preference, every pass: the workgroup-tiled kernels (wide layers), the strip-sharing / pipelined / transposing
+// kernels of the narrow layers (faster than the one-wave-per-task kernels of this file wherever both apply: cfg2
+// 30 / 13 / 9 us against 37 / 21 / 10 us), the kernels of this file, the fp32 kernels on bf16 storage.
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s) {
-    // other shapes: the fp32 pipelined kernel reading bf16 storage (same MFMAs, half the bytes), where it applies
-    if (!bf16_shape_supported(g)) {
-        if (bf16_strip_forward_supported(g)) return launch_forward_bf16_strip(g, x, w, bias, alpha, y, s);
-        return launch_forward_bf16_storage(g, x, w, bias, alpha, y, s);
-    }
-    if (bf16_tiled_forward_supported(g)) return launch_forward_bf16_tiled(g, x, w, bias, alpha, y, s);
+    if (bf16_shape_supported(g) && bf16_tiled_forward_supported(g))
+        return launch_forward_bf16_tiled(g, x, w, bias, alpha, y, s);
+    if (bf16_strip_forward_supported(g)) return launch_forward_bf16_strip(g, x, w, bias, alpha, y, s);
+    if (!bf16_shape_supported(g)) return launch_forward_bf16_storage(g, x, w, bias, alpha, y, s);
     const int fblocks = g.F / 64;
     auto go = [&](auto kern, int MT) {
         const int btiles = (g.B + 16 * MT - 1) / (16 * MT);
@@ -260,8 +261,12 @@ int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float
 }
 
 int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
-    if (!bf16_shape_supported(g)) return launch_backward_data_bf16_storage(g, dy, w, dx, s);
-    if (bf16_tiled_backward_data_supported(g)) return launch_backward_data_bf16_tiled(g, dy, w, dx, s);
+    if (bf16_shape_supported(g) && bf16_tiled_backward_data_supported(g))
+        return launch_backward_data_bf16_tiled(g, dy, w, dx, s);
+    {
+        const int rc = launch_backward_data_bf16_storage(g, dy, w, dx, s);   // the pipelined kernel with bf16 MFMAs
+        if (rc != LC_EUNSUPPORTED || !bf16_shape_supported(g)) return rc;
+    }
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int nblocks = (g.S * g.S * g.C + 63) / 64;
     auto go = [&](auto kern, int MT) {
@@ -279,11 +284,10 @@ int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, floa
 
 int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, float beta, float *dw,
                                  hipStream_t s) {
-    if (!bf16_shape_supported(g)) {
-        if (bf16_rows_backward_weights_supported(g)) return launch_backward_weights_bf16_rows(g, x, dy, beta, dw, s);
-        return launch_backward_weights_bf16_storage(g, x, dy, beta, dw, s);
-    }
-    if (bf16_tiled_backward_weights_supported(g)) return launch_backward_weights_bf16_tiled(g, x, dy, beta, dw, s);
+    if (bf16_shape_supported(g) && bf16_tiled_backward_weights_supported(g))
+        return launch_backward_weights_bf16_tiled(g, x, dy, beta, dw, s);
+    if (bf16_rows_backward_weights_supported(g)) return launch_backward_weights_bf16_rows(g, x, dy, beta, dw, s);
+    if (!bf16_shape_supported(g)) return launch_backward_weights_bf16_storage(g, x, dy, beta, dw, s);
     const int kblocks = (g.K + 127) / 128;
     const long long ntasks = (long long)g.L * kblocks;
     hipLaunchKernelGGL(lc_bwd_weights_bf16_kernel, dim3((unsigned)((ntasks + 3) / 4), g.F / 64), dim3(256), 0, s, g,
