@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void lcn_channel_kernel(Args a) {
     const int CBV = a.CB / V;
     float *m1 = lds, *m2 = lds + hh * hw * a.CB;
     const int tid = threadIdx.x;
-    int blk = blockIdx.x;
+    int blk = remap_xcd(blockIdx.x, gridDim.x);   // an image's tiles, whose halos overlap, stay in one XCD's L2
     const int chunk = blk % a.nchunk;
     blk /= a.nchunk;
     const int b = blk / a.tiles_per_img, tile = blk - b * a.tiles_per_img;

@@ -185,7 +185,9 @@ __global__ __launch_bounds__(256) void l2pool_tile_kernel(const float *__restric
                                                           int tiles_w, int tiles_per_img) {
     extern __shared__ __attribute__((aligned(16))) float patch[];   // [(TH+ks-1)*(TW+ks-1)][C]
     const int tid = threadIdx.x, CV = C >> 2;
-    const int b = blockIdx.x / tiles_per_img, tile = blockIdx.x - b * tiles_per_img;
+    // each XCD walks a contiguous range of tiles: the tiles of one image, whose halos overlap, share an L2
+    const int blk = remap_xcd(blockIdx.x, gridDim.x);
+    const int b = blk / tiles_per_img, tile = blk - b * tiles_per_img;
     const int ti = (tile / tiles_w) * kPoolTH, tj = (tile % tiles_w) * kPoolTW;
     const int PH = kPoolTH + ks - 1, PW = kPoolTW + ks - 1;
     // patch origin in the source grid: forward reads inputs (ti.., tj..); backward reads outputs (ti-ks+1.., tj-ks+1..)
@@ -293,7 +295,9 @@ __global__ __launch_bounds__(256) void lcn_kernel(const float *__restrict__ x, c
     __shared__ float t1[kLcnTile * kLcnTile], t2[kLcnTile * kLcnTile];
     const int r = (ks - 1) / 2, halo = kLcnTile + 2 * r;
     const int tid = threadIdx.x;
-    const int b = blockIdx.x / tiles_per_img, tile = blockIdx.x - b * tiles_per_img;
+    // each XCD walks a contiguous range of tiles: the tiles of one image, whose halos overlap, share an L2
+    const int blk = remap_xcd(blockIdx.x, gridDim.x);
+    const int b = blk / tiles_per_img, tile = blk - b * tiles_per_img;
     const int ti = (tile / tiles_w) * kLcnTile, tj = (tile % tiles_w) * kLcnTile;
     const int CV = C / VEC;
     const size_t img = (size_t)b * H * W;
@@ -494,7 +498,9 @@ __global__ __launch_bounds__(256) void lcn_fwd_cached_kernel(const float *__rest
     __shared__ float t1[kLcnTile * kLcnTile], t2[kLcnTile * kLcnTile];
     const int r = (ks - 1) / 2, halo = kLcnTile + 2 * r;
     const int tid = threadIdx.x, grp = tid / LPP, gl = tid % LPP;
-    const int b = blockIdx.x / tiles_per_img, tile = blockIdx.x - b * tiles_per_img;
+    // each XCD walks a contiguous range of tiles: the tiles of one image, whose halos overlap, share an L2
+    const int blk = remap_xcd(blockIdx.x, gridDim.x);
+    const int b = blk / tiles_per_img, tile = blk - b * tiles_per_img;
     const int ti = (tile / tiles_w) * kLcnTile, tj = (tile % tiles_w) * kLcnTile;
     const size_t img = (size_t)b * H * W;
     // window normalisers of the tile's rows and columns (read after phase 1's barrier)
