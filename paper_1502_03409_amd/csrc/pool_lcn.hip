@@ -7,6 +7,10 @@
 // the channels: the channel sums are wavefront reductions, the window sums a small LDS stencil.
 #include "lc_common.hpp"
 
+#ifndef LC_BAND_NTHR
+#define LC_BAND_NTHR 1024
+#endif
+
 namespace lc {
 
 // ------------------------------------------------------------------ L2 pooling
@@ -583,6 +587,173 @@ __global__ __launch_bounds__(256) void lcn_fwd_cached_kernel(const float *__rest
     }
 }
 
+// Band kernels for the one-stage pooled form, C = 4*LPP channels (LPP a power of two up to 16): a workgroup owns
+// RB whole rows of one image.  Its own pixels are loaded once and stay in registers (NV float4 per thread, of x and,
+// backward, of dy); only the (ks-1)/2 rows above and below the band are read a second time by the neighbouring
+// bands, so a 5x5 window over a band of 22 rows re-reads 18 % of the input where a 16x16 tile re-reads 56 %.
+// The maps of per-pixel channel sums carry a margin of (ks-1)/2 zero columns on both sides: phase 2 has no bounds
+// checks.  MODE 0: forward (x -> y, mu, rstd).  MODE 1: backward (x, mu, rstd, dy -> dx).
+template <int LPP, int MODE, int NTHR, int NV>
+__global__ __launch_bounds__(NTHR) void lcn_band_kernel(const float *__restrict__ x, const float *__restrict__ dy,
+                                                        float *__restrict__ out, float *__restrict__ mu,
+                                                        float *__restrict__ rstd, int H, int W, int ks, float eps,
+                                                        GaussTaps taps, int RB, int bands, int zpad) {
+    constexpr int C = 4 * LPP, NH = 2;
+    extern __shared__ __attribute__((aligned(16))) float band_lds[];
+    const int r = (ks - 1) / 2, MW = W + 2 * r, MH = RB + 2 * r;
+    float *m1 = band_lds, *m2 = m1 + MH * MW, *t1 = m2 + MH * MW, *t2 = t1 + RB * W;
+    float *zr = t2 + RB * W, *zc = zr + MH;                       // window normalisers of the staged rows, of all columns
+    const int tid = threadIdx.x, gl = tid % LPP;
+    const int blk = remap_xcd(blockIdx.x, gridDim.x);             // the bands of one image stay in one XCD
+    const int b = blk / bands, r0 = (blk - b * bands) * RB;
+    const size_t img = (size_t)b * H * W;
+    const int npix = RB * W;
+
+    for (int i = tid; i < MH + W; i += NTHR) {
+        if (i < MH) zr[i] = zpad ? 1.f : tap_norm(taps, r0 - r + i, H, r);
+        else zc[i - MH] = zpad ? 1.f : tap_norm(taps, i - MH, W, r);
+    }
+    // map cells outside the image are zero; every other cell is written exactly once below
+    for (int cell = tid; cell < MH * MW; cell += NTHR) {
+        const int hi = cell / MW, hj = cell - hi * MW;
+        const int row = r0 - r + hi, col = hj - r;
+        if (row < 0 || row >= H || col < 0 || col >= W) m1[cell] = m2[cell] = 0.f;
+    }
+    if (MODE == 1) __syncthreads();                               // the backward maps use zr and zc
+
+    // channel sums of one pixel (all LPP lanes of its group call this) -> the two maps of phase 2
+    auto put = [&](int row, int col, bool in, const float4 &v, const float4 &d) {
+        float a, c2;
+        float mp = 0.f, rsp = 0.f;
+        if (MODE == 0) {
+            a = (v.x + v.y) + (v.z + v.w);
+            c2 = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+        } else {
+            if (in) { mp = mu[img + (size_t)row * W + col]; rsp = rstd[img + (size_t)row * W + col]; }
+            a = (d.x + d.y) + (d.z + d.w);
+            c2 = (d.x * (v.x - mp) + d.y * (v.y - mp)) + (d.z * (v.z - mp) + d.w * (v.w - mp));
+        }
+        a = group_sum(a, LPP);
+        c2 = group_sum(c2, LPP);
+        if (gl == 0 && in) {
+            const int cell = (row - r0 + r) * MW + col + r;
+            if (MODE == 0) {
+                m1[cell] = a;
+                m2[cell] = c2;
+            } else {
+                // this pixel's own normaliser and statistics folded into what the transposed window sums need
+                const float z = zr[row - r0 + r] * zc[col] * (float)C;
+                const float bc = rsp * rsp * rsp * c2;
+                m1[cell] = (bc * mp - rsp * a) / z;
+                m2[cell] = bc / z;
+            }
+        }
+    };
+
+    // phase 1: every load of the workgroup is issued before the first reduction: the band's own pixels, kept in
+    // registers, and NH rounds of the rows above and below the band (further rounds, if any, follow)
+    float4 xv[NV], dv[MODE == 1 ? NV : 1], hx[NH], hd[MODE == 1 ? NH : 1];
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int nhalo = 2 * r * W * LPP;
+    auto halo_row = [&](int e) { const int hr = e / (W * LPP); return hr < r ? r0 - r + hr : r0 + RB + hr - r; };
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        const int pp = (q * NTHR + tid) / LPP;
+        const int row = r0 + pp / W, col = pp % W;
+        xv[q] = zero4;
+        if (MODE == 1) dv[q] = zero4;
+        if (pp < npix && row < H) {
+            const size_t o = (img + (size_t)row * W + col) * C + gl * 4;
+            xv[q] = *(const float4 *)(x + o);
+            if (MODE == 1) dv[q] = *(const float4 *)(dy + o);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < NH; ++q) {
+        const int e = q * NTHR + tid, row = halo_row(e), col = (e / LPP) % W;
+        hx[q] = zero4;
+        if (MODE == 1) hd[q] = zero4;
+        if (e < nhalo && row >= 0 && row < H) {
+            const size_t o = (img + (size_t)row * W + col) * C + gl * 4;
+            hx[q] = *(const float4 *)(x + o);
+            if (MODE == 1) hd[q] = *(const float4 *)(dy + o);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        const int pp = (q * NTHR + tid) / LPP;
+        const int row = r0 + pp / W, col = pp % W;
+        put(row, col, pp < npix && row < H, xv[q], MODE == 1 ? dv[q] : zero4);
+    }
+#pragma unroll
+    for (int q = 0; q < NH; ++q) {
+        const int e = q * NTHR + tid, row = halo_row(e), col = (e / LPP) % W;
+        put(row, col, e < nhalo && row >= 0 && row < H, hx[q], MODE == 1 ? hd[q] : zero4);
+    }
+    for (int e = NH * NTHR + tid; e < nhalo; e += NTHR) {
+        const int row = halo_row(e), col = (e / LPP) % W;
+        const bool in = row >= 0 && row < H;
+        float4 v = zero4, d = zero4;
+        if (in) {
+            const size_t o = (img + (size_t)row * W + col) * C + gl * 4;
+            v = *(const float4 *)(x + o);
+            if (MODE == 1) d = *(const float4 *)(dy + o);
+        }
+        put(row, col, in, v, d);
+    }
+    __syncthreads();
+
+    // phase 2: window sums, one thread per pixel of the band
+    for (int pp = tid; pp < npix; pp += NTHR) {
+        const int oi = pp / W, oj = pp - oi * W, row = r0 + oi;
+        if (row >= H) break;
+        float s1 = 0.f, s2 = 0.f;
+        for (int p = 0; p < ks; ++p) {
+            const float *a1 = m1 + (oi + p) * MW + oj, *a2 = m2 + (oi + p) * MW + oj;
+            float u1 = 0.f, u2 = 0.f;
+            for (int q = 0; q < ks; ++q) {
+                u1 += taps.g[q] * a1[q];
+                u2 += taps.g[q] * a2[q];
+            }
+            s1 += taps.g[p] * u1;
+            s2 += taps.g[p] * u2;
+        }
+        if (MODE == 0) {
+            const float z = zr[oi + r] * zc[oj] * (float)C;
+            const float m = s1 / z, q2 = s2 / z;
+            const float rs = 1.0f / sqrtf(fmaxf(q2 - m * m, 0.f) + eps);
+            mu[img + (size_t)row * W + oj] = m;
+            rstd[img + (size_t)row * W + oj] = rs;
+            t1[pp] = m;
+            t2[pp] = rs;
+        } else {
+            t1[pp] = s1;
+            t2[pp] = s2;
+        }
+    }
+    __syncthreads();
+
+    // phase 3: elementwise pass over the registers of phase 1a
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        const int pp = (q * NTHR + tid) / LPP;
+        const int row = r0 + pp / W, col = pp % W;
+        if (pp >= npix || row >= H) continue;
+        const size_t pix = img + (size_t)row * W + col;
+        const float u = t1[pp], v = t2[pp];
+        const float4 xq = xv[q];
+        if (MODE == 0) {
+            *(float4 *)(out + pix * C + gl * 4) =
+                make_float4((xq.x - u) * v, (xq.y - u) * v, (xq.z - u) * v, (xq.w - u) * v);
+        } else {
+            const float rs = rstd[pix];
+            const float4 d = dv[q];
+            *(float4 *)(out + pix * C + gl * 4) = make_float4(d.x * rs + u - xq.x * v, d.y * rs + u - xq.y * v,
+                                                             d.z * rs + u - xq.z * v, d.w * rs + u - xq.w * v);
+        }
+    }
+}
+
 namespace {
 
 int grid_for(long long total) {
@@ -669,6 +840,48 @@ int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx
     return LC_OK;
 }
 
+namespace {
+
+// Rows per band: as many as the registers hold (NV float4 per thread), split evenly over the image.  The band
+// kernel pays where a band is at least 8 rows and two window radii high; below that the 16x16 tiles re-read less.
+template <int LPP, int MODE>
+int launch_lcn_band_lpp(const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
+                        int ks, float eps, const GaussTaps &taps, hipStream_t s, int zero_pad, bool *done) {
+    constexpr int NTHR = LC_BAND_NTHR, NV = 8;
+    const int r = (ks - 1) / 2;
+    const int rb_max = (NTHR * NV) / (W * LPP);
+    if (rb_max < 8 || rb_max < 2 * r) return LC_OK;
+    const int bands = (H + rb_max - 1) / rb_max, RB = (H + bands - 1) / bands;
+    const size_t lds = ((size_t)2 * (RB + 2 * r) * (W + 2 * r) + (size_t)2 * RB * W + (RB + 2 * r) + W) * sizeof(float);
+    const long long nblk = (long long)B * bands;
+    if (lds > 64 * 1024 || nblk > 0x7fffffffLL) return LC_OK;
+    auto kern = lcn_band_kernel<LPP, MODE, NTHR, NV>;
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lcn: hipFuncSetAttribute")) return rc_lds;
+    *done = true;
+    hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(NTHR), lds, s, x, dy, out, mu, rstd, H, W, ks, eps, taps, RB,
+                       bands, zero_pad);
+    LC_HIP_LAUNCH_CHECK("lcn launch");
+    return LC_OK;
+}
+
+int launch_lcn_band(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
+                    int C, int ks, float eps, const GaussTaps &taps, hipStream_t s, int zero_pad, bool *done) {
+#define LC_BAND(LPP_)                                                                                               \
+    return mode == 0 ? launch_lcn_band_lpp<LPP_, 0>(x, dy, out, mu, rstd, B, H, W, ks, eps, taps, s, zero_pad, done) \
+                     : launch_lcn_band_lpp<LPP_, 1>(x, dy, out, mu, rstd, B, H, W, ks, eps, taps, s, zero_pad, done)
+    switch (C) {
+        case 4: LC_BAND(1);
+        case 8: LC_BAND(2);
+        case 16: LC_BAND(4);
+        case 32: LC_BAND(8);
+        case 64: LC_BAND(16);
+        default: return LC_OK;
+    }
+#undef LC_BAND
+}
+
+}  // namespace
+
 int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
                int C, int ks, float sigma, float eps, hipStream_t s, int zero_pad, float *field) {
     GaussTaps taps;
@@ -677,6 +890,11 @@ int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu,
     const int tiles_h = (H + kLcnTile - 1) / kLcnTile, tiles_w = (W + kLcnTile - 1) / kLcnTile;
     const long long nblk = (long long)B * tiles_h * tiles_w;
     if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
+    if (mode == 0 || mode == 1) {
+        bool done = false;
+        const int rc = launch_lcn_band(mode, x, dy, out, mu, rstd, B, H, W, C, ks, eps, taps, s, zero_pad, &done);
+        if (done) return rc;
+    }
     const int vec = (C % 4 == 0) ? 4 : 1;
     const int lpp = lanes_per_pixel(C / vec);
     dim3 grid((unsigned)nblk), block(256);
