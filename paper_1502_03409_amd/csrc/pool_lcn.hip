@@ -5,6 +5,8 @@
 // Pooling is not part of the paper's network (Sec. 3.1 leaves it out); LCN is applied after each layer
 // (Sec. 3.1) and is taken here as Gaussian-windowed local standardisation with statistics pooled over
 // the channels: the channel sums are wavefront reductions, the window sums a small LDS stencil.
+#include <algorithm>
+
 #include "lc_common.hpp"
 
 #ifndef LC_BAND_NTHR
@@ -257,6 +259,61 @@ __global__ __launch_bounds__(256) void l2pool_tile_kernel(const float *__restric
             } else {
                 *(f32x4 *)(out + o + (size_t)q * C) = *(const f32x4 *)(x + o + (size_t)q * C) * sacc;
             }
+        }
+    }
+}
+
+// Forward pooling as a stream, stride 1 and a KS x KS window: a thread owns one output column and channel quad
+// and walks down RS output rows.  Each input row it meets gives one horizontal sum of squares (KS loads whose
+// neighbours in the wave read the same lines); the last KS-1 of them stay in registers, so an output costs one new
+// row of loads.  No LDS and no barriers: every wave reads and writes all the time, and the loads of RU rows are in
+// flight together.  Segments of RS rows re-read KS-1 input rows of the segment above.
+template <int KS, int RU>
+__global__ __launch_bounds__(256) void l2pool_fwd_stream_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                int H, int W, int CV, int Ho, int Wo, int RS,
+                                                                int nseg, float eps, long long total) {
+    const long long e = (long long)remap_xcd(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int per_row = Wo * CV;
+    const int cj = (int)(e % per_row);
+    const long long t = e / per_row;
+    const int sg = (int)(t % nseg), b = (int)(t / nseg);
+    const int ro0 = sg * RS, ro1 = min(ro0 + RS, Ho);
+    const size_t xrow = (size_t)W * CV, yrow = (size_t)Wo * CV;     // row strides in float4
+    const f32x4 *xp = (const f32x4 *)x + (size_t)b * H * xrow + cj;  // column j, quad cv: offset j*CV + cv = cj
+    f32x4 *yp = (f32x4 *)y + (size_t)b * Ho * yrow + cj;
+    f32x4 ring[KS - 1];
+#pragma unroll
+    for (int d = 0; d < KS - 1; ++d) {
+        const f32x4 *p = xp + (size_t)min(ro0 + d, H - 1) * xrow;
+        f32x4 h = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int dj = 0; dj < KS; ++dj) { const f32x4 v = p[dj * CV]; h += v * v; }
+        ring[d] = h;
+    }
+    for (int ro = ro0; ro < ro1; ro += RU) {
+        f32x4 v[RU][KS];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            // rows past the segment are read from the last input row and never stored
+            const f32x4 *p = xp + (size_t)min(ro + u + KS - 1, H - 1) * xrow;
+#pragma unroll
+            for (int dj = 0; dj < KS; ++dj) v[u][dj] = p[dj * CV];
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            f32x4 h = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int dj = 0; dj < KS; ++dj) h += v[u][dj] * v[u][dj];
+            f32x4 sacc = h;
+#pragma unroll
+            for (int d = 0; d < KS - 1; ++d) sacc += ring[d];
+            if (ro + u < ro1)
+                yp[(size_t)(ro + u) * yrow] = (f32x4){sqrtf(eps + sacc[0]), sqrtf(eps + sacc[1]),
+                                                      sqrtf(eps + sacc[2]), sqrtf(eps + sacc[3])};
+#pragma unroll
+            for (int d = 0; d + 1 < KS - 1; ++d) ring[d] = ring[d + 1];
+            ring[KS - 2] = h;
         }
     }
 }
@@ -786,7 +843,19 @@ int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int 
                       hipStream_t s) {
     const int Ho = (H - ks) / st + 1, Wo = (W - ks) / st + 1;
     const size_t patch_bytes = (size_t)(kPoolTH + ks - 1) * (kPoolTW + ks - 1) * C * sizeof(float);
-    if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && patch_bytes <= 64 * 1024) {
+    if (C % 4 == 0 && st == 1 && ks == 3 && Ho > 0 && Wo > 0 && B > 0) {
+        // segments of RS rows, a multiple of the four rows a thread has in flight: enough segments for about
+        // sixteen waves per compute unit (cfg3's shape: 8 rows 11.7 us, 4 rows 12.1 us, 16 rows 13.5 us)
+        const int CV = C / 4;
+        const long long cols = (long long)B * Wo * CV;
+        const long long want = std::max<long long>((256LL * 16 * 64 + cols - 1) / cols, 1);
+        const int RS = (int)std::max<long long>(((Ho + want - 1) / want + 3) / 4 * 4, 4);
+        const int nseg = (Ho + RS - 1) / RS;
+        const long long total = cols * nseg, nblk = (total + 255) / 256;
+        if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
+        hipLaunchKernelGGL((l2pool_fwd_stream_kernel<3, 4>), dim3((unsigned)nblk), dim3(256), 0, s, x, y, H, W, CV, Ho,
+                           Wo, RS, nseg, eps, total);
+    } else if (C % 4 == 0 && st == 1 && ks <= kPoolMaxK && patch_bytes <= 64 * 1024) {
         const int th = (Ho + kPoolTH - 1) / kPoolTH, tw = (Wo + kPoolTW - 1) / kPoolTW;
         const long long nblk = (long long)B * th * tw;
         if (nblk > 0x7fffffffLL) return LC_EUNSUPPORTED;
