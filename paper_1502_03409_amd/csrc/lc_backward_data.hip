@@ -347,6 +347,170 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Layers of 32 filters per field (a row of w[l] and a field's dy are exactly one 128-byte line).  The pipelined
+// kernel above reads such a line in two halves a whole chunk apart, and the memory side moves whole lines: by the
+// time the second half is asked for, the line has left the L2 again and is fetched a second time.  Here a chunk is
+// one field row with all 32 filters, so both halves of a line are read within one step of each other: the staged
+// dy arrives as whole lines, and the weight ring (five half-steps deep, as above) asks for the halves of a row in
+// consecutive half-steps.  The chunk is twice as large, so there is one LDS buffer and two barriers per chunk:
+// the next chunk waits in the staging registers while the current one is multiplied.
+template <int MT, int NT, int NCELL, int AP>
+__global__ __launch_bounds__(256, 2) void lc_bwd_data_line_kernel(Geom g, const float *__restrict__ dy,
+                                                                  const float *__restrict__ w,
+                                                                  float *__restrict__ dx, int strips_per_row,
+                                                                  int RS, int nbt) {
+    typedef const __attribute__((address_space(1))) f32x4 *g4_ptr;
+    typedef const __attribute__((address_space(1))) float *gf_ptr;
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 8;   // R4: float4 per image and chunk (32 f per field)
+    constexpr int NTHR = 256, NSLOT = (BT * R4 + NTHR - 1) / NTHR, NHS = 2 * AP, RING = 5;
+    static_assert(NHS % RING == 0, "the ring's slot pattern must repeat every chunk");
+    extern __shared__ __attribute__((aligned(16))) float dys_line[];
+    float *dys = dys_line;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, kk = lane >> 4;
+    const int SC = g.S * g.C, NCV = g.S * SC;
+    // work order as in the pipelined kernel: full-cost cell rows first, a contiguous range per XCD with the batch
+    // tiles of a strip next to each other; the cheaper rows at the top and bottom edge last, dealt out evenly
+    const int r_lo = AP - 1, n_in = g.LH > r_lo ? g.LH - r_lo : 0;
+    const int per_row = strips_per_row * nbt, n_first = n_in * per_row;
+    int ri, t_id;
+    if ((int)blockIdx.x < n_first) {
+        t_id = remap_xcd(blockIdx.x, n_first);
+        ri = r_lo + t_id / per_row;
+    } else if (n_in > 0) {
+        t_id = blockIdx.x - n_first;
+        const int rb = t_id / per_row;
+        ri = rb < r_lo ? rb : g.LH + (rb - r_lo);
+    } else {
+        t_id = remap_xcd(blockIdx.x, gridDim.x);
+        ri = t_id / per_row;
+    }
+    const int wi0 = ((t_id / nbt) % strips_per_row) * NCELL;
+    const int b0 = (t_id % nbt) * BT;
+    const int wc = wave % NCELL;
+    const int wi = wi0 + wc;
+    const int n0 = (blockIdx.y * (4 / NCELL) + wave / NCELL) * NT * 16;
+
+    int kn[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int nn = n0 + nt * 16 + m;
+        const int nc = nn < NCV ? nn : 0;
+        const int dr = nc / SC;
+        kn[nt] = (dr * g.RC + (nc - dr * SC)) * g.F + 4 * kk;
+    }
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // chunks: the valid field rows i = ri - a
+    const int a_lo = max(0, ri - (g.LH - 1)), a_hi = min(AP - 1, ri);
+    const int nchunks = a_hi >= a_lo ? a_hi - a_lo + 1 : 0;
+    const int jlo = wi0 - (AP - 1);
+    const size_t dyimg = (size_t)g.L * g.F;
+
+    const int v0 = tid % R4, bq0 = tid / R4;
+    constexpr int DV = NTHR % R4, DB = NTHR / R4;
+    f32x4 st[NSLOT];
+    auto stage_load = [&](int c) {
+        const float *base = dy + (size_t)b0 * dyimg + (size_t)((ri - (a_lo + c)) * g.LW) * g.F;
+        int v = v0, b = bq0;
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) {
+            const int j = jlo + (v >> 3);
+            f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (b < BT && b0 + b < g.B && j >= 0 && j < g.LW)
+                t = *(g4_ptr)(base + (size_t)b * dyimg + j * g.F + (v & 7) * 4);
+            st[q] = t;
+            v += DV; b += DB;
+            if (v >= R4) { v -= R4; ++b; }
+        }
+    };
+    auto stage_store = [&]() {
+        int v = v0, b = bq0;
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) {
+            if (b < BT) {
+                float *dst = dys + b * RS + v * 4;      // 8-byte stores: 16-byte ones of a row-major tile conflict
+                *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
+                *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
+            }
+            v += DV; b += DB;
+            if (v >= R4) { v -= R4; ++b; }
+        }
+    };
+    // weights of half-step hs = 2 a' + fh of chunk c: filters 16 fh .. 16 fh + 15 of field (ri-a, wi-a'), clamped
+    auto wbase = [&](int c, int hs) -> gf_ptr {
+        const int a = a_lo + c, ap = hs >> 1;
+        int j = wi - ap;
+        j = j < 0 ? 0 : (j >= g.LW ? g.LW - 1 : j);
+        return (gf_ptr)w + ((size_t)((ri - a) * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F +
+               (hs & 1) * 16;
+    };
+
+    if (nchunks > 0) {
+        f32x4 wb[RING][NT];
+#pragma unroll
+        for (int hs = 0; hs < RING; ++hs) {
+            gf_ptr p0 = wbase(0, hs);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) wb[hs][nt] = *(g4_ptr)(p0 + kn[nt]);
+        }
+        stage_load(0);
+        for (int c = 0; c < nchunks; ++c) {
+            if (c > 0) __syncthreads();               // every wave has left chunk c-1
+            stage_store();
+            if (c + 1 < nchunks) stage_load(c + 1);
+            __syncthreads();
+            const float *arow = dys + m * RS + 4 * kk;
+            const int cn = c + 1 < nchunks ? c + 1 : c;
+#pragma unroll
+            for (int hs = 0; hs < NHS; ++hs) {
+                const int ap = hs >> 1, fh = hs & 1, slot = hs % RING;
+                const int js = wc - ap + AP - 1;
+                if (wi - ap >= 0 && wi - ap < g.LW) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const f32x4 av = *(const f32x4 *)(arow + mt * 16 * RS + js * 32 + fh * 16);
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+#pragma unroll
+                            for (int nt = 0; nt < NT; ++nt)
+                                acc[mt][nt] = mfma16(av[t], wb[slot][nt][t], acc[mt][nt]);
+                    }
+                }
+                gf_ptr pn = hs + RING < NHS ? wbase(c, hs + RING) : wbase(cn, hs + RING - NHS);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) wb[slot][nt] = *(g4_ptr)(pn + kn[nt]);
+                __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
+            }
+        }
+    }
+
+    if (wi * g.S >= g.W) return;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int nn = n0 + nt * 16 + m;
+        if (nn >= NCV) continue;
+        const int dr = nn / SC, rem = nn - dr * SC;
+        const int row = ri * g.S + dr, col = wi * g.S + rem / g.C;
+        if (row >= g.H || col >= g.W) continue;
+        const size_t pix = ((size_t)row * g.W + wi * g.S) * g.C + rem;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int b = b0 + mt * 16 + 4 * kk + r;
+                if (b < g.B) dx[(size_t)b * g.H * g.W * g.C + pix] = acc[mt][nt][r];
+            }
+    }
+}
+
 namespace {
 
 constexpr size_t kLdsTarget = 78 * 1024;
@@ -396,6 +560,24 @@ int launch_mt(const Geom &g, const float *dy, const float *w, float *dx, hipStre
 
 namespace {
 
+template <int MT, int NT, int NCELL, int AP>
+int launch_line(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
+    const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
+    const int NCV = g.S * g.S * g.C;
+    const int RS = JW * 32 + 4;                               // 16 bytes past a multiple of 128, as below
+    const size_t lds = (size_t)BT * RS * sizeof(float);
+    auto kern = lc_bwd_data_line_kernel<MT, NT, NCELL, AP>;
+    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
+    const int strips = (CW + NCELL - 1) / NCELL;
+    const int nblk = (4 / NCELL) * NT * 16;
+    const int nbt = (g.B + BT - 1) / BT;
+    dim3 grid(strips * CH * nbt, (NCV + nblk - 1) / nblk);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, RS, nbt);
+    LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
+    return LC_OK;
+}
+
 template <int MT, int NT, int NCELL, int AP, int NW = 4, typename T>
 int launch_fast(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s) {
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
@@ -443,6 +625,9 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
             if (ntt == 4) LC_BD(4, 4, 4);
             LC_BD(4, 4, 2);
         } else if (ap == 5) {
+            if constexpr (sizeof(T) == 4) {
+                if (ntt <= 3 && g.F == 32) { *done = true; return launch_line<4, 3, 4, 5>(g, (const float *)dy, (const float *)w, dx, s); }
+            }
             if (ntt <= 3) LC_BD(5, 3, 4);
             if (ntt == 4) LC_BD(5, 4, 4);
             LC_BD(5, 4, 2);
