@@ -226,11 +226,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     constexpr int DV = NTHR % R4, DB = NTHR / R4;
     XV st[NSLOT];
     auto stage_load = [&](int c) {
-#ifdef EXP_FH_OUTER
-        const int na_ = a_hi - a_lo + 1; const int fh = c / na_, a = a_lo + c - fh * na_;
-#else
         const int a = a_lo + c / nfh, fh = c - (c / nfh) * nfh;
-#endif
         const T *base = dy + (size_t)b0 * dyimg + (size_t)((ri - a) * g.LW) * g.F + fh * 16;
         int v = v0, b = bq0;
 #pragma unroll
@@ -264,11 +260,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     };
     // weights of step (chunk c, a'): field (ri-a, wi-a') clamped into the grid
     auto wbase = [&](int c, int ap) -> gf_ptr {
-#ifdef EXP_FH_OUTER
-        const int na_ = a_hi - a_lo + 1; const int fh = c / na_, a = a_lo + c - fh * na_;
-#else
         const int a = a_lo + c / nfh, fh = c - (c / nfh) * nfh;
-#endif
         int j = wi - ap;
         j = j < 0 ? 0 : (j >= g.LW ? g.LW - 1 : j);
         return (gf_ptr)w + ((size_t)((ri - a) * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F +
