@@ -83,6 +83,10 @@ SMALL = {
     "dense_k16": (wl.LCGeom(B=72, H=12, W=12, C=4, R=12, S=1, F=128), "halfnormal"),    # one field, 16-value chunks
     "wide_k16": (wl.LCGeom(B=72, H=14, W=16, C=4, R=4, S=2, F=128), "halfnormal"),      # 16-value chunks, many fields
     "single_img": (wl.LCGeom(B=1, H=9, W=9, C=2, R=3, S=3, F=5), "gaussian"),
+    # 32 filters under 5x5 covering fields: the backward-data kernel whose chunks hold whole 128-byte lines
+    "bd_line_edge": (wl.LCGeom(B=70, H=28, W=36, C=3, R=20, S=4, F=32), "pink"),        # fewer field rows than cover a cell: edge rows only
+    "bd_line_in": (wl.LCGeom(B=100, H=44, W=50, C=2, R=20, S=4, F=32), "gaussian"),     # interior and edge rows, ragged batch tile and strip
+    "bd_line_c1": (wl.LCGeom(B=64, H=40, W=30, C=1, R=10, S=2, F=32), "gaussian"),      # 4-value cells: one partly used tile
 }
 
 
@@ -313,7 +317,12 @@ def test_l2pool_matches_oracle(shape, ks, st):
 
 
 LCN_SHAPES = [((2, 9, 10, 3), 5), ((3, 20, 37, 32), 5), ((2, 16, 16, 8), 3), ((1, 3, 2, 5), 5), ((2, 33, 17, 6), 7),
-              ((1, 5, 40, 130), 5), ((4, 44, 44, 32), 5), ((128, 44, 44, 32), 5)]   # last: cfg3 at full size
+              ((1, 5, 40, 130), 5), ((4, 44, 44, 32), 5),
+              ((2, 45, 44, 32), 5),      # two bands of whole rows, the second one row short
+              ((2, 50, 20, 64), 7),      # 16 lanes per pixel, 7x7 window
+              ((3, 21, 30, 4), 5),       # one lane per pixel
+              ((2, 30, 150, 32), 5),     # rows too long for a band of eight: the tile kernels
+              ((128, 44, 44, 32), 5)]   # last: cfg3 at full size
 
 
 @pytest.mark.parametrize("shape,ks", LCN_SHAPES)
