@@ -7,10 +7,7 @@ One "step" is one pass of the whole hot path over one synthetic mini-batch of wo
 share of a first layer: B=128, 200x200x3 pink-noise images, 20x20x3 fields at stride 4, 32 filters per
 location), inputs already resident in HBM:
 
-    lc_forward -> l2pool_fwd -> lcn_fwd -> lcn_bwd -> l2pool_bwd -> lc_backward_weights -> lc_backward_data
-
-(the two backward contractions only need the gradient l2pool_bwd leaves; the weight gradient goes first because it
-finds that gradient still in the caches: 6 us per step)
+    lc_forward -> l2pool_fwd -> lcn_fwd -> lcn_bwd -> l2pool_bwd -> lc_backward_data -> lc_backward_weights
 
 `value` is the algorithmic flop of the three layer contractions (3 x 2*B*K*F*L) divided by the time of
 the whole step.  The JSON line also carries per-kernel times (HIP events on the launch stream, in untimed
@@ -96,16 +93,16 @@ def main() -> int:
     dx = torch.empty((g.B, g.H, g.W, g.C), device="cuda")
     dw = torch.empty((g.LH, g.LW, g.K, g.F), device="cuda")
 
-    names = ["lc_forward", "l2pool_fwd", "lcn_fwd", "lcn_bwd", "l2pool_bwd", "lc_backward_weights",
-             "lc_backward_data"]
+    names = ["lc_forward", "l2pool_fwd", "lcn_fwd", "lcn_bwd", "l2pool_bwd", "lc_backward_data",
+             "lc_backward_weights"]
     calls = [
         lambda: lc.lc_forward(G, xd, wd, None, 1.0, y),
         lambda: lc.l2pool_fwd(y, p, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS),
         lambda: lc.lcn_fwd(p, n, mu, rstd, wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS),
         lambda: lc.lcn_bwd(p, mu, rstd, dn, dp, wl.LCN_KSIZE, wl.LCN_SIGMA),
         lambda: lc.l2pool_bwd(y, p, dp, dyd, wl.POOL_KSIZE, wl.POOL_STRIDE),
-        lambda: lc.lc_backward_weights(G, xd, dyd, 0.0, dw),
         lambda: lc.lc_backward_data(G, dyd, wd, dx),
+        lambda: lc.lc_backward_weights(G, xd, dyd, 0.0, dw),
     ]
 
     def step(events=None, only=None):

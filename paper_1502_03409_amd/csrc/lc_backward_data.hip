@@ -340,14 +340,14 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
 }
 
 // ---------------------------------------------------------------------------------------------
-// Layers of 32 filters per field (a row of w[l] and a field's dy are exactly one 128-byte line).  The pipelined
-// kernel above reads such a line in two halves a whole chunk apart, and the memory side moves whole lines: by the
-// time the second half is asked for, the line has left the L2 again and is fetched a second time.  Here a chunk is
-// one field row with all 32 filters, so both halves of a line are read within one step of each other: the staged
-// dy arrives as whole lines, and the weight ring (five half-steps deep, as above) asks for the halves of a row in
-// consecutive half-steps.  The chunk is twice as large, so there is one LDS buffer and two barriers per chunk:
-// the next chunk waits in the staging registers while the current one is multiplied.
-template <int MT, int NT, int NCELL, int AP>
+// Layers whose filters come in blocks of 32 (32 filters of a row of w[l], or of a field's dy, are one 128-byte
+// line).  The pipelined kernel above reads such a line in two halves a whole chunk apart, and the memory side moves
+// whole lines: by the time the second half is asked for, the line has left the L2 again and is fetched a second
+// time.  Here a chunk is one field row with 32 filters, so both halves of a line are read within one step of each
+// other: the staged dy arrives as whole lines, and the weight ring (RING half-steps deep) asks for the halves of a
+// row in consecutive half-steps.  The chunk is twice as large, so there is one LDS buffer and two barriers per
+// chunk: the next chunk waits in the staging registers while the current one is multiplied.
+template <int MT, int NT, int NCELL, int AP, int RING>
 __global__ __launch_bounds__(256, 2) void lc_bwd_data_line_kernel(Geom g, const float *__restrict__ dy,
                                                                   const float *__restrict__ w,
                                                                   float *__restrict__ dx, int strips_per_row,
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_line_kernel(Geom g, const 
     typedef const __attribute__((address_space(1))) float *gf_ptr;
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 8;   // R4: float4 per image and chunk (32 f per field)
-    constexpr int NTHR = 256, NSLOT = (BT * R4 + NTHR - 1) / NTHR, NHS = 2 * AP, RING = 5;
+    constexpr int NTHR = 256, NSLOT = (BT * R4 + NTHR - 1) / NTHR, NHS = 2 * AP;
     static_assert(NHS % RING == 0, "the ring's slot pattern must repeat every chunk");
     extern __shared__ __attribute__((aligned(16))) float dys_line[];
     float *dys = dys_line;
@@ -400,9 +400,10 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_line_kernel(Geom g, const 
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // chunks: the valid field rows i = ri - a
+    // chunks: (a, fp) = the valid field rows i = ri - a, 32 filters fp*32 .. fp*32+31 at a time
     const int a_lo = max(0, ri - (g.LH - 1)), a_hi = min(AP - 1, ri);
-    const int nchunks = a_hi >= a_lo ? a_hi - a_lo + 1 : 0;
+    const int nfp = g.F >> 5;
+    const int nchunks = a_hi >= a_lo ? (a_hi - a_lo + 1) * nfp : 0;
     const int jlo = wi0 - (AP - 1);
     const size_t dyimg = (size_t)g.L * g.F;
 
@@ -410,7 +411,8 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_line_kernel(Geom g, const 
     constexpr int DV = NTHR % R4, DB = NTHR / R4;
     f32x4 st[NSLOT];
     auto stage_load = [&](int c) {
-        const float *base = dy + (size_t)b0 * dyimg + (size_t)((ri - (a_lo + c)) * g.LW) * g.F;
+        const int ca = c / nfp, fp = c - ca * nfp;
+        const float *base = dy + (size_t)b0 * dyimg + (size_t)((ri - (a_lo + ca)) * g.LW) * g.F + fp * 32;
         int v = v0, b = bq0;
 #pragma unroll
         for (int q = 0; q < NSLOT; ++q) {
@@ -438,11 +440,12 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_line_kernel(Geom g, const 
     };
     // weights of half-step hs = 2 a' + fh of chunk c: filters 16 fh .. 16 fh + 15 of field (ri-a, wi-a'), clamped
     auto wbase = [&](int c, int hs) -> gf_ptr {
-        const int a = a_lo + c, ap = hs >> 1;
+        const int ca = c / nfp, fp = c - ca * nfp;
+        const int a = a_lo + ca, ap = hs >> 1;
         int j = wi - ap;
         j = j < 0 ? 0 : (j >= g.LW ? g.LW - 1 : j);
         return (gf_ptr)w + ((size_t)((ri - a) * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F +
-               (hs & 1) * 16;
+               fp * 32 + (hs & 1) * 16;
     };
 
     if (nchunks > 0) {
@@ -552,14 +555,14 @@ int launch_mt(const Geom &g, const float *dy, const float *w, float *dx, hipStre
 
 namespace {
 
-template <int MT, int NT, int NCELL, int AP>
+template <int MT, int NT, int NCELL, int AP, int RING>
 int launch_line(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int NCV = g.S * g.S * g.C;
     const int RS = JW * 32 + 4;                               // 16 bytes past a multiple of 128, as below
     const size_t lds = (size_t)BT * RS * sizeof(float);
-    auto kern = lc_bwd_data_line_kernel<MT, NT, NCELL, AP>;
+    auto kern = lc_bwd_data_line_kernel<MT, NT, NCELL, AP, RING>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
     const int strips = (CW + NCELL - 1) / NCELL;
     const int nblk = (4 / NCELL) * NT * 16;
@@ -611,14 +614,19 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
         } else if (ap == 4) {
             // wide images: eight cells per workgroup stage 11 field columns instead of 2 x 7 (the paper's first
             // layer: 6.04 -> 5.89 ms); with 5 x 5 covering fields and 50 cells per row (cfg3) the same loses
+            // fp32, filters in blocks of 32: whole-line chunks (the paper's first layer: 6.08 -> 5.57 ms)
+            if constexpr (sizeof(T) == 4) {
+                if (ntt == 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 4, 4>(g, (const float *)dy, (const float *)w, dx, s); }
+            }
             if (ntt == 3 && (g.W + g.S - 1) / g.S >= 64) { *done = true; return launch_fast<4, 3, 8, 4, 8>(g, dy, w, dx, s); }
             if (ntt <= 2) LC_BD(4, 2, 4);
             if (ntt == 3) LC_BD(4, 3, 4);
             if (ntt == 4) LC_BD(4, 4, 4);
             LC_BD(4, 4, 2);
         } else if (ap == 5) {
+            // fp32, filters in blocks of 32: whole-line chunks (cfg3: 243 -> 233 us in the step)
             if constexpr (sizeof(T) == 4) {
-                if (ntt <= 3 && g.F == 32) { *done = true; return launch_line<4, 3, 4, 5>(g, (const float *)dy, (const float *)w, dx, s); }
+                if (ntt <= 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 5, 5>(g, (const float *)dy, (const float *)w, dx, s); }
             }
             if (ntt <= 3) LC_BD(5, 3, 4);
             if (ntt == 4) LC_BD(5, 4, 4);

@@ -87,6 +87,8 @@ SMALL = {
     "bd_line_edge": (wl.LCGeom(B=70, H=28, W=36, C=3, R=20, S=4, F=32), "pink"),        # fewer field rows than cover a cell: edge rows only
     "bd_line_in": (wl.LCGeom(B=100, H=44, W=50, C=2, R=20, S=4, F=32), "gaussian"),     # interior and edge rows, ragged batch tile and strip
     "bd_line_c1": (wl.LCGeom(B=64, H=40, W=30, C=1, R=10, S=2, F=32), "gaussian"),      # 4-value cells: one partly used tile
+    "bd_line_f64": (wl.LCGeom(B=72, H=32, W=28, C=3, R=20, S=4, F=64), "pink"),         # two blocks of 32 filters per field row
+    "bd_line4_f96": (wl.LCGeom(B=66, H=32, W=40, C=3, R=16, S=4, F=96), "pink"),        # 4x4 covering fields, three blocks of 32 filters
 }
 
 
