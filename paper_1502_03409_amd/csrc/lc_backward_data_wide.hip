@@ -198,9 +198,14 @@ bool backward_data_dense_supported(const Geom &g) {
 }
 
 int launch_backward_data_wide_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
-    if (backward_data_dense_supported(g)) return launch_wide<4, 2, true>(g, dy, w, dx, s);
-    if (!backward_data_wide_supported(g)) return LC_EUNSUPPORTED;
-    return launch_wide<4, 2, false>(g, dy, w, dx, s);
+    // batch tile of 128, 96 or 64 images: the one that pads the batch least, the larger one on a tie (B = 192: two
+    // tiles of 128 waste a quarter of the MFMAs)
+    const int mt = batch_tile_mt(g.B, true);
+    const bool dense = backward_data_dense_supported(g);
+    if (!dense && !backward_data_wide_supported(g)) return LC_EUNSUPPORTED;
+    if (mt == 2) return dense ? launch_wide<2, 2, true>(g, dy, w, dx, s) : launch_wide<2, 2, false>(g, dy, w, dx, s);
+    if (mt == 3) return dense ? launch_wide<3, 2, true>(g, dy, w, dx, s) : launch_wide<3, 2, false>(g, dy, w, dx, s);
+    return dense ? launch_wide<4, 2, true>(g, dy, w, dx, s) : launch_wide<4, 2, false>(g, dy, w, dx, s);
 }
 
 }  // namespace lc

@@ -116,6 +116,18 @@ int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where);
         }                                                \
     } while (0)
 
+// Batch tile of the workgroup-tiled kernels in units of 32 images: 4, 3 (if allowed) or 2, whichever pads the
+// batch least; the larger tile on a tie.
+inline int batch_tile_mt(int B, bool allow3) {
+    int best = 4, waste = 1 << 30;
+    for (int mt = 4; mt >= 2; --mt) {
+        if (mt == 3 && !allow3) continue;
+        const int bt = 32 * mt, wst = (B + bt - 1) / bt * bt - B;
+        if (wst < waste) { waste = wst; best = mt; }
+    }
+    return best;
+}
+
 // kernels' host launchers (one per translation unit)
 // alpha_dev (nullable): device scalar that overrides alpha
 int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,

@@ -180,10 +180,10 @@ int wide_slices(const Geom &g) {
     return ns < 2 ? 1 : ns;
 }
 
-template <int KCH>
+template <int KCH, int MT = 4>
 int launch_wide(const Geom &g, const float *x, const float *w, const float *bias, float alpha, const float *alpha_dev,
                 float *y, float *partial, int nslices, hipStream_t s) {
-    constexpr int MT = 4, PD = 2, BT = 32 * MT;
+    constexpr int PD = 2, BT = 32 * MT;
     const size_t lds = (size_t)2 * BT * (KCH + 4) * sizeof(float);
     auto kern = lc_forward_wide_kernel<MT, PD, KCH>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward (wide): hipFuncSetAttribute")) return rc_lds;
@@ -227,7 +227,16 @@ int launch_forward_wide_f32(const Geom &g, const float *x, const float *w, const
     // 128-image tiles measured faster than 256-image ones here (1062 vs 1116 us on 256 x 64x64x32, 128 filters)
     int ns = wide_slices(g);
     if (ns > 1 && (!ws || ws_bytes < forward_wide_workspace_bytes(g))) ns = 1;   // no workspace: one slice
-    if (chunk_floats(g) == 32) return launch_wide<32>(g, x, w, bias, alpha, alpha_dev, y, (float *)ws, ns, s);
+    // batch tile of 128, 96 or 64 images: the one that pads the batch least, the larger one on a tie (B = 192: two
+    // tiles of 128 waste a quarter of the MFMAs); 16-value chunks stage two rows per thread, which rules 96 out
+    const bool k32 = chunk_floats(g) == 32;
+    const int mt = batch_tile_mt(g.B, k32);
+    if (k32) {
+        if (mt == 2) return launch_wide<32, 2>(g, x, w, bias, alpha, alpha_dev, y, (float *)ws, ns, s);
+        if (mt == 3) return launch_wide<32, 3>(g, x, w, bias, alpha, alpha_dev, y, (float *)ws, ns, s);
+        return launch_wide<32>(g, x, w, bias, alpha, alpha_dev, y, (float *)ws, ns, s);
+    }
+    if (mt == 2) return launch_wide<16, 2>(g, x, w, bias, alpha, alpha_dev, y, (float *)ws, ns, s);
     return launch_wide<16>(g, x, w, bias, alpha, alpha_dev, y, (float *)ws, ns, s);
 }
 

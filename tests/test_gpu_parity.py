@@ -83,6 +83,8 @@ SMALL = {
     "dense_k16": (wl.LCGeom(B=72, H=12, W=12, C=4, R=12, S=1, F=128), "halfnormal"),    # one field, 16-value chunks
     "wide_k16": (wl.LCGeom(B=72, H=14, W=16, C=4, R=4, S=2, F=128), "halfnormal"),      # 16-value chunks, many fields
     "single_img": (wl.LCGeom(B=1, H=9, W=9, C=2, R=3, S=3, F=5), "gaussian"),
+    # workgroup-tiled kernels: batches that 64-image tiles pad least (the other cases take 96 or 128)
+    "wide_b320": (wl.LCGeom(B=320, H=8, W=10, C=32, R=4, S=2, F=128), "halfnormal"),
     # 32 filters under 5x5 covering fields: the backward-data kernel whose chunks hold whole 128-byte lines
     "bd_line_edge": (wl.LCGeom(B=70, H=28, W=36, C=3, R=20, S=4, F=32), "pink"),        # fewer field rows than cover a cell: edge rows only
     "bd_line_in": (wl.LCGeom(B=100, H=44, W=50, C=2, R=20, S=4, F=32), "gaussian"),     # interior and edge rows, ragged batch tile and strip
