@@ -314,7 +314,13 @@ int launch_backward_weights_fast_path(const Geom &g, const T *x1, const T *dy1, 
     const int va = patch_vector_width(g);
     if ((g.B & 3) == 0 && va == 4) {
         if (g.F % 64 == 0) { *done = true; return launch_fast_pf<1, 4, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
-        if (g.F % 32 == 0) { *done = true; return launch_fast_pf<2, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+        if (g.F % 32 == 0) {
+            *done = true;
+            // blocks of 192 patch elements where they pad K less than blocks of 128 (K = 576: 3 blocks instead of 5)
+            const int pad2 = (g.K + 127) / 128 * 128 - g.K, pad3 = (g.K + 191) / 192 * 192 - g.K;
+            if (pad3 < pad2) return launch_fast_pf<3, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+            return launch_fast_pf<2, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+        }
         if (g.F % 16 == 0) { *done = true; return launch_fast_pf<2, 4, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
     }
     if ((g.B & 3) == 0 && va == 2) {
