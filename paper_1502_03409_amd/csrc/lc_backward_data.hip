@@ -346,7 +346,10 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
 // time.  Here a chunk is one field row with 32 filters, so both halves of a line are read within one step of each
 // other: the staged dy arrives as whole lines, and the weight ring (RING half-steps deep) asks for the halves of a
 // row in consecutive half-steps.  The chunk is twice as large, so there is one LDS buffer and two barriers per
-// chunk: the next chunk waits in the staging registers while the current one is multiplied.
+// chunk: the next chunk waits in the staging registers while the current one is multiplied.  With those 64
+// staging registers a ring of five half-steps no longer fits 256 registers (5 values spilled and reloaded inside
+// the loop, each reload waiting for every load issued before it); two half-steps fit and measured faster
+// (cfg3: 233 -> 225 us in the step; one half-step: 264 us).
 template <int MT, int NT, int NCELL, int AP, int RING>
 __global__ __launch_bounds__(256, 2) void lc_bwd_data_line_kernel(Geom g, const float *__restrict__ dy,
                                                                   const float *__restrict__ w,
@@ -616,7 +619,7 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
             // layer: 6.04 -> 5.89 ms); with 5 x 5 covering fields and 50 cells per row (cfg3) the same loses
             // fp32, filters in blocks of 32: whole-line chunks (the paper's first layer: 6.08 -> 5.57 ms)
             if constexpr (sizeof(T) == 4) {
-                if (ntt == 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 4, 4>(g, (const float *)dy, (const float *)w, dx, s); }
+                if (ntt == 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 4, 2>(g, (const float *)dy, (const float *)w, dx, s); }
             }
             if (ntt == 3 && (g.W + g.S - 1) / g.S >= 64) { *done = true; return launch_fast<4, 3, 8, 4, 8>(g, dy, w, dx, s); }
             if (ntt <= 2) LC_BD(4, 2, 4);
@@ -626,7 +629,7 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
         } else if (ap == 5) {
             // fp32, filters in blocks of 32: whole-line chunks (cfg3: 243 -> 233 us in the step)
             if constexpr (sizeof(T) == 4) {
-                if (ntt <= 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 5, 5>(g, (const float *)dy, (const float *)w, dx, s); }
+                if (ntt <= 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 5, 2>(g, (const float *)dy, (const float *)w, dx, s); }
             }
             if (ntt <= 3) LC_BD(5, 3, 4);
             if (ntt == 4) LC_BD(5, 4, 4);
