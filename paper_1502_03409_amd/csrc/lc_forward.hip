@@ -8,6 +8,8 @@
 // of it.  A wave holds the whole batch tile for its location: each weight is fetched from global
 // memory exactly once per batch tile, straight into the MFMA B operand (lanes run along f, the
 // contiguous axis of w), and reused for MT MFMAs.
+#include <cstdlib>
+
 #include "lc_common.hpp"
 
 namespace lc {
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const float *__
 constexpr int kFwdStageSlotsWide = 6;   // eight-wave workgroups: half the registers per lane
 constexpr int kFwdStageSlots = 12;  // dwordx4 staging registers per lane: chunk <= 12*256*16 B = 48 KB
 
-template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T = float>
+template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T = float, int SPC = 0>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kernel(Geom g, const T *__restrict__ x,
                                                               const T *__restrict__ w,
                                                               const float *__restrict__ bias, float alpha,
@@ -194,8 +196,28 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
     }
     const int col0 = j0 * SC;
     XV st[SLOTS];
+    // SPC > 0 (k-steps per chunk known at compile time; one whole patch row per chunk, every staging slot in use):
+    // every slot loads, from an address clamped into the image (what lands beyond the batch or the row only reaches
+    // rows and waves that are not stored), and the k-step loop is unrolled, so the number of loads between a
+    // chunk's staging loads and their use is a constant the compiler can wait on exactly.  With counts it cannot
+    // see it waits for every outstanding load before the LDS stores and again before the chunk's first MFMA, which
+    // drains the weight ring and exposes the staging loads' latency once per chunk.
+    int so[SPC > 0 ? SLOTS : 1];
+    if constexpr (SPC > 0) {
+        const int lim0 = WC - col0;
+#pragma unroll
+        for (int q = 0; q < SLOTS; ++q) {
+            const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xfff;
+            so[q] = min(b, g.B - 1 - b0) * (int)img + min(v, max(lim0 - 4, 0));
+        }
+    }
     auto stage_load = [&](int kh, int sc) {
         const T *row = x + (size_t)b0 * img + (size_t)(i * g.S + kh) * WC + col0 + sc * CQ;
+        if constexpr (SPC > 0) {
+#pragma unroll
+            for (int q = 0; q < SLOTS; ++q) st[q] = *(gx4_ptr)(row + so[q]);
+            return;
+        }
         const int lim = WC - col0 - sc * CQ;          // floats of this image row that exist from the chunk start on
 #pragma unroll
         for (int q = 0; q < SLOTS; ++q) {
@@ -210,7 +232,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
     auto stage_store = [&]() {
 #pragma unroll
         for (int q = 0; q < SLOTS; ++q) {
-            if (q < nslots && sb[q] >= 0) {
+            if (SPC > 0 || (q < nslots && sb[q] >= 0)) {   // SPC > 0: every slot is in use
                 const int b = (sb[q] >> 16) & 0x3fff, r = (sb[q] >> 12) & 15, v = sb[q] & 0xfff;
                 // rows of images 8..15 (mod 16) sit 2 floats to the right (see xwin below)
                 float *dst = xs + b * RS + r * sqc + ((b >> 2) & 2) + v;
@@ -227,6 +249,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
     const size_t wstep = (size_t)g.F;           // in units of float: 4 rows per k-step -> 4*F floats
     WV wr[UNR];
     int wleft = nsteps;                         // k-steps not yet requested
+    if constexpr (SPC > 0) {
+        stage_load(0, 0);
+    }
 #pragma unroll
     for (int s = 0; s < UNR; ++s) {
         wr[s] = *wp;
@@ -239,36 +264,59 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
     const float *xwin = xs + (size_t)(lane & 15) * RS + ((lane >> 2) & 2) + wl * SC + kk;
     const int spc = CQ >> 2;                    // k-steps per patch row of a chunk, a multiple of UNR
     const int nsub = g.RC / CQ;                 // NR > 1 only with whole rows (nsub == 1)
-    stage_load(0, 0);
-    for (int kh = 0; kh < g.R; kh += NR) {
-        for (int sc = 0; sc < nsub; ++sc) {
-            __syncthreads();                    // all waves are done reading the previous chunk
-            stage_store();
+    auto ksteps = [&](const float *xrow, int s0) {
+#pragma unroll
+        for (int ss = 0; ss < UNR; ++ss) {
+            float a[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a[mt] = xrow[mt * 16 * RS + 4 * (s0 + ss)];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int u = 0; u < NT; ++u)
+                    acc[mt][u] = mfma16(a[mt], raw_get<T, NT>(wr[ss], u), acc[mt][u]);
+            wr[ss] = *wp;
+            --wleft;
+            wp = (gw_ptr)((gt_ptr)wp + (wleft > 0 ? 4 * wstep : 0));
+            // MFMAs and global loads keep their order (LDS reads and address arithmetic may move across)
+            __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
+        }
+    };
+    if constexpr (SPC > 0) {
+        // One whole patch row per chunk.  The next chunk's staging loads go out after the first UNR k-steps: every
+        // ring load that is still awaited then is younger than they are, so no wait on the ring has to cover them
+        // (the counter retires loads in order), and they have the rest of the chunk to arrive.  They are always
+        // issued (the last chunk loads its own row again): a path without them would make the compiler assume,
+        // where the paths join, that none are in flight.  For the same reason a chunk's staging loads and the LDS
+        // stores that use them sit in the same loop iteration: the compiler then sees every load between them.
+        __syncthreads();
+        stage_store();                          // chunk 0
+        __syncthreads();
+        for (int kh = 0; kh < g.R; ++kh) {
+            ksteps(xwin, 0);
+            stage_load(min(kh + 1, g.R - 1), 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s0 = UNR; s0 < SPC; s0 += UNR) ksteps(xwin, s0);
+            __syncthreads();                    // all waves are done reading this chunk
+            stage_store();                      // the next one (after the last chunk: its own row again, unused)
             __syncthreads();
-            {
-                int nsc = sc + 1, nkh = kh;
-                if (nsc == nsub) { nsc = 0; nkh += NR; }
-                if (nkh < g.R) stage_load(nkh, nsc);
-            }
-            for (int r = 0; r < NR; ++r) {
-                const float *xrow = xwin + r * sqc;
-                for (int s0 = 0; s0 < spc; s0 += UNR) {
-#pragma unroll
-                    for (int ss = 0; ss < UNR; ++ss) {
-                        float a[MT];
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt) a[mt] = xrow[mt * 16 * RS + 4 * (s0 + ss)];
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                            for (int u = 0; u < NT; ++u)
-                                acc[mt][u] = mfma16(a[mt], raw_get<T, NT>(wr[ss], u), acc[mt][u]);
-                        wr[ss] = *wp;
-                        --wleft;
-                        wp = (gw_ptr)((gt_ptr)wp + (wleft > 0 ? 4 * wstep : 0));
-                        // MFMAs and global loads keep their order (LDS reads and address arithmetic may move across)
-                        __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
-                    }
+        }
+    } else {
+        stage_load(0, 0);
+        for (int kh = 0; kh < g.R; kh += NR) {
+            for (int sc = 0; sc < nsub; ++sc) {
+                __syncthreads();                    // all waves are done reading the previous chunk
+                stage_store();
+                __syncthreads();
+                {
+                    int nsc = sc + 1, nkh = kh;
+                    if (nsc == nsub) { nsc = 0; nkh += NR; }
+                    if (nkh < g.R) stage_load(nkh, nsc);
+                }
+                for (int r = 0; r < NR; ++r) {
+                    const float *xrow = xwin + r * sqc;
+                    for (int s0 = 0; s0 < spc; s0 += UNR) ksteps(xrow, s0);
                 }
             }
         }
@@ -336,14 +384,14 @@ int fast_row_stride(int sqc) {
     return ((sqc + 31) / 32) * 32 + 4;
 }
 
-template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T>
+template <int MT, int NT, int NLOC, int UNR, int NW = 4, int SPC = 0, typename T>
 int launch_fast(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                 const float *alpha_dev, float *y, int CQ, int NR, int work_first, int work_count, hipStream_t s) {
     constexpr int BT = 16 * MT, NFW = NW / NLOC;
     const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;   // staged floats per image and patch row
     const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
-    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW, T>;
+    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW, T, SPC>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward: hipFuncSetAttribute")) return rc_lds;
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int nbt = (g.B + BT - 1) / BT;
@@ -370,7 +418,13 @@ int launch_fast_tiered(const Geom &g, const T *x, const T *w, const float *bias,
     if constexpr (MT == 8) {
         if (zb == 1 && rounds >= 1 && rounds <= 6 && rem > 0 && rem <= slots / 4) {
             const int first = rounds * slots;
-            int rc = launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s);
+            // whole patch rows of 15 k-steps that fill every staging slot: the variant with compile-time counts
+            const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;
+            const bool fixed = UNR == 5 && sizeof(T) == 4 && CQ == g.RC && (CQ >> 2) == 15 &&
+                               16 * MT * (sqc / 4) == kFwdStageSlots * 256 &&
+                               (long long)g.B * g.H * g.W * g.C < (1LL << 31) && !getenv("LC_NO_SPC");
+            int rc = fixed ? launch_fast<MT, NT, NLOC, UNR, 4, 15>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s)
+                           : launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s);
             if (rc != LC_OK) return rc;
             // the short workgroups stage four patch rows at a time (same LDS footprint as the long ones),
             // so that a chunk's MFMAs still cover the latency of fetching the next one
