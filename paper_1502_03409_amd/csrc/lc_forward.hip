@@ -8,8 +8,6 @@
 // of it.  A wave holds the whole batch tile for its location: each weight is fetched from global
 // memory exactly once per batch tile, straight into the MFMA B operand (lanes run along f, the
 // contiguous axis of w), and reused for MT MFMAs.
-#include <cstdlib>
-
 #include "lc_common.hpp"
 
 namespace lc {
@@ -422,7 +420,7 @@ int launch_fast_tiered(const Geom &g, const T *x, const T *w, const float *bias,
             const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;
             const bool fixed = UNR == 5 && sizeof(T) == 4 && CQ == g.RC && (CQ >> 2) == 15 &&
                                16 * MT * (sqc / 4) == kFwdStageSlots * 256 &&
-                               (long long)g.B * g.H * g.W * g.C < (1LL << 31) && !getenv("LC_NO_SPC");
+                               (long long)g.B * g.H * g.W * g.C < (1LL << 31);
             int rc = fixed ? launch_fast<MT, NT, NLOC, UNR, 4, 15>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s)
                            : launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s);
             if (rc != LC_OK) return rc;
