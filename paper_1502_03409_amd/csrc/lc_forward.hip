@@ -186,8 +186,13 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
         for (int q = 0; q < SLOTS; ++q) {
             const int r = vv / sq4, v = vv - r * sq4;
             sb[q] = (b << 16) | (r << 12) | (v * 4);
-            if (b >= BT) sb[q] = (int)0x80000000;
-            else if (b0 + b >= g.B) sb[q] |= 0x40000000;
+            if (b >= BT) {
+                // past the end of the chunk: unused, or (SPC > 0, every slot loads and stores) a second copy of the
+                // chunk's last element
+                sb[q] = SPC > 0 ? ((BT - 1) << 16) | ((NR - 1) << 12) | ((sq4 - 1) * 4) : (int)0x80000000;
+            } else if (b0 + b >= g.B) {
+                sb[q] |= 0x40000000;
+            }
             vv += dv; b += db;
             if (vv >= per_img) { vv -= per_img; ++b; }
         }
@@ -419,7 +424,7 @@ int launch_fast_tiered(const Geom &g, const T *x, const T *w, const float *bias,
             // whole patch rows of 15 k-steps that fill every staging slot: the variant with compile-time counts
             const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;
             const bool fixed = UNR == 5 && sizeof(T) == 4 && CQ == g.RC && (CQ >> 2) == 15 &&
-                               16 * MT * (sqc / 4) == kFwdStageSlots * 256 &&
+                               (16 * MT * (sqc / 4) + 255) / 256 == kFwdStageSlots &&
                                (long long)g.B * g.H * g.W * g.C < (1LL << 31);
             int rc = fixed ? launch_fast<MT, NT, NLOC, UNR, 4, 15>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s)
                            : launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, first, s);
@@ -500,8 +505,14 @@ int launch_fast_wide(const Geom &g, const T *x, const T *w, const float *bias, f
     int CQ;
     if (spr % 8 == 0 && (CQ = pick_chunk(g, 128, 8, 8, budget, 512, kFwdStageSlotsWide)))
         return launch_fast<8, 1, 8, 8, 8>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
-    if (spr % 6 == 0 && (CQ = pick_chunk(g, 128, 8, 6, budget, 512, kFwdStageSlotsWide)))
+    if (spr % 6 == 0 && (CQ = pick_chunk(g, 128, 8, 6, budget, 512, kFwdStageSlotsWide))) {
+        // whole patch rows of 12 k-steps that need every staging slot: the variant with compile-time counts
+        const int sq4 = ((CQ + 7 * g.S * g.C + 3) & ~3) / 4;
+        if (sizeof(T) == 4 && CQ == g.RC && spr == 12 && (128 * sq4 + 511) / 512 == kFwdStageSlotsWide &&
+            (long long)g.B * g.H * g.W * g.C < (1LL << 31))
+            return launch_fast<8, 1, 8, 6, 8, 12>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
         return launch_fast<8, 1, 8, 6, 8>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
+    }
     if (spr % 5 == 0 && (CQ = pick_chunk(g, 128, 8, 5, budget, 512, kFwdStageSlotsWide)))
         return launch_fast<8, 1, 8, 5, 8>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);
     *done = false;
