@@ -123,7 +123,7 @@ __device__ __forceinline__ float vget(const typename VecT<N>::T &v, int i) {
 }
 
 template <int G, int VA, int NT, int PF, typename T = float>
-__global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const T *__restrict__ x1,
+__global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kernel(Geom g, const T *__restrict__ x1,
                                                                   const T *__restrict__ dy1,
                                                                   const T *__restrict__ x2,
                                                                   const T *__restrict__ dy2, float beta,
@@ -217,15 +217,44 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const 
     }
 
     float *ol = out + (size_t)loc * g.K * g.F + f0 + NT * m;
+    if (beta == 0.f) {
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int t = 0; t < VA; ++t) {
+                    const int k = k0 + gg * VA * 16 + VA * (4 * kk + r) + t;
+                    if (k >= g.K) continue;
+                    BV v;
+                    if constexpr (NT == 1) {
+                        v = gamma * acc[gg][t][0][r];
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < NT; ++u) v[u] = gamma * acc[gg][t][u][r];
+                    }
+                    *(BV *)(ol + (size_t)k * g.F) = v;
+                }
+        return;
+    }
+    // beta != 0 (the fused update), a code path of its own: the old values of four rows are requested together,
+    // before the first is used.  A load under its own condition in front of each store makes the compiler wait
+    // for it on the spot: one round trip to memory per row, 32 of them in a row.  (All 16 or 32 rows at once cost
+    // the registers of a wave per SIMD on the narrow layers.)  Rows beyond K read row 0 instead and are not stored.
 #pragma unroll
     for (int gg = 0; gg < G; ++gg)
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < 4; ++r) {
+            BV old[VA];
+#pragma unroll
+            for (int t = 0; t < VA; ++t) {
+                const int k = k0 + gg * VA * 16 + VA * (4 * kk + r) + t;
+                old[t] = *(const BV *)(ol + (size_t)(k < g.K ? k : 0) * g.F);
+            }
 #pragma unroll
             for (int t = 0; t < VA; ++t) {
                 const int k = k0 + gg * VA * 16 + VA * (4 * kk + r) + t;
                 if (k >= g.K) continue;
-                BV *o = (BV *)(ol + (size_t)k * g.F);
                 BV v;
                 if constexpr (NT == 1) {
                     v = gamma * acc[gg][t][0][r];
@@ -233,9 +262,9 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_fast_kernel(Geom g, const 
 #pragma unroll
                     for (int u = 0; u < NT; ++u) v[u] = gamma * acc[gg][t][u][r];
                 }
-                if (beta != 0.f) v += beta * *o;
-                *o = v;
+                *(BV *)(ol + (size_t)k * g.F) = v + beta * old[t];
             }
+        }
 }
 
 namespace {
