@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const float *__
 constexpr int kFwdStageSlotsWide = 6;   // eight-wave workgroups: half the registers per lane
 constexpr int kFwdStageSlots = 12;  // dwordx4 staging registers per lane: chunk <= 12*256*16 B = 48 KB
 
-template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T = float, int SPC = 0>
+template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T = float, int SPC = 0, int NRT = 1>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kernel(Geom g, const T *__restrict__ x,
                                                               const T *__restrict__ w,
                                                               const float *__restrict__ bias, float alpha,
@@ -210,8 +210,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
         const int lim0 = WC - col0;
 #pragma unroll
         for (int q = 0; q < SLOTS; ++q) {
-            const int b = (sb[q] >> 16) & 0x3fff, v = sb[q] & 0xfff;
-            so[q] = min(b, g.B - 1 - b0) * (int)img + min(v, max(lim0 - 4, 0));
+            const int b = (sb[q] >> 16) & 0x3fff, r = (sb[q] >> 12) & 15, v = sb[q] & 0xfff;
+            so[q] = min(b, g.B - 1 - b0) * (int)img + r * WC + min(v, max(lim0 - 4, 0));
         }
     }
     auto stage_load = [&](int kh, int sc) {
@@ -295,12 +295,16 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
         __syncthreads();
         stage_store();                          // chunk 0
         __syncthreads();
-        for (int kh = 0; kh < g.R; ++kh) {
+        for (int kh = 0; kh < g.R; kh += NRT) {          // NRT patch rows per chunk (R a multiple of NRT)
             ksteps(xwin, 0);
-            stage_load(min(kh + 1, g.R - 1), 0);
+            stage_load(min(kh + NRT, g.R - NRT), 0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int s0 = UNR; s0 < SPC; s0 += UNR) ksteps(xwin, s0);
+#pragma unroll
+            for (int r = 1; r < NRT; ++r)
+#pragma unroll
+                for (int s0 = 0; s0 < SPC; s0 += UNR) ksteps(xwin + r * sqc, s0);
             __syncthreads();                    // all waves are done reading this chunk
             stage_store();                      // the next one (after the last chunk: its own row again, unused)
             __syncthreads();
@@ -387,14 +391,14 @@ int fast_row_stride(int sqc) {
     return ((sqc + 31) / 32) * 32 + 4;
 }
 
-template <int MT, int NT, int NLOC, int UNR, int NW = 4, int SPC = 0, typename T>
+template <int MT, int NT, int NLOC, int UNR, int NW = 4, int SPC = 0, int NRT = 1, typename T>
 int launch_fast(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                 const float *alpha_dev, float *y, int CQ, int NR, int work_first, int work_count, hipStream_t s) {
     constexpr int BT = 16 * MT, NFW = NW / NLOC;
     const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;   // staged floats per image and patch row
     const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
-    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW, T, SPC>;
+    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW, T, SPC, NRT>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward: hipFuncSetAttribute")) return rc_lds;
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int nbt = (g.B + BT - 1) / BT;
@@ -436,7 +440,10 @@ int launch_fast_tiered(const Geom &g, const T *x, const T *w, const float *bias,
                 for (int c : {4, 3, 2})
                     if (g.R % c == 0) { nr = c; break; }
             }
-            // their k-steps are short (2 x NT MFMAs), so the weight ring is made as deep as a whole patch row
+            // their k-steps are short (2 x NT MFMAs), so the weight ring is made as deep as a whole patch row;
+            // four whole rows of 15 k-steps that fill every staging slot: the variant with compile-time counts
+            if ((CQ >> 2) == 15 && fixed && nr == 4 && 32 * 4 * (sqc / 4) == kFwdStageSlots * 256)
+                return launch_fast<2, NT, NLOC, 15, 4, 15, 4>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, first, ntask - first, s);
             if ((CQ >> 2) % 15 == 0)
                 return launch_fast<2, NT, NLOC, 15>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, first, ntask - first, s);
             if ((CQ >> 2) % 16 == 0)
