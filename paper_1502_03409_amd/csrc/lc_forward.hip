@@ -462,6 +462,16 @@ int launch_fast_tiered(const Geom &g, const T *x, const T *w, const float *bias,
                     (size_t)16 * MT * fast_row_stride(c * sqc) * 4 <= 52 * 1024 && c <= 15) { nr = c; break; }
         }
     }
+    // 32-image tiles whose chunks (whole patch rows) fill every staging slot: the variants with compile-time counts
+    if constexpr (MT == 2 && UNR == 8 && sizeof(T) == 4) {
+        const int sq4 = ((CQ + (NLOC - 1) * g.S * g.C + 3) & ~3) / 4;
+        const bool fits = CQ == g.RC && 32 * nr * sq4 == kFwdStageSlots * 256 && g.R % nr == 0 &&
+                          (long long)g.B * g.H * g.W * g.C < (1LL << 31);
+        if (fits && (CQ >> 2) == 24 && nr == 2)
+            return launch_fast<MT, NT, NLOC, UNR, 4, 24, 2>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, 0, ntask, s);
+        if (fits && (CQ >> 2) == 48 && nr == 1)
+            return launch_fast<MT, NT, NLOC, UNR, 4, 48, 1>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, 0, ntask, s);
+    }
     return launch_fast<MT, NT, NLOC, UNR>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, 0, ntask, s);
 }
 
