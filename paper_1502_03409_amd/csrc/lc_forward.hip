@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const float *__
 constexpr int kFwdStageSlotsWide = 6;   // eight-wave workgroups: half the registers per lane
 constexpr int kFwdStageSlots = 12;  // dwordx4 staging registers per lane: chunk <= 12*256*16 B = 48 KB
 
-template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T = float, int SPC = 0, int NRT = 1>
+template <int MT, int NT, int NLOC, int UNR, int NW = 4, typename T = float, int SPC = 0, int NRT = 1, int NSL = 0>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kernel(Geom g, const T *__restrict__ x,
                                                               const T *__restrict__ w,
                                                               const float *__restrict__ bias, float alpha,
@@ -149,7 +149,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
     typedef const __attribute__((address_space(1))) XV *gx4_ptr;
     typedef const __attribute__((address_space(1))) T *gt_ptr;
     constexpr int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW;   // NW waves: NLOC fields x NFW filter blocks
-    constexpr int SLOTS = NW == 8 ? kFwdStageSlotsWide : kFwdStageSlots;
+    // staging slots per lane; NSL > 0 (with SPC > 0, where every slot loads): exactly as many as a chunk needs
+    constexpr int SLOTS = NSL > 0 ? NSL : (NW == 8 ? kFwdStageSlotsWide : kFwdStageSlots);
     extern __shared__ __attribute__((aligned(16))) float xs[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kk = lane >> 4;
@@ -391,14 +392,14 @@ int fast_row_stride(int sqc) {
     return ((sqc + 31) / 32) * 32 + 4;
 }
 
-template <int MT, int NT, int NLOC, int UNR, int NW = 4, int SPC = 0, int NRT = 1, typename T>
+template <int MT, int NT, int NLOC, int UNR, int NW = 4, int SPC = 0, int NRT = 1, int NSL = 0, typename T>
 int launch_fast(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                 const float *alpha_dev, float *y, int CQ, int NR, int work_first, int work_count, hipStream_t s) {
     constexpr int BT = 16 * MT, NFW = NW / NLOC;
     const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;   // staged floats per image and patch row
     const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
-    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW, T, SPC, NRT>;
+    auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW, T, SPC, NRT, NSL>;
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward: hipFuncSetAttribute")) return rc_lds;
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int nbt = (g.B + BT - 1) / BT;
@@ -461,6 +462,13 @@ int launch_fast_tiered(const Geom &g, const T *x, const T *w, const float *bias,
                 if (g.R % c == 0 && (size_t)16 * MT * c * (sqc / 4) <= (size_t)kFwdStageSlots * 256 &&
                     (size_t)16 * MT * fast_row_stride(c * sqc) * 4 <= 52 * 1024 && c <= 15) { nr = c; break; }
         }
+    }
+    // 32-image tiles, two patch rows of 12 k-steps in eight staging slots (cfg2): compile-time counts
+    if constexpr (MT == 2 && UNR == 6 && sizeof(T) == 4) {
+        const int sq4 = ((CQ + (NLOC - 1) * g.S * g.C + 3) & ~3) / 4;
+        if (CQ == g.RC && (CQ >> 2) == 12 && nr == 2 && g.R % 2 == 0 && (32 * 2 * sq4 + 255) / 256 == 8 &&
+            (long long)g.B * g.H * g.W * g.C < (1LL << 31))
+            return launch_fast<MT, NT, NLOC, UNR, 4, 12, 2, 8>(g, x, w, bias, alpha, alpha_dev, y, CQ, nr, 0, ntask, s);
     }
     // 32-image tiles whose chunks (whole patch rows) fill every staging slot: the variants with compile-time counts
     if constexpr (MT == 2 && UNR == 8 && sizeof(T) == 4) {
