@@ -64,7 +64,9 @@ enum lc_status {
     LC_EALIGN = -3,       /* a data pointer is not 16-byte aligned */
     LC_EWORKSPACE = -4,   /* ws is NULL or smaller than lc_workspace_bytes() */
     LC_EUNSUPPORTED = -5, /* valid request this build has no kernel for */
-    LC_EHIP = -6          /* a HIP call failed; see lc_last_error() */
+    LC_EHIP = -6,         /* a HIP call failed; see lc_last_error() */
+    LC_EINTERNAL = -7     /* a launch plan failed the library's own host checks (a bug here, not in the call);
+                             nothing was launched; lc_last_error() names the violated condition */
 };
 
 enum lc_dtype { LC_F32 = 0, LC_BF16 = 1 };
@@ -160,7 +162,11 @@ int lcn_variant_bwd(const float *x, const float *mu, const float *rstd, const fl
  *   then, if LC_SAE_PROJECT_ROWS, every filter w[l,:,f] is rescaled to unit L2 norm.
  * x [B,H,W,C] read only; w [LH,LW,K,F], b [H,W,C] and the device scalar alpha are updated in place;
  * h_out (NULL or [B,LH,LW,F]) receives h computed with the weights from before the update;
- * cost_out is a device scalar that receives J.  Scratch: lc_workspace_bytes(g, LC_OP_SAE_STEP, LC_F32). */
+ * cost_out is a device scalar that receives J.  Scratch: lc_workspace_bytes(g, LC_OP_SAE_STEP, LC_F32).
+ * Preconditions the host cannot check (alpha lives on the device): with LC_SAE_LEARN_ALPHA alpha must be
+ * non-zero, because its gradient sum (W x) * dJ/dh is formed as (1/alpha) sum h * dJ/dh; with alpha = 0 the
+ * encoder is dead anyway (h = 0 for every input) and the step leaves alpha at NaN.  With LC_SAE_PROJECT_ROWS a
+ * filter whose updated values are all exactly zero has no direction and is left as it is (zeros). */
 int sae_step(const lc_geom_t *g, const float *x, float *w, float *b, float *alpha, float lambda,
              float eps_sparse, float lr, uint32_t flags, float *h_out, float *cost_out, void *ws,
              size_t ws_bytes, void *hip_stream);

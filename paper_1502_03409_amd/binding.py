@@ -17,20 +17,26 @@ import torch
 _HERE = Path(__file__).resolve().parent
 LIB_PATH = _HERE / "liblc.so"
 
-LC_OK, LC_EINVAL, LC_ENULL, LC_EALIGN, LC_EWORKSPACE, LC_EUNSUPPORTED, LC_EHIP = 0, -1, -2, -3, -4, -5, -6
+LC_OK, LC_EINVAL, LC_ENULL, LC_EALIGN, LC_EWORKSPACE, LC_EUNSUPPORTED, LC_EHIP, LC_EINTERNAL = 0, -1, -2, -3, -4, -5, -6, -7
 LC_F32, LC_BF16 = 0, 1
 LC_OP_FORWARD, LC_OP_BACKWARD_DATA, LC_OP_BACKWARD_WEIGHTS, LC_OP_SAE_STEP = 0, 1, 2, 3
 LC_SAE_PROJECT_ROWS, LC_SAE_LEARN_ALPHA = 1, 2
 _STATUS = {0: "LC_OK", -1: "LC_EINVAL", -2: "LC_ENULL", -3: "LC_EALIGN", -4: "LC_EWORKSPACE",
-           -5: "LC_EUNSUPPORTED", -6: "LC_EHIP"}
+           -5: "LC_EUNSUPPORTED", -6: "LC_EHIP", -7: "LC_EINTERNAL"}
 
 EXPORTS = ("lc_geom_derive", "lc_workspace_bytes", "lc_forward", "lc_backward_data", "lc_backward_weights",
            "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
-           "lcn_variant_bwd", "sae_step", "lc_last_error")
+           "lcn_variant_bwd", "sae_step", "lc_last_error", "lc_plan_query")
 
 
 class LcGeom(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "H", "W", "C", "R", "S", "F")]
+
+
+class LcLaunch(C.Structure):
+    """One planned kernel launch (``lc_launch_t`` of ``include/lc_plan.h``)."""
+    _fields_ = [("kernel", C.c_char * 32), ("tparam", C.c_int32 * 12), ("arg", C.c_int32 * 12),
+                ("grid", C.c_uint32 * 3), ("block", C.c_uint32), ("lds_bytes", C.c_uint64)]
 
 
 class LcError(RuntimeError):
@@ -68,6 +74,7 @@ def lib() -> C.CDLL:
         L.lcn_variant_bwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, C.c_uint32, vp, C.c_size_t, vp]
         L.sae_step.argtypes = [G, vp, vp, vp, vp, f32, f32, f32, u32, vp, vp, vp, sz, vp]
         L.lc_last_error.restype = C.c_char_p
+        L.lc_plan_query.argtypes = [G, C.c_int, C.c_int, C.POINTER(LcLaunch), i32, C.POINTER(i32)]
         for name in EXPORTS:
             if name not in ("lc_workspace_bytes", "lc_last_error"):
                 getattr(L, name).restype = C.c_int
@@ -77,7 +84,7 @@ def lib() -> C.CDLL:
 
 def _check(fn: str, rc: int) -> None:
     if rc != LC_OK:
-        detail = lib().lc_last_error().decode() if rc == LC_EHIP else ""
+        detail = lib().lc_last_error().decode() if rc in (LC_EHIP, LC_EINTERNAL) else ""
         raise LcError(fn, rc, detail)
 
 
@@ -93,6 +100,18 @@ def geom_derive(g: LcGeom) -> Tuple[int, int, int]:
 
 def workspace_bytes(g: LcGeom, op: int, dtype: int = LC_F32) -> int:
     return int(lib().lc_workspace_bytes(C.byref(g), op, dtype))
+
+
+def plan_query(g: LcGeom, op: int, dtype: int = LC_F32, max_out: int = 16):
+    """The launches ``op`` would make for this geometry, as a list of dicts (host only; nothing is launched)."""
+    out = (LcLaunch * max_out)()
+    n = C.c_int32()
+    _check("lc_plan_query", lib().lc_plan_query(C.byref(g), op, dtype, out, max_out, C.byref(n)))
+    if n.value > max_out:
+        return plan_query(g, op, dtype, n.value)
+    return [{"kernel": out[i].kernel.decode(), "tparam": list(out[i].tparam), "arg": list(out[i].arg),
+             "grid": tuple(out[i].grid), "block": int(out[i].block), "lds_bytes": int(out[i].lds_bytes)}
+            for i in range(n.value)]
 
 
 def _stream() -> int:

@@ -5,6 +5,7 @@
 #include <map>
 #include <mutex>
 #include <utility>
+#include <vector>
 
 #include "lc_common.hpp"
 
@@ -14,6 +15,45 @@ static thread_local char g_err[256] = "";
 
 void set_hip_error(hipError_t e, const char *where) {
     snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+}
+
+void set_error_text(const char *text) { snprintf(g_err, sizeof(g_err), "%s", text); }
+
+// ---------------------------------------------------------------------------------------------
+// Launch plans: see lc_common.hpp.
+static thread_local std::vector<LaunchPlan> *g_capture = nullptr;
+
+bool plan_capture() { return g_capture != nullptr; }
+void plan_capture_add(const LaunchPlan &p) { g_capture->push_back(p); }
+
+LaunchPlan make_plan(const char *kernel, std::initializer_list<int> tparam, std::initializer_list<int> arg, dim3 grid,
+                     unsigned block, size_t lds_bytes) {
+    LaunchPlan p;
+    memset(&p, 0, sizeof(p));
+    snprintf(p.kernel, sizeof(p.kernel), "%s", kernel);
+    int n = 0;
+    for (int v : tparam)
+        if (n < 12) p.tparam[n++] = v;
+    n = 0;
+    for (int v : arg)
+        if (n < 12) p.arg[n++] = v;
+    p.grid[0] = grid.x; p.grid[1] = grid.y; p.grid[2] = grid.z;
+    p.block = block;
+    p.lds_bytes = lds_bytes;
+    return p;
+}
+
+int plan_fail(const LaunchPlan &p, const char *what) {
+    snprintf(g_err, sizeof(g_err), "%s: launch plan violates: %s", p.kernel, what);
+    return LC_EINTERNAL;
+}
+
+int check_launch_shape(const LaunchPlan &p) {
+    LC_PLAN_REQUIRE(p, p.grid[0] >= 1 && p.grid[0] <= 0x7fffffffu);
+    LC_PLAN_REQUIRE(p, p.grid[1] >= 1 && p.grid[1] <= 65535u && p.grid[2] >= 1 && p.grid[2] <= 65535u);
+    LC_PLAN_REQUIRE(p, p.block >= 64 && p.block <= 1024 && p.block % 64 == 0);
+    LC_PLAN_REQUIRE(p, p.lds_bytes <= 160u * 1024u);
+    return LC_OK;
 }
 
 // Kernels that stage more than 48 KB need their dynamic LDS limit raised; the attribute is set once per
@@ -108,6 +148,38 @@ int lc_backward_weights(const lc_geom_t *g, const void *x, const void *dy, float
     if (dtype == LC_BF16) return launch_backward_weights_bf16(q, x, dy, beta, dw, (hipStream_t)hip_stream);
     return launch_backward_weights_f32(q, (const float *)x, (const float *)dy, nullptr, nullptr, beta, 1.f, dw,
                                        (hipStream_t)hip_stream);
+}
+
+int lc_plan_query(const lc_geom_t *g, int op, int dtype, lc_launch_t *out, int32_t max_out, int32_t *n_out) {
+    Geom q;
+    if (!make_geom(g, &q)) return LC_EINVAL;
+    if (dtype != LC_F32 && dtype != LC_BF16) return LC_EINVAL;
+    if (max_out < 0 || (max_out > 0 && !out) || !n_out) return LC_EINVAL;
+    if (op == LC_OP_SAE_STEP && dtype != LC_F32) return LC_EINVAL;
+    // never dereferenced: the launchers only do address arithmetic on the host, and nothing is launched
+    char *fake = (char *)(uintptr_t)0x100000;
+    float *ff = (float *)fake;
+    std::vector<LaunchPlan> plans;
+    g_capture = &plans;
+    int rc = LC_EINVAL;
+    const hipStream_t s = nullptr;
+    if (op == LC_OP_FORWARD) {
+        rc = dtype == LC_BF16 ? launch_forward_bf16(q, fake, fake, nullptr, 1.f, ff, s)
+                              : launch_forward_f32(q, ff, ff, nullptr, 1.f, nullptr, ff, s, fake,
+                                                   forward_wide_workspace_bytes(q));
+    } else if (op == LC_OP_BACKWARD_DATA) {
+        rc = dtype == LC_BF16 ? launch_backward_data_bf16(q, fake, fake, ff, s) : launch_backward_data_f32(q, ff, ff, ff, s);
+    } else if (op == LC_OP_BACKWARD_WEIGHTS) {
+        rc = dtype == LC_BF16 ? launch_backward_weights_bf16(q, fake, fake, 0.f, ff, s)
+                              : launch_backward_weights_f32(q, ff, ff, nullptr, nullptr, 0.f, 1.f, ff, s);
+    } else if (op == LC_OP_SAE_STEP) {
+        rc = launch_sae_step(q, ff, ff, ff, ff, 0.1f, 1e-6f, 1e-3f, LC_SAE_PROJECT_ROWS | LC_SAE_LEARN_ALPHA, ff, ff, fake, s);
+    }
+    g_capture = nullptr;
+    if (rc != LC_OK) return rc;
+    *n_out = (int32_t)plans.size();
+    for (int32_t k = 0; k < max_out && k < (int32_t)plans.size(); ++k) out[k] = plans[k];
+    return LC_OK;
 }
 
 static int check_map(int32_t B, int32_t H, int32_t W, int32_t C) {

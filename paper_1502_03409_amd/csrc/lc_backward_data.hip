@@ -19,10 +19,12 @@
 
 namespace lc {
 
-template <int MT, int NT, int NCELL, int VF>
-__global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *__restrict__ dy,
-                                                          const float *__restrict__ w, float *__restrict__ dx,
+// T: storage type of dy and w (float, or bf16 bit patterns widened on their way in).
+template <int MT, int NT, int NCELL, int VF, typename T>
+__global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const T *__restrict__ dy,
+                                                          const T *__restrict__ w, float *__restrict__ dx,
                                                           int strips_per_row, int AP, int JW, int fcs, int rs) {
+    typedef typename RawVec<T, 4>::V WV4;     // four consecutive filters of one weight row as loaded
     constexpr int BT = 16 * MT, NNW = 4 / NCELL;
     extern __shared__ __attribute__((aligned(16))) float dys[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
                     const int js = q >> fcs, f = fc0 + (q & (FC - 1)), j = jlo + js;
                     float v = 0.f;
                     if (j >= 0 && j < g.LW && f < g.F && b0 + bb < g.B)
-                        v = dy[(size_t)(b0 + bb) * dyimg + (size_t)(i * g.LW + j) * g.F + f];
+                        v = ld_f32(dy + (size_t)(b0 + bb) * dyimg + (size_t)(i * g.LW + j) * g.F + f);
                     dys[bb * rs + q] = v;
                     q += dq;
                     bb += db;
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
                 const int j = wi - ap;
                 if (j < 0 || j >= g.LW) continue;          // uniform over the wave
                 const int js = j - jlo;
-                const float *wl = w + ((size_t)(i * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F + fc0;
+                const T *wl = w + ((size_t)(i * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F + fc0;
                 bool ok[NT];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
@@ -101,9 +103,9 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
                     if (VF == 4) {
 #pragma unroll
                         for (int nt = 0; nt < NT; ++nt) {
-                            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                            if (ok[nt] && fc0 + fl < g.F) t = *(const float4 *)(wl + (size_t)kn[nt] * g.F + fl);
-                            bv[nt][0] = t.x; bv[nt][1 % VF] = t.y; bv[nt][2 % VF] = t.z; bv[nt][3 % VF] = t.w;
+                            f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
+                            if (ok[nt] && fc0 + fl < g.F) t = raw_widen4<T>(*(const WV4 *)(wl + (size_t)kn[nt] * g.F + fl));
+                            bv[nt][0] = t[0]; bv[nt][1 % VF] = t[1]; bv[nt][2 % VF] = t[2]; bv[nt][3 % VF] = t[3];
                         }
 #pragma unroll
                         for (int mt = 0; mt < MT; ++mt) {
@@ -113,7 +115,7 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const float *_
                     } else {
 #pragma unroll
                         for (int nt = 0; nt < NT; ++nt)
-                            bv[nt][0] = (ok[nt] && fc0 + fl < g.F) ? wl[(size_t)kn[nt] * g.F + fl] : 0.f;
+                            bv[nt][0] = (ok[nt] && fc0 + fl < g.F) ? ld_f32(wl + (size_t)kn[nt] * g.F + fl) : 0.f;
 #pragma unroll
                         for (int mt = 0; mt < MT; ++mt) av[mt][0] = arow[mt * 16 * rs + fq];
                     }
@@ -520,8 +522,28 @@ int row_stride(int rowlen, int vf) {
     return ((rowlen + 31) / 32) * 32 + res;
 }
 
-template <int MT, int NT, int NCELL, int VF>
-int launch_one(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+// Host check of a lc_bwd_data_kernel launch.  tparam = {MT, NT, NCELL, VF, bytes per operand element}; arg = {strips of cells per cell row,
+// AP = ceil(R/S), staged field columns JW, log2 of the filter chunk, LDS row stride}.  The kernel masks every
+// ragged edge itself.
+int check_backward_data_generic(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], NT = p.tparam[1], NCELL = p.tparam[2], VF = p.tparam[3];
+    const int strips = p.arg[0], AP = p.arg[1], JW = p.arg[2], fcs = p.arg[3], rs = p.arg[4];
+    const int BT = 16 * MT, NNW = 4 / NCELL, NCV = g.S * g.S * g.C;
+    const int CH = ceil_div(g.H, g.S), CW = ceil_div(g.W, g.S);
+    LC_PLAN_REQUIRE(p, p.block == 256 && (NCELL == 1 || NCELL == 2 || NCELL == 4) && (VF == 1 || VF == 4));
+    LC_PLAN_REQUIRE(p, AP == ceil_div(g.R, g.S) && JW == std::min(NCELL + AP - 1, g.LW));
+    // 16-byte accesses along f need whole vectors of four filters
+    LC_PLAN_REQUIRE(p, VF == 1 || g.F % 4 == 0);
+    LC_PLAN_REQUIRE(p, fcs >= (VF == 4 ? 4 : 2) && fcs <= 20 && rs >= (JW << fcs) && (VF == 1 || rs % 4 == 0));
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)BT * rs * sizeof(float));
+    LC_PLAN_REQUIRE(p, strips == ceil_div(CW, NCELL) && (long long)p.grid[0] == (long long)strips * CH);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[1] * NNW * NT * 16 >= NCV && (long long)(p.grid[1] - 1) * NNW * NT * 16 < NCV);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[2] * BT >= g.B && (long long)(p.grid[2] - 1) * BT < g.B);
+    return LC_OK;
+}
+
+template <int MT, int NT, int NCELL, int VF, typename T>
+int launch_one(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s) {
     constexpr int BT = 16 * MT, NNW = 4 / NCELL;
     const int AP = (g.R + g.S - 1) / g.S, JW = std::min(NCELL + AP - 1, g.LW);
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
@@ -532,17 +554,18 @@ int launch_one(const Geom &g, const float *dy, const float *w, float *dx, hipStr
     const int rs = row_stride(JW << fcs, VF);
     const size_t lds = (size_t)BT * rs * sizeof(float);
     if (lds > 160 * 1024) return LC_EUNSUPPORTED;
-    auto kern = lc_bwd_data_kernel<MT, NT, NCELL, VF>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
+    auto kern = lc_bwd_data_kernel<MT, NT, NCELL, VF, T>;
     const int strips = (CW + NCELL - 1) / NCELL;
     dim3 grid(strips * CH, (NCV + NNW * NT * 16 - 1) / (NNW * NT * 16), (g.B + BT - 1) / BT);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, AP, JW, fcs, rs);
-    LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
+    const LaunchPlan plan = make_plan("lc_bwd_data_generic", {MT, NT, NCELL, VF, (int)sizeof(T)}, {strips, AP, JW, fcs, rs},
+                                      grid, 256, lds);
+    if (int rc = check_backward_data_generic(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_data launch", kern, s, g, dy, w, dx, strips, AP, JW, fcs, rs);
     return LC_OK;
 }
 
-template <int MT>
-int launch_mt(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+template <int MT, typename T>
+int launch_mt(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s) {
     const int ntt = (g.S * g.S * g.C + 15) / 16;  // tiles of 16 cell values
     if ((g.F & 3) != 0) return launch_one<MT, 4, 1, 1>(g, dy, w, dx, s);
     if (ntt == 1) return launch_one<MT, 1, 4, 4>(g, dy, w, dx, s);
@@ -558,6 +581,36 @@ int launch_mt(const Geom &g, const float *dy, const float *w, float *dx, hipStre
 
 namespace {
 
+// Host check of a lc_bwd_data_fast_kernel or lc_bwd_data_line_kernel launch (LINE = 1: chunks of 32 filters, one LDS
+// buffer; 0: chunks of 16 filters, two buffers).
+// tparam = {MT, NT, NCELL, AP, NW, bytes per operand element, LINE, RING}; arg = {strips of cells per cell row, LDS
+// row stride in elements, batch tiles}.
+int check_backward_data_fast(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], NT = p.tparam[1], NCELL = p.tparam[2], AP = p.tparam[3], NW = p.tparam[4];
+    const int ES = p.tparam[5], LINE = p.tparam[6];
+    const int strips = p.arg[0], RS = p.arg[1], nbt = p.arg[2];
+    LC_PLAN_REQUIRE(p, NCELL > 0 && NW % NCELL == 0 && (ES == 4 || ES == 2) && (LINE == 0 || (ES == 4 && NW == 4)));
+    const int BT = 16 * MT, JW = NCELL + AP - 1, FCH = LINE ? 32 : 16, NCV = g.S * g.S * g.C;
+    const int CH = ceil_div(g.H, g.S), CW = ceil_div(g.W, g.S);
+    LC_PLAN_REQUIRE(p, (int)p.block == 64 * NW);
+    // fields tile the cells exactly, AP of them across a cell; filters in whole chunks
+    LC_PLAN_REQUIRE(p, g.R % g.S == 0 && AP == g.R / g.S && g.F % FCH == 0);
+    // staged dy: JW field columns of FCH filters per image in one LDS row, whole vectors of four
+    LC_PLAN_REQUIRE(p, RS >= JW * FCH && RS % 4 == 0);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)(LINE ? 1 : 2) * BT * RS * ES);
+    // 32-bit offsets inside a field's K x F matrix (kn) and inside one image's dy (j * F)
+    LC_PLAN_REQUIRE(p, (long long)g.K * g.F < (1LL << 31) && (long long)g.LW * g.F < (1LL << 31));
+    // every cell row (the rows past the last covered one get zeros), every strip of cells, every batch tile
+    LC_PLAN_REQUIRE(p, strips == ceil_div(CW, NCELL) && nbt == ceil_div(g.B, BT));
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == (long long)strips * CH * nbt);
+    // the kernel's work order puts the cell rows [AP-1, LH) first and the rest behind them: all CH rows are reached
+    // only if there are at least as many cell rows as that order assumes
+    LC_PLAN_REQUIRE(p, CH >= g.LH + AP - 1);
+    const int nblk = (NW / NCELL) * NT * 16;
+    LC_PLAN_REQUIRE(p, (long long)p.grid[1] * nblk >= NCV && (long long)(p.grid[1] - 1) * nblk < NCV && p.grid[2] == 1);
+    return LC_OK;
+}
+
 template <int MT, int NT, int NCELL, int AP, int RING>
 int launch_line(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
@@ -566,13 +619,13 @@ int launch_line(const Geom &g, const float *dy, const float *w, float *dx, hipSt
     const int RS = JW * 32 + 4;                               // 16 bytes past a multiple of 128, as below
     const size_t lds = (size_t)BT * RS * sizeof(float);
     auto kern = lc_bwd_data_line_kernel<MT, NT, NCELL, AP, RING>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
     const int strips = (CW + NCELL - 1) / NCELL;
     const int nblk = (4 / NCELL) * NT * 16;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(strips * CH * nbt, (NCV + nblk - 1) / nblk);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, dy, w, dx, strips, RS, nbt);
-    LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
+    const LaunchPlan plan = make_plan("lc_bwd_data_line", {MT, NT, NCELL, AP, 4, 4, 1, RING}, {strips, RS, nbt}, grid, 256, lds);
+    if (int rc = check_backward_data_fast(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_data launch", kern, s, g, dy, w, dx, strips, RS, nbt);
     return LC_OK;
 }
 
@@ -586,13 +639,14 @@ int launch_fast(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s
     const int RS = sizeof(T) == 2 ? ((JW * 16 + 63) / 64) * 64 + 8 : ((JW * 16 + 31) / 32) * 32 + 4;
     const size_t lds = (size_t)2 * BT * RS * sizeof(T);          // two buffers
     auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP, NW, T>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data: hipFuncSetAttribute")) return rc_lds;
     const int strips = (CW + NCELL - 1) / NCELL;
     const int nblk = (NW / NCELL) * NT * 16;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(strips * CH * nbt, (NCV + nblk - 1) / nblk);
-    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, g, dy, w, dx, strips, RS, nbt);
-    LC_HIP_LAUNCH_CHECK("lc_backward_data launch");
+    const LaunchPlan plan = make_plan("lc_bwd_data_fast", {MT, NT, NCELL, AP, NW, (int)sizeof(T), 0, AP}, {strips, RS, nbt},
+                                      grid, 64 * NW, lds);
+    if (int rc = check_backward_data_fast(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_data launch", kern, s, g, dy, w, dx, strips, RS, nbt);
     return LC_OK;
 }
 
@@ -646,6 +700,19 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
 
 }  // namespace
 
+namespace {
+
+// the masked kernel (any shape), batch tile by batch size
+template <typename T>
+int launch_backward_data_generic(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s) {
+    if (g.B > 64) return launch_mt<8>(g, dy, w, dx, s);
+    if (g.B > 32) return launch_mt<4>(g, dy, w, dx, s);
+    if (g.B > 16) return launch_mt<2>(g, dy, w, dx, s);
+    return launch_mt<1>(g, dy, w, dx, s);
+}
+
+}  // namespace
+
 int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     // cells of 128-value blocks: one cell per workgroup, dy through LDS, 128 x 128 output tiles
     if (backward_data_wide_supported(g) || backward_data_dense_supported(g))
@@ -655,16 +722,21 @@ int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, flo
         const int rc = launch_backward_data_fast_path(g, dy, w, dx, s, &done);
         if (done) return rc;
     }
-    if (g.B > 64) return launch_mt<8>(g, dy, w, dx, s);
-    if (g.B > 32) return launch_mt<4>(g, dy, w, dx, s);
-    if (g.B > 16) return launch_mt<2>(g, dy, w, dx, s);
-    return launch_mt<1>(g, dy, w, dx, s);
+    return launch_backward_data_generic(g, dy, w, dx, s);
+}
+
+// shapes the pipelined kernel takes (on bf16 storage it multiplies with bf16 matrix instructions)
+bool backward_data_bf16_pipelined_supported(const Geom &g) {
+    if (!(g.F % 16 == 0 && g.R % g.S == 0 && g.B > 32)) return false;
+    const int ap = g.R / g.S;
+    return ap == 2 || ap == 3 || ap == 4 || ap == 5 || ap == 8;
 }
 
 int launch_backward_data_bf16_storage(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
     bool done = false;
     const int rc = launch_backward_data_fast_path(g, (const bf16_t *)dy, (const bf16_t *)w, dx, s, &done);
-    return done ? rc : LC_EUNSUPPORTED;
+    if (done) return rc;
+    return launch_backward_data_generic(g, (const bf16_t *)dy, (const bf16_t *)w, dx, s);
 }
 
 }  // namespace lc

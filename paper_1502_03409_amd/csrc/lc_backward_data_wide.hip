@@ -166,19 +166,42 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_wide_kernel(Geom g, const 
     }
 }
 
+// Host check of a lc_bwd_data_wide_kernel launch.  tparam = {MT, PD, DENSE}; arg = {cells per row, 128-value blocks
+// per cell, batch tiles}.
+int check_backward_data_wide(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], DENSE = p.tparam[2];
+    const int CW = p.arg[0], nblk = p.arg[1], btiles = p.arg[2];
+    const int BT = 32 * MT;
+    LC_PLAN_REQUIRE(p, p.block == 256);
+    LC_PLAN_REQUIRE(p, g.F % kChunk == 0 && btiles == ceil_div(g.B, BT));
+    // 32-bit element offsets of dy and inside a field's K x F matrix
+    LC_PLAN_REQUIRE(p, (long long)g.B * g.L * g.F < (1LL << 31) && (long long)g.K * g.F < (1LL << 31));
+    long long cells;
+    if (DENSE) {
+        LC_PLAN_REQUIRE(p, g.L == 1 && g.R == g.H && g.R == g.W && nblk == 1);
+        cells = ceil_div(g.K, 128);
+    } else {
+        LC_PLAN_REQUIRE(p, g.R % g.S == 0 && (g.S * g.S * g.C) % 128 == 0 && nblk == g.S * g.S * g.C / 128);
+        LC_PLAN_REQUIRE(p, CW == ceil_div(g.W, g.S));
+        cells = (long long)ceil_div(g.H, g.S) * CW;
+    }
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == cells * nblk * btiles && p.grid[1] == 1 && p.grid[2] == 1);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)2 * BT * kRowFloats * sizeof(float));
+    return LC_OK;
+}
+
 template <int MT, int PD, bool DENSE>
 int launch_wide(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     constexpr int BT = 32 * MT;
     const size_t lds = (size_t)2 * BT * kRowFloats * sizeof(float);
     auto kern = lc_bwd_data_wide_kernel<MT, PD, DENSE>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data (wide): hipFuncSetAttribute"))
-        return rc_lds;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int nblk = DENSE ? 1 : g.S * g.S * g.C / 128, btiles = (g.B + BT - 1) / BT;
     const long long cells = DENSE ? (g.K + 127) / 128 : (long long)CH * CW;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(cells * nblk * btiles)), dim3(256), lds, s, g, dy, w, dx, CW, nblk,
-                       btiles);
-    LC_HIP_LAUNCH_CHECK("lc_backward_data (wide) launch");
+    const LaunchPlan plan = make_plan("lc_bwd_data_wide", {MT, PD, DENSE ? 1 : 0}, {CW, nblk, btiles},
+                                      dim3((unsigned)(cells * nblk * btiles)), 256, lds);
+    if (int rc = check_backward_data_wide(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_data (wide) launch", kern, s, g, dy, w, dx, CW, nblk, btiles);
     return LC_OK;
 }
 

@@ -10,12 +10,14 @@
 
 namespace lc {
 
-template <int MTW, int NT>
-__global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const float *__restrict__ x1,
-                                                             const float *__restrict__ dy1,
-                                                             const float *__restrict__ x2,
-                                                             const float *__restrict__ dy2, float beta, float gamma,
-                                                             float *__restrict__ out, int kblocks, int ntasks) {
+// T: storage type of x and dy (float, or bf16 bit patterns widened on their way in).
+template <int MTW, int NT, typename T>
+__global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const T *__restrict__ x1,
+                                                             const T *__restrict__ dy1,
+                                                             const T *__restrict__ x2,
+                                                             const T *__restrict__ dy2, float beta, float gamma,
+                                                             float *__restrict__ out, float *__restrict__ ssq,
+                                                             int kblocks, int ntasks) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, kk = lane >> 4;
     const int task = remap_xcd(blockIdx.x, gridDim.x) * 4 + wave;
@@ -48,20 +50,20 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const float
     const int Bfull = g.B & ~3;
     const bool edge = (k0 + MTW * 16 > g.K) || (f0 + NT * 16 > g.F);
     for (int p = 0; p < 2; ++p) {
-        const float *x = p ? x2 : x1;
-        const float *dy = p ? dy2 : dy1;
+        const T *x = p ? x2 : x1;
+        const T *dy = p ? dy2 : dy1;
         if (!x) break;
-        const float *xa = x + (size_t)kk * img;
-        const float *da = dy + ((size_t)kk * g.L + loc) * g.F + f0 + m;
+        const T *xa = x + (size_t)kk * img;
+        const T *da = dy + ((size_t)kk * g.L + loc) * g.F + f0 + m;
         const size_t dstep = (size_t)g.L * g.F;
         if (!edge) {
 #pragma unroll 2
             for (int b0 = 0; b0 < Bfull; b0 += 4) {
                 float a[MTW], bv[NT];
 #pragma unroll
-                for (int mt = 0; mt < MTW; ++mt) a[mt] = xa[(size_t)b0 * img + off[mt]];
+                for (int mt = 0; mt < MTW; ++mt) a[mt] = ld_f32(xa + (size_t)b0 * img + off[mt]);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) bv[nt] = da[(size_t)b0 * dstep + nt * 16];
+                for (int nt = 0; nt < NT; ++nt) bv[nt] = ld_f32(da + (size_t)b0 * dstep + nt * 16);
 #pragma unroll
                 for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
@@ -73,9 +75,9 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const float
             const bool bok = b0 + kk < g.B;
             float a[MTW], bv[NT];
 #pragma unroll
-            for (int mt = 0; mt < MTW; ++mt) a[mt] = (bok && kok[mt]) ? xa[(size_t)b0 * img + off[mt]] : 0.f;
+            for (int mt = 0; mt < MTW; ++mt) a[mt] = (bok && kok[mt]) ? ld_f32(xa + (size_t)b0 * img + off[mt]) : 0.f;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bv[nt] = (bok && fok[nt]) ? da[(size_t)b0 * dstep + nt * 16] : 0.f;
+            for (int nt = 0; nt < NT; ++nt) bv[nt] = (bok && fok[nt]) ? ld_f32(da + (size_t)b0 * dstep + nt * 16) : 0.f;
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
@@ -84,6 +86,9 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const float
     }
 
     float *ol = out + (size_t)loc * g.K * g.F;
+    float sq[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) sq[nt] = 0.f;
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
@@ -94,10 +99,22 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const float
             for (int nt = 0; nt < NT; ++nt) {
                 if (!fok[nt]) continue;
                 float *o = ol + (size_t)k * g.F + f0 + nt * 16 + m;
-                const float v = gamma * acc[mt][nt][r];
-                *o = (beta != 0.f) ? beta * *o + v : v;
+                float v = gamma * acc[mt][nt][r];
+                if (beta != 0.f) v += beta * *o;
+                *o = v;
+                sq[nt] += v * v;
             }
         }
+    // per-filter sums of squares of the rows this wave stored: partial [location][k block][filter]
+    if (ssq) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float t = sq[nt];
+            t += __shfl_xor(t, 16, 64);
+            t += __shfl_xor(t, 32, 64);
+            if (kk == 0 && fok[nt]) ssq[((size_t)loc * kblocks + (k0 / (MTW * 16))) * g.F + f0 + nt * 16 + m] = t;
+        }
+    }
 }
 
 
@@ -127,8 +144,8 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
                                                                   const T *__restrict__ dy1,
                                                                   const T *__restrict__ x2,
                                                                   const T *__restrict__ dy2, float beta,
-                                                                  float gamma, float *__restrict__ out, int kblocks,
-                                                                  int ntasks) {
+                                                                  float gamma, float *__restrict__ out,
+                                                                  float *__restrict__ ssq, int kblocks, int ntasks) {
     typedef typename RawVec<T, VA>::V AV;     // VA consecutive patch elements as loaded (fp32, or bf16 bit patterns)
     typedef typename RawVec<T, NT>::V BR;     // NT consecutive dy values as loaded
     typedef typename VecT<NT>::T BV;          // NT consecutive outputs
@@ -217,6 +234,35 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
     }
 
     float *ol = out + (size_t)loc * g.K * g.F + f0 + NT * m;
+    // per-filter sums of squares of the rows this wave stores (only formed when ssq is given)
+    float sq[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) sq[u] = 0.f;
+    auto add_squares = [&](const BV &v) {
+        if constexpr (NT == 1) {
+            sq[0] += v * v;
+        } else {
+#pragma unroll
+            for (int u = 0; u < NT; ++u) sq[u] += v[u] * v[u];
+        }
+    };
+    auto store_squares = [&]() {
+#pragma unroll
+        for (int u = 0; u < NT; ++u) {
+            sq[u] += __shfl_xor(sq[u], 16, 64);
+            sq[u] += __shfl_xor(sq[u], 32, 64);
+        }
+        if (kk == 0) {
+            BV t;
+            if constexpr (NT == 1) {
+                t = sq[0];
+            } else {
+#pragma unroll
+                for (int u = 0; u < NT; ++u) t[u] = sq[u];
+            }
+            *(BV *)(ssq + ((size_t)loc * kblocks + (k0 / KB)) * g.F + f0 + NT * m) = t;
+        }
+    };
     if (beta == 0.f) {
 #pragma unroll
         for (int gg = 0; gg < G; ++gg)
@@ -234,7 +280,9 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
                         for (int u = 0; u < NT; ++u) v[u] = gamma * acc[gg][t][u][r];
                     }
                     *(BV *)(ol + (size_t)k * g.F) = v;
+                    if (ssq) add_squares(v);
                 }
+        if (ssq) store_squares();
         return;
     }
     // beta != 0 (the fused update), a code path of its own: the old values of four rows are requested together,
@@ -262,30 +310,47 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
 #pragma unroll
                     for (int u = 0; u < NT; ++u) v[u] = gamma * acc[gg][t][u][r];
                 }
-                *(BV *)(ol + (size_t)k * g.F) = v + beta * old[t];
+                v += beta * old[t];
+                *(BV *)(ol + (size_t)k * g.F) = v;
+                if (ssq) add_squares(v);
             }
         }
+    if (ssq) store_squares();
 }
 
 namespace {
 
-template <int MTW, int NT>
-int launch_one(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2, float beta,
-               float gamma, float *out, hipStream_t s) {
+// Host check of a lc_bwd_weights_kernel launch.  tparam = {MTW, NT, bytes per operand element}; arg = {blocks of 16*MTW patch elements per
+// field, wave tasks}.  The kernel masks every ragged edge itself.
+int check_backward_weights_generic(const Geom &g, const LaunchPlan &p) {
+    const int MTW = p.tparam[0], NT = p.tparam[1];
+    const int kblocks = p.arg[0], ntasks = p.arg[1];
+    LC_PLAN_REQUIRE(p, p.block == 256);
+    LC_PLAN_REQUIRE(p, kblocks == ceil_div(g.K, 16 * MTW) && (long long)ntasks == (long long)g.L * kblocks);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] * 4 >= ntasks && (long long)(p.grid[0] - 1) * 4 < ntasks);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[1] * NT * 16 >= g.F && (long long)(p.grid[1] - 1) * NT * 16 < g.F && p.grid[2] == 1);
+    return LC_OK;
+}
+
+template <int MTW, int NT, typename T>
+int launch_one(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
+               float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s) {
     const int kt = (g.K + 15) / 16;
     const int kblocks = (kt + MTW - 1) / MTW;
     const long long ntasks = (long long)g.L * kblocks;
     if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
     dim3 grid((unsigned)((ntasks + 3) / 4), (g.F + NT * 16 - 1) / (NT * 16));
-    hipLaunchKernelGGL((lc_bwd_weights_kernel<MTW, NT>), grid, dim3(256), 0, s, g, x1, dy1, x2, dy2, beta, gamma,
-                       out, kblocks, (int)ntasks);
-    LC_HIP_LAUNCH_CHECK("lc_backward_weights launch");
+    const LaunchPlan plan = make_plan("lc_bwd_weights_generic", {MTW, NT, (int)sizeof(T)}, {kblocks, (int)ntasks}, grid, 256, 0);
+    if (int rc = check_backward_weights_generic(g, plan)) return rc;
+    if (kblocks_out) *kblocks_out = kblocks;
+    LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_kernel<MTW, NT, T>), s, g, x1, dy1, x2, dy2, beta, gamma,
+              out, ssq, kblocks, (int)ntasks);
     return LC_OK;
 }
 
-template <int NT>
-int launch_nt(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2, float beta,
-              float gamma, float *out, hipStream_t s) {
+template <int NT, typename T>
+int launch_nt(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
+              float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s) {
     // tiles of 16 patch elements per wave: the candidate with the least padding of K, larger first
     const int kt = (g.K + 15) / 16;
     const int cand[4] = {8, 6, 5, 4};
@@ -295,10 +360,10 @@ int launch_nt(const Geom &g, const float *x1, const float *dy1, const float *x2,
         if (wst < waste) { waste = wst; best = c; }
     }
     switch (best) {
-        case 8: return launch_one<8, NT>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-        case 6: return launch_one<6, NT>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-        case 5: return launch_one<5, NT>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-        default: return launch_one<4, NT>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+        case 8: return launch_one<8, NT>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+        case 6: return launch_one<6, NT>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+        case 5: return launch_one<5, NT>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+        default: return launch_one<4, NT>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
     }
 }
 
@@ -306,17 +371,37 @@ int launch_nt(const Geom &g, const float *x1, const float *dy1, const float *x2,
 
 namespace {
 
+// Host check of a lc_bwd_weights_fast_kernel launch.  tparam = {G, VA, NT, PF, bytes per operand element};
+// arg = {blocks of G*VA*16 patch elements per field, wave tasks}.
+int check_backward_weights_fast(const Geom &g, const LaunchPlan &p) {
+    const int G = p.tparam[0], VA = p.tparam[1], NT = p.tparam[2], PF = p.tparam[3];
+    const int kblocks = p.arg[0], ntasks = p.arg[1];
+    const int KB = G * VA * 16;
+    LC_PLAN_REQUIRE(p, p.block == 256 && (VA == 1 || VA == 2 || VA == 4) && (NT == 1 || NT == 2 || NT == 4));
+    // a lane's VA patch elements never straddle two patch rows; filters in whole tiles
+    LC_PLAN_REQUIRE(p, g.RC % VA == 0 && g.F % (NT * 16) == 0 && (int)p.grid[1] == g.F / (NT * 16) && p.grid[2] == 1);
+    // the batch in whole ring turns of PF steps of four images
+    LC_PLAN_REQUIRE(p, PF >= 1 && g.B % (4 * PF) == 0);
+    LC_PLAN_REQUIRE(p, kblocks == ceil_div(g.K, KB) && (long long)ntasks == (long long)g.L * kblocks);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] * 4 >= ntasks && (long long)(p.grid[0] - 1) * 4 < ntasks);
+    // 32-bit offsets inside one image
+    LC_PLAN_REQUIRE(p, (long long)g.H * g.W * g.C < (1LL << 31));
+    return LC_OK;
+}
+
 template <int G, int VA, int NT, int PF, typename T>
 int launch_fast(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
-                float gamma, float *out, hipStream_t s) {
+                float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s) {
     constexpr int KB = G * VA * 16;
     const int kblocks = (g.K + KB - 1) / KB;
     const long long ntasks = (long long)g.L * kblocks;
     if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
     dim3 grid((unsigned)((ntasks + 3) / 4), g.F / (NT * 16));
-    hipLaunchKernelGGL((lc_bwd_weights_fast_kernel<G, VA, NT, PF, T>), grid, dim3(256), 0, s, g, x1, dy1, x2, dy2, beta,
-                       gamma, out, kblocks, (int)ntasks);
-    LC_HIP_LAUNCH_CHECK("lc_backward_weights launch");
+    const LaunchPlan plan = make_plan("lc_bwd_weights_fast", {G, VA, NT, PF, (int)sizeof(T)}, {kblocks, (int)ntasks}, grid, 256, 0);
+    if (int rc = check_backward_weights_fast(g, plan)) return rc;
+    if (kblocks_out) *kblocks_out = kblocks;
+    LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_fast_kernel<G, VA, NT, PF, T>), s, g, x1, dy1, x2, dy2,
+              beta, gamma, out, ssq, kblocks, (int)ntasks);
     return LC_OK;
 }
 
@@ -329,57 +414,71 @@ int patch_vector_width(const Geom &g) {
 
 template <int G, int VA, int NT, typename T>
 int launch_fast_pf(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
-                   float gamma, float *out, hipStream_t s) {
-    if (g.B % 16 == 0) return launch_fast<G, VA, NT, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-    if (g.B % 8 == 0) return launch_fast<G, VA, NT, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-    return launch_fast<G, VA, NT, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+                   float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s) {
+    if (g.B % 16 == 0) return launch_fast<G, VA, NT, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+    if (g.B % 8 == 0) return launch_fast<G, VA, NT, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+    return launch_fast<G, VA, NT, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
 }
 
 // The whole-line kernel for aligned shapes; *done tells whether a kernel was launched.  T = float or bf16_t.
 template <typename T>
 int launch_backward_weights_fast_path(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
-                                      float gamma, float *out, hipStream_t s, bool *done) {
+                                      float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s, bool *done) {
     *done = false;
     const int va = patch_vector_width(g);
     if ((g.B & 3) == 0 && va == 4) {
-        if (g.F % 64 == 0) { *done = true; return launch_fast_pf<1, 4, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+        if (g.F % 64 == 0) { *done = true; return launch_fast_pf<1, 4, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s); }
         if (g.F % 32 == 0) {
             *done = true;
             // blocks of 192 patch elements where they pad K less than blocks of 128 (K = 576: 3 blocks instead of 5)
             const int pad2 = (g.K + 127) / 128 * 128 - g.K, pad3 = (g.K + 191) / 192 * 192 - g.K;
-            if (pad3 < pad2) return launch_fast_pf<3, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-            return launch_fast_pf<2, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+            if (pad3 < pad2) return launch_fast_pf<3, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+            return launch_fast_pf<2, 4, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
         }
-        if (g.F % 16 == 0) { *done = true; return launch_fast_pf<2, 4, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+        if (g.F % 16 == 0) { *done = true; return launch_fast_pf<2, 4, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s); }
     }
     if ((g.B & 3) == 0 && va == 2) {
-        if (g.F % 64 == 0) { *done = true; return launch_fast_pf<2, 2, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
-        if (g.F % 32 == 0) { *done = true; return launch_fast_pf<4, 2, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
-        if (g.F % 16 == 0) { *done = true; return launch_fast_pf<4, 2, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, s); }
+        if (g.F % 64 == 0) { *done = true; return launch_fast_pf<2, 2, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s); }
+        if (g.F % 32 == 0) { *done = true; return launch_fast_pf<4, 2, 2>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s); }
+        if (g.F % 16 == 0) { *done = true; return launch_fast_pf<4, 2, 1>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s); }
     }
     return LC_OK;
 }
 
 }  // namespace
 
+namespace {
+
+// the masked kernel (any shape), filter tiles per wave by F
+template <typename T>
+int launch_backward_weights_generic(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
+                                    float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s) {
+    if (g.F <= 16) return launch_nt<1>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+    if (g.F <= 32) return launch_nt<2>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+    return launch_nt<4>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+}
+
+}  // namespace
+
 int launch_backward_weights_f32(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2,
-                                float beta, float gamma, float *out, hipStream_t s) {
+                                float beta, float gamma, float *out, hipStream_t s, float *ssq, int *kblocks_out) {
     {
         bool done = false;
-        const int rc = launch_backward_weights_fast_path(g, x1, dy1, x2, dy2, beta, gamma, out, s, &done);
+        const int rc = launch_backward_weights_fast_path(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s, &done);
         if (done) return rc;
     }
-    if (g.F <= 16) return launch_nt<1>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-    if (g.F <= 32) return launch_nt<2>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
-    return launch_nt<4>(g, x1, dy1, x2, dy2, beta, gamma, out, s);
+    return launch_backward_weights_generic(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
 }
 
 int launch_backward_weights_bf16_storage(const Geom &g, const void *x, const void *dy, float beta, float *dw,
                                          hipStream_t s) {
+    const bf16_t *none = nullptr;
     bool done = false;
-    const int rc = launch_backward_weights_fast_path(g, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)nullptr,
-                                                     (const bf16_t *)nullptr, beta, 1.f, dw, s, &done);
-    return done ? rc : LC_EUNSUPPORTED;
+    const int rc = launch_backward_weights_fast_path(g, (const bf16_t *)x, (const bf16_t *)dy, none, none, beta, 1.f, dw,
+                                                     nullptr, nullptr, s, &done);
+    if (done) return rc;
+    return launch_backward_weights_generic(g, (const bf16_t *)x, (const bf16_t *)dy, none, none, beta, 1.f, dw, nullptr,
+                                           nullptr, s);
 }
 
 }  // namespace lc

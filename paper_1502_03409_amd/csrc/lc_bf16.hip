@@ -241,45 +241,92 @@ bool bf16_shape_supported(const Geom &g) {
 // Order of preference, every pass: the workgroup-tiled kernels (wide layers), the strip-sharing / pipelined / transposing
 // kernels of the narrow layers (faster than the one-wave-per-task kernels of this file wherever both apply: cfg2
 // 30 / 13 / 9 us against 37 / 21 / 10 us), the kernels of this file, the fp32 kernels on bf16 storage.
+// Host checks of the one-wave-per-task kernels of this file.  tparam = {MT}; arg as listed per function.
+namespace {
+
+// arg = {filter blocks of 64, batch tiles, wave tasks}
+int check_forward_bf16_simple(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], fblocks = p.arg[0], btiles = p.arg[1], ntasks = p.arg[2];
+    LC_PLAN_REQUIRE(p, p.block == 256 && bf16_shape_supported(g));
+    LC_PLAN_REQUIRE(p, fblocks == g.F / 64 && btiles == ceil_div(g.B, 16 * MT));
+    LC_PLAN_REQUIRE(p, (long long)ntasks == (long long)g.L * fblocks * btiles);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] * 4 >= ntasks && (long long)(p.grid[0] - 1) * 4 < ntasks);
+    return LC_OK;
+}
+
+// arg = {cells per row, blocks of 64 cell values, batch tiles, wave tasks}
+int check_backward_data_bf16_simple(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], CW = p.arg[0], nblocks = p.arg[1], btiles = p.arg[2], ntasks = p.arg[3];
+    LC_PLAN_REQUIRE(p, p.block == 256 && bf16_shape_supported(g));
+    LC_PLAN_REQUIRE(p, CW == ceil_div(g.W, g.S) && nblocks == ceil_div(g.S * g.S * g.C, 64) && btiles == ceil_div(g.B, 16 * MT));
+    LC_PLAN_REQUIRE(p, (long long)ntasks == (long long)ceil_div(g.H, g.S) * CW * nblocks * btiles);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] * 4 >= ntasks && (long long)(p.grid[0] - 1) * 4 < ntasks);
+    LC_PLAN_REQUIRE(p, (long long)g.K * g.F < (1LL << 31));
+    return LC_OK;
+}
+
+// arg = {blocks of 128 patch elements per field, wave tasks}
+int check_backward_weights_bf16_simple(const Geom &g, const LaunchPlan &p) {
+    const int kblocks = p.arg[0], ntasks = p.arg[1];
+    LC_PLAN_REQUIRE(p, p.block == 256 && bf16_shape_supported(g));
+    LC_PLAN_REQUIRE(p, kblocks == ceil_div(g.K, 128) && (long long)ntasks == (long long)g.L * kblocks);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] * 4 >= ntasks && (long long)(p.grid[0] - 1) * 4 < ntasks);
+    LC_PLAN_REQUIRE(p, (int)p.grid[1] == g.F / 64 && (long long)g.H * g.W * g.C < (1LL << 31));
+    return LC_OK;
+}
+
+template <int MT>
+int launch_forward_simple(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
+                          hipStream_t s) {
+    const int fblocks = g.F / 64, btiles = (g.B + 16 * MT - 1) / (16 * MT);
+    const long long ntasks = (long long)g.L * fblocks * btiles;
+    if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
+    const LaunchPlan plan = make_plan("lc_forward_bf16_simple", {MT}, {fblocks, btiles, (int)ntasks},
+                                      dim3((unsigned)((ntasks + 3) / 4)), 256, 0);
+    if (int rc = check_forward_bf16_simple(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_forward (bf16) launch", lc_forward_bf16_kernel<MT>, s, g, (const unsigned short *)x,
+              (const unsigned short *)w, bias, alpha, y, fblocks, btiles, (int)ntasks);
+    return LC_OK;
+}
+
+template <int MT>
+int launch_backward_data_simple(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
+    const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
+    const int nblocks = (g.S * g.S * g.C + 63) / 64, btiles = (g.B + 16 * MT - 1) / (16 * MT);
+    const long long ntasks = (long long)CH * CW * nblocks * btiles;
+    if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
+    const LaunchPlan plan = make_plan("lc_bwd_data_bf16_simple", {MT}, {CW, nblocks, btiles, (int)ntasks},
+                                      dim3((unsigned)((ntasks + 3) / 4)), 256, 0);
+    if (int rc = check_backward_data_bf16_simple(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_data (bf16) launch", lc_bwd_data_bf16_kernel<MT>, s, g, (const unsigned short *)dy,
+              (const unsigned short *)w, dx, CW, nblocks, btiles, (int)ntasks);
+    return LC_OK;
+}
+
+}  // namespace
+
+// LC_BF16 covers every valid geometry.  Order of preference, every pass: the workgroup-tiled kernels (wide layers),
+// the strip-sharing / pipelined / transposing kernels of the narrow layers (faster than the one-wave-per-task
+// kernels of this file wherever both apply), the kernels of this file, the fp32 pipelined kernels on bf16 storage,
+// and for every other shape the masked fp32 kernels on bf16 storage.
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s) {
     if (bf16_shape_supported(g) && bf16_tiled_forward_supported(g))
         return launch_forward_bf16_tiled(g, x, w, bias, alpha, y, s);
     if (bf16_strip_forward_supported(g)) return launch_forward_bf16_strip(g, x, w, bias, alpha, y, s);
     if (!bf16_shape_supported(g)) return launch_forward_bf16_storage(g, x, w, bias, alpha, y, s);
-    const int fblocks = g.F / 64;
-    auto go = [&](auto kern, int MT) {
-        const int btiles = (g.B + 16 * MT - 1) / (16 * MT);
-        const long long ntasks = (long long)g.L * fblocks * btiles;
-        hipLaunchKernelGGL(kern, dim3((unsigned)((ntasks + 3) / 4)), dim3(256), 0, s, g, (const unsigned short *)x,
-                           (const unsigned short *)w, bias, alpha, y, fblocks, btiles, (int)ntasks);
-    };
-    if (g.B >= 64) go(lc_forward_bf16_kernel<4>, 4);
-    else go(lc_forward_bf16_kernel<1>, 1);
-    LC_HIP_LAUNCH_CHECK("lc_forward (bf16) launch");
-    return LC_OK;
+    if (g.B >= 64) return launch_forward_simple<4>(g, x, w, bias, alpha, y, s);
+    return launch_forward_simple<1>(g, x, w, bias, alpha, y, s);
 }
 
 int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
     if (bf16_shape_supported(g) && bf16_tiled_backward_data_supported(g))
         return launch_backward_data_bf16_tiled(g, dy, w, dx, s);
-    {
-        const int rc = launch_backward_data_bf16_storage(g, dy, w, dx, s);   // the pipelined kernel with bf16 MFMAs
-        if (rc != LC_EUNSUPPORTED || !bf16_shape_supported(g)) return rc;
-    }
-    const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
-    const int nblocks = (g.S * g.S * g.C + 63) / 64;
-    auto go = [&](auto kern, int MT) {
-        const int btiles = (g.B + 16 * MT - 1) / (16 * MT);
-        const long long ntasks = (long long)CH * CW * nblocks * btiles;
-        hipLaunchKernelGGL(kern, dim3((unsigned)((ntasks + 3) / 4)), dim3(256), 0, s, g, (const unsigned short *)dy,
-                           (const unsigned short *)w, dx, CW, nblocks, btiles, (int)ntasks);
-    };
-    if (g.B >= 128) go(lc_bwd_data_bf16_kernel<8>, 8);
-    else if (g.B >= 64) go(lc_bwd_data_bf16_kernel<4>, 4);
-    else go(lc_bwd_data_bf16_kernel<1>, 1);
-    LC_HIP_LAUNCH_CHECK("lc_backward_data (bf16) launch");
-    return LC_OK;
+    if (!bf16_shape_supported(g) || backward_data_bf16_pipelined_supported(g))
+        return launch_backward_data_bf16_storage(g, dy, w, dx, s);   // pipelined (bf16 MFMAs) or masked kernel
+    if (g.B >= 128) return launch_backward_data_simple<8>(g, dy, w, dx, s);
+    if (g.B >= 64) return launch_backward_data_simple<4>(g, dy, w, dx, s);
+    return launch_backward_data_simple<1>(g, dy, w, dx, s);
 }
 
 int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, float beta, float *dw,
@@ -290,9 +337,12 @@ int launch_backward_weights_bf16(const Geom &g, const void *x, const void *dy, f
     if (!bf16_shape_supported(g)) return launch_backward_weights_bf16_storage(g, x, dy, beta, dw, s);
     const int kblocks = (g.K + 127) / 128;
     const long long ntasks = (long long)g.L * kblocks;
-    hipLaunchKernelGGL(lc_bwd_weights_bf16_kernel, dim3((unsigned)((ntasks + 3) / 4), g.F / 64), dim3(256), 0, s, g,
-                       (const unsigned short *)x, (const unsigned short *)dy, beta, dw, kblocks, (int)ntasks);
-    LC_HIP_LAUNCH_CHECK("lc_backward_weights (bf16) launch");
+    if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
+    const LaunchPlan plan = make_plan("lc_bwd_weights_bf16_simple", {}, {kblocks, (int)ntasks},
+                                      dim3((unsigned)((ntasks + 3) / 4), g.F / 64), 256, 0);
+    if (int rc = check_backward_weights_bf16_simple(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_weights (bf16) launch", lc_bwd_weights_bf16_kernel, s, g, (const unsigned short *)x,
+              (const unsigned short *)dy, beta, dw, kblocks, (int)ntasks);
     return LC_OK;
 }
 

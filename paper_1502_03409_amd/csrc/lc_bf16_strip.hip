@@ -11,6 +11,8 @@
 // slow one) and transposes them in registers into NT operands of four consecutive patch values each.  A patch row
 // that is not a multiple of 16 ends in a partial block: its lanes beyond the row feed zeros as weights (the LDS
 // holds the neighbouring field's pixels there).  The weights of a whole chunk are in flight ahead of their use.
+#include <algorithm>
+
 #include "lc_common.hpp"
 
 namespace lc {
@@ -191,6 +193,31 @@ __global__ __launch_bounds__(64 * NW, NT == 4 ? 2 : 3) void lc_forward_bf16_stri
 // start four banks apart; the row keeps 16 values of padding behind the staged strip
 int strip_row_stride(int sqc) { return ((sqc + 8 + 63) / 64) * 64 + 8; }   // at least 16 values of padding
 
+// Host check of a lc_forward_bf16_strip_kernel launch.  tparam = {MT, NT, NLOC, NB, NW}; arg = {CQ, sq4, RS (bf16
+// values), batch tiles, first strip, strips in this launch, strips per field row}.
+int check_forward_bf16_strip(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], NT = p.tparam[1], NLOC = p.tparam[2], NB = p.tparam[3], NW = p.tparam[4];
+    const int CQ = p.arg[0], sq4 = p.arg[1], RS = p.arg[2], nbt = p.arg[3], first = p.arg[4], count = p.arg[5];
+    const int strips = p.arg[6];
+    LC_PLAN_REQUIRE(p, NLOC > 0 && NW % NLOC == 0 && (NT == 1 || NT == 2 || NT == 4));
+    const int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW, SC = g.S * g.C, WC = g.W * g.C, sqc = 4 * sq4;
+    LC_PLAN_REQUIRE(p, (int)p.block == NTHR);
+    // 8-byte accesses of four bf16 values: patch rows, image rows and field offsets in whole vectors
+    LC_PLAN_REQUIRE(p, g.RC % 4 == 0 && WC % 4 == 0 && SC % 4 == 0);
+    LC_PLAN_REQUIRE(p, g.F % (NFW * NT * 16) == 0 && (int)p.grid[1] == g.F / (NFW * NT * 16) && p.grid[2] == 1);
+    // chunks of CQ values in NB blocks of 16 (the last one may be partial)
+    LC_PLAN_REQUIRE(p, CQ > 0 && CQ % 4 == 0 && g.RC % CQ == 0 && NB == ceil_div(CQ, 16));
+    LC_PLAN_REQUIRE(p, sqc >= CQ + (NLOC - 1) * SC && sqc <= 0xffff && BT <= 0x3fff);
+    LC_PLAN_REQUIRE(p, (long long)BT * sq4 <= (long long)kStripSlots * NTHR);
+    // a partial last block reads up to 12 values past a field's window; 16 values behind the staged row are cleared
+    LC_PLAN_REQUIRE(p, RS % 4 == 0 && RS >= sqc + 16);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)BT * RS * sizeof(bf16_t));
+    LC_PLAN_REQUIRE(p, strips == ceil_div(g.LW, NLOC) && nbt == ceil_div(g.B, BT));
+    LC_PLAN_REQUIRE(p, first >= 0 && count >= 1 && first + count <= strips * g.LH);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == (long long)count * nbt);
+    return LC_OK;
+}
+
 template <int MT, int NT, int NB>
 int launch_strip(const Geom &g, const bf16_t *x, const bf16_t *w, const float *bias, float alpha, float *y, int CQ,
                  int work_first, int work_count, hipStream_t s) {
@@ -199,14 +226,15 @@ int launch_strip(const Geom &g, const bf16_t *x, const bf16_t *w, const float *b
     const int RS = strip_row_stride(sqc);
     const size_t lds = (size_t)BT * RS * sizeof(bf16_t);
     auto kern = lc_forward_bf16_strip_kernel<MT, NT, NLOC, NB, NW>;
-    if (int rc = allow_dynamic_lds((const void *)kern, lds, "lc_forward (bf16 strip): hipFuncSetAttribute")) return rc;
     const int strips = (g.LW + NLOC - 1) / NLOC, nbt = (g.B + BT - 1) / BT;
     const long long nwg = (long long)work_count * nbt;
     if (nwg > 0x7fffffffLL) return LC_EUNSUPPORTED;
     dim3 grid((unsigned)nwg, g.F / (NT * 16));
-    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, g, x, w, bias, alpha, y, strips, CQ, sqc / 4, RS, nbt,
-                       work_first);
-    LC_HIP_LAUNCH_CHECK("lc_forward (bf16 strip) launch");
+    const LaunchPlan plan = make_plan("lc_forward_bf16_strip", {MT, NT, NLOC, NB, NW},
+                                      {CQ, sqc / 4, RS, nbt, work_first, work_count, strips}, grid, 64 * NW, lds);
+    if (int rc = check_forward_bf16_strip(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_forward (bf16 strip) launch", kern, s, g, x, w, bias, alpha, y, strips, CQ, sqc / 4, RS, nbt,
+              work_first);
     return LC_OK;
 }
 
@@ -363,6 +391,20 @@ __global__ __launch_bounds__(256, 4) void lc_bwd_weights_bf16_rows_kernel(Geom g
             }
 }
 
+// Host check of a lc_bwd_weights_bf16_rows_kernel launch.  tparam = {G, NT, PF}; arg = {blocks of 64*G patch elements
+// per field, wave tasks}.
+int check_backward_weights_bf16_rows(const Geom &g, const LaunchPlan &p) {
+    const int G = p.tparam[0], NT = p.tparam[1], PF = p.tparam[2];
+    const int kblocks = p.arg[0], ntasks = p.arg[1];
+    LC_PLAN_REQUIRE(p, p.block == 256 && (NT == 1 || NT == 2 || NT == 4));
+    LC_PLAN_REQUIRE(p, g.RC % 4 == 0 && g.F % (NT * 16) == 0 && (int)p.grid[1] == g.F / (NT * 16) && p.grid[2] == 1);
+    LC_PLAN_REQUIRE(p, PF >= 1 && g.B % (16 * PF) == 0);
+    LC_PLAN_REQUIRE(p, kblocks == ceil_div(g.K, 64 * G) && (long long)ntasks == (long long)g.L * kblocks);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] * 4 >= ntasks && (long long)(p.grid[0] - 1) * 4 < ntasks);
+    LC_PLAN_REQUIRE(p, (long long)g.H * g.W * g.C < (1LL << 31));
+    return LC_OK;
+}
+
 template <int G, int NT, int PF>
 int launch_rows(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, float *out, hipStream_t s) {
     constexpr int KB = G * 64;
@@ -370,9 +412,10 @@ int launch_rows(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, fl
     const long long ntasks = (long long)g.L * kblocks;
     if (ntasks > (1LL << 30)) return LC_EUNSUPPORTED;
     dim3 grid((unsigned)((ntasks + 3) / 4), g.F / (NT * 16));
-    hipLaunchKernelGGL((lc_bwd_weights_bf16_rows_kernel<G, NT, PF>), grid, dim3(256), 0, s, g, x, dy, beta, out, kblocks,
-                       (int)ntasks);
-    LC_HIP_LAUNCH_CHECK("lc_backward_weights (bf16 rows) launch");
+    const LaunchPlan plan = make_plan("lc_bwd_weights_bf16_rows", {G, NT, PF}, {kblocks, (int)ntasks}, grid, 256, 0);
+    if (int rc = check_backward_weights_bf16_rows(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_weights (bf16 rows) launch", (lc_bwd_weights_bf16_rows_kernel<G, NT, PF>), s, g, x, dy,
+              beta, out, kblocks, (int)ntasks);
     return LC_OK;
 }
 
@@ -529,14 +572,33 @@ int wstrip_row_stride(const Geom &g, int sqc) {
     return ((need - 8 + 63) / 64) * 64 + 8;
 }
 
+// Host check of a lc_bwd_weights_bf16_strip_kernel launch.  tparam = {NT, NBK}; arg = {strips per field row, sq4, RS
+// (bf16 values), patch rows per workgroup}.
+int check_backward_weights_bf16_strip(const Geom &g, const LaunchPlan &p) {
+    const int NT = p.tparam[0], NBK = p.tparam[1];
+    const int strips = p.arg[0], sq4 = p.arg[1], RS = p.arg[2], rows_per_wg = p.arg[3];
+    const int SC = g.S * g.C, WC = g.W * g.C, sqc = 4 * sq4;
+    LC_PLAN_REQUIRE(p, p.block == 256 && (NT == 1 || NT == 2 || NT == 4));
+    LC_PLAN_REQUIRE(p, g.RC % 4 == 0 && SC % 4 == 0 && WC % 4 == 0 && g.B <= 128);
+    LC_PLAN_REQUIRE(p, g.F % (NT * 16) == 0 && (int)p.grid[1] == g.F / (NT * 16));
+    // a patch row in NBK blocks of 64 values; the last field's blocks read past its patch row inside the LDS row
+    LC_PLAN_REQUIRE(p, NBK * 64 >= g.RC);
+    LC_PLAN_REQUIRE(p, sqc >= g.RC + 3 * SC && sqc <= 0xffff);
+    LC_PLAN_REQUIRE(p, (long long)128 * sq4 <= (long long)kStripSlots * 256);
+    LC_PLAN_REQUIRE(p, RS % 4 == 0 && RS >= sqc && RS >= 3 * SC + 64 * ceil_div(g.RC, 64));
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= ((size_t)128 * RS + 64) * sizeof(bf16_t));
+    LC_PLAN_REQUIRE(p, strips == ceil_div(g.LW, 4) && (long long)p.grid[0] == (long long)strips * g.LH);
+    LC_PLAN_REQUIRE(p, rows_per_wg >= 1 && (long long)p.grid[2] * rows_per_wg >= g.R &&
+                           (long long)(p.grid[2] - 1) * rows_per_wg < g.R);
+    return LC_OK;
+}
+
 template <int NT, int NBK>
 int launch_wstrip(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, float *out, hipStream_t s) {
     const int sqc = (g.RC + 3 * g.S * g.C + 3) & ~3;
     const int RS = wstrip_row_stride(g, sqc);
     const size_t lds = ((size_t)128 * RS + 64) * sizeof(bf16_t);
     auto kern = lc_bwd_weights_bf16_strip_kernel<NT, NBK>;
-    if (int rc = allow_dynamic_lds((const void *)kern, lds, "lc_backward_weights (bf16 strip): hipFuncSetAttribute"))
-        return rc;
     const int strips = (g.LW + 3) / 4;
     const long long nwork = (long long)strips * g.LH;
     if (nwork > 0x7fffffffLL) return LC_EUNSUPPORTED;
@@ -545,8 +607,10 @@ int launch_wstrip(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, 
     while (zsplit < g.R && nwork * (g.F / (NT * 16)) * zsplit < 4 * 256) ++zsplit;
     const int rows_per_wg = (g.R + zsplit - 1) / zsplit;
     dim3 grid((unsigned)nwork, g.F / (NT * 16), (g.R + rows_per_wg - 1) / rows_per_wg);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, dy, beta, out, strips, sqc / 4, RS, rows_per_wg);
-    LC_HIP_LAUNCH_CHECK("lc_backward_weights (bf16 strip) launch");
+    const LaunchPlan plan = make_plan("lc_bwd_weights_bf16_strip", {NT, NBK}, {strips, sqc / 4, RS, rows_per_wg}, grid, 256, lds);
+    if (int rc = check_backward_weights_bf16_strip(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_weights (bf16 strip) launch", kern, s, g, x, dy, beta, out, strips, sqc / 4, RS,
+              rows_per_wg);
     return LC_OK;
 }
 

@@ -7,6 +7,8 @@
 // loads rows 8kk..8kk+7 of the step at filters 4n..4n+3 (16 lanes cover whole 128-byte lines) and two
 // 4x4 register transposes turn them into the k-contiguous operands of v_mfma_f32_16x16x32_bf16 for the
 // four filter tiles, in which column n of tile u is filter 4n+u.
+#include <algorithm>
+
 #include "lc_common.hpp"
 
 namespace lc {
@@ -151,17 +153,35 @@ __global__ __launch_bounds__(128 * WM, 2) void lc_forward_bf16_tiled_kernel(Geom
         }
 }
 
+// Host check of a lc_forward_bf16_tiled_kernel launch.  tparam = {MT, PD, WM}; arg = {filter blocks, batch tiles}.
+int check_forward_bf16_tiled(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], WM = p.tparam[2];
+    const int fblocks = p.arg[0], btiles = p.arg[1];
+    const int BT = 16 * MT * WM;
+    LC_PLAN_REQUIRE(p, (int)p.block == 128 * WM);
+    // 128 filters per workgroup; patch rows in whole chunks of 64 values whose starts are 16-byte aligned
+    LC_PLAN_REQUIRE(p, g.F % 128 == 0 && fblocks == g.F / 128 && g.RC % kChunk == 0);
+    LC_PLAN_REQUIRE(p, (g.S * g.C) % 8 == 0 && (g.W * g.C) % 8 == 0);
+    // the staging map: tid >> 3 covers 16*WM image rows per slot, MT slots
+    LC_PLAN_REQUIRE(p, btiles == ceil_div(g.B, BT));
+    LC_PLAN_REQUIRE(p, (long long)g.B * g.H * g.W * g.C < (1LL << 31));
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == (long long)g.L * fblocks * btiles && p.grid[1] == 1 && p.grid[2] == 1);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)2 * BT * kRowBytes);
+    return LC_OK;
+}
+
 template <int MT, int PD, int WM>
 int launch_tiled(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                  hipStream_t s) {
     constexpr int BT = 16 * MT * WM;
     const size_t lds = (size_t)2 * BT * kRowBytes;
     auto kern = lc_forward_bf16_tiled_kernel<MT, PD, WM>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward (bf16): hipFuncSetAttribute")) return rc_lds;
     const int fblocks = g.F / 128, btiles = (g.B + BT - 1) / BT;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(g.L * fblocks * btiles)), dim3(128 * WM), lds, s, g,
-                       (const unsigned short *)x, (const unsigned short *)w, bias, alpha, y, fblocks, btiles);
-    LC_HIP_LAUNCH_CHECK("lc_forward (bf16, tiled) launch");
+    const LaunchPlan plan = make_plan("lc_forward_bf16_tiled", {MT, PD, WM}, {fblocks, btiles},
+                                      dim3((unsigned)(g.L * fblocks * btiles)), 128 * WM, lds);
+    if (int rc = check_forward_bf16_tiled(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_forward (bf16, tiled) launch", kern, s, g, (const unsigned short *)x, (const unsigned short *)w,
+              bias, alpha, y, fblocks, btiles);
     return LC_OK;
 }
 
@@ -307,17 +327,34 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_data_bf16_tiled_kernel(Geom g, 
     }
 }
 
+// Host check of a lc_bwd_data_bf16_tiled_kernel launch.  tparam = {MT, PD}; arg = {cells per row, 128-value blocks per
+// cell, batch tiles}.
+int check_backward_data_bf16_tiled(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0];
+    const int CW = p.arg[0], nblk = p.arg[1], btiles = p.arg[2];
+    const int BT = 32 * MT;
+    LC_PLAN_REQUIRE(p, p.block == 256);
+    LC_PLAN_REQUIRE(p, g.R % g.S == 0 && g.F % kChunk == 0 && (g.S * g.S * g.C) % 128 == 0);
+    LC_PLAN_REQUIRE(p, nblk == g.S * g.S * g.C / 128 && CW == ceil_div(g.W, g.S) && btiles == ceil_div(g.B, BT));
+    LC_PLAN_REQUIRE(p, (long long)g.B * g.L * g.F < (1LL << 31) && (long long)g.K * g.F < (1LL << 31));
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == (long long)ceil_div(g.H, g.S) * CW * nblk * btiles && p.grid[1] == 1 &&
+                           p.grid[2] == 1);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)2 * BT * kRowBytes);
+    return LC_OK;
+}
+
 template <int MT, int PD>
 int launch_bwd_data_tiled(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s) {
     constexpr int BT = 32 * MT;
     const size_t lds = (size_t)2 * BT * kRowBytes;
     auto kern = lc_bwd_data_bf16_tiled_kernel<MT, PD>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_data (bf16): hipFuncSetAttribute")) return rc_lds;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int nblk = g.S * g.S * g.C / 128, btiles = (g.B + BT - 1) / BT;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(CH * CW * nblk * btiles)), dim3(256), lds, s, g,
-                       (const unsigned short *)dy, (const unsigned short *)w, dx, CW, nblk, btiles);
-    LC_HIP_LAUNCH_CHECK("lc_backward_data (bf16, tiled) launch");
+    const LaunchPlan plan = make_plan("lc_bwd_data_bf16_tiled", {MT, PD}, {CW, nblk, btiles},
+                                      dim3((unsigned)(CH * CW * nblk * btiles)), 256, lds);
+    if (int rc = check_backward_data_bf16_tiled(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_data (bf16, tiled) launch", kern, s, g, (const unsigned short *)dy,
+              (const unsigned short *)w, dx, CW, nblk, btiles);
     return LC_OK;
 }
 
@@ -427,13 +464,31 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_weights_bf16_tiled_kernel(Geom 
     }
 }
 
+// Host check of a lc_bwd_weights_bf16_tiled_kernel launch.  tparam = {RING}; arg = {filter blocks, workgroups per
+// (field, filter block), steps of 32 images, LDS row bytes}.
+int check_backward_weights_bf16_tiled(const Geom &g, const LaunchPlan &p) {
+    const int RING = p.tparam[0];
+    const int fblocks = p.arg[0], ksplit = p.arg[1], nst = p.arg[2], rowb = p.arg[3];
+    LC_PLAN_REQUIRE(p, p.block == 256);
+    // 64-row blocks inside one patch row; 8-byte patch vectors; 128 filters per workgroup
+    LC_PLAN_REQUIRE(p, g.RC % 64 == 0 && (g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0);
+    LC_PLAN_REQUIRE(p, g.F % 128 == 0 && fblocks == g.F / 128);
+    // the batch in whole ring turns of 32-image steps, all of it transposed into LDS
+    LC_PLAN_REQUIRE(p, RING >= 1 && nst % RING == 0 && nst * 32 >= g.B && rowb >= nst * 64 && rowb % 16 == 0);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)128 * rowb);
+    // every wave of a workgroup has at least one row block
+    LC_PLAN_REQUIRE(p, ksplit >= 1 && ksplit * 4 <= std::max(g.K / 64, 4));
+    LC_PLAN_REQUIRE(p, (long long)g.B * g.H * g.W * g.C < (1LL << 31));
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == (long long)g.L * fblocks * ksplit && p.grid[1] == 1 && p.grid[2] == 1);
+    return LC_OK;
+}
+
 template <int RING>
 int launch_bwd_weights_tiled(const Geom &g, const void *x, const void *dy, float beta, float *dw, hipStream_t s) {
     const int nst = ((g.B + 31) / 32 + RING - 1) / RING * RING;
     const int rowb = nst * 64 + 16;
     const size_t lds = (size_t)128 * rowb;
     auto kern = lc_bwd_weights_bf16_tiled_kernel<RING>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_backward_weights (bf16): hipFuncSetAttribute")) return rc_lds;
     // split the row blocks of a field over 1..4 workgroups, whichever fills whole rounds of the chip best
     const int fblocks = g.F / 128, nkb = g.K / 64;
     const long long base = (long long)g.L * fblocks, slots = 512;
@@ -444,9 +499,11 @@ int launch_bwd_weights_tiled(const Geom &g, const void *x, const void *dy, float
         const double eff = (double)tasks / (double)(rounds * slots);
         if (eff > best + 0.02) { best = eff; ksplit = ks; }
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(base * ksplit)), dim3(256), lds, s, g, (const unsigned short *)x,
-                       (const unsigned short *)dy, beta, dw, fblocks, ksplit, nst, rowb);
-    LC_HIP_LAUNCH_CHECK("lc_backward_weights (bf16, tiled) launch");
+    const LaunchPlan plan = make_plan("lc_bwd_weights_bf16_tiled", {RING}, {fblocks, ksplit, nst, rowb},
+                                      dim3((unsigned)(base * ksplit)), 256, lds);
+    if (int rc = check_backward_weights_bf16_tiled(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_weights (bf16, tiled) launch", kern, s, g, (const unsigned short *)x,
+              (const unsigned short *)dy, beta, dw, fblocks, ksplit, nst, rowb);
     return LC_OK;
 }
 

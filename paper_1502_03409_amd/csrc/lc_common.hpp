@@ -4,7 +4,10 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <initializer_list>
+
 #include "../../include/lc.h"
+#include "../../include/lc_plan.h"
 
 namespace lc {
 
@@ -89,6 +92,12 @@ __device__ __forceinline__ float raw_get(const typename RawVec<T, N>::V &v, int 
         return (i & 1) ? bf16_hi(v[i >> 1]) : bf16_lo(v[i >> 1]);
     }
 }
+// one stored element as fp32
+template <typename T>
+__device__ __forceinline__ float ld_f32(const T *p) {
+    if constexpr (sizeof(T) == 4) return *p;
+    else return bf16_lo(*p);
+}
 template <typename T>
 __device__ __forceinline__ f32x4 raw_widen4(const typename RawVec<T, 4>::V &v) {
     if constexpr (sizeof(T) == 4) return v;
@@ -104,6 +113,46 @@ __device__ __forceinline__ f32x4 mfma16_bf16(u32x2 a, u32x2 b, f32x4 c) {
 }
 
 void set_hip_error(hipError_t e, const char *where);
+void set_error_text(const char *text);
+
+// ---------------------------------------------------------------------------------------------
+// Launch plans.  A launcher writes the launch down first (LaunchPlan), runs the host check that belongs to
+// the kernel family (check_* next to each kernel: the tiles cover the problem exactly once, a chunk fits the
+// staging registers and the LDS, clamped addresses stay inside the tensors) and then goes through LC_LAUNCH,
+// which applies the limits every launch has, and either launches or, inside lc_plan_query, keeps the record.
+typedef lc_launch_t LaunchPlan;
+
+LaunchPlan make_plan(const char *kernel, std::initializer_list<int> tparam, std::initializer_list<int> arg, dim3 grid,
+                     unsigned block, size_t lds_bytes);
+// grid, block and LDS limits of the device; LC_OK or LC_EINTERNAL
+int check_launch_shape(const LaunchPlan &p);
+// records "<kernel>: <what>" as the thread's last error and returns LC_EINTERNAL
+int plan_fail(const LaunchPlan &p, const char *what);
+bool plan_capture();                          // true on a thread that is inside lc_plan_query
+void plan_capture_add(const LaunchPlan &p);
+
+#define LC_PLAN_REQUIRE(p, cond)                                  \
+    do {                                                          \
+        if (!(cond)) return lc::plan_fail(p, #cond);              \
+    } while (0)
+
+// Launch `kern` as planned in `plan` (or only record the plan).  `where` names the launch in error messages.
+#define LC_LAUNCH(plan, where, kern, stream, ...)                                                              \
+    do {                                                                                                       \
+        if (int rc_shape__ = lc::check_launch_shape(plan)) return rc_shape__;                                  \
+        if (lc::plan_capture()) {                                                                              \
+            lc::plan_capture_add(plan);                                                                        \
+            break;                                                                                             \
+        }                                                                                                      \
+        if (int rc_lds__ = lc::allow_dynamic_lds((const void *)(kern), (size_t)(plan).lds_bytes, where))       \
+            return rc_lds__;                                                                                   \
+        hipLaunchKernelGGL(kern, dim3((plan).grid[0], (plan).grid[1], (plan).grid[2]), dim3((plan).block),     \
+                           (size_t)(plan).lds_bytes, stream, __VA_ARGS__);                                     \
+        LC_HIP_LAUNCH_CHECK(where);                                                                            \
+    } while (0)
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
 // raises a kernel's dynamic LDS limit when `bytes` needs it (once per kernel and device); LC_OK or LC_EHIP
 int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where);
 
@@ -160,8 +209,9 @@ int launch_backward_data_wide_f32(const Geom &g, const float *dy, const float *w
 int launch_forward_bf16(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                         hipStream_t s);
 int launch_backward_data_bf16(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s);
-// bf16 storage through the fp32 pipelined kernels (operands widened on the way in, fp32 MFMAs): the aligned shapes
-// of those kernels; LC_EUNSUPPORTED otherwise
+// bf16 storage through the fp32 kernels' structure: the pipelined kernels for the aligned shapes (bf16 MFMAs in the
+// backward-data pass, operands widened on the way in elsewhere), the masked kernels for every other shape
+bool backward_data_bf16_pipelined_supported(const Geom &g);
 int launch_forward_bf16_storage(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                                 hipStream_t s);
 int launch_backward_data_bf16_storage(const Geom &g, const void *dy, const void *w, float *dx, hipStream_t s);
@@ -189,8 +239,12 @@ size_t sae_workspace_bytes(const Geom &g);
 int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
                     float lr, uint32_t flags, float *h_out, float *cost_out, void *ws, hipStream_t s);
 int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s);
-// out[l,k,f] = beta*out + gamma * sum over pairs p of sum_b patch(x_p)[b,l,k] * dy_p[b,l,f]; x2/dy2 may be NULL
+// out[l,k,f] = beta*out + gamma * sum over pairs p of sum_b patch(x_p)[b,l,k] * dy_p[b,l,f]; x2/dy2 may be NULL.
+// ssq (nullable): receives, per location, block of patch elements and filter, the sum of squares of the values
+// stored, as [L][*kblocks_out][F] floats; at most backward_weights_max_kblocks(g) blocks per location.
 int launch_backward_weights_f32(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2,
-                                float beta, float gamma, float *out, hipStream_t s);
+                                float beta, float gamma, float *out, hipStream_t s, float *ssq = nullptr,
+                                int *kblocks_out = nullptr);
+inline int backward_weights_max_kblocks(const Geom &g) { return (g.K + 63) / 64; }   // the smallest block is 64 rows
 
 }  // namespace lc

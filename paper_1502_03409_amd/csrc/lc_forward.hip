@@ -12,9 +12,9 @@
 
 namespace lc {
 
-template <int MT, int NT, int NLOC, bool MASK>
+template <int MT, int NT, int NLOC, bool MASK, typename T>
 __device__ __forceinline__ void fwd_row(f32x4 (&acc)[MT][NT], const float *__restrict__ xs_win, int rs,
-                                        const float *__restrict__ wrow, int F, int RC, int kk, bool (&fok)[NT]) {
+                                        const T *__restrict__ wrow, int F, int RC, int kk, bool (&fok)[NT]) {
     const int lane_m = threadIdx.x & 15;
 #pragma unroll 2
     for (int kq = 0; kq < RC; kq += 4) {
@@ -23,9 +23,9 @@ __device__ __forceinline__ void fwd_row(f32x4 (&acc)[MT][NT], const float *__res
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             if (MASK)
-                bw[nt] = (kok && fok[nt]) ? wrow[(size_t)kq * F + nt * 16] : 0.f;
+                bw[nt] = (kok && fok[nt]) ? ld_f32(wrow + (size_t)kq * F + nt * 16) : 0.f;
             else
-                bw[nt] = wrow[(size_t)kq * F + nt * 16];
+                bw[nt] = ld_f32(wrow + (size_t)kq * F + nt * 16);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -39,9 +39,10 @@ __device__ __forceinline__ void fwd_row(f32x4 (&acc)[MT][NT], const float *__res
     }
 }
 
-template <int MT, int NT, int NLOC>
-__global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const float *__restrict__ x,
-                                                         const float *__restrict__ w,
+// T: storage type of x and w (float, or bf16 bit patterns widened on their way in)
+template <int MT, int NT, int NLOC, typename T>
+__global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const T *__restrict__ x,
+                                                         const T *__restrict__ w,
                                                          const float *__restrict__ bias, float alpha,
                                                          const float *__restrict__ alpha_dev,
                                                          float *__restrict__ y, int strips_per_row, int sq, int rs) {
@@ -74,17 +75,17 @@ __global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const float *__
     const int col0 = j0 * g.S * g.C;                       // first float of the strip inside an image row
     const int nvalid = min(sq, g.W * g.C - col0);          // strip floats that exist in the image
     const size_t img = (size_t)g.H * g.W * g.C;
-    const float *wl_base = w + (size_t)loc * g.K * g.F + f0 + n;
+    const T *wl_base = w + (size_t)loc * g.K * g.F + f0 + n;
     const float *xs_win = xs + wl * g.S * g.C + kk;
 
     for (int kh = 0; kh < g.R; ++kh) {
         __syncthreads();
         {
-            const float *xrow = x + (size_t)(i * g.S + kh) * g.W * g.C + col0;
+            const T *xrow = x + (size_t)(i * g.S + kh) * g.W * g.C + col0;
             int q = q_first, bb = b_first;
             while (bb < BT) {
                 float v = 0.f;
-                if (q < nvalid && b0 + bb < g.B) v = xrow[(size_t)(b0 + bb) * img + q];
+                if (q < nvalid && b0 + bb < g.B) v = ld_f32(xrow + (size_t)(b0 + bb) * img + q);
                 xs[bb * rs + q] = v;
                 q += dq;
                 bb += db;
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(256) void lc_forward_kernel(Geom g, const float *__
         }
         __syncthreads();
         if (active) {
-            const float *wrow = wl_base + (size_t)(kh * g.RC + kk) * g.F;
+            const T *wrow = wl_base + (size_t)(kh * g.RC + kk) * g.F;
             if (need_mask)
                 fwd_row<MT, NT, NLOC, true>(acc, xs_win, rs, wrow, g.F, g.RC, kk, fok);
             else
@@ -366,8 +367,27 @@ int lds_row_stride(int sq) {
     return rs;
 }
 
-template <int MT, int NT, int NLOC>
-int launch_one(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+// Host check of a lc_forward_kernel launch.  tparam = {MT, NT, NLOC, bytes per operand element}; arg = {strips per field row, staged floats
+// per image (sq), LDS row stride (rs)}.  The kernel masks every ragged edge itself, so what has to hold is that
+// the grid covers (strip, filter block, batch tile) and that a staged strip row fits its LDS row.
+int check_forward_generic(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], NT = p.tparam[1], NLOC = p.tparam[2];
+    const int strips = p.arg[0], sq = p.arg[1], rs = p.arg[2];
+    const int BT = 16 * MT, NFW = 4 / NLOC;
+    LC_PLAN_REQUIRE(p, NLOC == 1 || NLOC == 2 || NLOC == 4);
+    LC_PLAN_REQUIRE(p, p.block == 256);
+    LC_PLAN_REQUIRE(p, strips == ceil_div(g.LW, NLOC) && (long long)p.grid[0] == (long long)strips * g.LH);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[1] * NFW * NT * 16 >= g.F && (long long)(p.grid[1] - 1) * NFW * NT * 16 < g.F);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[2] * BT >= g.B && (long long)(p.grid[2] - 1) * BT < g.B);
+    LC_PLAN_REQUIRE(p, sq == (g.R + (NLOC - 1) * g.S) * g.C);
+    // a wave reads up to 3 floats past its window's last whole 4-element step
+    LC_PLAN_REQUIRE(p, rs >= sq + 3);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)BT * rs * sizeof(float));
+    return LC_OK;
+}
+
+template <int MT, int NT, int NLOC, typename T>
+int launch_one(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                const float *alpha_dev, float *y, hipStream_t s) {
     constexpr int BT = 16 * MT, NFW = 4 / NLOC;
     const int strips = (g.LW + NLOC - 1) / NLOC;
@@ -375,11 +395,11 @@ int launch_one(const Geom &g, const float *x, const float *w, const float *bias,
     const int rs = lds_row_stride(sq);
     const size_t lds = ((size_t)BT * rs + 8) * sizeof(float);
     if (lds > 160 * 1024) return LC_EUNSUPPORTED;
-    auto kern = lc_forward_kernel<MT, NT, NLOC>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward: hipFuncSetAttribute")) return rc_lds;
+    auto kern = lc_forward_kernel<MT, NT, NLOC, T>;
     dim3 grid(strips * g.LH, (g.F + NFW * NT * 16 - 1) / (NFW * NT * 16), (g.B + BT - 1) / BT);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, sq, rs);
-    LC_HIP_LAUNCH_CHECK("lc_forward launch");
+    const LaunchPlan plan = make_plan("lc_forward_generic", {MT, NT, NLOC, (int)sizeof(T)}, {strips, sq, rs}, grid, 256, lds);
+    if (int rc = check_forward_generic(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_forward launch", kern, s, g, x, w, bias, alpha, alpha_dev, y, strips, sq, rs);
     return LC_OK;
 }
 
@@ -392,21 +412,64 @@ int fast_row_stride(int sqc) {
     return ((sqc + 31) / 32) * 32 + 4;
 }
 
+// Host check of a lc_forward_fast_kernel launch.
+// tparam = {MT, NT, NLOC, UNR, NW, bytes per operand element, SPC, NRT, staging slots per lane};
+// arg = {CQ, sq4, RS, NR, first strip, strips in this launch, batch tiles, strips per field row}.
+int check_forward_fast(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], NT = p.tparam[1], NLOC = p.tparam[2], UNR = p.tparam[3], NW = p.tparam[4];
+    const int ES = p.tparam[5], SPC = p.tparam[6], NRT = p.tparam[7], SLOTS = p.tparam[8];
+    const int CQ = p.arg[0], sq4 = p.arg[1], RS = p.arg[2], NR = p.arg[3], first = p.arg[4], count = p.arg[5];
+    const int nbt = p.arg[6], strips = p.arg[7];
+    LC_PLAN_REQUIRE(p, NLOC > 0 && NW % NLOC == 0 && (ES == 4 || ES == 2) && (NT == 1 || NT == 2 || NT == 4));
+    const int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW, SC = g.S * g.C, WC = g.W * g.C, sqc = 4 * sq4;
+    LC_PLAN_REQUIRE(p, (int)p.block == NTHR);
+    // four-element vector accesses: patch rows, image rows and strip starts in whole vectors
+    LC_PLAN_REQUIRE(p, g.RC % 4 == 0 && WC % 4 == 0 && (NLOC * SC) % 4 == 0);
+    // filters in whole tiles, every block of filters exactly once
+    LC_PLAN_REQUIRE(p, g.F % (NFW * NT * 16) == 0 && (int)p.grid[1] == g.F / (NFW * NT * 16) && p.grid[2] == 1);
+    // the contraction: chunks of CQ floats of a patch row in ring turns of UNR k-steps; several patch rows per chunk
+    // only as whole rows
+    LC_PLAN_REQUIRE(p, CQ > 0 && CQ % (4 * UNR) == 0 && g.RC % CQ == 0);
+    LC_PLAN_REQUIRE(p, NR >= 1 && NR <= 15 && g.R % NR == 0 && (NR == 1 || CQ == g.RC));
+    LC_PLAN_REQUIRE(p, g.K / 4 >= UNR);
+    // the staged strip: covers every field's window, fits the packed slot index, the staging registers and its LDS row
+    LC_PLAN_REQUIRE(p, sqc >= CQ + (NLOC - 1) * SC && sqc <= 4096 && BT <= 0x3fff);
+    LC_PLAN_REQUIRE(p, (long long)BT * NR * sq4 <= (long long)SLOTS * NTHR);
+    LC_PLAN_REQUIRE(p, RS % 2 == 0 && RS >= NR * sqc + 2);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)BT * RS * sizeof(float));
+    // the strips of this launch, each with every batch tile
+    LC_PLAN_REQUIRE(p, strips == ceil_div(g.LW, NLOC) && nbt == ceil_div(g.B, BT));
+    LC_PLAN_REQUIRE(p, first >= 0 && count >= 1 && first + count <= strips * g.LH);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == (long long)count * nbt);
+    if (SPC > 0) {
+        // compile-time counts: one chunk = NRT whole patch rows of SPC k-steps, fp32 only, 32-bit staging offsets;
+        // every slot loads from an address clamped into the image, which needs four floats from every strip's start
+        LC_PLAN_REQUIRE(p, ES == 4 && CQ == g.RC && SPC == CQ / 4 && NRT == NR && SPC % UNR == 0);
+        LC_PLAN_REQUIRE(p, (long long)g.B * g.H * g.W * g.C < (1LL << 31));
+        LC_PLAN_REQUIRE(p, WC - (strips - 1) * NLOC * SC >= 4);
+    } else {
+        LC_PLAN_REQUIRE(p, NRT == 1);
+    }
+    return LC_OK;
+}
+
 template <int MT, int NT, int NLOC, int UNR, int NW = 4, int SPC = 0, int NRT = 1, int NSL = 0, typename T>
 int launch_fast(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
                 const float *alpha_dev, float *y, int CQ, int NR, int work_first, int work_count, hipStream_t s) {
     constexpr int BT = 16 * MT, NFW = NW / NLOC;
+    constexpr int SLOTS = NSL > 0 ? NSL : (NW == 8 ? kFwdStageSlotsWide : kFwdStageSlots);   // as in the kernel
     const int sqc = (CQ + (NLOC - 1) * g.S * g.C + 3) & ~3;   // staged floats per image and patch row
     const int RS = fast_row_stride(NR * sqc);
     const size_t lds = (size_t)BT * RS * sizeof(float);
     auto kern = lc_forward_fast_kernel<MT, NT, NLOC, UNR, NW, T, SPC, NRT, NSL>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward: hipFuncSetAttribute")) return rc_lds;
     const int strips = (g.LW + NLOC - 1) / NLOC;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(work_count * nbt, g.F / (NFW * NT * 16));
-    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS, NR,
-                       work_first, nbt);
-    LC_HIP_LAUNCH_CHECK("lc_forward launch");
+    const LaunchPlan plan = make_plan("lc_forward_fast", {MT, NT, NLOC, UNR, NW, (int)sizeof(T), SPC, NRT, SLOTS},
+                                      {CQ, sqc / 4, RS, NR, work_first, work_count, nbt, strips}, grid, 64 * NW, lds);
+    if (int rc = check_forward_fast(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_forward launch", kern, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS, NR,
+              work_first, nbt);
     return LC_OK;
 }
 
@@ -584,7 +647,8 @@ int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float 
         while (fast_workgroups(g, mt, nt) < kComputeUnits * kBigTilesPerCu && (mt > 2 || nt > 1)) {
             if (nt > 1 && (nt >= mt || mt == 2)) nt >>= 1; else mt >>= 1;
         }
-        const bool one_tile = g.F % 32 != 0 || nt == 1;
+        // the eight-wave kernel's grid covers F in whole tiles of 16 filters; other F take the masked kernel below
+        const bool one_tile = g.F % 16 == 0 && (g.F % 32 != 0 || nt == 1);
         if (mt == 8 && one_tile && g.LW >= 8 && (8 * g.S * g.C) % 4 == 0)
             rc = launch_fast_wide(g, x, w, bias, alpha, alpha_dev, y, s, &done);
         if (!done && mt == 8) rc = launch_fast_mt<8>(g, x, w, bias, alpha, alpha_dev, y, s, &done, nt);
@@ -598,19 +662,13 @@ int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float 
 
 }  // namespace
 
-int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
-                       const float *alpha_dev, float *y, hipStream_t s, void *ws, size_t ws_bytes) {
-    // aligned shapes take the pipelined kernel: patch rows that are whole dwordx4 runs, strips that start on a
-    // 16-byte boundary (4 fields x S x C floats, or 2 when 128 filters are split over the waves)
-    // layers with 128-filter blocks: one field per workgroup, patches through LDS, 128 x 128 output tiles
-    if (forward_wide_supported(g)) return launch_forward_wide_f32(g, x, w, bias, alpha, alpha_dev, y, ws, ws_bytes, s);
-    {
-        bool done = false;
-        const int rc = launch_forward_fast_path(g, x, w, bias, alpha, alpha_dev, y, s, &done);
-        if (done) return rc;
-    }
-    // Pick the tile: as many images per wave as the batch offers (weights are re-read once per batch
-    // tile), then as many filters as fit the accumulator budget, then the widest strip that fits LDS.
+namespace {
+
+// The masked kernel (any shape).  Picks the tile: as many images per wave as the batch offers (weights are re-read
+// once per batch tile), then as many filters as fit the accumulator budget, then the widest strip that fits LDS.
+template <typename T>
+int launch_forward_generic(const Geom &g, const T *x, const T *w, const float *bias, float alpha,
+                           const float *alpha_dev, float *y, hipStream_t s) {
     const int mt = g.B > 64 ? 8 : g.B > 32 ? 4 : g.B > 16 ? 2 : 1;
     const int ft = (g.F + 15) / 16;  // filter tiles
     auto strip_bytes = [&](int nloc, int MT) {
@@ -643,11 +701,28 @@ int launch_forward_f32(const Geom &g, const float *x, const float *w, const floa
 #undef LC_TRY
 }
 
+}  // namespace
+
+int launch_forward_f32(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                       const float *alpha_dev, float *y, hipStream_t s, void *ws, size_t ws_bytes) {
+    // layers with 128-filter blocks: one field per workgroup, patches through LDS, 128 x 128 output tiles
+    if (forward_wide_supported(g)) return launch_forward_wide_f32(g, x, w, bias, alpha, alpha_dev, y, ws, ws_bytes, s);
+    // aligned shapes take the pipelined kernel: patch rows that are whole dwordx4 runs, strips that start on a
+    // 16-byte boundary (4 fields x S x C floats, or 2 when 128 filters are split over the waves)
+    {
+        bool done = false;
+        const int rc = launch_forward_fast_path(g, x, w, bias, alpha, alpha_dev, y, s, &done);
+        if (done) return rc;
+    }
+    return launch_forward_generic(g, x, w, bias, alpha, alpha_dev, y, s);
+}
+
 int launch_forward_bf16_storage(const Geom &g, const void *x, const void *w, const float *bias, float alpha, float *y,
                                 hipStream_t s) {
     bool done = false;
     const int rc = launch_forward_fast_path(g, (const bf16_t *)x, (const bf16_t *)w, bias, alpha, nullptr, y, s, &done);
-    return done ? rc : LC_EUNSUPPORTED;
+    if (done) return rc;
+    return launch_forward_generic(g, (const bf16_t *)x, (const bf16_t *)w, bias, alpha, nullptr, y, s);
 }
 
 }  // namespace lc

@@ -180,23 +180,46 @@ int wide_slices(const Geom &g) {
     return ns < 2 ? 1 : ns;
 }
 
+// Host check of a lc_forward_wide_kernel launch.  tparam = {MT, PD, KCH}; arg = {filter blocks, batch tiles, slices}.
+int check_forward_wide(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], KCH = p.tparam[2];
+    const int fblocks = p.arg[0], btiles = p.arg[1], nslices = p.arg[2];
+    const int BT = 32 * MT, SEGS = KCH / 4, SR = 256 / SEGS;
+    LC_PLAN_REQUIRE(p, p.block == 256 && (KCH == 32 || KCH == 16));
+    // 128 filters per workgroup; patch rows in whole chunks whose starts are 16-byte aligned in every image row
+    LC_PLAN_REQUIRE(p, g.F % 128 == 0 && fblocks == g.F / 128);
+    LC_PLAN_REQUIRE(p, g.RC % KCH == 0 && (g.S * g.C) % 4 == 0 && (g.W * g.C) % 4 == 0);
+    // the staging map: 256 threads move SR image rows per slot, BT / SR whole slots
+    LC_PLAN_REQUIRE(p, BT % SR == 0 && BT / SR >= 1);
+    LC_PLAN_REQUIRE(p, btiles == ceil_div(g.B, BT));
+    // 32-bit element offsets of x
+    LC_PLAN_REQUIRE(p, (long long)g.B * g.H * g.W * g.C < (1LL << 31));
+    const int nchunks = g.R * (g.RC / KCH);
+    LC_PLAN_REQUIRE(p, nslices >= 1 && nslices <= nchunks);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == (long long)g.L * fblocks * btiles * nslices && p.grid[1] == 1 &&
+                           p.grid[2] == 1);
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)2 * BT * (KCH + 4) * sizeof(float));
+    return LC_OK;
+}
+
 template <int KCH, int MT = 4>
 int launch_wide(const Geom &g, const float *x, const float *w, const float *bias, float alpha, const float *alpha_dev,
                 float *y, float *partial, int nslices, hipStream_t s) {
     constexpr int PD = 2, BT = 32 * MT;
     const size_t lds = (size_t)2 * BT * (KCH + 4) * sizeof(float);
     auto kern = lc_forward_wide_kernel<MT, PD, KCH>;
-    if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lc_forward (wide): hipFuncSetAttribute")) return rc_lds;
     const int fblocks = g.F / 128, btiles = (g.B + BT - 1) / BT;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(g.L * fblocks * btiles * nslices)), dim3(256), lds, s, g, x, w, bias, alpha,
-                       alpha_dev, y, partial, fblocks, btiles, nslices);
-    LC_HIP_LAUNCH_CHECK("lc_forward (wide) launch");
+    const LaunchPlan plan = make_plan("lc_forward_wide", {MT, PD, KCH}, {fblocks, btiles, nslices},
+                                      dim3((unsigned)(g.L * fblocks * btiles * nslices)), 256, lds);
+    if (int rc = check_forward_wide(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_forward (wide) launch", kern, s, g, x, w, bias, alpha, alpha_dev, y, partial, fblocks, btiles,
+              nslices);
     if (nslices > 1) {
         const size_t n4 = (size_t)g.B * g.L * g.F / 4;
         const unsigned blocks = (unsigned)std::min<size_t>((n4 + 255) / 256, 256 * 16);
-        hipLaunchKernelGGL(lc_forward_slices_kernel, dim3(blocks), dim3(256), 0, s, partial, nslices, n4, g.L * g.F / 4,
-                           bias, alpha, alpha_dev, y);
-        LC_HIP_LAUNCH_CHECK("lc_forward (slices) launch");
+        const LaunchPlan sum = make_plan("lc_forward_slices", {}, {nslices}, dim3(blocks), 256, 0);
+        LC_LAUNCH(sum, "lc_forward (slices) launch", lc_forward_slices_kernel, s, partial, nslices, n4, g.L * g.F / 4,
+                  bias, alpha, alpha_dev, y);
     }
     return LC_OK;
 }

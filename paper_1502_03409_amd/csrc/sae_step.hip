@@ -134,28 +134,35 @@ __global__ __launch_bounds__(256) void sae_finalize_kernel(const float *__restri
     }
 }
 
-// Rescale every filter w[l,:,f] to unit Euclidean norm (the constraint of Eq. 1).  One workgroup per
-// location; filters are handled in blocks of FB = min(F,256) columns, 256/FB threads per column.
-__global__ __launch_bounds__(256) void sae_project_kernel(float *__restrict__ w, int K, int F) {
-    __shared__ float part[256];
-    extern __shared__ float inv[];  // F floats
-    float *wl = w + (size_t)blockIdx.x * K * F;
-    const int FB = F < 256 ? F : 256, KG = 256 / FB;
-    const int fl = threadIdx.x % FB, kg = threadIdx.x / FB;
-    for (int f0 = 0; f0 < F; f0 += FB) {
-        float s = 0.f;
-        if (kg < KG && f0 + fl < F)
-            for (int k = kg; k < K; k += KG) { const float v = wl[(size_t)k * F + f0 + fl]; s += v * v; }
-        part[threadIdx.x] = s;
-        __syncthreads();
-        if (threadIdx.x < FB && f0 + threadIdx.x < F) {
-            float t = 0.f;
-            for (int q = 0; q < KG; ++q) t += part[q * FB + threadIdx.x];
-            inv[f0 + threadIdx.x] = 1.0f / sqrtf(t);
-        }
-        __syncthreads();
+// Projection onto the constraint of Eq. 1 (every filter w[l,:,f] of unit Euclidean norm) in two small passes behind
+// the fused update, whose epilogue already left per-block sums of squares of the updated weights:
+//   inv[l,f] = 1 / sqrt(sum over the k blocks of ssq[l,kb,f])   (fixed order: deterministic);
+//   w[l,k,f] *= inv[l,f]                                         (one read and one write of w, any number of fields).
+// A filter that is all zeros has no direction: it is left as it is (inv = 0 avoids 0 * inf).
+__global__ __launch_bounds__(256) void sae_row_norm_kernel(const float *__restrict__ ssq, int kblocks, int F,
+                                                           long long LF, float *__restrict__ inv) {
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;     // e = l * F + f
+    if (e >= LF) return;
+    const long long l = e / F;
+    const int f = (int)(e - l * F);
+    const float *p = ssq + (size_t)l * kblocks * F + f;
+    float t = 0.f;
+    for (int kb = 0; kb < kblocks; ++kb) t += p[(size_t)kb * F];
+    inv[e] = t > 0.f ? 1.0f / sqrtf(t) : 0.f;
+}
+
+template <int V>
+__global__ __launch_bounds__(256) void sae_rescale_kernel(float *__restrict__ w, const float *__restrict__ inv, int F,
+                                                          long long KF, long long n) {
+    typedef typename FVec<V>::T VT;
+    const long long nv = n / V;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < nv; e += (long long)gridDim.x * 256) {
+        const long long o = e * V, l = o / KF;
+        const int f = (int)(o % F);
+        VT v = ((const VT *)w)[e];
+        const VT s = *(const VT *)(inv + l * F + f);
+        ((VT *)w)[e] = v * s;
     }
-    for (int e = threadIdx.x; e < K * F; e += 256) wl[e] *= inv[e % F];
 }
 
 }  // namespace
@@ -169,7 +176,11 @@ size_t sae_workspace_bytes(const Geom &g) {
     const size_t nh = (size_t)g.B * g.L * g.F, nx = (size_t)g.B * g.H * g.W * g.C;
     const size_t img = (size_t)g.H * g.W * g.C;
     return 2 * align256(nh * 4) + align256(nx * 4) + align256(kBatchChunks * img * 4) +
-           3 * align256(kPartialsMax * 4);
+           3 * align256(kPartialsMax * 4) +
+           // projection: per-block sums of squares of the updated weights, and the filters' inverse norms
+           align256((size_t)g.L * backward_weights_max_kblocks(g) * g.F * 4) + align256((size_t)g.L * g.F * 4) +
+           // the slices of lc_forward on a layer with very few fields (0 otherwise)
+           align256(forward_wide_workspace_bytes(g));
 }
 
 int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *alpha, float lambda, float eps_sparse,
@@ -183,42 +194,62 @@ int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *al
     float *dbp = (float *)p;  p += align256((size_t)kBatchChunks * img * 4);
     float *part_r = (float *)p; p += align256(kPartialsMax * 4);
     float *part_s = (float *)p; p += align256(kPartialsMax * 4);
-    float *part_hg = (float *)p;
+    float *part_hg = (float *)p; p += align256(kPartialsMax * 4);
+    float *ssq = (float *)p;  p += align256((size_t)g.L * backward_weights_max_kblocks(g) * g.F * 4);
+    float *inv = (float *)p;  p += align256((size_t)g.L * g.F * 4);
+    void *fwd_ws = p;
+    const size_t fwd_ws_bytes = forward_wide_workspace_bytes(g);
     float *h = h_out ? h_out : h_ws;
+    const bool project = flags & LC_SAE_PROJECT_ROWS;
 
     int rc;
-    if ((rc = launch_forward_f32(g, x, w, nullptr, 1.f, alpha, h, s)) != LC_OK) return rc;
+    if ((rc = launch_forward_f32(g, x, w, nullptr, 1.f, alpha, h, s, fwd_ws, fwd_ws_bytes)) != LC_OK) return rc;
     if ((rc = launch_backward_data_f32(g, h, w, u, s)) != LC_OK) return rc;
     int n_r, bias_chunks = 0;     // bias_chunks > 0: the b update waits for the finalize kernel
     if ((img & 3) == 0 && (img / 4 + 255) / 256 * kBatchChunks <= kPartialsMax) {
         const int img4 = img / 4, gx = (img4 + 255) / 256;
         const int nchunk = g.B < kBatchChunks ? g.B : kBatchChunks, bchunk = (g.B + nchunk - 1) / nchunk;
         const int gy = (g.B + bchunk - 1) / bchunk;
-        hipLaunchKernelGGL(sae_residual_kernel, dim3(gx, gy), dim3(256), 0, s, u, x, b, g.B, img4, bchunk, dbp, part_r);
-        LC_HIP_LAUNCH_CHECK("sae_step residual launch");
+        const LaunchPlan plan = make_plan("sae_residual", {4}, {img4, bchunk}, dim3(gx, gy), 256, 0);
+        LC_PLAN_REQUIRE(plan, gx * gy <= kPartialsMax && gy <= kBatchChunks && (long long)gy * bchunk >= g.B);
+        LC_LAUNCH(plan, "sae_step residual launch", sae_residual_kernel, s, u, x, b, g.B, img4, bchunk, dbp, part_r);
         bias_chunks = gy;
         n_r = gx * gy;
     } else {
         n_r = (int)((img + 255) / 256 < kPartials ? (img + 255) / 256 : kPartials);
-        hipLaunchKernelGGL(sae_residual_scalar_kernel, dim3(n_r), dim3(256), 0, s, u, x, b, g.B, img, lr, part_r);
-        LC_HIP_LAUNCH_CHECK("sae_step residual launch");
+        const LaunchPlan plan = make_plan("sae_residual", {1}, {img}, dim3(n_r), 256, 0);
+        LC_LAUNCH(plan, "sae_step residual launch", sae_residual_scalar_kernel, s, u, x, b, g.B, img, lr, part_r);
     }
-    if ((rc = launch_forward_f32(g, u, w, nullptr, 1.f, nullptr, gh, s)) != LC_OK) return rc;
+    if ((rc = launch_forward_f32(g, u, w, nullptr, 1.f, nullptr, gh, s, fwd_ws, fwd_ws_bytes)) != LC_OK) return rc;
     const int n_s = (int)((nh + 255) / 256 < (size_t)kPartials ? (nh + 255) / 256 : kPartials);
-    hipLaunchKernelGGL(sae_sparsity_kernel, dim3(n_s), dim3(256), 0, s, h, gh, alpha, lambda / (float)g.B, eps_sparse,
-                       (long long)nh, part_s, part_hg);
-    LC_HIP_LAUNCH_CHECK("sae_step sparsity launch");
-    // w <- w - lr * ( patch(u) h^T + patch(x) (alpha gh)^T )
-    if ((rc = launch_backward_weights_f32(g, u, h, x, gh, 1.f, -lr, w, s)) != LC_OK) return rc;
-    if (flags & LC_SAE_PROJECT_ROWS) {
-        hipLaunchKernelGGL(sae_project_kernel, dim3(g.L), dim3(256), g.F * sizeof(float), s, w, g.K, g.F);
-        LC_HIP_LAUNCH_CHECK("sae_step projection launch");
+    {
+        const LaunchPlan plan = make_plan("sae_sparsity", {}, {n_s}, dim3(n_s), 256, 0);
+        LC_LAUNCH(plan, "sae_step sparsity launch", sae_sparsity_kernel, s, h, gh, alpha, lambda / (float)g.B, eps_sparse,
+                  (long long)nh, part_s, part_hg);
+    }
+    // w <- w - lr * ( patch(u) h^T + patch(x) (alpha gh)^T ), with the sums of squares of the new weights on the side
+    int kblocks = 0;
+    if ((rc = launch_backward_weights_f32(g, u, h, x, gh, 1.f, -lr, w, s, project ? ssq : nullptr, &kblocks)) != LC_OK)
+        return rc;
+    if (project) {
+        const long long LF = (long long)g.L * g.F, KF = (long long)g.K * g.F, nw = (long long)g.L * KF;
+        const LaunchPlan pn = make_plan("sae_row_norm", {}, {kblocks}, dim3((unsigned)((LF + 255) / 256)), 256, 0);
+        LC_PLAN_REQUIRE(pn, kblocks >= 1 && kblocks <= backward_weights_max_kblocks(g));
+        LC_LAUNCH(pn, "sae_step projection launch", sae_row_norm_kernel, s, ssq, kblocks, g.F, LF, inv);
+        // vectors of four filters where a row of w is made of them (a vector then never straddles two filters' rows)
+        const int V = g.F % 4 == 0 ? 4 : 1;
+        const long long nv = nw / V;
+        const unsigned blocks = (unsigned)(nv / 256 + 1 < 256 * 32 ? nv / 256 + 1 : 256 * 32);
+        const LaunchPlan pr = make_plan("sae_rescale", {V}, {}, dim3(blocks), 256, 0);
+        if (V == 4)
+            LC_LAUNCH(pr, "sae_step projection launch", sae_rescale_kernel<4>, s, w, inv, g.F, KF, nw);
+        else
+            LC_LAUNCH(pr, "sae_step projection launch", sae_rescale_kernel<1>, s, w, inv, g.F, KF, nw);
     }
     const int bias_blocks = bias_chunks > 0 ? (int)((img + 255) / 256) : 0;
-    hipLaunchKernelGGL(sae_finalize_kernel, dim3(1 + bias_blocks), dim3(256), 0, s, part_r, n_r, part_s, part_hg, n_s,
-                       lambda, g.B, lr, (flags & LC_SAE_LEARN_ALPHA) ? 1 : 0, alpha, cost_out, b, dbp, (int)img,
-                       bias_chunks);
-    LC_HIP_LAUNCH_CHECK("sae_step finalize launch");
+    const LaunchPlan pf = make_plan("sae_finalize", {}, {n_r, n_s, bias_chunks}, dim3(1 + bias_blocks), 256, 0);
+    LC_LAUNCH(pf, "sae_step finalize launch", sae_finalize_kernel, s, part_r, n_r, part_s, part_hg, n_s, lambda, g.B, lr,
+              (flags & LC_SAE_LEARN_ALPHA) ? 1 : 0, alpha, cost_out, b, dbp, (int)img, bias_chunks);
     return LC_OK;
 }
 

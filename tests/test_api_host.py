@@ -14,9 +14,12 @@ FAKE = 0x10000  # a 16-byte aligned non-null "pointer"; validation fails before 
 
 
 def header_functions():
-    src = open(os.path.join(ROOT, "include", "lc.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(?:int|size_t|const char \*)\s*\*?\s*(\w+)\s*\(", src)))
+    names = set()
+    for header in ("lc.h", "lc_plan.h"):
+        src = open(os.path.join(ROOT, "include", header)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names |= set(re.findall(r"\b(?:int|size_t|const char \*)\s*\*?\s*(\w+)\s*\(", src))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():

@@ -1,0 +1,309 @@
+"""Launch plans of the three layer primitives, checked on the host (no GPU): lc_plan_query runs the launchers'
+own planning and host checks; this file walks many seeded geometries through it and re-derives, independently of
+the C++ checks, what a plan has to satisfy: LDS within the kernel's budget, staging registers that hold a chunk,
+every tile of the problem covered exactly once by the grid (the kernels' block-index arithmetic is replayed here),
+and clamped staging addresses inside the tensor.  Geometry follows Sec. 3.1 (fields of size R at stride S)."""
+import numpy as np
+import pytest
+
+import paper_1502_03409_amd as lc
+import workloads as wl
+from paper_1502_03409_amd import binding as B
+
+OPS = (B.LC_OP_FORWARD, B.LC_OP_BACKWARD_DATA, B.LC_OP_BACKWARD_WEIGHTS)
+LDS_PER_CU = 160 * 1024
+
+
+def cdiv(a, b):
+    return -(-a // b)
+
+
+def remap_xcd(wg, n_wg, xcds=8):
+    """Work index of hardware workgroup `wg`: each of the 8 XCDs walks a contiguous range (as the kernels do)."""
+    per = cdiv(n_wg, xcds)
+    full = n_wg - (per - 1) * xcds
+    xcd, slot = wg % xcds, wg // xcds
+    start = xcd * per if xcd < full else full * per + (xcd - full) * (per - 1)
+    return start + slot
+
+
+def test_remap_is_a_permutation():
+    for n in (1, 7, 8, 9, 63, 64, 65, 552, 1300):
+        assert sorted(remap_xcd(w, n) for w in range(n)) == list(range(n))
+
+
+def sample_geometries(n, seed):
+    """Seeded layer geometries of every kind the launchers distinguish: aligned and ragged, few and many fields,
+    narrow and wide filter banks, tiny and large batches."""
+    r = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        kind = len(out) % 5
+        if kind == 0:      # anything goes
+            S, R, C = int(r.integers(1, 7)), int(r.integers(1, 13)), int(r.integers(1, 9))
+            F, Bn = int(r.integers(1, 70)), int(r.integers(1, 150))
+        elif kind == 1:    # aligned narrow layers (the pipelined kernels)
+            S = int(r.choice([1, 2, 3, 4]))
+            R = S * int(r.choice([1, 2, 3, 4, 5, 6, 8]))
+            C = int(r.choice([1, 2, 3, 4, 6, 8, 12, 16]))
+            F, Bn = 16 * int(r.integers(1, 9)), int(r.choice([17, 33, 48, 64, 65, 72, 96, 100, 127, 128, 130, 192, 256]))
+        elif kind == 2:    # wide layers (the workgroup-tiled kernels)
+            S = int(r.choice([1, 2, 4]))
+            R = S * int(r.integers(1, 5))
+            C = int(r.choice([8, 16, 32, 64]))
+            F, Bn = 128 * int(r.integers(1, 4)), int(r.choice([65, 80, 96, 128, 150, 192, 256, 320]))
+        elif kind == 3:    # large grids of small fields: enough workgroups for the tiered and eight-wave plans
+            S = int(r.choice([2, 4]))
+            R = S * int(r.choice([2, 4, 5]))
+            C = int(r.choice([1, 2, 3, 4]))
+            F, Bn = int(r.choice([16, 24, 32, 40, 48])), int(r.choice([65, 72, 100, 127, 128]))
+        else:              # one or very few fields (the dense last layer is the one-field case)
+            S, C = 1, int(r.choice([3, 4, 8, 24]))
+            R = int(r.integers(4, 40))
+            F, Bn = int(r.choice([10, 64, 128, 256, 1024])), int(r.choice([20, 80, 192]))
+        if kind == 3:
+            H, W = R + S * int(r.integers(20, 60)), R + S * int(r.integers(20, 60)) + int(r.integers(0, 3))
+        elif kind == 4:
+            H, W = R + int(r.integers(0, 2)), R + int(r.integers(0, 2))
+        else:
+            H, W = R + int(r.integers(0, 30)), R + int(r.integers(0, 40))
+        g = wl.LCGeom(B=Bn, H=H, W=W, C=C, R=R, S=S, F=F)
+        if g.params > 3e8 or g.B * g.H * g.W * g.C > 2 ** 30:
+            continue
+        out.append(g)
+    return out
+
+
+NAMED = dict(wl.CONFIG_GEOM, paper_layer1=wl.PAPER_LAYER1, paper_layer3=wl.PAPER_LAYER3,
+             cfg3_b72=wl.CONFIG_GEOM["cfg3"].with_batch(72), cfg3_b127=wl.CONFIG_GEOM["cfg3"].with_batch(127))
+
+
+# ------------------------------------------------------------------------------------------ per-family replays
+def covered_forward_fast(g, plans):
+    """(strip, batch tile, filter block) -> count over all launches, replaying the kernel's index arithmetic."""
+    seen = {}
+    for p in plans:
+        MT, NT, NLOC, UNR, NW = p["tparam"][:5]
+        first, count, nbt, strips = p["arg"][4:8]
+        gx, gy, _ = p["grid"]
+        assert gx == count * nbt
+        for bx in range(gx):
+            t_id = remap_xcd(bx, gx)
+            work, bt = first + t_id // nbt, t_id % nbt
+            for by in range(gy):
+                for wave in range(NW):
+                    wl_, wf = wave % NLOC, wave // NLOC
+                    i, j = work // strips, (work % strips) * NLOC + wl_
+                    if j >= g.LW:
+                        continue
+                    f0 = (by * (NW // NLOC) + wf) * NT * 16
+                    for mt in range(MT):
+                        for nt in range(NT):
+                            key = (i, j, bt * MT + mt, f0 // 16 + nt)
+                            seen[key] = seen.get(key, 0) + 1
+    return seen
+
+
+def check_forward_fast(g, plans):
+    total = 0
+    for p in plans:
+        MT, NT, NLOC, UNR, NW, ES, SPC, NRT, SLOTS = p["tparam"][:9]
+        CQ, sq4, RS, NR, first, count, nbt, strips = p["arg"][:8]
+        BT, NTHR, SC, WC = 16 * MT, 64 * NW, g.S * g.C, g.W * g.C
+        assert p["block"] == NTHR
+        # LDS: budget of the launcher (three four-wave workgroups, or two eight-wave ones, per compute unit)
+        assert p["lds_bytes"] <= (78 if NW == 8 else 52) * 1024 and p["lds_bytes"] == BT * RS * 4
+        # staging slots x threads hold one chunk of dwordx4
+        assert SLOTS * NTHR >= BT * NR * sq4
+        assert 4 * sq4 >= CQ + (NLOC - 1) * SC and RS >= NR * 4 * sq4 + 2
+        assert (g.R * g.C) % CQ == 0 and CQ % (4 * UNR) == 0 and g.R % NR == 0
+        assert p["grid"][1] * (NW // NLOC) * NT * 16 == g.F
+        total += count
+        if SPC > 0:
+            # every staging slot loads from a clamped address: the largest one must end inside x
+            img = g.H * WC
+            for work in (first, first + count - 1):
+                i, j0 = work // strips, (work % strips) * NLOC
+                col0 = j0 * SC
+                lim0 = WC - col0
+                assert lim0 >= 4
+                for b0 in {0, (nbt - 1) * BT}:
+                    for kh in (0, g.R - NRT):
+                        row = b0 * img + (i * g.S + kh) * WC + col0
+                        so_max = min(BT - 1, g.B - 1 - b0) * img + (NR - 1) * WC + min(4 * sq4 - 4, max(lim0 - 4, 0))
+                        assert row + so_max + 4 <= g.B * img
+                        assert row >= 0
+    strips = plans[0]["arg"][7]
+    assert total == strips * g.LH
+    # the launches take consecutive ranges of strips
+    nxt = 0
+    for p in plans:
+        assert p["arg"][4] == nxt
+        nxt += p["arg"][5]
+
+
+def covered_backward_data_fast(g, p):
+    MT, NT, NCELL, AP, NW = p["tparam"][:5]
+    strips, RS, nbt = p["arg"][:3]
+    gx, gy, _ = p["grid"]
+    r_lo = AP - 1
+    n_in = g.LH - r_lo if g.LH > r_lo else 0
+    per_row = strips * nbt
+    n_first = n_in * per_row
+    seen = {}
+    for bx in range(gx):
+        if bx < n_first:
+            t_id = remap_xcd(bx, n_first)
+            ri = r_lo + t_id // per_row
+        elif n_in > 0:
+            t_id = bx - n_first
+            rb = t_id // per_row
+            ri = rb if rb < r_lo else g.LH + (rb - r_lo)
+        else:
+            t_id = remap_xcd(bx, gx)
+            ri = t_id // per_row
+        wi0 = ((t_id // nbt) % strips) * NCELL
+        bt = t_id % nbt
+        key = (ri, wi0, bt)
+        seen[key] = seen.get(key, 0) + 1
+    return seen
+
+
+def check_backward_data_fast(g, p):
+    MT, NT, NCELL, AP, NW, ES, LINE = p["tparam"][:7]
+    strips, RS, nbt = p["arg"][:3]
+    BT, JW, FCH = 16 * MT, NCELL + AP - 1, 32 if LINE else 16
+    CH, CW, NCV = cdiv(g.H, g.S), cdiv(g.W, g.S), g.S * g.S * g.C
+    assert g.R % g.S == 0 and AP == g.R // g.S and g.F % FCH == 0
+    assert RS >= JW * FCH and p["lds_bytes"] == (1 if LINE else 2) * BT * RS * ES
+    assert p["lds_bytes"] <= LDS_PER_CU
+    assert p["grid"][0] == strips * CH * nbt and strips == cdiv(CW, NCELL) and nbt == cdiv(g.B, BT)
+    assert p["grid"][1] == cdiv(NCV, (NW // NCELL) * NT * 16)
+
+
+FAMILY_LDS_BUDGET = {   # bytes per workgroup the launchers aim at (several workgroups per compute unit)
+    "lc_forward_generic": LDS_PER_CU, "lc_bwd_data_generic": LDS_PER_CU, "lc_forward_wide": 80 * 1024,
+    "lc_bwd_data_wide": 80 * 1024, "lc_forward_bf16_strip": 48 * 1024, "lc_bwd_weights_bf16_strip": 48 * 1024,
+    "lc_forward_bf16_tiled": 80 * 1024, "lc_bwd_data_bf16_tiled": 80 * 1024, "lc_bwd_weights_bf16_tiled": LDS_PER_CU,
+}
+
+
+def check_plans(g, op, dtype, plans, replay):
+    assert len(plans) >= 1
+    for p in plans:
+        assert p["lds_bytes"] <= FAMILY_LDS_BUDGET.get(p["kernel"], LDS_PER_CU), p
+        assert 64 <= p["block"] <= 1024 and p["block"] % 64 == 0
+        assert all(d >= 1 for d in p["grid"]) and p["grid"][1] <= 65535 and p["grid"][2] <= 65535
+    fams = {p["kernel"] for p in plans}
+    if fams == {"lc_forward_fast"}:
+        check_forward_fast(g, plans)
+        if replay:
+            seen = covered_forward_fast(g, plans)
+            MT = plans[0]["tparam"][0]
+            want = {(i, j, bt, ft) for i in range(g.LH) for j in range(g.LW)
+                    for bt in range(cdiv(g.B, 16)) for ft in range(g.F // 16)}
+            got = {k for k in seen if k[2] < cdiv(g.B, 16)}
+            assert got == want and all(seen[k] == 1 for k in got), (g, MT)
+    elif fams <= {"lc_bwd_data_fast", "lc_bwd_data_line"}:
+        assert len(plans) == 1
+        check_backward_data_fast(g, plans[0])
+        if replay:
+            p = plans[0]
+            NCELL, strips, nbt = p["tparam"][2], p["arg"][0], p["arg"][2]
+            seen = covered_backward_data_fast(g, p)
+            want = {(ri, ws * NCELL, bt) for ri in range(cdiv(g.H, g.S)) for ws in range(strips) for bt in range(nbt)}
+            assert set(seen) == want and all(v == 1 for v in seen.values()), g
+    elif fams == {"lc_bwd_weights_fast"} or fams == {"lc_bwd_weights_generic"} or fams == {"lc_bwd_weights_bf16_rows"}:
+        p = plans[0]
+        kblocks, ntasks = p["arg"][:2]
+        assert ntasks == g.L * kblocks and p["grid"][0] == cdiv(ntasks, 4)
+        rows = {"lc_bwd_weights_fast": p["tparam"][0] * p["tparam"][1] * 16,
+                "lc_bwd_weights_generic": p["tparam"][0] * 16,
+                "lc_bwd_weights_bf16_rows": p["tparam"][0] * 64}[p["kernel"]]
+        ntile = p["tparam"][2] if p["kernel"] == "lc_bwd_weights_fast" else p["tparam"][1]
+        assert kblocks * rows >= g.K > (kblocks - 1) * rows
+        assert p["grid"][1] * ntile * 16 >= g.F > (p["grid"][1] - 1) * ntile * 16
+
+
+# ------------------------------------------------------------------------------------------------------ tests
+@pytest.mark.parametrize("name", list(NAMED))
+def test_named_workloads_plan_and_cover(name):
+    g = NAMED[name]
+    G = lc.geom(*g.as_tuple())
+    small = g.L * cdiv(g.B, 16) * cdiv(g.F, 16) <= 3_000_000
+    for op in OPS:
+        for dtype in (B.LC_F32, B.LC_BF16):
+            check_plans(g, op, dtype, lc.plan_query(G, op, dtype), replay=small)
+    plans = lc.plan_query(G, B.LC_OP_SAE_STEP)
+    names = [p["kernel"] for p in plans]
+    assert names[-1] == "sae_finalize" and "sae_row_norm" in names and "sae_rescale" in names
+
+
+def test_headline_workload_takes_the_tiered_forward_plan():
+    """cfg3's forward pass: 512 strips of 128-image tiles with compile-time counts, the last 40 strips as
+    32-image tiles, together every strip once."""
+    g = wl.CONFIG_GEOM["cfg3"]
+    plans = lc.plan_query(lc.geom(*g.as_tuple()), B.LC_OP_FORWARD)
+    assert [p["kernel"] for p in plans] == ["lc_forward_fast", "lc_forward_fast"]
+    assert plans[0]["tparam"][:9] == [8, 2, 4, 5, 4, 4, 15, 1, 12] and plans[0]["arg"][4:6] == [0, 512]
+    assert plans[1]["tparam"][:9] == [2, 2, 4, 15, 4, 4, 15, 4, 12] and plans[1]["arg"][4:6] == [512, 40]
+
+
+def test_filter_counts_off_the_tile_size_never_take_a_tiled_plan():
+    """Layers with at least 512 workgroups of work and F not a multiple of 16 (Sec. 3.1 allows any F): the
+    pipelined kernels' grids count F in whole tiles, so these must go to the masked kernel."""
+    for F in (20, 24, 40, 17, 63):
+        for base in (wl.LCGeom(B=128, H=128, W=128, C=3, R=16, S=2, F=F), wl.LCGeom(B=100, H=102, W=102, C=4, R=8, S=2, F=F)):
+            plans = lc.plan_query(lc.geom(*base.as_tuple()), B.LC_OP_FORWARD)
+            assert [p["kernel"] for p in plans] == ["lc_forward_generic"], (base, plans)
+            p = plans[0]
+            NLOC, NT = p["tparam"][2], p["tparam"][1]
+            assert p["grid"][1] * (4 // NLOC) * NT * 16 >= F
+
+
+def test_eight_wave_forward_variants_are_reachable():
+    """The shapes the GPU parity suite uses for the eight-wave forward kernel do take it, with rings of 8, 6 and 5."""
+    want = {(8, 1, 8, 8, 8): wl.LCGeom(B=100, H=102, W=102, C=4, R=8, S=2, F=16),
+            (8, 1, 8, 6, 8): wl.LCGeom(B=100, H=100, W=100, C=3, R=8, S=2, F=16),
+            (8, 1, 8, 5, 8): wl.LCGeom(B=100, H=104, W=104, C=2, R=10, S=2, F=16)}
+    for tp, g in want.items():
+        plans = lc.plan_query(lc.geom(*g.as_tuple()), B.LC_OP_FORWARD)
+        assert len(plans) == 1 and tuple(plans[0]["tparam"][:5]) == tp and plans[0]["tparam"][6] == 0, plans
+    g = wl.LCGeom(B=72, H=102, W=102, C=4, R=8, S=2, F=48)
+    plans = lc.plan_query(lc.geom(*g.as_tuple()), B.LC_OP_FORWARD)
+    assert tuple(plans[0]["tparam"][:5]) == (8, 1, 8, 8, 8) and plans[0]["grid"][1] == 3
+
+
+@pytest.mark.parametrize("chunk", range(8))
+def test_seeded_geometries_plan_within_their_invariants(chunk):
+    """10 400 seeded geometries x three primitives x two operand types: every plan passes the library's host
+    checks (lc_plan_query would return LC_EINTERNAL otherwise) and the independent ones above; the grid
+    arithmetic is replayed block by block for the smaller ones."""
+    geoms = sample_geometries(1300, seed=1000 + chunk)
+    families = set()
+    for n, g in enumerate(geoms):
+        G = lc.geom(*g.as_tuple())
+        for op in OPS:
+            for dtype in (B.LC_F32, B.LC_BF16):
+                try:
+                    plans = lc.plan_query(G, op, dtype)
+                except lc.LcError as e:
+                    # the only refusal left: a ragged layer whose patch row does not fit the LDS of the masked kernel
+                    assert e.code == B.LC_EUNSUPPORTED and op == B.LC_OP_FORWARD and g.R * g.C > 2000, (g, op, dtype, e)
+                    continue
+                replay = n % 8 == 0 and g.L * cdiv(g.B, 16) * cdiv(g.F, 16) <= 400_000
+                check_plans(g, op, dtype, plans, replay)
+                families.update(p["kernel"] for p in plans)
+    # the sampler reaches every family of the fp32 path and the bf16 ones
+    assert {"lc_forward_fast", "lc_forward_generic", "lc_forward_wide", "lc_bwd_data_fast", "lc_bwd_data_generic",
+            "lc_bwd_data_wide", "lc_bwd_weights_fast", "lc_bwd_weights_generic"} <= families, families
+
+
+def test_bf16_is_never_refused_on_shape_alone():
+    """Any geometry the fp32 path takes, the bf16 path takes too (shapes outside the bf16 matrix-instruction kernels
+    run the masked kernels on bf16 storage)."""
+    for g in (wl.CONFIG_GEOM["cfg1"], wl.LCGeom(B=8, H=9, W=9, C=3, R=3, S=2, F=10), wl.LCGeom(B=5, H=23, W=26, C=2, R=5, S=3, F=10),
+              wl.LCGeom(B=1, H=9, W=9, C=2, R=3, S=3, F=5), wl.LCGeom(B=70, H=14, W=15, C=5, R=4, S=4, F=19)):
+        G = lc.geom(*g.as_tuple())
+        for op in OPS:
+            assert len(lc.plan_query(G, op, B.LC_BF16)) >= 1

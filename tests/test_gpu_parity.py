@@ -116,30 +116,78 @@ def test_lc_primitives_match_oracle(name):
     assert rel_fro(dw1, ref_dw + prev) <= TOL
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg4", "paper_layer1", "paper_layer3"])
-def test_lc_primitives_full_size_sampled(name):
-    """Full-size workloads in the launch configuration the benchmark times: a sample of outputs
-    against the oracle's single-output evaluators, plus the adjoint identities on the GPU results.
-    paper_layer1 / paper_layer3 are the first and the dense last layer at the sizes the architecture
-    section states (Sec. 3.1)."""
-    if name in ("paper_layer1", "paper_layer3"):
-        # paper_layer3: the dense last layer as a single field covering its whole input (Sec. 3.1)
-        g, kind = (wl.PAPER_LAYER1, "pink") if name == "paper_layer1" else (wl.PAPER_LAYER3, "halfnormal")
-        print(f"case {name} geom {g}", flush=True)
-        x, w, dy = wl.lc_inputs_blocked(g, kind, seed=0)
-    else:
-        g, kind = wl.CONFIG_GEOM[name], wl.CONFIG_IMAGE_KIND[name]
-        print(f"case {name} geom {g}", flush=True)
-        x, w, dy = wl.lc_inputs(g, kind, seed=0)
+# Shapes at the size where the launchers change their plan: at least 512 workgroups of the largest tile.  Whole
+# tensors against the oracle, outputs pre-filled with NaN.
+LARGE = {
+    "cfg3": (wl.CONFIG_GEOM["cfg3"], "pink"),
+    "cfg4": (wl.CONFIG_GEOM["cfg4"], "halfnormal"),
+    # the grid of cfg3 with ragged batches: the forward pass runs as a main launch of 128-image tiles plus a
+    # remainder launch of 32-image tiles, both with clamped staging addresses beyond the batch
+    "cfg3_b72": (wl.CONFIG_GEOM["cfg3"].with_batch(72), "pink"),
+    "cfg3_b127": (wl.CONFIG_GEOM["cfg3"].with_batch(127), "pink"),
+    # 16 filters per field, eight fields per workgroup: rings of 8, 6 and 5 k-steps, and 48 filters (three blocks)
+    "eight_u8": (wl.LCGeom(B=100, H=102, W=102, C=4, R=8, S=2, F=16), "halfnormal"),
+    "eight_u6": (wl.LCGeom(B=100, H=100, W=100, C=3, R=8, S=2, F=16), "pink"),
+    "eight_u5": (wl.LCGeom(B=100, H=104, W=104, C=2, R=10, S=2, F=16), "pink"),
+    "eight_f48": (wl.LCGeom(B=72, H=102, W=102, C=4, R=8, S=2, F=48), "halfnormal"),
+    # filter counts that are no multiple of 16 on the same grids: the masked kernels
+    "eight_f24": (wl.LCGeom(B=100, H=102, W=102, C=4, R=8, S=2, F=24), "halfnormal"),
+    "eight_f40": (wl.LCGeom(B=100, H=100, W=100, C=3, R=8, S=2, F=40), "pink"),
+}
+
+
+@pytest.mark.parametrize("name", list(LARGE))
+def test_lc_primitives_large_whole_tensor(name):
+    """Every output of the three layer primitives against the oracle at the sizes the benchmark times
+    (Sec. 3.1 geometry; Eq. 1's W x, W^T h and the weight gradient)."""
+    g, kind = LARGE[name]
+    print(f"case large {name} geom {g}", flush=True)
+    x, w, dy = wl.lc_inputs(g, kind, seed=0)
     t = g.as_tuple()
     G = lc.geom(*t)
     xd, wd, dyd = dev(x), dev(w), dev(dy)
-    y = torch.empty((g.B, g.LH, g.LW, g.F), device="cuda")
-    dx = torch.empty((g.B, g.H, g.W, g.C), device="cuda")
-    dw = torch.empty((g.LH, g.LW, g.K, g.F), device="cuda")
+    y = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
+    dx = torch.full((g.B, g.H, g.W, g.C), float("nan"), device="cuda")
+    dw = torch.full((g.LH, g.LW, g.K, g.F), float("nan"), device="cuda")
     lc.lc_forward(G, xd, wd, None, 1.0, y, lc.LC_F32, forward_workspace(G))
     lc.lc_backward_data(G, dyd, wd, dx)
     lc.lc_backward_weights(G, xd, dyd, 0.0, dw)
+    yh, dxh, dwh = host(y), host(dx), host(dw)
+    del xd, wd, dyd, y, dx, dw
+    e = rel_fro(yh, oracle.lc_forward(t, x, w))
+    print(f"  lc_forward rel err {e:.2e}", flush=True)
+    assert e <= TOL
+    ref = oracle.lc_backward_data(t, dy, w)
+    e = rel_fro(dxh, ref)
+    print(f"  lc_backward_data rel err {e:.2e}", flush=True)
+    assert e <= TOL
+    assert np.all(dxh[ref == 0.0] == 0.0)
+    del ref
+    e = rel_fro(dwh, oracle.lc_backward_weights(t, x, dy))
+    print(f"  lc_backward_weights rel err {e:.2e}", flush=True)
+    assert e <= TOL
+
+
+@pytest.mark.parametrize("name", ["paper_layer1", "paper_layer3"])
+def test_lc_primitives_full_size_sampled(name):
+    """The paper's first layer and its dense last layer (a single field covering its whole input) at the sizes
+    the architecture section states (Sec. 3.1): 6.1 GB and 1.5 GB of weights, too large for the whole-tensor
+    oracle.  A sample of outputs against the oracle's single-output evaluators, plus the adjoint identities on
+    the GPU results."""
+    g, kind = (wl.PAPER_LAYER1, "pink") if name == "paper_layer1" else (wl.PAPER_LAYER3, "halfnormal")
+    print(f"case {name} geom {g}", flush=True)
+    x, w, dy = wl.lc_inputs_blocked(g, kind, seed=0)
+    t = g.as_tuple()
+    G = lc.geom(*t)
+    xd, wd, dyd = dev(x), dev(w), dev(dy)
+    y = torch.full((g.B, g.LH, g.LW, g.F), float("nan"), device="cuda")
+    dx = torch.full((g.B, g.H, g.W, g.C), float("nan"), device="cuda")
+    dw = torch.full((g.LH, g.LW, g.K, g.F), float("nan"), device="cuda")
+    lc.lc_forward(G, xd, wd, None, 1.0, y, lc.LC_F32, forward_workspace(G))
+    lc.lc_backward_data(G, dyd, wd, dx)
+    lc.lc_backward_weights(G, xd, dyd, 0.0, dw)
+    # no output was left unwritten
+    assert not torch.isnan(y).any() and not torch.isnan(dx).any() and not torch.isnan(dw).any()
     # adjoint identities, evaluated in fp64 on the device results
     lhs = torch.dot(y.double().flatten(), dyd.double().flatten()).item()
     rhs = torch.dot(xd.double().flatten(), dx.double().flatten()).item()
