@@ -220,6 +220,36 @@ def sae_step(g, x, w, b, alpha=1.0, lam=0.1, eps_s=1e-6, lr=1e-3, flags=0):
     return float(J), w, b, float(a.value), h
 
 
+def sae_step_one_field(g, x, w, b, alpha=1.0, lam=0.1, eps_s=1e-6, lr=1e-3, flags=0):
+    """`sae_step` for a layer of ONE field that covers its whole input (R = H = W: the dense last layer of
+    Sec. 3.1).  There `W x` of Eq. 1 is a plain matrix product, so the same steps, in the same order as the C
+    oracle takes them, are written with numpy's fp64 matmul, which makes the paper-sized layer (92,256 x 4096
+    weights) affordable.  Returns (J, w_new, b_new, alpha_new, h) like `sae_step`."""
+    B, H, W, Cc, R, S, F = g
+    if not (R == H == W):
+        raise ValueError("one field covering the whole input is required")
+    K = R * R * Cc
+    X = _d(x).reshape(B, K)
+    Wm = _d(w).reshape(K, F)
+    a = X @ Wm                                    # W x
+    h = alpha * a
+    r = h @ Wm.T + _d(b).reshape(1, K) - X        # W^T h + b - x
+    s = np.sqrt(h * h + eps_s)
+    J = (np.sum(r * r) + lam * np.sum(s)) / B
+    u = (2.0 / B) * r
+    db = u.sum(axis=0)
+    gh = u @ Wm + (lam / B) * h / s               # dJ/dh
+    da = np.sum(a * gh)
+    dW = u.T @ h + X.T @ (alpha * gh)             # decoder path + encoder path of the tied weights
+    Wn = Wm - lr * dW
+    bn = _d(b).reshape(K) - lr * db
+    an = alpha - lr * da if flags & 2 else alpha
+    if flags & 1:
+        n2 = np.sum(Wn * Wn, axis=0)
+        Wn = Wn * np.where(n2 > 0.0, 1.0 / np.sqrt(np.where(n2 > 0.0, n2, 1.0)), 0.0)[None, :]
+    return float(J), Wn.reshape(1, 1, K, F), bn.reshape(H, W, Cc), float(an), h.reshape(B, 1, 1, F)
+
+
 def lc_forward_at(g, x, w, bias, alpha, b, i, j, f):
     x, w = _f(x), _f(w)
     bp = None

@@ -477,7 +477,8 @@ double orc_sae_step(int B, int H, int W, int C, int R, int S, int F,
             for (int f = 0; f < F; ++f) {
                 double n2 = 0.0;
                 for (int k = 0; k < K; ++k) { const double v = w[(l * K + k) * F + f]; n2 += v * v; }
-                const double inv = 1.0 / sqrt(n2);
+                /* a filter that is all zeros has no direction to normalise: it stays as it is */
+                const double inv = n2 > 0.0 ? 1.0 / sqrt(n2) : 0.0;
                 for (int k = 0; k < K; ++k) w[(l * K + k) * F + f] *= inv;
             }
     }

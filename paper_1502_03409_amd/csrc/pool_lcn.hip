@@ -9,11 +9,11 @@
 
 #include "lc_common.hpp"
 
-#ifndef LC_BAND_NTHR
-#define LC_BAND_NTHR 1024
-#endif
-
 namespace lc {
+
+// threads per workgroup of the band kernels: a band of whole image rows lives in their registers (512 threads with
+// bands half as long measured the same)
+constexpr int kBandThreads = 1024;
 
 // ------------------------------------------------------------------ L2 pooling
 template <int VEC>
@@ -916,7 +916,7 @@ namespace {
 template <int LPP, int MODE>
 int launch_lcn_band_lpp(const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
                         int ks, float eps, const GaussTaps &taps, hipStream_t s, int zero_pad, bool *done) {
-    constexpr int NTHR = LC_BAND_NTHR, NV = 8;
+    constexpr int NTHR = kBandThreads, NV = 8;
     const int r = (ks - 1) / 2;
     const int rb_max = (NTHR * NV) / (W * LPP);
     if (rb_max < 8 || rb_max < 2 * r) return LC_OK;

@@ -539,6 +539,42 @@ def test_sae_step_is_grad_plus_sgd_update():
     np.testing.assert_array_equal(h, h2)
 
 
+def test_sae_projection_leaves_a_zero_filter_alone():
+    """Eq. 1's constraint ||W^(k)||_2 = 1 cannot be met by a filter that is all zeros: such a filter has zero
+    response, zero gradient through both tied paths, and nothing to normalise.  It stays zero (no NaN), and every
+    other filter comes out with unit norm."""
+    g = SAE_G
+    t = g.as_tuple()
+    r, x, w, b = _sae_inputs(23)
+    w = w.copy()
+    w[1, 0, :, 2] = 0.0
+    _, dw, _, _, _ = oracle.sae_grad(t, x, w, b, 0.9, 0.1, 1e-6)
+    assert np.all(dw[1, 0, :, 2] == 0.0)
+    _, w2, _, _, _ = oracle.sae_step(t, x, w, b, 0.9, 0.1, 1e-6, 0.05, flags=1)
+    assert np.all(np.isfinite(w2)) and np.all(w2[1, 0, :, 2] == 0.0)
+    norms = np.linalg.norm(w2, axis=2)
+    norms[1, 0, 2] = 1.0
+    np.testing.assert_allclose(norms, 1.0, rtol=1e-12)
+
+
+def test_one_field_step_written_with_matmuls_equals_the_loop_oracle():
+    """The dense last layer (Sec. 3.1) is the one-field case; its matmul form must be the loop oracle's step."""
+    g = wl.LCGeom(B=6, H=5, W=5, C=3, R=5, S=1, F=7)
+    t = g.as_tuple()
+    r = np.random.default_rng(31)
+    x = r.standard_normal((g.B, g.H, g.W, g.C))
+    w = r.standard_normal((1, 1, g.K, g.F)) / np.sqrt(g.K)
+    b = 0.1 * r.standard_normal((g.H, g.W, g.C))
+    for flags in range(4):
+        ref = oracle.sae_step(t, x, w, b, 0.8, 0.01, 1e-6, 0.05, flags)
+        got = oracle.sae_step_one_field(t, x, w, b, 0.8, 0.01, 1e-6, 0.05, flags)
+        assert abs(ref[0] - got[0]) <= 1e-13 * abs(ref[0])
+        np.testing.assert_allclose(got[1], ref[1], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(got[2], ref[2], rtol=1e-12, atol=1e-14)
+        assert abs(ref[3] - got[3]) <= 1e-13
+        np.testing.assert_allclose(got[4], ref[4], rtol=1e-12, atol=1e-14)
+
+
 # ------------------------------------------------------------ input generators
 def test_synthetic_inputs_have_the_stated_statistics():
     g = wl.LCGeom(B=3, H=32, W=32, C=3, R=8, S=4, F=4)

@@ -92,6 +92,7 @@ CONFIG_IMAGE_KIND = {
 POOL_KSIZE, POOL_STRIDE, POOL_EPS = 3, 1, 1e-6
 LCN_KSIZE, LCN_SIGMA, LCN_EPS = 5, 1.0, 1e-4
 SAE_LAMBDA, SAE_EPS, SAE_LR = 0.1, 1e-6, 1e-3
+SAE_LAMBDA_DENSE = 0.01     # the sparsity weight the paper gives for its dense third layer (next to Eq. 1)
 
 
 def _standardise(x: np.ndarray) -> np.ndarray:
