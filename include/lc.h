@@ -156,6 +156,19 @@ int lcn_variant_bwd(const float *x, const float *mu, const float *rstd, const fl
                     int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma, uint32_t flags, void *ws,
                     size_t ws_bytes, void *hip_stream);
 
+/* lcn_variant_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, checks and results as
+ * lcn_variant_bwd, minus ws / ws_bytes: the scratch of the two-stage gradient lives in a device array inside the
+ * library, LCN_STATIC_SCRATCH_BYTES long, that every GPU the library runs on holds until the process ends.  The
+ * call allocates and frees nothing.  A map whose lcn_variant_workspace_bytes() exceeds that size is refused with
+ * LC_EWORKSPACE (lc_last_error() says why) before anything is launched.  All calls on one GPU share that GPU's
+ * array: two calls that overlap in time on one GPU (different streams or threads) race on it; calls on one stream,
+ * or ordered by events, do not.  The first call on a device looks the array's address up (LC_EHIP if that fails). */
+#define LCN_STATIC_SCRATCH_BYTES (32u << 20)
+int lcn_variant_bwd_static(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B,
+                           int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma, uint32_t flags,
+                           void *hip_stream);
+
 /* One SGD step on the RICA cost of Eq. 1 for one layer (fp32):
  *   h = alpha W x;  xh = W^T h + b;  J = (1/B) [ sum (xh - x)^2 + lambda * sum sqrt(h^2 + eps_sparse) ]
  *   w -= lr dJ/dw (both uses of the tied weights);  b -= lr dJ/db;  alpha -= lr dJ/dalpha if LC_SAE_LEARN_ALPHA;

@@ -26,7 +26,7 @@ _STATUS = {0: "LC_OK", -1: "LC_EINVAL", -2: "LC_ENULL", -3: "LC_EALIGN", -4: "LC
 
 EXPORTS = ("lc_geom_derive", "lc_workspace_bytes", "lc_forward", "lc_backward_data", "lc_backward_weights",
            "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
-           "lcn_variant_bwd", "sae_step", "lc_last_error", "lc_plan_query")
+           "lcn_variant_bwd", "lcn_variant_bwd_static", "sae_step", "lc_last_error", "lc_plan_query")
 
 
 class LcGeom(C.Structure):
@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
         L.lcn_variant_workspace_bytes.restype = C.c_size_t
         L.lcn_variant_fwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, C.c_uint32, vp]
         L.lcn_variant_bwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, C.c_uint32, vp, C.c_size_t, vp]
+        L.lcn_variant_bwd_static.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, C.c_uint32, vp]
         L.sae_step.argtypes = [G, vp, vp, vp, vp, f32, f32, f32, u32, vp, vp, vp, sz, vp]
         L.lc_last_error.restype = C.c_char_p
         L.lc_plan_query.argtypes = [G, C.c_int, C.c_int, C.POINTER(LcLaunch), i32, C.POINTER(i32)]
@@ -84,7 +85,8 @@ def lib() -> C.CDLL:
 
 def _check(fn: str, rc: int) -> None:
     if rc != LC_OK:
-        detail = lib().lc_last_error().decode() if rc in (LC_EHIP, LC_EINTERNAL) else ""
+        with_text = rc in (LC_EHIP, LC_EINTERNAL) or (rc == LC_EWORKSPACE and fn == "lcn_variant_bwd_static")
+        detail = lib().lc_last_error().decode() if with_text else ""
         raise LcError(fn, rc, detail)
 
 
@@ -231,6 +233,19 @@ def lcn_variant_bwd(x, mu, rstd, dy, dx, ksize: int, gauss_sigma: float, flags: 
         _dev(x, None, torch.float32, "x"), _dev(mu, stat, torch.float32, "mu"),
         _dev(rstd, stat, torch.float32, "rstd"), _dev(dy, x.shape, torch.float32, "dy"),
         _dev(dx, x.shape, torch.float32, "dx"), B, H, W, Cc, ksize, gauss_sigma, flags, wp, wb, _stream()))
+
+
+LCN_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def lcn_variant_bwd_static(x, mu, rstd, dy, dx, ksize: int, gauss_sigma: float, flags: int) -> None:
+    """`lcn_variant_bwd` with the library's own static scratch array (no workspace, no allocation)."""
+    B, H, W, Cc = x.shape
+    stat = (B, H, W, Cc) if flags & LCN_PER_CHANNEL else (B, H, W)
+    _check("lcn_variant_bwd_static", lib().lcn_variant_bwd_static(
+        _dev(x, None, torch.float32, "x"), _dev(mu, stat, torch.float32, "mu"),
+        _dev(rstd, stat, torch.float32, "rstd"), _dev(dy, x.shape, torch.float32, "dy"),
+        _dev(dx, x.shape, torch.float32, "dx"), B, H, W, Cc, ksize, gauss_sigma, flags, _stream()))
 
 
 def sae_step(g: LcGeom, x, w, b, alpha, lam: float, eps_sparse: float, lr: float, flags: int, h_out, cost_out,

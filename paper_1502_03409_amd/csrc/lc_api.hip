@@ -74,7 +74,7 @@ int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where) {
     return LC_OK;
 }
 
-static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+static inline bool aligned16(const void *p) { return ptr_aligned16(p); }
 
 }  // namespace lc
 
@@ -182,11 +182,7 @@ int lc_plan_query(const lc_geom_t *g, int op, int dtype, lc_launch_t *out, int32
     return LC_OK;
 }
 
-static int check_map(int32_t B, int32_t H, int32_t W, int32_t C) {
-    if (B < 1 || H < 1 || W < 1 || C < 1) return LC_EINVAL;
-    if ((long long)H * W * C > (1LL << 30) || (long long)B * H * W > (1LL << 40)) return LC_EINVAL;
-    return LC_OK;
-}
+static int check_map(int32_t B, int32_t H, int32_t W, int32_t C) { return check_map_dims(B, H, W, C); }
 
 int l2pool_fwd(const float *x, float *y, int32_t B, int32_t H, int32_t W, int32_t C, int32_t ksize, int32_t stride,
                float eps, void *hip_stream) {
@@ -242,11 +238,7 @@ int lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int32_t B,
 int lcn_variant_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B,
                     int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma, uint32_t flags, void *ws,
                     size_t ws_bytes, void *hip_stream) {
-    if (check_map(B, H, W, C) != LC_OK || (flags & ~7u)) return LC_EINVAL;
-    if (ksize < 1 || ksize > 15 || (ksize & 1) == 0 || !(gauss_sigma > 0.f)) return LC_EINVAL;
-    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(mu); LC_REQUIRE_PTR(rstd); LC_REQUIRE_PTR(dy); LC_REQUIRE_PTR(dx);
-    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(mu); LC_REQUIRE_ALIGNED(rstd); LC_REQUIRE_ALIGNED(dy); LC_REQUIRE_ALIGNED(dx);
-    if (dx == x || dx == dy) return LC_EINVAL;
+    if (int rc = check_lcn_variant_bwd_args(x, mu, rstd, dy, dx, B, H, W, C, ksize, gauss_sigma, flags)) return rc;
     if (flags & LCN_TWO_STAGE) {
         if (ws == nullptr || ws_bytes < lc::lcn_variant_scratch_bytes(B, H, W, C, flags)) return LC_EWORKSPACE;
         LC_REQUIRE_ALIGNED(ws);

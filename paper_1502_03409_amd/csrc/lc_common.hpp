@@ -153,6 +153,26 @@ void plan_capture_add(const LaunchPlan &p);
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// argument checks shared by the entry points that take a [B,H,W,C] map
+inline int check_map_dims(int32_t B, int32_t H, int32_t W, int32_t C) {
+    if (B < 1 || H < 1 || W < 1 || C < 1) return LC_EINVAL;
+    if ((long long)H * W * C > (1LL << 30) || (long long)B * H * W > (1LL << 40)) return LC_EINVAL;
+    return LC_OK;
+}
+inline bool ptr_aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+// everything lcn_variant_bwd checks before it looks at its workspace
+inline int check_lcn_variant_bwd_args(const float *x, const float *mu, const float *rstd, const float *dy, float *dx,
+                                      int32_t B, int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma,
+                                      uint32_t flags) {
+    if (check_map_dims(B, H, W, C) != LC_OK || (flags & ~7u)) return LC_EINVAL;
+    if (ksize < 1 || ksize > 15 || (ksize & 1) == 0 || !(gauss_sigma > 0.f)) return LC_EINVAL;
+    if (!x || !mu || !rstd || !dy || !dx) return LC_ENULL;
+    if (!ptr_aligned16(x) || !ptr_aligned16(mu) || !ptr_aligned16(rstd) || !ptr_aligned16(dy) || !ptr_aligned16(dx))
+        return LC_EALIGN;
+    if (dx == x || dx == dy) return LC_EINVAL;
+    return LC_OK;
+}
+
 // raises a kernel's dynamic LDS limit when `bytes` needs it (once per kernel and device); LC_OK or LC_EHIP
 int allow_dynamic_lds(const void *kernel, size_t bytes, const char *where);
 

@@ -7,6 +7,8 @@
 // up to 32 channels of the quantity under the window in LDS (as float4 where C % 4 == 0), and each thread forms
 // the Gaussian window sums for one pixel and four channels at a time.  Bandwidth-bound: the forward passes read
 // the tile once (the centre value is taken from LDS), the halo ring comes from L2.
+#include <mutex>
+
 #include "lc_common.hpp"
 
 namespace lc {
@@ -282,3 +284,59 @@ int launch_lcn_variant_bwd(const float *x, const float *mu, const float *rstd, c
 }
 
 }  // namespace lc
+
+// ---------------------------------------------------------------------------------------------
+// lcn_variant_bwd_static: lcn_variant_bwd for callers that cannot allocate.  The scratch field of the two-stage
+// gradient (one float per statistic) lives in a file-scope device array instead of a caller's workspace.  Every GPU
+// the library runs on holds its own copy of the array at its own address until the process ends; the address is
+// looked up once per device, on the first call there, and only that pointer (never the array's name, which in host
+// code is a stand-in and no device address) is handed to the kernels.  Nothing in the array has to start at zero:
+// the first pass writes every element the second pass reads.
+namespace lc {
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)LCN_STATIC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char lcn_static_scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// the calling thread's current device's copy of the array; LC_OK or LC_EHIP
+int static_scratch(void **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_hip_error(e, "lcn_variant_bwd_static: hipGetDevice"); return LC_EHIP; }
+    if (dev < 0 || dev >= kMaxDevices) { set_error_text("lcn_variant_bwd_static: device index out of range"); return LC_EHIP; }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(lcn_static_scratch));
+        if (e != hipSuccess || !p) { set_hip_error(e, "lcn_variant_bwd_static: hipGetSymbolAddress"); return LC_EHIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LC_OK;
+}
+
+}  // namespace
+}  // namespace lc
+
+extern "C" int lcn_variant_bwd_static(const float *x, const float *mu, const float *rstd, const float *dy, float *dx,
+                                      int32_t B, int32_t H, int32_t W, int32_t C, int32_t ksize, float gauss_sigma,
+                                      uint32_t flags, void *hip_stream) {
+    using namespace lc;
+    if (int rc = check_lcn_variant_bwd_args(x, mu, rstd, dy, dx, B, H, W, C, ksize, gauss_sigma, flags)) return rc;
+    const size_t need = lcn_variant_scratch_bytes(B, H, W, C, flags);
+    if (need > kStaticScratchBytes) {
+        set_error_text("lcn_variant_bwd_static: the two-stage gradient of this map needs more scratch than the "
+                       "library's static array holds (LCN_STATIC_SCRATCH_BYTES); use lcn_variant_bwd with a workspace");
+        return LC_EWORKSPACE;
+    }
+    void *scratch = nullptr;
+    if (need > 0)
+        if (int rc = static_scratch(&scratch)) return rc;
+    return launch_lcn_variant_bwd(x, mu, rstd, dy, dx, B, H, W, C, ksize, gauss_sigma, flags, scratch, need,
+                                  (hipStream_t)hip_stream);
+}
+

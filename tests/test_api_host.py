@@ -112,3 +112,15 @@ def test_binding_rejects_cpu_tensors():
     y = torch.zeros(2, 6, 6, 4)
     with pytest.raises(ValueError):
         lc.lc_forward(g, x, w, None, 1.0, y)
+
+
+def test_static_scratch_entry_point_checks_on_the_host():
+    """lcn_variant_bwd_static: the checks of lcn_variant_bwd, and a map whose scratch exceeds the library's static
+    array is refused before anything touches the GPU, with a message that says why."""
+    L = lc.lib()
+    assert L.lcn_variant_bwd_static(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 5, 1.0, 1, None) == B.LC_EINVAL
+    assert L.lcn_variant_bwd_static(FAKE, FAKE, None, FAKE, FAKE + 16, 1, 8, 8, 4, 5, 1.0, 4, None) == B.LC_ENULL
+    assert L.lcn_variant_bwd_static(FAKE, FAKE, FAKE, FAKE, FAKE + 16, 1, 8, 8, 4, 5, 1.0, 9, None) == B.LC_EINVAL
+    assert L.lcn_variant_workspace_bytes(40, 64, 64, 64, 5) > B.LCN_STATIC_SCRATCH_BYTES
+    assert L.lcn_variant_bwd_static(FAKE, FAKE, FAKE, FAKE, FAKE + 16, 40, 64, 64, 64, 5, 1.0, 5, None) == B.LC_EWORKSPACE
+    assert b"static" in L.lc_last_error()
