@@ -119,6 +119,13 @@ def main() -> int:
         if events is not None and only is None:
             events[len(calls)].record(stream)
 
+    # The GPU's clocks need some tens of milliseconds of load to settle (the first steps of a process run 10-15 %
+    # slower): at least 60 ms of the same work, outside every timed region, then the warm-up steps asked for.
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < 60.0:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -152,12 +159,21 @@ def main() -> int:
 
     # roofline of the dominant kernel (largest share of the step)
     achieved = flop_pass / (dom_ms * 1e-3) / 1e12
-    traffic = None
+    # HBM bytes per launch: not measurable from inside this process (rocprofv3 --pmc counters); taken from the
+    # committed counter summary of the same kernels and workload, and labelled so
+    traffic, traffic_source = None, None
     tfile = os.path.join(ROOT, "profiles", "hbm_traffic_cfg3.json")
     if os.path.exists(tfile):
         traffic = json.load(open(tfile)).get(dom)
+        traffic_source = "profiles/hbm_traffic_cfg3.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, earlier run)"
     roofline = {"kernel": dom, "bound": "mfma", "launch_ms": round(dom_ms, 4), "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": traffic}
+                "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
+                "traffic_source": traffic_source}
+    # the dominant kernel as the per-kernel breakdown saw it and as the timed region saw it must agree
+    warnings = []
+    if abs(kern_ms[dom] - dom_ms) > 0.03 * dom_ms:
+        warnings.append(f"{dom}: {kern_ms[dom]:.4f} ms in the per-kernel breakdown against {dom_ms:.4f} ms in the "
+                        "timed region (more than 3 % apart: clocks not settled, or another process on the GPU)")
     nbytes = {
         "l2pool_fwd": 4 * (y.numel() + p.numel()),
         "lcn_fwd": 4 * (2 * p.numel() + 2 * mu.numel()),
@@ -189,6 +205,8 @@ def main() -> int:
         "kernels": kernels,
         "roofline": roofline,
     }
+    if warnings:
+        out["warnings"] = warnings
     del dw, dx, dyd, dp, dn, n, p, y, xd, wd
 
     # ---------------------------------------------------------------- workload cfg5: three-stage RICA step
@@ -209,90 +227,92 @@ def main() -> int:
 
 def bench_sae(lc, wl, np, torch, dev, steps, warmup):
     """cfg5: all three stages take one SGD step on the same mini-batch; stage s+1 reads
-    lcn_fwd(l2pool_fwd(h_s)).  Returns images/s of the whole three-stage step."""
-    stages = []
-    x1 = wl.pink_images(np.random.default_rng(0), 128, 128, 128, 3)
-    inp = dev(x1)
-    for si, key in enumerate(("cfg5_s1", "cfg5_s2", "cfg5_s3")):
-        g = wl.CONFIG_GEOM[key]
-        G = lc.geom(*g.as_tuple())
-        rw = np.random.default_rng(100 + si)
-        st = {
-            "g": g, "G": G, "x": inp,
-            "w": dev((rw.standard_normal((g.LH, g.LW, g.K, g.F)) / np.sqrt(g.K)).astype(np.float32)),
-            "b": torch.zeros((g.H, g.W, g.C), device="cuda"),
-            "alpha": torch.ones(1, device="cuda"), "cost": torch.zeros(1, device="cuda"),
-            "h": torch.empty((g.B, g.LH, g.LW, g.F), device="cuda"),
-            "ws": torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda"),
-            "p": torch.empty((g.B, g.LH - 2, g.LW - 2, g.F), device="cuda"),
-        }
-        st["n"] = torch.empty_like(st["p"])
-        st["mu"] = torch.empty(st["p"].shape[:3], device="cuda")
-        st["rstd"] = torch.empty_like(st["mu"])
-        stages.append(st)
-        inp = st["n"]
+    lcn_fwd(l2pool_fwd(h_s)).  Returns images/s of the whole three-stage step: the sequential schedule (flags 0 as
+    the workload states it, and with row projection and learned alpha), and the layer pipeline of Sec. 3.1 with a
+    forward-only copy of each stage refreshed every P steps."""
+    from paper_1502_03409_amd.pipeline import SaePipeline
 
-    def step():
-        for st in stages:
-            lc.sae_step(st["G"], st["x"], st["w"], st["b"], st["alpha"], wl.SAE_LAMBDA, wl.SAE_EPS, wl.SAE_LR, 0,
-                        st["h"], st["cost"], st["ws"])
-            lc.l2pool_fwd(st["h"], st["p"], wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS)
-            lc.lcn_fwd(st["p"], st["n"], st["mu"], st["rstd"], wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)
+    keys = ("cfg5_s1", "cfg5_s2", "cfg5_s3")
+    geoms = [wl.CONFIG_GEOM[k] for k in keys]
+    flop = sum(5 * g.flop_per_pass for g in geoms)
+    x1 = dev(wl.pink_images(np.random.default_rng(0), 128, 128, 128, 3))
 
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
-    flop = sum(5 * st["g"].flop_per_pass for st in stages)
-    tf = flop / (ms * 1e-3) / 1e12
-    res = {"workload": "cfg5: three-stage RICA step, B=128 128x128x3", "ms_per_step": round(ms, 4),
-           "images_per_s": round(128 / (ms * 1e-3), 1), "TFLOP/s": round(tf, 2),
-           "frac_fp32_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4), "steps": steps,
-           "costs": [round(float(st["cost"].item()), 4) for st in stages]}
+    def weights():
+        out = []
+        for si, g in enumerate(geoms):
+            rw = np.random.default_rng(100 + si)
+            out.append(dev((rw.standard_normal((g.LH, g.LW, g.K, g.F)) / np.sqrt(g.K)).astype(np.float32)))
+        return out
 
-    # The layer pipeline of Sec. 3.1 (semi-parallel training figure): stage s+1 trains on features that a forward-only
-    # copy of stage s produced a little earlier, so the stages do not wait for each other.  Here: the
-    # three stages run on three HIP streams (default priority) and stage s+1 reads the features stage s
-    # wrote one step before (two feature buffers per stage, one join of the streams per step).
-    streams = [torch.cuda.Stream() for _ in stages]
-    for st in stages:
-        st["n2"] = [st["n"], torch.empty_like(st["n"])]
-    for st in stages[:-1]:
-        st["n2"][1].copy_(st["n2"][0])
-    torch.cuda.synchronize()
+    def timed(step, join=None):
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < 60.0:      # settle the clocks on this very work
+            for _ in range(4):
+                step()
+            torch.cuda.synchronize()
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        if join:
+            join()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
 
-    def pstep(t):
-        for si, (st, sm) in enumerate(zip(stages, streams)):
-            xin = stages[0]["x"] if si == 0 else stages[si - 1]["n2"][(t - 1) % 2]
-            with torch.cuda.stream(sm):
-                lc.sae_step(st["G"], xin, st["w"], st["b"], st["alpha"], wl.SAE_LAMBDA, wl.SAE_EPS, wl.SAE_LR, 0,
+    def line(ms, extra=None):
+        tf = flop / (ms * 1e-3) / 1e12
+        e = {"ms_per_step": round(ms, 4), "images_per_s": round(128 / (ms * 1e-3), 1), "TFLOP/s": round(tf, 2),
+             "frac_fp32_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4)}
+        e.update(extra or {})
+        return e
+
+    # ---- sequential: every stage trains on the features its predecessor's training instance just produced
+    def sequential(flags):
+        # a learned alpha sums its gradient over every unit of a layer: it needs a far smaller step to stay stable
+        lr = wl.SAE_LR if not flags & 2 else 1e-2 * wl.SAE_LR
+        stages, inp = [], x1
+        for g, w in zip(geoms, weights()):
+            G = lc.geom(*g.as_tuple())
+            st = {"G": G, "x": inp, "w": w, "b": torch.zeros((g.H, g.W, g.C), device="cuda"),
+                  "alpha": torch.ones(1, device="cuda"), "cost": torch.zeros(1, device="cuda"),
+                  "h": torch.empty((g.B, g.LH, g.LW, g.F), device="cuda"),
+                  "ws": torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda"),
+                  "p": torch.empty((g.B, g.LH - 2, g.LW - 2, g.F), device="cuda")}
+            st["n"] = torch.empty_like(st["p"])
+            st["mu"] = torch.empty(st["p"].shape[:3], device="cuda")
+            st["rstd"] = torch.empty_like(st["mu"])
+            stages.append(st)
+            inp = st["n"]
+
+        def step():
+            for st in stages:
+                lc.sae_step(st["G"], st["x"], st["w"], st["b"], st["alpha"], wl.SAE_LAMBDA, wl.SAE_EPS, lr, flags,
                             st["h"], st["cost"], st["ws"])
                 lc.l2pool_fwd(st["h"], st["p"], wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS)
-                lc.lcn_fwd(st["p"], st["n2"][t % 2], st["mu"], st["rstd"], wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)
-        evs = []
-        for sm in streams:
-            e = torch.cuda.Event()
-            e.record(sm)
-            evs.append(e)
-        for sm in streams:
-            for e in evs:
-                sm.wait_event(e)
+                lc.lcn_fwd(st["p"], st["n"], st["mu"], st["rstd"], wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)
 
-    for t in range(warmup):
-        pstep(t)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(warmup, warmup + steps):
-        pstep(t)
-    torch.cuda.synchronize()
-    pms = (time.perf_counter() - t0) * 1e3 / steps
-    res["pipelined"] = {"schedule": "three streams, stage s+1 reads stage s's features of the previous step",
-                        "ms_per_step": round(pms, 4), "images_per_s": round(128 / (pms * 1e-3), 1),
-                        "TFLOP/s": round(flop / (pms * 1e-3) / 1e12, 2)}
+        ms = timed(step)
+        return line(ms, {"flags": flags, "lr": lr, "costs": [round(float(st["cost"].item()), 4) for st in stages]})
+
+    res = {"workload": "cfg5: three-stage RICA step, B=128 128x128x3", "steps": steps}
+    res.update(sequential(0))
+    res["project_rows_learn_alpha"] = sequential(3)
+
+    # ---- the layer pipeline of Sec. 3.1: training instance + forward-only instance per stage, one stream per stage
+    for P in (1, 10):
+        pipe = SaePipeline([lc.geom(*g.as_tuple()) for g in geoms], weights(),
+                           [torch.zeros((g.H, g.W, g.C), device="cuda") for g in geoms], [1.0] * 3, [wl.SAE_LAMBDA] * 3,
+                           sync_period=P, eps_sparse=wl.SAE_EPS, lr=wl.SAE_LR, flags=0,
+                           pool=(wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS), lcn=(wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS))
+        ms = timed(lambda: pipe.step(x1), pipe.join)
+        res[f"pipeline_sync{P}"] = line(ms, {
+            "schedule": f"one stream per stage; forward-only copy of stages 1-2 refreshed every {P} step(s) feeds the "
+                        "next stage (one more forward pass per stage than the sequential schedule; TFLOP/s still "
+                        "counts 5 passes per stage)"})
+        del pipe
+        torch.cuda.empty_cache()
     return res
 
 
@@ -378,6 +398,26 @@ def bench_others(lc, wl, torch, iters):
                                     "shape": dict(zip("BHWCRSF", g.as_tuple()))}
     del x, w, b, h, ws
     torch.cuda.empty_cache()
+
+    # RICA as Eq. 1 prints it (unit-norm rows, learned alpha) on the paper's first layer and on its dense last layer
+    # (lambda = 0.01 there)
+    for name, g, lam in (("paper_layer1_sae_step_project_alpha", wl.PAPER_LAYER1, wl.SAE_LAMBDA),
+                         ("paper_layer3_dense_sae_step_project_alpha", wl.PAPER_LAYER3, wl.SAE_LAMBDA_DENSE)):
+        G = lc.geom(*g.as_tuple())
+        x = torch.randn((g.B, g.H, g.W, g.C), device="cuda").abs()
+        w = torch.randn((g.LH, g.LW, g.K, g.F), device="cuda") / g.K ** 0.5
+        b = torch.zeros((g.H, g.W, g.C), device="cuda")
+        a, cost = torch.ones(1, device="cuda"), torch.zeros(1, device="cuda")
+        h = torch.empty((g.B, g.LH, g.LW, g.F), device="cuda")
+        ws = torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda")
+        f = lambda: lc.sae_step(G, x, w, b, a, lam, wl.SAE_EPS, 1e-5, 3, h, cost, ws)
+        ms = timed_ms(torch, stream, f, iters)
+        tf = 5 * g.flop_per_pass / (ms * 1e-3) / 1e12
+        res[name] = {"ms": round(ms, 3), "images_per_s": round(g.B / (ms * 1e-3), 1), "TFLOP/s": round(tf, 1),
+                     "frac_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4), "lambda": lam, "flags": 3,
+                     "shape": dict(zip("BHWCRSF", g.as_tuple()))}
+        del x, w, b, h, ws
+        torch.cuda.empty_cache()
 
     # the LCN variants at cfg3's shape (flags: 1 per-channel statistics, 2 zero-padded borders, 4 two stages)
     g = wl.CONFIG_GEOM["cfg3"]

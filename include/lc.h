@@ -95,6 +95,13 @@ size_t lc_workspace_bytes(const lc_geom_t *g, int op, int dtype);
 int lc_forward(const lc_geom_t *g, const void *x, const void *w, const float *bias, float alpha, float *y,
                int dtype, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* lc_forward with fp32 operands and the scale read from device memory when the kernel runs: alpha_dev points to
+ * one float on the device (4-byte aligned).  For a scale that lives on the device because it is being learned
+ * there (sae_step's alpha, Eq. 1): a forward-only copy of a layer can follow it without a round trip to the host.
+ * Everything else as lc_forward with dtype = LC_F32. */
+int lc_forward_dev_scale(const lc_geom_t *g, const float *x, const float *w, const float *bias,
+                         const float *alpha_dev, float *y, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Reconstruction through the transposed filters, the "W^T (.)" of Eq. 1 (also the gradient of
  * lc_forward with respect to x for alpha = 1):
  *   dx[b,p,q,c] = sum over locations (i,j) whose field contains (p,q), sum_f w[i,j,k,f] * dy[b,i,j,f]

@@ -24,7 +24,7 @@ LC_SAE_PROJECT_ROWS, LC_SAE_LEARN_ALPHA = 1, 2
 _STATUS = {0: "LC_OK", -1: "LC_EINVAL", -2: "LC_ENULL", -3: "LC_EALIGN", -4: "LC_EWORKSPACE",
            -5: "LC_EUNSUPPORTED", -6: "LC_EHIP", -7: "LC_EINTERNAL"}
 
-EXPORTS = ("lc_geom_derive", "lc_workspace_bytes", "lc_forward", "lc_backward_data", "lc_backward_weights",
+EXPORTS = ("lc_geom_derive", "lc_workspace_bytes", "lc_forward", "lc_forward_dev_scale", "lc_backward_data", "lc_backward_weights",
            "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
            "lcn_variant_bwd", "lcn_variant_bwd_static", "sae_step", "lc_last_error", "lc_plan_query")
 
@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
         L.lc_workspace_bytes.argtypes = [G, C.c_int, C.c_int]
         L.lc_workspace_bytes.restype = sz
         L.lc_forward.argtypes = [G, vp, vp, vp, f32, vp, C.c_int, vp, sz, vp]
+        L.lc_forward_dev_scale.argtypes = [G, vp, vp, vp, vp, vp, vp, sz, vp]
         L.lc_backward_data.argtypes = [G, vp, vp, vp, C.c_int, vp, sz, vp]
         L.lc_backward_weights.argtypes = [G, vp, vp, f32, vp, C.c_int, vp, sz, vp]
         L.l2pool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, f32, vp]
@@ -152,6 +153,15 @@ def lc_forward(g: LcGeom, x, w, bias, alpha: float, y, dtype: int = LC_F32, ws=N
         C.byref(g), _dev(x, (g.B, g.H, g.W, g.C), dt, "x"), _dev(w, (LH, LW, K, g.F), dt, "w"),
         _dev(bias, (LH, LW, g.F), torch.float32, "bias"), alpha, _dev(y, (g.B, LH, LW, g.F), torch.float32, "y"),
         dtype, wp, wb, _stream()))
+
+
+def lc_forward_dev_scale(g: LcGeom, x, w, bias, alpha_dev, y, ws=None) -> None:
+    LH, LW, K = geom_derive(g)
+    wp, wb = _ws(ws)
+    _check("lc_forward_dev_scale", lib().lc_forward_dev_scale(
+        C.byref(g), _dev(x, (g.B, g.H, g.W, g.C), torch.float32, "x"), _dev(w, (LH, LW, K, g.F), torch.float32, "w"),
+        _dev(bias, (LH, LW, g.F), torch.float32, "bias"), _dev(alpha_dev, None, torch.float32, "alpha_dev"),
+        _dev(y, (g.B, LH, LW, g.F), torch.float32, "y"), wp, wb, _stream()))
 
 
 def lc_backward_data(g: LcGeom, dy, w, dx, dtype: int = LC_F32, ws=None) -> None:

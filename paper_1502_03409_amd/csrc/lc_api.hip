@@ -124,6 +124,17 @@ int lc_forward(const lc_geom_t *g, const void *x, const void *w, const float *bi
                               ws_bytes);
 }
 
+int lc_forward_dev_scale(const lc_geom_t *g, const float *x, const float *w, const float *bias, const float *alpha_dev,
+                         float *y, void *ws, size_t ws_bytes, void *hip_stream) {
+    Geom q;
+    if (!make_geom(g, &q)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(w); LC_REQUIRE_PTR(y); LC_REQUIRE_PTR(alpha_dev);
+    LC_REQUIRE_ALIGNED(ws);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(w); LC_REQUIRE_ALIGNED(y); LC_REQUIRE_ALIGNED(bias);
+    if ((uintptr_t)alpha_dev & 3u) return LC_EALIGN;
+    return launch_forward_f32(q, x, w, bias, 1.f, alpha_dev, y, (hipStream_t)hip_stream, ws, ws_bytes);
+}
+
 int lc_backward_data(const lc_geom_t *g, const void *dy, const void *w, float *dx, int dtype, void *ws,
                      size_t ws_bytes, void *hip_stream) {
     (void)ws; (void)ws_bytes;

@@ -11,7 +11,7 @@
 namespace lc {
 
 // T: storage type of x and dy (float, or bf16 bit patterns widened on their way in).
-template <int MTW, int NT, typename T>
+template <int MTW, int NT, typename T, bool SSQ>
 __global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const T *__restrict__ x1,
                                                              const T *__restrict__ dy1,
                                                              const T *__restrict__ x2,
@@ -102,11 +102,11 @@ __global__ __launch_bounds__(256) void lc_bwd_weights_kernel(Geom g, const T *__
                 float v = gamma * acc[mt][nt][r];
                 if (beta != 0.f) v += beta * *o;
                 *o = v;
-                sq[nt] += v * v;
+                if (SSQ) sq[nt] += v * v;
             }
         }
     // per-filter sums of squares of the rows this wave stored: partial [location][k block][filter]
-    if (ssq) {
+    if (SSQ) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             float t = sq[nt];
@@ -139,7 +139,9 @@ __device__ __forceinline__ float vget(const typename VecT<N>::T &v, int i) {
     if constexpr (N == 1) return v; else return v[i];
 }
 
-template <int G, int VA, int NT, int PF, typename T = float>
+// SSQ: also leave, per location, block of patch elements and filter, the sum of squares of the values stored (a
+// code path of its own: the plain weight gradient carries none of it).
+template <int G, int VA, int NT, int PF, typename T = float, bool SSQ = false>
 __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kernel(Geom g, const T *__restrict__ x1,
                                                                   const T *__restrict__ dy1,
                                                                   const T *__restrict__ x2,
@@ -280,9 +282,9 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
                         for (int u = 0; u < NT; ++u) v[u] = gamma * acc[gg][t][u][r];
                     }
                     *(BV *)(ol + (size_t)k * g.F) = v;
-                    if (ssq) add_squares(v);
+                    if constexpr (SSQ) add_squares(v);
                 }
-        if (ssq) store_squares();
+        if constexpr (SSQ) store_squares();
         return;
     }
     // beta != 0 (the fused update), a code path of its own: the old values of four rows are requested together,
@@ -312,10 +314,10 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
                 }
                 v += beta * old[t];
                 *(BV *)(ol + (size_t)k * g.F) = v;
-                if (ssq) add_squares(v);
+                if constexpr (SSQ) add_squares(v);
             }
         }
-    if (ssq) store_squares();
+    if constexpr (SSQ) store_squares();
 }
 
 namespace {
@@ -343,8 +345,12 @@ int launch_one(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *d
     const LaunchPlan plan = make_plan("lc_bwd_weights_generic", {MTW, NT, (int)sizeof(T)}, {kblocks, (int)ntasks}, grid, 256, 0);
     if (int rc = check_backward_weights_generic(g, plan)) return rc;
     if (kblocks_out) *kblocks_out = kblocks;
-    LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_kernel<MTW, NT, T>), s, g, x1, dy1, x2, dy2, beta, gamma,
-              out, ssq, kblocks, (int)ntasks);
+    if (ssq)
+        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_kernel<MTW, NT, T, true>), s, g, x1, dy1, x2, dy2,
+                  beta, gamma, out, ssq, kblocks, (int)ntasks);
+    else
+        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_kernel<MTW, NT, T, false>), s, g, x1, dy1, x2, dy2,
+                  beta, gamma, out, ssq, kblocks, (int)ntasks);
     return LC_OK;
 }
 
@@ -400,8 +406,12 @@ int launch_fast(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *
     const LaunchPlan plan = make_plan("lc_bwd_weights_fast", {G, VA, NT, PF, (int)sizeof(T)}, {kblocks, (int)ntasks}, grid, 256, 0);
     if (int rc = check_backward_weights_fast(g, plan)) return rc;
     if (kblocks_out) *kblocks_out = kblocks;
-    LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_fast_kernel<G, VA, NT, PF, T>), s, g, x1, dy1, x2, dy2,
-              beta, gamma, out, ssq, kblocks, (int)ntasks);
+    if (ssq)
+        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_fast_kernel<G, VA, NT, PF, T, true>), s, g, x1, dy1,
+                  x2, dy2, beta, gamma, out, ssq, kblocks, (int)ntasks);
+    else
+        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_fast_kernel<G, VA, NT, PF, T, false>), s, g, x1, dy1,
+                  x2, dy2, beta, gamma, out, ssq, kblocks, (int)ntasks);
     return LC_OK;
 }
 
