@@ -158,7 +158,20 @@ __global__ __launch_bounds__(256) void lc_bwd_data_kernel(Geom g, const T *__res
 // lane (n,kk) loads w[k(n)][fh*16 + 4kk .. +3] as one dwordx4, and lane (m,kk) reads the same four f
 // of image m from LDS, so component t of both vectors is contraction index 4kk+t of MFMA number t.
 // Fields outside the grid are staged as zeros (their weights are read from a clamped, valid address),
-// so the inner loop has no branches.
+// so the inner loop has no divergent branches.
+//
+// The loop is written so that it holds next to no vector ALU instructions.  A SIMD issues matrix and vector ALU
+// instructions through one port, and a wave whose next MFMA waits for the matrix pipe holds that port: address
+// arithmetic of the other wave on the SIMD does not slip in between, it runs when the MFMAs are through and
+// its time adds to theirs (measured with cycle stamps: a step of 16 MFMAs per wave took 640 cycles where 512
+// were matrix work, and the staging between chunks another 2000).  Hence
+//   - the wave index is read into a scalar register, so the weight pointers (the same for every lane up to the
+//     lane's own offset kn) are scalar arithmetic and the loads take a scalar base plus a 32-bit lane offset;
+//   - where a lane's staging slots lie, in global memory relative to the chunk and in LDS, does not depend
+//     on the chunk: both offsets are worked out once; a slot that stages nothing (a field column outside the grid,
+//     an image past the batch) loads from the chunk's first vector and writes to a dump vector of the lane's own
+//     behind the buffer, and its place in the buffer is zeroed once, before the loop;
+//   - the LDS reads of a step differ from those of the next by a compile-time offset.
 template <int MT, int NT, int NCELL, int AP, int NW = 4, typename T = float>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_kernel(
     Geom g, const T *__restrict__ dy, const T *__restrict__ w, float *__restrict__ dx, int strips_per_row,
@@ -166,14 +179,17 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     typedef typename RawVec<T, 4>::V XV;      // four consecutive dy or w values as loaded (fp32, or bf16 bit patterns)
     typedef const __attribute__((address_space(1))) XV *g4_ptr;
     typedef const __attribute__((address_space(1))) T *gf_ptr;
+    typedef const __attribute__((address_space(1))) char *gb_ptr;
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 4;   // R4: 4-element vectors per image and chunk
     constexpr int NTHR = 64 * NW;                                   // NW waves: NCELL cells x NW/NCELL value blocks
     constexpr int NSLOT = (BT * R4 + NTHR - 1) / NTHR;
+    constexpr int ES = sizeof(T);
     extern __shared__ __attribute__((aligned(16))) float dys_f32[];
     T *dys = (T *)dys_f32;                    // staged dy in the operands' own storage type; RS counts elements
     constexpr bool kHalf = sizeof(T) == 2;    // bf16: one 16x16x16 bf16 MFMA takes the place of four fp32 steps
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = lane & 15, kk = lane >> 4;
     const int SC = g.S * g.C, NCV = g.S * SC;
     // Work order.  Cell rows that all AP field rows cover cost the same and come first: each XCD walks a
@@ -203,13 +219,13 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     const int nfh = g.F >> 4;
 
     // cell values this lane supplies weights for / stores
-    int kn[NT];
+    unsigned kn[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int nn = n0 + nt * 16 + m;
         const int nc = nn < NCV ? nn : 0;
         const int dr = nc / SC;
-        kn[nt] = (dr * g.RC + (nc - dr * SC)) * g.F + 4 * kk;    // float offset inside a field's K x F matrix
+        kn[nt] = (unsigned)((dr * g.RC + (nc - dr * SC)) * g.F + 4 * kk) * ES;    // byte offset inside a field's K x F matrix
     }
 
     f32x4 acc[MT][NT];
@@ -224,50 +240,59 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
     const int jlo = wi0 - (AP - 1);
     const size_t dyimg = (size_t)g.L * g.F;
 
-    const int v0 = tid % R4, bq0 = tid / R4;
+    // LDS: two halves, each a buffer of BT rows of RS elements followed by one dump vector per lane
+    const int HALF = BT * RS + NTHR * 4;
     constexpr int DV = NTHR % R4, DB = NTHR / R4;
-    XV st[NSLOT];
-    auto stage_load = [&](int c) {
-        const int a = a_lo + c / nfh, fh = c - (c / nfh) * nfh;
-        const T *base = dy + (size_t)b0 * dyimg + (size_t)((ri - a) * g.LW) * g.F + fh * 16;
-        int v = v0, b = bq0;
+    unsigned goff[NSLOT], loff[NSLOT];   // byte offsets of a slot: from the chunk's first vector / inside a half
+    {
+        int v = tid % R4, b = tid / R4;
 #pragma unroll
         for (int q = 0; q < NSLOT; ++q) {
             const int j = jlo + (v >> 2);
-            XV t = XV{};
-            if (b < BT && b0 + b < g.B && j >= 0 && j < g.LW)
-                t = *(g4_ptr)(base + (size_t)b * dyimg + j * g.F + (v & 3) * 4);
-            st[q] = t;
-            v += DV; b += DB;
-            if (v >= R4) { v -= R4; ++b; }
-        }
-    };
-    auto stage_store = [&](int buf) {
-        int v = v0, b = bq0;
-#pragma unroll
-        for (int q = 0; q < NSLOT; ++q) {
-            if (b < BT) {
-                // two 8-byte stores: 16-byte LDS stores of a row-major tile run into bank conflicts
-                T *dst = dys + buf * BT * RS + b * RS + v * 4;
-                if constexpr (kHalf) {
-                    *(XV *)dst = st[q];
-                } else {
-                    *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
-                    *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
-                }
+            const bool ok = b < BT && b0 + b < g.B && j >= 0 && j < g.LW;
+            goff[q] = ok ? (unsigned)(((size_t)b * dyimg + (size_t)j * g.F + (v & 3) * 4) * ES) : 0u;
+            loff[q] = (ok ? (unsigned)(b * RS + v * 4) : (unsigned)(BT * RS + tid * 4)) * ES;
+            if (b < BT && !ok) {
+                *(XV *)(dys + b * RS + v * 4) = XV{};
+                *(XV *)(dys + HALF + b * RS + v * 4) = XV{};
             }
             v += DV; b += DB;
             if (v >= R4) { v -= R4; ++b; }
         }
+    }
+    XV st[NSLOT];
+    // the chunk's first vector: image b0, field row ri - a, field column 0, filters fh*16..
+    auto chunk_base = [&](int a, int fh) -> gf_ptr {
+        return (gf_ptr)dy + (size_t)b0 * dyimg + (size_t)((ri - a) * g.LW) * g.F + fh * 16;
     };
-    // weights of step (chunk c, a'): field (ri-a, wi-a') clamped into the grid
-    auto wbase = [&](int c, int ap) -> gf_ptr {
-        const int a = a_lo + c / nfh, fh = c - (c / nfh) * nfh;
+    auto stage_load = [&](gf_ptr base) {
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) st[q] = *(g4_ptr)((gb_ptr)base + goff[q]);
+    };
+    auto stage_store = [&](int buf) {
+        T *half = dys + buf * HALF;
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) {
+            // two 8-byte stores: 16-byte LDS stores of a row-major tile run into bank conflicts
+            T *dst = (T *)((char *)half + loff[q]);
+            if constexpr (kHalf) {
+                *(XV *)dst = st[q];
+            } else {
+                *(f32x2 *)dst = (f32x2){st[q][0], st[q][1]};
+                *(f32x2 *)(dst + 2) = (f32x2){st[q][2], st[q][3]};
+            }
+        }
+    };
+    // weights of step a' of chunk (a, fh): field (ri-a, wi-a') clamped into the grid; the same for every lane
+    auto wbase = [&](int a, int fh, int ap) -> gf_ptr {
         int j = wi - ap;
         j = j < 0 ? 0 : (j >= g.LW ? g.LW - 1 : j);
         return (gf_ptr)w + ((size_t)((ri - a) * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F +
                fh * 16;
     };
+    // chunk c is (a, fh) = (a_lo + c / nfh, c % nfh), counted along rather than divided out
+    struct Chunk { int a, fh; };
+    auto after = [&](Chunk c) -> Chunk { return c.fh + 1 == nfh ? Chunk{c.a + 1, 0} : Chunk{c.a, c.fh + 1}; };
 
     if (nchunks > 0) {
         // weight ring: slot a' holds the weights of step a' of the current chunk and is refilled, right
@@ -275,51 +300,291 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
         XV wb[AP][NT];
 #pragma unroll
         for (int ap = 0; ap < AP; ++ap) {
-            gf_ptr p0 = wbase(0, ap);
+            gf_ptr p0 = wbase(a_lo, 0, ap);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = *(g4_ptr)(p0 + kn[nt]);
+            for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = *(g4_ptr)((gb_ptr)p0 + kn[nt]);
         }
         // two LDS buffers: chunk c is read from buffer c & 1 while chunk c+1, whose loads were issued a whole
         // chunk earlier, goes from the staging registers into the other one; one barrier per chunk
-        const int BUF = BT * RS;
-        stage_load(0);
+        Chunk c0 = {a_lo, 0}, c1 = after(c0), c2 = after(c1);     // chunks c, c+1, c+2
+        stage_load(chunk_base(c0.a, c0.fh));
         stage_store(0);
-        if (nchunks > 1) stage_load(1);
+        if (nchunks > 1) stage_load(chunk_base(c1.a, c1.fh));
         __syncthreads();
+        // the lane's dy vector of image m + 16 mt under the wave's cell at step a' lies at
+        // abase + mt*16*RS + (AP-1-a')*16: field column wc - a' + AP - 1 of the staged strip
+        const T *abase = dys + m * RS + 4 * kk + wc * 16;
         for (int c = 0; c < nchunks; ++c) {
-            const T *arow = dys + (c & 1) * BUF + m * RS + 4 * kk;
-            const int cn = c + 1 < nchunks ? c + 1 : c;
+            const T *arow = abase + (c & 1) * HALF;
+            const bool more = c + 1 < nchunks;
+            const Chunk cw = more ? c1 : c0;      // the last chunk reloads its own weights: a valid address, the values are not used
+            // The A operands of step a'+1 are read from LDS before the MFMAs of step a': left to itself the compiler
+            // issues every LDS read right in front of the MFMAs that use it and waits for it there.
+            XV av[2][MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) av[0][mt] = *(const XV *)(arow + mt * 16 * RS + (AP - 1) * 16);
 #pragma unroll
             for (int ap = 0; ap < AP; ++ap) {
-                const int js = wc - ap + AP - 1;
-                // a field column outside the grid contributes nothing: skip its MFMAs (uniform over the wave)
+                if (ap + 1 < AP) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        av[(ap + 1) & 1][mt] = *(const XV *)(arow + mt * 16 * RS + (AP - 2 - ap) * 16);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // a field column outside the grid contributes nothing: skip its MFMAs (the same for the whole wave)
                 if (wi - ap >= 0 && wi - ap < g.LW) {
+                    if constexpr (kHalf) {
+                        // the vectors already are the operands: four consecutive f of image m / of cell value n
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const XV av = *(const XV *)(arow + mt * 16 * RS + js * 16);
-                        if constexpr (kHalf) {
-                            // the vectors already are the operands: four consecutive f of image m / of cell value n
+                        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16_bf16(av, wb[ap][nt], acc[mt][nt]);
-                        } else {
+                            for (int nt = 0; nt < NT; ++nt)
+                                acc[mt][nt] = mfma16_bf16(av[ap & 1][mt], wb[ap][nt], acc[mt][nt]);
+                    } else {
 #pragma unroll
-                            for (int t = 0; t < 4; ++t)
+                        for (int t = 0; t < 4; ++t)
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                                 for (int nt = 0; nt < NT; ++nt)
-                                    acc[mt][nt] = mfma16(av[t], wb[ap][nt][t], acc[mt][nt]);
-                        }
+                                    acc[mt][nt] = mfma16(av[ap & 1][mt][t], wb[ap][nt][t], acc[mt][nt]);
                     }
                 }
-                gf_ptr pn = wbase(cn, ap);
+                gf_ptr pn = wbase(cw.a, cw.fh, ap);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = *(g4_ptr)(pn + kn[nt]);
-                __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x80);
+                for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = *(g4_ptr)((gb_ptr)pn + kn[nt]);
+                __builtin_amdgcn_sched_barrier(0);
             }
             // the other buffer was last read in chunk c-1, which every wave left at the previous barrier
-            if (c + 1 < nchunks) stage_store((c + 1) & 1);
-            if (c + 2 < nchunks) stage_load(c + 2);
+            if (more) stage_store((c + 1) & 1);
+            if (c + 2 < nchunks) stage_load(chunk_base(c2.a, c2.fh));
+            c0 = c1; c1 = c2; c2 = after(c2);
             __syncthreads();
         }
+    }
+
+    if (wi * g.S >= g.W) return;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int nn = n0 + nt * 16 + m;
+        if (nn >= NCV) continue;
+        const int dr = nn / SC, rem = nn - dr * SC;
+        const int row = ri * g.S + dr, col = wi * g.S + rem / g.C;
+        if (row >= g.H || col >= g.W) continue;
+        const size_t pix = ((size_t)row * g.W + wi * g.S) * g.C + rem;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int b = b0 + mt * 16 + 4 * kk + r;
+                if (b < g.B) dx[(size_t)b * g.H * g.W * g.C + pix] = acc[mt][nt][r];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The pipelined kernel for fp32 operands with a hand-kept memory schedule.  Same decomposition, chunks and steps as
+// lc_bwd_data_fast_kernel; what differs is how the operands travel:
+//   - dy goes from global memory straight into LDS (16 bytes per lane, lane i of a wave's load lands 16 i bytes past
+//     the load's LDS base): no staging registers, no LDS stores, no address arithmetic per chunk.  An LDS buffer is the
+//     batch tile's rows one after the other, each row JW field columns x 16 filters plus one pad vector (row stride
+//     16 bytes past a multiple of 64: the 16 rows a wave reads at once start four banks apart), so vector P of the
+//     buffer belongs to lane P % NTHR of load P / NTHR, and where that lane reads from does not depend on the chunk.
+//     A lane whose vector stages nothing (a field column outside the grid, an image past the batch) is switched off
+//     for the load and its vector is zeroed once, before the loop; lanes on pad vectors and past the last row load
+//     the chunk's first vector into space nobody reads, so every wave's every load has a live lane and the number
+//     of loads in flight is the same for all waves;
+//   - the loads are inline assembly, which the compiler's wait insertion does not see, and every wait on them is
+//     written out below.  The memory counter counts loads in program order, and the order is fixed:
+//         chunk c:  [NSLOT dy loads of chunk c+1]  then per step a': wait, MFMAs, [NT weight loads of step a', chunk c+1]
+//     so at step a' the weights of (c, a') are followed by AP*NT - NT + NSLOT younger loads (those may stay in flight),
+//     and at the chunk's end the dy loads are followed by AP*NT: each wait is for a load issued a whole chunk
+//     earlier.  The compiler, not knowing the order of chunks, waits for all but the seven youngest loads at every step,
+//     which at the first steps of a chunk are the dy loads just issued.
+// The last chunk loads its own dy and weights once more (valid addresses; the values are not used) so that the
+// counts hold in every iteration.
+typedef const __attribute__((address_space(1))) char *gbyte_ptr;
+
+// 16 bytes per lane from base + off straight into LDS at lds_addr + 16 * lane (lds_addr: byte address, wave-uniform)
+__device__ __forceinline__ void load_lds16(gbyte_ptr base, unsigned off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(off), "s"(base)
+                 : "memory");
+}
+// 16 bytes per lane into registers; the value may be used only after wait_loads has been called on it
+__device__ __forceinline__ f32x4 load_nowait16(gbyte_ptr base, unsigned off) {
+    f32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
+    return v;
+}
+// wait until at most N of the loads issued so far are still in flight; v is a value that load delivers
+template <int N>
+__device__ __forceinline__ void wait_loads(f32x4 &v) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int MT, int NT, int NCELL, int AP, int NW>
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_direct_kernel(
+    Geom g, const float *__restrict__ dy, const float *__restrict__ w, float *__restrict__ dx, int strips_per_row,
+    int nbt) {
+    constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 4;   // R4: 4-filter vectors per image and chunk
+    constexpr int RV = R4 + 1, RS = RV * 4;                          // LDS row: R4 vectors and a pad; RS floats
+    constexpr int NTHR = 64 * NW;                                   // NW waves: NCELL cells x NW/NCELL value blocks
+    constexpr int NV = BT * RV, NSLOT = (NV + NTHR - 1) / NTHR;     // vectors per buffer, loads per lane and chunk
+    constexpr int BUF = NSLOT * NTHR * 4;                           // floats per buffer, the last load's slack included
+    static_assert(RV <= 64, "every wave's load must cover a pad vector");
+    static_assert(AP * NT - NT + NSLOT <= 63 && AP * NT <= 63, "the memory counter has six bits");
+    extern __shared__ __attribute__((aligned(16))) float dys[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 15, kk = lane >> 4;
+    const int SC = g.S * g.C, NCV = g.S * SC;
+    // work order as in lc_bwd_data_fast_kernel: full-cost cell rows first, a contiguous range per XCD with the batch
+    // tiles of a strip next to each other; the cheaper rows at the top and bottom edge last, dealt out evenly
+    const int r_lo = AP - 1, n_in = g.LH > r_lo ? g.LH - r_lo : 0;
+    const int per_row = strips_per_row * nbt, n_first = n_in * per_row;
+    int ri, t_id;
+    if ((int)blockIdx.x < n_first) {
+        t_id = remap_xcd(blockIdx.x, n_first);
+        ri = r_lo + t_id / per_row;
+    } else if (n_in > 0) {
+        t_id = blockIdx.x - n_first;
+        const int rb = t_id / per_row;
+        ri = rb < r_lo ? rb : g.LH + (rb - r_lo);
+    } else {
+        t_id = remap_xcd(blockIdx.x, gridDim.x);
+        ri = t_id / per_row;
+    }
+    const int wi0 = ((t_id / nbt) % strips_per_row) * NCELL;
+    const int b0 = (t_id % nbt) * BT;
+    const int wc = wave % NCELL;
+    const int wi = wi0 + wc;
+    const int n0 = (blockIdx.y * (NW / NCELL) + wave / NCELL) * NT * 16;
+    const int nfh = g.F >> 4;
+
+    // cell values this lane supplies weights for / stores
+    unsigned kn[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int nn = n0 + nt * 16 + m;
+        const int nc = nn < NCV ? nn : 0;
+        const int dr = nc / SC;
+        kn[nt] = (unsigned)((dr * g.RC + (nc - dr * SC)) * g.F + 4 * kk) * 4u;    // byte offset inside a field's K x F matrix
+    }
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // chunks: (a, fh) with a valid field row i = ri - a
+    const int a_lo = max(0, ri - (g.LH - 1)), a_hi = min(AP - 1, ri);   // inclusive; empty if a_lo > a_hi
+    const int nchunks = a_hi >= a_lo ? (a_hi - a_lo + 1) * nfh : 0;
+    const int jlo = wi0 - (AP - 1);
+    const size_t dyimg = (size_t)g.L * g.F;
+
+    if (nchunks > 0) {
+        // weights of step a' of chunk (a, fh): field (ri-a, wi-a') clamped into the grid; the same for every lane
+        auto wbase = [&](int a, int fh, int ap) -> gbyte_ptr {
+            int j = wi - ap;
+            j = j < 0 ? 0 : (j >= g.LW ? g.LW - 1 : j);
+            return (gbyte_ptr)(w + ((size_t)((ri - a) * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F +
+                               fh * 16);
+        };
+        // weight ring: slot a' holds the weights of step a' of the current chunk and is refilled, right
+        // after its use, with step a' of the next chunk: loads run one whole chunk ahead of the MFMAs
+        f32x4 wb[AP][NT];
+#pragma unroll
+        for (int ap = 0; ap < AP; ++ap) {
+            gbyte_ptr p0 = wbase(a_lo, 0, ap);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait16(p0, kn[nt]);
+        }
+
+        // where this lane's vector of load q comes from (bytes past the chunk's first vector), whether it loads at
+        // all; vectors that stage nothing are zeroed in both buffers
+        unsigned goff[NSLOT];
+        bool live[NSLOT];
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) {
+            const int P = q * NTHR + tid, b = P / RV, v = P - b * RV;
+            const int j = jlo + (v >> 2);
+            const bool data = P < NV && v < R4;
+            const bool ok = data && b0 + b < g.B && j >= 0 && j < g.LW;
+            goff[q] = ok ? (unsigned)(((size_t)b * dyimg + (size_t)j * g.F + (v & 3) * 4) * 4) : 0u;
+            live[q] = ok || !data;
+            if (data && !ok) {
+                *(f32x4 *)(dys + P * 4) = (f32x4){0.f, 0.f, 0.f, 0.f};
+                *(f32x4 *)(dys + BUF + P * 4) = (f32x4){0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) float *)dys + wave * 64 * 16;
+        // chunk c is (a, fh) = (a_lo + c / nfh, c % nfh), counted along rather than divided out
+        struct Chunk { int a, fh; };
+        auto after = [&](Chunk c) -> Chunk { return c.fh + 1 == nfh ? Chunk{c.a + 1, 0} : Chunk{c.a, c.fh + 1}; };
+        auto stage = [&](Chunk ch, int buf) {
+            gbyte_ptr base = (gbyte_ptr)(dy + (size_t)b0 * dyimg + (size_t)((ri - ch.a) * g.LW) * g.F + ch.fh * 16);
+            const unsigned l = lds0 + buf * (BUF * 4);
+#pragma unroll
+            for (int q = 0; q < NSLOT; ++q)
+                if (live[q]) load_lds16(base, goff[q], l + q * (NTHR * 16));
+        };
+
+        Chunk c0 = {a_lo, 0}, c1 = after(c0);     // chunks c and c+1
+        stage(c0, 0);
+        wait_loads<0>();
+        __syncthreads();
+        // the lane's dy vector of image m + 16 mt under the wave's cell at step a' lies at
+        // abase + mt*16*RS + (AP-1-a')*16: field column wc - a' + AP - 1 of the staged strip
+        const float *abase = dys + m * RS + 4 * kk + wc * 16;
+        for (int c = 0; c < nchunks; ++c) {
+            const Chunk cn = c + 1 < nchunks ? c1 : c0;
+            stage(cn, (c + 1) & 1);
+            const float *arow = abase + (c & 1) * BUF;
+            f32x4 av[2][MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) av[0][mt] = *(const f32x4 *)(arow + mt * 16 * RS + (AP - 1) * 16);
+#pragma unroll
+            for (int ap = 0; ap < AP; ++ap) {
+                if (ap + 1 < AP) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        av[(ap + 1) & 1][mt] = *(const f32x4 *)(arow + mt * 16 * RS + (AP - 2 - ap) * 16);
+                }
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) wait_loads<AP * NT - NT + NSLOT>(wb[ap][nt]);
+                __builtin_amdgcn_sched_barrier(0);
+                // a field column outside the grid contributes nothing: skip its MFMAs (the same for the whole wave)
+                if (wi - ap >= 0 && wi - ap < g.LW) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int nt = 0; nt < NT; ++nt)
+                                acc[mt][nt] = mfma16(av[ap & 1][mt][t], wb[ap][nt][t], acc[mt][nt]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                gbyte_ptr pn = wbase(cn.a, cn.fh, ap);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait16(pn, kn[nt]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // this lane's dy loads of the next chunk have landed (the AP*NT weight loads behind them may fly on);
+            // behind the barrier, everybody's have, and everybody is through with the buffer the chunk after next overwrites
+            wait_loads<AP * NT>();
+            c0 = c1; c1 = after(c1);
+            __syncthreads();
+        }
+        // the weights loaded last are not used: they must have landed before their registers are given up
+#pragma unroll
+        for (int ap = 0; ap < AP; ++ap)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) wait_loads<0>(wb[ap][nt]);
     }
 
     if (wi * g.S >= g.W) return;
@@ -589,15 +854,27 @@ int check_backward_data_fast(const Geom &g, const LaunchPlan &p) {
     const int MT = p.tparam[0], NT = p.tparam[1], NCELL = p.tparam[2], AP = p.tparam[3], NW = p.tparam[4];
     const int ES = p.tparam[5], LINE = p.tparam[6];
     const int strips = p.arg[0], RS = p.arg[1], nbt = p.arg[2];
-    LC_PLAN_REQUIRE(p, NCELL > 0 && NW % NCELL == 0 && (ES == 4 || ES == 2) && (LINE == 0 || (ES == 4 && NW == 4)));
-    const int BT = 16 * MT, JW = NCELL + AP - 1, FCH = LINE ? 32 : 16, NCV = g.S * g.S * g.C;
+    LC_PLAN_REQUIRE(p, NCELL > 0 && NW % NCELL == 0 && (ES == 4 || ES == 2) &&
+                           (LINE == 0 || (LINE == 1 && ES == 4 && NW == 4) || (LINE == 2 && ES == 4)));
+    const int BT = 16 * MT, JW = NCELL + AP - 1, FCH = LINE == 1 ? 32 : 16, NCV = g.S * g.S * g.C;
     const int CH = ceil_div(g.H, g.S), CW = ceil_div(g.W, g.S);
     LC_PLAN_REQUIRE(p, (int)p.block == 64 * NW);
     // fields tile the cells exactly, AP of them across a cell; filters in whole chunks
     LC_PLAN_REQUIRE(p, g.R % g.S == 0 && AP == g.R / g.S && g.F % FCH == 0);
     // staged dy: JW field columns of FCH filters per image in one LDS row, whole vectors of four
     LC_PLAN_REQUIRE(p, RS >= JW * FCH && RS % 4 == 0);
-    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)(LINE ? 1 : 2) * BT * RS * ES);
+    if (LINE == 0)        // two halves: a buffer and one dump vector per lane
+        LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)2 * (BT * RS + 64 * NW * 4) * ES);
+    else if (LINE == 1)   // one buffer
+        LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)BT * RS * ES);
+    else {                // two buffers of whole loads (16 bytes per lane); a row is JW*4 vectors and a pad
+        const int nslot = ceil_div(BT * (JW * 4 + 1), 64 * NW);
+        LC_PLAN_REQUIRE(p, RS == (JW * 4 + 1) * 4 && JW * 4 + 1 <= 64 && p.lds_bytes >= (size_t)2 * nslot * 64 * NW * 16);
+        // the kernel's waits count the loads in flight: a six-bit counter
+        LC_PLAN_REQUIRE(p, AP * NT - NT + nslot <= 63 && AP * NT <= 63);
+    }
+    // pipelined kernels: 32-bit byte offsets of a lane's staging slots from the chunk's first vector
+    LC_PLAN_REQUIRE(p, LINE == 1 || (long long)BT * g.L * g.F * ES < (1LL << 32));
     // 32-bit offsets inside a field's K x F matrix (kn) and inside one image's dy (j * F)
     LC_PLAN_REQUIRE(p, (long long)g.K * g.F < (1LL << 31) && (long long)g.LW * g.F < (1LL << 31));
     // every cell row (the rows past the last covered one get zeros), every strip of cells, every batch tile
@@ -629,15 +906,36 @@ int launch_line(const Geom &g, const float *dy, const float *w, float *dx, hipSt
     return LC_OK;
 }
 
+// fp32 operands: the kernel with dy loaded straight into LDS
+template <int MT, int NT, int NCELL, int AP, int NW>
+int launch_direct(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
+    constexpr int BT = 16 * MT, JW = NCELL + AP - 1, RV = JW * 4 + 1, NTHR = 64 * NW;
+    constexpr int NSLOT = (BT * RV + NTHR - 1) / NTHR;
+    const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
+    const int NCV = g.S * g.S * g.C;
+    const size_t lds = (size_t)2 * NSLOT * NTHR * 16;
+    auto kern = lc_bwd_data_direct_kernel<MT, NT, NCELL, AP, NW>;
+    const int strips = (CW + NCELL - 1) / NCELL;
+    const int nblk = (NW / NCELL) * NT * 16;
+    const int nbt = (g.B + BT - 1) / BT;
+    dim3 grid(strips * CH * nbt, (NCV + nblk - 1) / nblk);
+    const LaunchPlan plan = make_plan("lc_bwd_data_direct", {MT, NT, NCELL, AP, NW, 4, 2, AP}, {strips, RV * 4, nbt}, grid,
+                                      NTHR, lds);
+    if (int rc = check_backward_data_fast(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_backward_data launch", kern, s, g, dy, w, dx, strips, nbt);
+    return LC_OK;
+}
+
 template <int MT, int NT, int NCELL, int AP, int NW = 4, typename T>
 int launch_fast(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s) {
+    if constexpr (sizeof(T) == 4) return launch_direct<MT, NT, NCELL, AP, NW>(g, dy, w, dx, s);
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int NCV = g.S * g.S * g.C;
     // row stride: 16 bytes past a multiple of 128 bytes, so that the 16 image rows a wave reads at once start
     // four banks apart (fp32: 16-byte reads of 4 f; bf16: 8-byte reads)
     const int RS = sizeof(T) == 2 ? ((JW * 16 + 63) / 64) * 64 + 8 : ((JW * 16 + 31) / 32) * 32 + 4;
-    const size_t lds = (size_t)2 * BT * RS * sizeof(T);          // two buffers
+    const size_t lds = (size_t)2 * (BT * RS + 64 * NW * 4) * sizeof(T);   // two halves: buffer + a dump vector per lane
     auto kern = lc_bwd_data_fast_kernel<MT, NT, NCELL, AP, NW, T>;
     const int strips = (CW + NCELL - 1) / NCELL;
     const int nblk = (NW / NCELL) * NT * 16;
@@ -650,13 +948,16 @@ int launch_fast(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s
     return LC_OK;
 }
 
+// The pipelined kernels address a batch tile's dy (64 images) with 32-bit byte offsets.
+inline bool pipelined_offsets_fit(const Geom &g) { return (long long)64 * g.L * g.F * 4 < (1LL << 32); }
+
 // The pipelined kernel for filters in blocks of 16 and fields that tile the cells exactly; *done tells whether a
 // kernel was launched.  T = float or bf16_t (bf16 storage widened on the way in).
 template <typename T>
 int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float *dx, hipStream_t s, bool *done) {
     *done = false;
     // pipelined kernel: filters in blocks of 16, fields that tile the cells exactly, a batch tile of 64 images
-    if (g.F % 16 == 0 && g.R % g.S == 0 && g.B > 32) {
+    if (g.F % 16 == 0 && g.R % g.S == 0 && g.B > 32 && pipelined_offsets_fit(g)) {
         const int ap = g.R / g.S, ntt = (g.S * g.S * g.C + 15) / 16;   // steps per chunk, tiles of 16 cell values
 #define LC_BD(AP_, NT_, NCELL_) do { *done = true; return launch_fast<4, NT_, NCELL_, AP_>(g, dy, w, dx, s); } while (0)
         if (ap == 2) {
@@ -727,7 +1028,7 @@ int launch_backward_data_f32(const Geom &g, const float *dy, const float *w, flo
 
 // shapes the pipelined kernel takes (on bf16 storage it multiplies with bf16 matrix instructions)
 bool backward_data_bf16_pipelined_supported(const Geom &g) {
-    if (!(g.F % 16 == 0 && g.R % g.S == 0 && g.B > 32)) return false;
+    if (!(g.F % 16 == 0 && g.R % g.S == 0 && g.B > 32 && pipelined_offsets_fit(g))) return false;
     const int ap = g.R / g.S;
     return ap == 2 || ap == 3 || ap == 4 || ap == 5 || ap == 8;
 }

@@ -170,12 +170,23 @@ def covered_backward_data_fast(g, p):
 
 
 def check_backward_data_fast(g, p):
-    MT, NT, NCELL, AP, NW, ES, LINE = p["tparam"][:7]
+    # KIND 0: pipelined kernel staging through registers (bf16 storage); 1: whole-line chunks; 2: dy straight into LDS
+    MT, NT, NCELL, AP, NW, ES, KIND = p["tparam"][:7]
     strips, RS, nbt = p["arg"][:3]
-    BT, JW, FCH = 16 * MT, NCELL + AP - 1, 32 if LINE else 16
+    BT, JW, FCH = 16 * MT, NCELL + AP - 1, 32 if KIND == 1 else 16
     CH, CW, NCV = cdiv(g.H, g.S), cdiv(g.W, g.S), g.S * g.S * g.C
     assert g.R % g.S == 0 and AP == g.R // g.S and g.F % FCH == 0
-    assert RS >= JW * FCH and p["lds_bytes"] == (1 if LINE else 2) * BT * RS * ES
+    assert RS >= JW * FCH
+    if KIND == 0:      # two halves of a buffer plus one dump vector of four elements per lane
+        assert p["lds_bytes"] == 2 * (BT * RS + 64 * NW * 4) * ES
+    elif KIND == 1:    # one buffer
+        assert p["lds_bytes"] == BT * RS * ES
+    else:              # two buffers of whole 16-byte-per-lane loads; a row is JW*4 vectors and a pad vector
+        RV = JW * 4 + 1
+        nslot = cdiv(BT * RV, 64 * NW)
+        assert ES == 4 and RS == RV * 4 and RV <= 64 and p["lds_bytes"] == 2 * nslot * 64 * NW * 16
+        assert AP * NT - NT + nslot <= 63 and AP * NT <= 63      # loads in flight the kernel's waits count
+    assert KIND == 1 or BT * g.LH * g.LW * g.F * ES < 2 ** 32     # 32-bit byte offsets of the staging slots
     assert p["lds_bytes"] <= LDS_PER_CU
     assert p["grid"][0] == strips * CH * nbt and strips == cdiv(CW, NCELL) and nbt == cdiv(g.B, BT)
     assert p["grid"][1] == cdiv(NCV, (NW // NCELL) * NT * 16)
@@ -204,7 +215,7 @@ def check_plans(g, op, dtype, plans, replay):
                     for bt in range(cdiv(g.B, 16)) for ft in range(g.F // 16)}
             got = {k for k in seen if k[2] < cdiv(g.B, 16)}
             assert got == want and all(seen[k] == 1 for k in got), (g, MT)
-    elif fams <= {"lc_bwd_data_fast", "lc_bwd_data_line"}:
+    elif fams <= {"lc_bwd_data_fast", "lc_bwd_data_line", "lc_bwd_data_direct"}:
         assert len(plans) == 1
         check_backward_data_fast(g, plans[0])
         if replay:
