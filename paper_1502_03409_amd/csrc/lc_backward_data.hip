@@ -426,8 +426,8 @@ __device__ __forceinline__ void wait_loads() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int MT, int NT, int NCELL, int AP, int NW>
-__global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_direct_kernel(
+template <int MT, int NT, int NCELL, int AP, int NW, int NBUF>
+__global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bwd_data_direct_kernel(
     Geom g, const float *__restrict__ dy, const float *__restrict__ w, float *__restrict__ dx, int strips_per_row,
     int nbt) {
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1, R4 = JW * 4;   // R4: 4-filter vectors per image and chunk
@@ -488,19 +488,25 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_direct_k
     const size_t dyimg = (size_t)g.L * g.F;
 
     if (nchunks > 0) {
-        // weights of step a' of chunk (a, fh): field (ri-a, wi-a') clamped into the grid; the same for every lane
-        auto wbase = [&](int a, int fh, int ap) -> gbyte_ptr {
+        // weights of step a' of chunk (a, fh): field (ri-a, wi-a') clamped into the grid; the same for every lane.
+        // Row (ri-a) of the grid, kernel row S*a and filters fh*16.. give the chunk's pointer; the step adds the field
+        // column and kernel column, which no chunk changes: wstep[a'] is worked out once.
+        size_t wstep[AP];
+#pragma unroll
+        for (int ap = 0; ap < AP; ++ap) {
             int j = wi - ap;
             j = j < 0 ? 0 : (j >= g.LW ? g.LW - 1 : j);
-            return (gbyte_ptr)(w + ((size_t)((ri - a) * g.LW + j) * g.K + (size_t)g.S * a * g.RC + g.S * ap * g.C) * g.F +
-                               fh * 16);
+            wstep[ap] = ((size_t)j * g.K + (size_t)(g.S * ap * g.C)) * g.F * 4;
+        }
+        auto wchunk = [&](int a, int fh) -> gbyte_ptr {
+            return (gbyte_ptr)(w + ((size_t)((ri - a) * g.LW) * g.K + (size_t)g.S * a * g.RC) * g.F + fh * 16);
         };
         // weight ring: slot a' holds the weights of step a' of the current chunk and is refilled, right
         // after its use, with step a' of the next chunk: loads run one whole chunk ahead of the MFMAs
         f32x4 wb[AP][NT];
 #pragma unroll
         for (int ap = 0; ap < AP; ++ap) {
-            gbyte_ptr p0 = wbase(a_lo, 0, ap);
+            gbyte_ptr p0 = wchunk(a_lo, 0) + wstep[ap];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait16(p0, kn[nt]);
         }
@@ -519,7 +525,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_direct_k
             live[q] = ok || !data;
             if (data && !ok) {
                 *(f32x4 *)(dys + P * 4) = (f32x4){0.f, 0.f, 0.f, 0.f};
-                *(f32x4 *)(dys + BUF + P * 4) = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if constexpr (NBUF == 2) *(f32x4 *)(dys + BUF + P * 4) = (f32x4){0.f, 0.f, 0.f, 0.f};
             }
         }
         const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) float *)dys + wave * 64 * 16;
@@ -535,50 +541,73 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_direct_k
         };
 
         Chunk c0 = {a_lo, 0}, c1 = after(c0);     // chunks c and c+1
-        stage(c0, 0);
-        wait_loads<0>();
-        __syncthreads();
         // the lane's dy vector of image m + 16 mt under the wave's cell at step a' lies at
         // abase + mt*16*RS + (AP-1-a')*16: field column wc - a' + AP - 1 of the staged strip
         const float *abase = dys + m * RS + 4 * kk + wc * 16;
+        if constexpr (NBUF == 2) {
+            stage(c0, 0);
+            wait_loads<0>();
+            __syncthreads();
+        }
         for (int c = 0; c < nchunks; ++c) {
             const Chunk cn = c + 1 < nchunks ? c1 : c0;
-            stage(cn, (c + 1) & 1);
-            const float *arow = abase + (c & 1) * BUF;
+            const float *arow = abase;
+            if constexpr (NBUF == 2) {
+                stage(cn, (c + 1) & 1);
+                arow += (c & 1) * BUF;
+            } else {
+                // one buffer, and several workgroups on a compute unit to work while this one waits for its dy
+                if (c > 0) __syncthreads();      // everybody is through with chunk c-1
+                stage(c0, 0);
+                wait_loads<0>();                 // with it, the weights of this chunk have landed
+                __syncthreads();
+            }
             f32x4 av[2][MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) av[0][mt] = *(const f32x4 *)(arow + mt * 16 * RS + (AP - 1) * 16);
+            gbyte_ptr wn = wchunk(cn.a, cn.fh);
 #pragma unroll
             for (int ap = 0; ap < AP; ++ap) {
+                const bool inside = wi - ap >= 0 && wi - ap < g.LW;   // a field column outside the grid contributes
+                                                                      // nothing: its MFMAs are skipped (by the whole wave)
+                if constexpr (NBUF == 2) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) wait_loads<AP * NT - NT + NSLOT>(wb[ap][nt]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                auto mfmas = [&](int t) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[mt][nt] = mfma16(av[ap & 1][mt][t], wb[ap][nt][t], acc[mt][nt]);
+                };
+                if (inside) { mfmas(0); mfmas(1); }
+                __builtin_amdgcn_sched_barrier(0);
+                // Issued behind the first MFMAs, the LDS reads of the next step and the pointer arithmetic of the
+                // weight loads run while the matrix pipe works them off: a wave issues in order, and whatever stands
+                // in front of the step's first MFMA is time the pipe idles when the SIMD's other wave is not ready.
                 if (ap + 1 < AP) {
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
                         av[(ap + 1) & 1][mt] = *(const f32x4 *)(arow + mt * 16 * RS + (AP - 2 - ap) * 16);
                 }
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) wait_loads<AP * NT - NT + NSLOT>(wb[ap][nt]);
+                gbyte_ptr pn = wn + wstep[ap];
                 __builtin_amdgcn_sched_barrier(0);
-                // a field column outside the grid contributes nothing: skip its MFMAs (the same for the whole wave)
-                if (wi - ap >= 0 && wi - ap < g.LW) {
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                            for (int nt = 0; nt < NT; ++nt)
-                                acc[mt][nt] = mfma16(av[ap & 1][mt][t], wb[ap][nt][t], acc[mt][nt]);
-                }
+                if (inside) { mfmas(2); mfmas(3); }
                 __builtin_amdgcn_sched_barrier(0);
-                gbyte_ptr pn = wbase(cn.a, cn.fh, ap);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait16(pn, kn[nt]);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // this lane's dy loads of the next chunk have landed (the AP*NT weight loads behind them may fly on);
-            // behind the barrier, everybody's have, and everybody is through with the buffer the chunk after next overwrites
-            wait_loads<AP * NT>();
+            if constexpr (NBUF == 2) {
+                // this lane's dy loads of the next chunk have landed (the AP*NT weight loads behind them may fly on);
+                // behind the barrier, everybody's have, and everybody is through with the buffer the chunk after next
+                // overwrites
+                wait_loads<AP * NT>();
+                __syncthreads();
+            }
             c0 = c1; c1 = after(c1);
-            __syncthreads();
         }
         // the weights loaded last are not used: they must have landed before their registers are given up
 #pragma unroll
@@ -848,7 +877,7 @@ namespace {
 
 // Host check of a lc_bwd_data_fast_kernel or lc_bwd_data_line_kernel launch (LINE = 1: chunks of 32 filters, one LDS
 // buffer; 0: chunks of 16 filters, two buffers).
-// tparam = {MT, NT, NCELL, AP, NW, bytes per operand element, LINE, RING}; arg = {strips of cells per cell row, LDS
+// tparam = {MT, NT, NCELL, AP, NW, bytes per operand element, LINE (2: dy straight into LDS), RING, LDS buffers}; arg = {strips of cells per cell row, LDS
 // row stride in elements, batch tiles}.
 int check_backward_data_fast(const Geom &g, const LaunchPlan &p) {
     const int MT = p.tparam[0], NT = p.tparam[1], NCELL = p.tparam[2], AP = p.tparam[3], NW = p.tparam[4];
@@ -869,7 +898,9 @@ int check_backward_data_fast(const Geom &g, const LaunchPlan &p) {
         LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)BT * RS * ES);
     else {                // two buffers of whole loads (16 bytes per lane); a row is JW*4 vectors and a pad
         const int nslot = ceil_div(BT * (JW * 4 + 1), 64 * NW);
-        LC_PLAN_REQUIRE(p, RS == (JW * 4 + 1) * 4 && JW * 4 + 1 <= 64 && p.lds_bytes >= (size_t)2 * nslot * 64 * NW * 16);
+        const int NBUF = p.tparam[8];
+        LC_PLAN_REQUIRE(p, (NBUF == 1 || NBUF == 2) && RS == (JW * 4 + 1) * 4 && JW * 4 + 1 <= 64 &&
+                               p.lds_bytes >= (size_t)NBUF * nslot * 64 * NW * 16);
         // the kernel's waits count the loads in flight: a six-bit counter
         LC_PLAN_REQUIRE(p, AP * NT - NT + nslot <= 63 && AP * NT <= 63);
     }
@@ -907,20 +938,20 @@ int launch_line(const Geom &g, const float *dy, const float *w, float *dx, hipSt
 }
 
 // fp32 operands: the kernel with dy loaded straight into LDS
-template <int MT, int NT, int NCELL, int AP, int NW>
+template <int MT, int NT, int NCELL, int AP, int NW, int NBUF = 2>
 int launch_direct(const Geom &g, const float *dy, const float *w, float *dx, hipStream_t s) {
     constexpr int BT = 16 * MT, JW = NCELL + AP - 1, RV = JW * 4 + 1, NTHR = 64 * NW;
     constexpr int NSLOT = (BT * RV + NTHR - 1) / NTHR;
     const int CH = (g.H + g.S - 1) / g.S, CW = (g.W + g.S - 1) / g.S;
     const int NCV = g.S * g.S * g.C;
-    const size_t lds = (size_t)2 * NSLOT * NTHR * 16;
-    auto kern = lc_bwd_data_direct_kernel<MT, NT, NCELL, AP, NW>;
+    const size_t lds = (size_t)NBUF * NSLOT * NTHR * 16;
+    auto kern = lc_bwd_data_direct_kernel<MT, NT, NCELL, AP, NW, NBUF>;
     const int strips = (CW + NCELL - 1) / NCELL;
     const int nblk = (NW / NCELL) * NT * 16;
     const int nbt = (g.B + BT - 1) / BT;
     dim3 grid(strips * CH * nbt, (NCV + nblk - 1) / nblk);
-    const LaunchPlan plan = make_plan("lc_bwd_data_direct", {MT, NT, NCELL, AP, NW, 4, 2, AP}, {strips, RV * 4, nbt}, grid,
-                                      NTHR, lds);
+    const LaunchPlan plan = make_plan("lc_bwd_data_direct", {MT, NT, NCELL, AP, NW, 4, 2, AP, NBUF}, {strips, RV * 4, nbt},
+                                      grid, NTHR, lds);
     if (int rc = check_backward_data_fast(g, plan)) return rc;
     LC_LAUNCH(plan, "lc_backward_data launch", kern, s, g, dy, w, dx, strips, nbt);
     return LC_OK;
@@ -991,7 +1022,13 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
             LC_BD(5, 4, 2);
         } else if (ap == 8) {
             // one tile of cell values per wave: eight cells per workgroup share the staged fields
-            if (ntt == 1) { *done = true; return launch_fast<4, 1, 8, 8, 8>(g, dy, w, dx, s); }
+            if (ntt == 1) {
+                *done = true;
+#ifdef LC_BD_NBUF1
+                if constexpr (sizeof(T) == 4) return launch_direct<4, 1, 8, 8, 8, 1>(g, dy, w, dx, s);
+#endif
+                return launch_fast<4, 1, 8, 8, 8>(g, dy, w, dx, s);
+            }
             LC_BD(8, 2, 2);
         }
 #undef LC_BD

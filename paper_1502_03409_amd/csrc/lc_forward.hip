@@ -353,6 +353,229 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The fast path for fp32 operands and whole patch rows per chunk, with a hand-kept memory schedule.  Same
+// decomposition as lc_forward_fast_kernel (a workgroup is a strip of NLOC fields of one field row times a batch tile;
+// a chunk is NRT patch rows of the strip; a k-step is one MFMA per accumulator); what differs:
+//   - x goes from global memory straight into LDS (16 bytes per lane, lane i of a wave's load lands 16 i bytes past
+//     the load's LDS base): no staging registers, no LDS stores.  A buffer is the batch tile's rows one after the
+//     other, each NRT patch-row pieces of sq4 vectors (plus a pad vector where that makes the vector count odd: the
+//     16 rows a wave reads at once then start four banks apart); vector P of the buffer belongs to lane P % NTHR of
+//     load P / NTHR and comes from the same place in every chunk, relative to the chunk's first vector.  Every lane
+//     loads: images past the batch and columns past the image row are clamped into x, where they only feed rows and
+//     waves that store nothing; pad vectors and the slack behind the last row load the chunk's first vector.
+//   - a lane's A operands of four k-steps are four consecutive floats of the patch row, one 16-byte LDS read where
+//     the old order needed four 4-byte reads: k-step t of group gi contracts k = 16 gi + 4 kk + t instead of
+//     16 gi + 4 t + kk (a sum over k: any order both operands agree on), so lane (n,kk) loads row
+//     16 gi + 4 kk + t of w[l].  A patch row of SPC k-steps is SPC/4 such groups and a tail group of SPC%4 steps
+//     (k = 16 (SPC/4) + (SPC%4) kk + t).
+//   - weight pointers are scalar (the wave index is read into a scalar register; a lane adds its fixed offset), and
+//     the loads are inline assembly with every wait written out.  The memory counter counts loads in program order:
+//         chunk c:  [NSLOT x loads of chunk c+1]  then per k-step p: wait, MFMAs, [one weight load, of k-step p+U]
+//     so the weights of k-step p are followed by U-1 younger weight loads and, for p < U, by the chunk's x loads.
+// The last chunk loads its own x and weights once more (valid addresses, values unused) so that the counts hold.
+typedef const __attribute__((address_space(1))) char *gbyte_ptr;
+
+__device__ __forceinline__ void fwd_load_lds16(gbyte_ptr base, unsigned off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(off), "s"(base)
+                 : "memory");
+}
+// NT consecutive floats per lane into registers; usable only after fwd_wait has been called on the value
+template <int NT>
+__device__ __forceinline__ typename FVec<NT>::T fwd_load_nowait(gbyte_ptr base, unsigned off) {
+    typename FVec<NT>::T v;
+    if constexpr (NT == 1) asm volatile("global_load_dword %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
+    else if constexpr (NT == 2) asm volatile("global_load_dwordx2 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
+    else asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
+    return v;
+}
+// wait until at most N of the loads issued so far are in flight; v is a value one of the finished loads delivers
+template <int N, typename V>
+__device__ __forceinline__ void fwd_wait(V &v) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void fwd_wait() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int MT, int NT, int NLOC, int NW, int SPC, int NRT, int NSLOT, int U, int NBUF>
+__global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_forward_direct_kernel(
+    Geom g, const float *__restrict__ x, const float *__restrict__ w, const float *__restrict__ bias, float alpha,
+    const float *__restrict__ alpha_dev, float *__restrict__ y, int strips_per_row, int sq4, int RV, int work_offset,
+    int nbt) {
+    typedef typename FVec<NT>::T WV;          // NT consecutive weights / outputs
+    constexpr int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW;
+    constexpr int NS = SPC * NRT;             // k-steps per chunk
+    constexpr int NG4 = SPC / 4, GT = SPC % 4, NG = NG4 + (GT ? 1 : 0);
+    constexpr int BUF = NSLOT * NTHR * 4;     // floats per buffer
+    static_assert(NS % U == 0 && U <= NS, "the weight ring turns a whole number of times per chunk");
+    static_assert(U - 1 + NSLOT <= 63 && NS <= 63, "the memory counter has six bits");
+    extern __shared__ __attribute__((aligned(16))) float xs[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, kk = lane >> 4;
+    const int t_id = remap_xcd(blockIdx.x, gridDim.x);
+    const int work = work_offset + t_id / nbt;
+    const int i = work / strips_per_row, j0 = (work - i * strips_per_row) * NLOC;
+    const int b0 = (t_id % nbt) * BT;
+    const int wl = wave % NLOC, wf = wave / NLOC;
+    const int j = j0 + wl;
+    const int f0 = (blockIdx.y * NFW + wf) * NT * 16;
+    const bool active = j < g.LW;
+    const int loc = i * g.LW + (active ? j : g.LW - 1);   // idle waves shadow the last field of the row
+    const int SC = g.S * g.C, WC = g.W * g.C, RS = RV * 4;
+    const size_t img = (size_t)g.H * WC;
+    const int col0 = j0 * SC;
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) acc[mt][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // weights: w[loc] is K rows of F floats; the lane's part of the address is its row inside a group and its filters
+    gbyte_ptr wloc = (gbyte_ptr)(w + (size_t)loc * g.K * g.F + f0);
+    const unsigned wlane4 = (unsigned)((4 * kk * g.F + NT * n) * 4), wlaneT = (unsigned)((GT * kk * g.F + NT * n) * 4);
+    // row of w[l], relative to the chunk's first, that k-step p of a chunk contracts for lanes kk = 0
+    auto step_row = [&](int p) -> int {
+        const int r = p / SPC, sidx = p - r * SPC, gi = sidx / 4;
+        return r * g.RC + (gi < NG4 ? 16 * gi + (sidx & 3) : 16 * NG4 + (sidx - 4 * NG4));
+    };
+    auto step_lane = [&](int p) -> unsigned { return (p % SPC) / 4 < NG4 ? wlane4 : wlaneT; };
+    auto wchunk = [&](int kh) -> gbyte_ptr { return wloc + (size_t)kh * g.RC * g.F * 4; };
+    WV wr[U];
+#pragma unroll
+    for (int p = 0; p < U; ++p) wr[p] = fwd_load_nowait<NT>(wloc + (size_t)step_row(p) * g.F * 4, step_lane(p));
+
+    // where this lane's vector of load q comes from: bytes past the chunk's first vector (image b0, image row
+    // i*S + kh, column col0)
+    unsigned goff[NSLOT];
+    {
+        const int lim = WC - col0 - 4;        // last float offset from col0 at which a whole vector is inside the row
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) {
+            const int P = q * NTHR + tid, b = P / RV, v = P - b * RV;
+            const int r = v / sq4, vv = v - r * sq4;
+            const bool data = b < BT && r < NRT;
+            const int bc = min(b, g.B - 1 - b0);
+            goff[q] = data ? (unsigned)(((size_t)bc * img + (size_t)r * WC + min(4 * vv, max(lim, 0))) * 4) : 0u;
+        }
+    }
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) float *)xs + wave * 64 * 16;
+    auto stage = [&](int kh, int buf) {
+        gbyte_ptr base = (gbyte_ptr)(x + (size_t)b0 * img + (size_t)(i * g.S + kh) * WC + col0);
+        const unsigned l = lds0 + buf * (BUF * 4);
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) fwd_load_lds16(base, goff[q], l + q * (NTHR * 16));
+    };
+
+    // the lane's four floats of group gi, patch row r of the chunk, image m + 16 mt: abase + mt*16*RS + r*sq4*4 + 16 gi
+    const float *abase = xs + (lane & 15) * RS + wl * SC + 4 * kk;
+    const float *abaseT = xs + (lane & 15) * RS + wl * SC + 16 * NG4 + GT * kk;
+    if constexpr (NBUF == 2) {
+        stage(0, 0);
+        fwd_wait<0>();
+        __syncthreads();
+    }
+    int c = 0;
+    for (int kh = 0; kh < g.R; kh += NRT, ++c) {
+        const int khn = kh + NRT < g.R ? kh + NRT : kh;       // the last chunk reloads itself
+        const float *arow = abase, *arowT = abaseT;
+        if constexpr (NBUF == 2) {
+            stage(khn, (c + 1) & 1);
+            arow += (c & 1) * BUF;
+            arowT += (c & 1) * BUF;
+        } else {
+            if (c > 0) __syncthreads();      // everybody is through with the previous chunk
+            stage(kh, 0);
+            fwd_wait<0>();
+            __syncthreads();
+        }
+        gbyte_ptr wc = wchunk(kh), wn = wchunk(khn);
+        // the lane's A operands of group gi of patch row r: four consecutive floats (8-byte aligned: two halves in
+        // one LDS instruction), or the tail group's GT floats
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        float a[2][MT][4];
+        auto read_group = [&](int r, int gi, float (&dst)[MT][4]) {
+            if (gi < NG4) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const f32x2 lo = *(const f32x2 *)(arow + mt * 16 * RS + r * sq4 * 4 + 16 * gi);
+                    const f32x2 hi = *(const f32x2 *)(arow + mt * 16 * RS + r * sq4 * 4 + 16 * gi + 2);
+                    dst[mt][0] = lo[0]; dst[mt][1] = lo[1]; dst[mt][2] = hi[0]; dst[mt][3] = hi[1];
+                }
+            } else {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int t = 0; t < GT; ++t) dst[mt][t] = arowT[mt * 16 * RS + r * sq4 * 4 + t];
+            }
+        };
+        read_group(0, 0, a[0]);
+#pragma unroll
+        for (int r = 0; r < NRT; ++r) {
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) {
+                const int G = gi < NG4 ? 4 : GT, cur = (r * NG + gi) & 1;
+#pragma unroll
+                for (int t = 0; t < G; ++t) {
+                    const int p = r * SPC + 4 * gi + t;       // k-step of the chunk
+                    // (the loop is unrolled: p is a constant by the time this is compiled)
+                    if (p < U) fwd_wait<U - 1 + NSLOT>(wr[p % U]);
+                    else fwd_wait<U - 1>(wr[p % U]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int u = 0; u < NT; ++u)
+                            acc[mt][u] = mfma16(a[cur][mt][t], fget<NT>(wr[p % U], u), acc[mt][u]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // behind the group's first MFMAs: the LDS reads of the next group
+                    if (t == 0) {
+                        if (gi + 1 < NG) read_group(r, gi + 1, a[cur ^ 1]);
+                        else if (r + 1 < NRT) read_group(r + 1, 0, a[cur ^ 1]);
+                    }
+                    const int pn = p + U;                     // the k-step whose weights take this ring slot
+                    gbyte_ptr wp = pn < NS ? wc : wn;
+                    const int pp = pn < NS ? pn : pn - NS;
+                    wr[p % U] = fwd_load_nowait<NT>(wp + (size_t)step_row(pp) * g.F * 4, step_lane(pp));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        if constexpr (NBUF == 2) {
+            // this lane's x loads of the next chunk have landed (the NS weight loads behind them may fly on)
+            fwd_wait<NS>();
+            __syncthreads();
+        }
+    }
+    // the weights loaded last are not used: they must have landed before their registers are given up
+#pragma unroll
+    for (int p = 0; p < U; ++p) fwd_wait<0>(wr[p]);
+
+    if (!active) return;
+    if (alpha_dev) alpha = *alpha_dev;
+    WV bv;
+    if constexpr (NT == 1) bv = 0.f; else bv = (WV)(0.f);
+    if (bias) bv = *(const WV *)(bias + (size_t)loc * g.F + f0 + NT * n);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int b = b0 + mt * 16 + 4 * kk + r;
+            if (b >= g.B) continue;
+            WV o;
+            if constexpr (NT == 1) {
+                o = alpha * acc[mt][0][r] + bv;
+            } else {
+#pragma unroll
+                for (int u = 0; u < NT; ++u) o[u] = alpha * acc[mt][u][r] + bv[u];
+            }
+            *(WV *)(y + ((size_t)b * g.L + loc) * g.F + f0 + NT * n) = o;
+        }
+}
+
 namespace {
 
 struct FwdPlan { int MT, NT, NLOC; };
@@ -470,6 +693,62 @@ int launch_fast(const Geom &g, const T *x, const T *w, const float *bias, float 
     if (int rc = check_forward_fast(g, plan)) return rc;
     LC_LAUNCH(plan, "lc_forward launch", kern, s, g, x, w, bias, alpha, alpha_dev, y, strips, CQ, sqc / 4, RS, NR,
               work_first, nbt);
+    return LC_OK;
+}
+
+// Host check of a lc_forward_direct_kernel launch.
+// tparam = {MT, NT, NLOC, U (weight ring, k-steps), NW, 4, SPC, NRT, NSLOT (x loads per lane and chunk), NBUF};
+// arg = {RC, sq4, LDS row stride in floats, NRT, first strip, strips in this launch, batch tiles, strips per field row}.
+int check_forward_direct(const Geom &g, const LaunchPlan &p) {
+    const int MT = p.tparam[0], NT = p.tparam[1], NLOC = p.tparam[2], U = p.tparam[3], NW = p.tparam[4];
+    const int SPC = p.tparam[6], NRT = p.tparam[7], NSLOT = p.tparam[8], NBUF = p.tparam[9];
+    const int sq4 = p.arg[1], RS = p.arg[2], first = p.arg[4], count = p.arg[5], nbt = p.arg[6], strips = p.arg[7];
+    LC_PLAN_REQUIRE(p, NLOC > 0 && NW % NLOC == 0 && (NT == 1 || NT == 2 || NT == 4) && (NBUF == 1 || NBUF == 2));
+    const int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW, SC = g.S * g.C, WC = g.W * g.C, NS = SPC * NRT;
+    LC_PLAN_REQUIRE(p, (int)p.block == NTHR && p.arg[0] == g.RC && p.arg[3] == NRT);
+    // whole patch rows of SPC k-steps, NRT of them per chunk; 16-byte vectors of x from every strip's start; the
+    // 8-byte LDS reads of a field's window
+    LC_PLAN_REQUIRE(p, g.RC == 4 * SPC && NRT >= 1 && g.R % NRT == 0 && WC % 4 == 0 && (NLOC * SC) % 4 == 0 && SC % 2 == 0);
+    LC_PLAN_REQUIRE(p, g.F % (NFW * NT * 16) == 0 && (int)p.grid[1] == g.F / (NFW * NT * 16) && p.grid[2] == 1);
+    // the staged strip covers every field's window; an LDS row is NRT pieces of sq4 vectors, an odd number of vectors
+    LC_PLAN_REQUIRE(p, 4 * sq4 >= g.RC + (NLOC - 1) * SC && RS % 4 == 0 && RS / 4 >= NRT * sq4 && (RS / 4) % 2 == 1);
+    LC_PLAN_REQUIRE(p, (long long)NSLOT * NTHR >= (long long)BT * (RS / 4));
+    LC_PLAN_REQUIRE(p, p.lds_bytes >= (size_t)NBUF * NSLOT * NTHR * 16);
+    // the waits in the kernel count the loads in flight (a six-bit counter); the ring turns whole times per chunk
+    LC_PLAN_REQUIRE(p, U >= 1 && U <= NS && NS % U == 0 && U - 1 + NSLOT <= 63 && NS <= 63);
+    // 32-bit byte offsets into x; clamped vectors stay inside the image row
+    LC_PLAN_REQUIRE(p, (long long)g.B * g.H * g.W * g.C * 4 < (1LL << 32));
+    LC_PLAN_REQUIRE(p, strips == ceil_div(g.LW, NLOC) && nbt == ceil_div(g.B, BT));
+    LC_PLAN_REQUIRE(p, WC - (strips - 1) * NLOC * SC >= 4);
+    LC_PLAN_REQUIRE(p, first >= 0 && count >= 1 && first + count <= strips * g.LH);
+    LC_PLAN_REQUIRE(p, (long long)p.grid[0] == (long long)count * nbt);
+    return LC_OK;
+}
+
+// whether lc_forward_direct_kernel<.., SPC, NRT, NSLOT, ..> takes the layer (fp32 operands)
+template <int MT, int NLOC, int NW, int SPC, int NRT, int NSLOT>
+bool forward_direct_fits(const Geom &g) {
+    const int SC = g.S * g.C, WC = g.W * g.C, strips = (g.LW + NLOC - 1) / NLOC;
+    const int sq4 = ((g.RC + (NLOC - 1) * SC + 3) & ~3) / 4, RV = (NRT * sq4) | 1;
+    return g.RC == 4 * SPC && g.R % NRT == 0 && WC % 4 == 0 && (NLOC * SC) % 4 == 0 && SC % 2 == 0 &&
+           (16 * MT * RV + 64 * NW - 1) / (64 * NW) == NSLOT && (long long)g.B * g.H * g.W * g.C * 4 < (1LL << 32) &&
+           WC - (strips - 1) * NLOC * SC >= 4;
+}
+
+template <int MT, int NT, int NLOC, int NW, int SPC, int NRT, int NSLOT, int U, int NBUF>
+int launch_direct(const Geom &g, const float *x, const float *w, const float *bias, float alpha,
+                  const float *alpha_dev, float *y, int work_first, int work_count, hipStream_t s) {
+    constexpr int BT = 16 * MT, NFW = NW / NLOC, NTHR = 64 * NW;
+    const int sq4 = ((g.RC + (NLOC - 1) * g.S * g.C + 3) & ~3) / 4, RV = (NRT * sq4) | 1;
+    const size_t lds = (size_t)NBUF * NSLOT * NTHR * 16;
+    auto kern = lc_forward_direct_kernel<MT, NT, NLOC, NW, SPC, NRT, NSLOT, U, NBUF>;
+    const int strips = (g.LW + NLOC - 1) / NLOC;
+    const int nbt = (g.B + BT - 1) / BT;
+    dim3 grid(work_count * nbt, g.F / (NFW * NT * 16));
+    const LaunchPlan plan = make_plan("lc_forward_direct", {MT, NT, NLOC, U, NW, 4, SPC, NRT, NSLOT, NBUF},
+                                      {g.RC, sq4, RV * 4, NRT, work_first, work_count, nbt, strips}, grid, NTHR, lds);
+    if (int rc = check_forward_direct(g, plan)) return rc;
+    LC_LAUNCH(plan, "lc_forward launch", kern, s, g, x, w, bias, alpha, alpha_dev, y, strips, sq4, RV, work_first, nbt);
     return LC_OK;
 }
 
@@ -596,6 +875,15 @@ int launch_fast_wide(const Geom &g, const T *x, const T *w, const float *bias, f
     if (spr % 6 == 0 && (CQ = pick_chunk(g, 128, 8, 6, budget, 512, kFwdStageSlotsWide))) {
         // whole patch rows of 12 k-steps that need every staging slot: the variant with compile-time counts
         const int sq4 = ((CQ + 7 * g.S * g.C + 3) & ~3) / 4;
+        if constexpr (sizeof(T) == 4) {
+#ifdef LC_FWD_NBUF1
+            constexpr int kBuf = 1;
+#else
+            constexpr int kBuf = 2;
+#endif
+            if (forward_direct_fits<8, 8, 8, 12, 1, 6>(g))
+                return launch_direct<8, 1, 8, 8, 12, 1, 6, 12, kBuf>(g, x, w, bias, alpha, alpha_dev, y, 0, ntask, s);
+        }
         if (sizeof(T) == 4 && CQ == g.RC && spr == 12 && (128 * sq4 + 511) / 512 == kFwdStageSlotsWide &&
             (long long)g.B * g.H * g.W * g.C < (1LL << 31))
             return launch_fast<8, 1, 8, 6, 8, 12>(g, x, w, bias, alpha, alpha_dev, y, CQ, 1, 0, ntask, s);

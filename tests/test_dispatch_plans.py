@@ -142,6 +142,40 @@ def check_forward_fast(g, plans):
         nxt += p["arg"][5]
 
 
+def check_forward_direct(g, plans):
+    """The forward kernel that loads x straight into LDS: same work split as lc_forward_fast."""
+    total = 0
+    for p in plans:
+        MT, NT, NLOC, U, NW, ES, SPC, NRT, NSLOT, NBUF = p["tparam"][:10]
+        RC, sq4, RS, NR, first, count, nbt, strips = p["arg"][:8]
+        BT, NTHR, SC, WC, NS = 16 * MT, 64 * NW, g.S * g.C, g.W * g.C, SPC * NRT
+        assert p["block"] == NTHR and ES == 4 and NBUF in (1, 2)
+        assert RC == g.R * g.C == 4 * SPC and NR == NRT and g.R % NRT == 0
+        assert WC % 4 == 0 and (NLOC * SC) % 4 == 0 and SC % 2 == 0
+        assert 4 * sq4 >= RC + (NLOC - 1) * SC and RS % 4 == 0 and RS // 4 >= NRT * sq4 and (RS // 4) % 2 == 1
+        assert NSLOT * NTHR >= BT * (RS // 4) and p["lds_bytes"] == NBUF * NSLOT * NTHR * 16 <= LDS_PER_CU
+        assert NS % U == 0 and U - 1 + NSLOT <= 63 and NS <= 63      # loads in flight the kernel's waits count
+        assert p["grid"][1] * (NW // NLOC) * NT * 16 == g.F
+        assert g.B * g.H * WC * 4 < 2 ** 32
+        total += count
+        # every lane loads from an address clamped into x: the largest one ends inside x
+        img = g.H * WC
+        for work in (first, first + count - 1):
+            i, j0 = work // strips, (work % strips) * NLOC
+            col0 = j0 * SC
+            assert WC - col0 >= 4
+            for b0 in {0, (nbt - 1) * BT}:
+                for kh in (0, g.R - NRT):
+                    row = b0 * img + (i * g.S + kh) * WC + col0
+                    off_max = min(BT - 1, g.B - 1 - b0) * img + (NRT - 1) * WC + min(4 * sq4 - 4, WC - col0 - 4)
+                    assert 0 <= row and row + off_max + 4 <= g.B * img
+    assert total == plans[0]["arg"][7] * g.LH
+    nxt = 0
+    for p in plans:
+        assert p["arg"][4] == nxt
+        nxt += p["arg"][5]
+
+
 def covered_backward_data_fast(g, p):
     MT, NT, NCELL, AP, NW = p["tparam"][:5]
     strips, RS, nbt = p["arg"][:3]
@@ -206,8 +240,8 @@ def check_plans(g, op, dtype, plans, replay):
         assert 64 <= p["block"] <= 1024 and p["block"] % 64 == 0
         assert all(d >= 1 for d in p["grid"]) and p["grid"][1] <= 65535 and p["grid"][2] <= 65535
     fams = {p["kernel"] for p in plans}
-    if fams == {"lc_forward_fast"}:
-        check_forward_fast(g, plans)
+    if fams == {"lc_forward_fast"} or fams == {"lc_forward_direct"}:
+        (check_forward_fast if fams == {"lc_forward_fast"} else check_forward_direct)(g, plans)
         if replay:
             seen = covered_forward_fast(g, plans)
             MT = plans[0]["tparam"][0]
