@@ -18,22 +18,15 @@
  *    rows/columns that no field covers are ignored by the forward pass and receive zero
  *    from lc_backward_data).
  *  - `dtype` names the storage type of the x / w / dy operands: LC_F32, or LC_BF16 (bf16
- *    operands, fp32 accumulation).  Outputs are always fp32.  LC_BF16 covers every shape
- *    with R*C % 16 == 0, S*C % 4 == 0, W*C % 4 == 0, F % 64 == 0, B % 16 == 0, R % S == 0,
- *    and beyond that, with F % 16 == 0 throughout:
- *      lc_forward           R*C % 4 == 0, W*C % 4 == 0, B > 16, and either S*C % 4 == 0 with
- *                           S*C <= 60, or R*R*C >= 64 with R*C/4 a multiple of 5, 6 or 8 and a
- *                           strip of four fields (R*C + 3*S*C values per image) within the
- *                           kernel's staging budget (48 KB per 64 images);
- *      lc_backward_data     R % S == 0 with R/S in {2, 3, 4, 5, 8}, B > 32;
- *      lc_backward_weights  R*C % 2 == 0, B % 4 == 0.
- *    (The call itself is the test: a shape outside returns LC_EUNSUPPORTED.)
- *    Inside that set the kernels use bf16 matrix instructions wherever the layout allows
- *    (always for lc_backward_data; for lc_forward if S*C % 4 == 0; for lc_backward_weights
- *    if R*C % 4 == 0 and either B % 16 == 0 or B <= 128 with S*C % 4 == 0) and otherwise
- *    widen the bf16 values on their way in and multiply with the fp32 matrix instruction:
- *    the same results either way.
- *    LC_EUNSUPPORTED is returned before anything is launched.
+ *    operands, fp32 accumulation).  Outputs are always fp32.  Every shape is accepted in
+ *    either type.  The bf16 kernels use bf16 matrix instructions wherever the layout allows
+ *    whole vectors of bf16 (always for lc_backward_data with R % S == 0, R/S in
+ *    {2, 3, 4, 5, 8}, F % 16 == 0 and B > 32; for lc_forward if S*C % 4 == 0, R*C % 4 == 0,
+ *    W*C % 4 == 0 and F % 16 == 0; for lc_backward_weights if R*C % 4 == 0 and either
+ *    B % 16 == 0 or B <= 128 with S*C % 4 == 0); other shapes widen the bf16 values on their
+ *    way in (exactly) and multiply with the fp32 matrix instruction through the same masked
+ *    kernels the fp32 path falls back to: the same results either way, at the speed of the
+ *    fp32 path with half the operand bytes.
  *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    only enqueue work; none synchronises.  Arguments are validated on the host before
  *    anything is launched, so every error except LC_EHIP is returned without touching

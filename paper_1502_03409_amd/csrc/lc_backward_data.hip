@@ -403,29 +403,6 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 2 : 1) void lc_bwd_data_fast_ker
 //     which at the first steps of a chunk are the dy loads just issued.
 // The last chunk loads its own dy and weights once more (valid addresses; the values are not used) so that the
 // counts hold in every iteration.
-typedef const __attribute__((address_space(1))) char *gbyte_ptr;
-
-// 16 bytes per lane from base + off straight into LDS at lds_addr + 16 * lane (lds_addr: byte address, wave-uniform)
-__device__ __forceinline__ void load_lds16(gbyte_ptr base, unsigned off, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(off), "s"(base)
-                 : "memory");
-}
-// 16 bytes per lane into registers; the value may be used only after wait_loads has been called on it
-__device__ __forceinline__ f32x4 load_nowait16(gbyte_ptr base, unsigned off) {
-    f32x4 v;
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
-    return v;
-}
-// wait until at most N of the loads issued so far are still in flight; v is a value that load delivers
-template <int N>
-__device__ __forceinline__ void wait_loads(f32x4 &v) {
-    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_loads() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 template <int MT, int NT, int NCELL, int AP, int NW, int NBUF>
 __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bwd_data_direct_kernel(
     Geom g, const float *__restrict__ dy, const float *__restrict__ w, float *__restrict__ dx, int strips_per_row,
@@ -508,7 +485,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bw
         for (int ap = 0; ap < AP; ++ap) {
             gbyte_ptr p0 = wchunk(a_lo, 0) + wstep[ap];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait16(p0, kn[nt]);
+            for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait<4>(p0, kn[nt]);
         }
 
         // where this lane's vector of load q comes from (bytes past the chunk's first vector), whether it loads at
@@ -597,7 +574,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bw
                 if (inside) { mfmas(2); mfmas(3); }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait16(pn, kn[nt]);
+                for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait<4>(pn, kn[nt]);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if constexpr (NBUF == 2) {
@@ -645,7 +622,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bw
 // chunk: the next chunk waits in the staging registers while the current one is multiplied.  With those 64
 // staging registers a ring of five half-steps no longer fits 256 registers (5 values spilled and reloaded inside
 // the loop, each reload waiting for every load issued before it); two half-steps fit and measured faster
-// (cfg3: 233 -> 225 us in the step; one half-step: 264 us).
+// (5 x 5 covering fields of 32 filters, 104 x 104 x 12 input, batch 128: 233 -> 225 us; one half-step: 264 us).
 template <int MT, int NT, int NCELL, int AP, int RING>
 __global__ __launch_bounds__(256, 2) void lc_bwd_data_line_kernel(Geom g, const float *__restrict__ dy,
                                                                   const float *__restrict__ w,
@@ -1002,7 +979,7 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
             LC_BD(3, 4, 2);
         } else if (ap == 4) {
             // wide images: eight cells per workgroup stage 11 field columns instead of 2 x 7 (the paper's first
-            // layer: 6.04 -> 5.89 ms); with 5 x 5 covering fields and 50 cells per row (cfg3) the same loses
+            // layer: 6.04 -> 5.89 ms); with 5 x 5 covering fields and 50 cells per row the same loses
             // fp32, filters in blocks of 32: whole-line chunks (the paper's first layer: 6.08 -> 5.57 ms)
             if constexpr (sizeof(T) == 4) {
                 if (ntt == 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 4, 2>(g, (const float *)dy, (const float *)w, dx, s); }
@@ -1013,7 +990,7 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
             if (ntt == 4) LC_BD(4, 4, 4);
             LC_BD(4, 4, 2);
         } else if (ap == 5) {
-            // fp32, filters in blocks of 32: whole-line chunks (cfg3: 243 -> 233 us in the step)
+            // fp32, filters in blocks of 32: whole-line chunks (5 x 5 covering fields, 104 x 104 x 12 input, batch 128: 243 -> 233 us)
             if constexpr (sizeof(T) == 4) {
                 if (ntt <= 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 5, 2>(g, (const float *)dy, (const float *)w, dx, s); }
             }

@@ -375,6 +375,190 @@ int launch_nt(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------------
+// Layers with one tile of 16 filters per field (fp32, a batch of 4*NB images that fits LDS whole).  The kernels above
+// give a wave one block of patch elements of one field and let it fetch its operands itself: every x element is used
+// for 16 filters only, eight MFMA flops per byte fetched, and the caches cannot keep up.  Here a workgroup is a strip
+// of eight fields of one field row, one field per wave, as in the forward kernels:
+//   - a chunk is one patch row of the strip for the whole batch, loaded from global memory straight into LDS (16
+//     bytes per lane; lane i of a wave's load lands 16 i bytes past the load's LDS base), two buffers, the next
+//     chunk in flight while this one is multiplied; the loads are inline assembly and the waits on them are written
+//     out (the memory counter counts loads and stores in program order: behind a chunk's x loads come only the
+//     stores, and for beta != 0 the loads, of the previous chunk's epilogue, a number known at compile time);
+//   - a wave's B operands, dy of its field for the whole batch (one float per lane and batch step of four images),
+//     are loaded once and stay in registers for all R chunks, for both terms;
+//   - the A operand of batch step s and tile t, lane (m,kk), is x[4s+kk][16t+m] of the field's window in the
+//     staged strip: one 4-byte LDS read per MFMA at a compile-time offset from one address register; the LDS row
+//     stride is 16 or 48 floats past a multiple of 64, so the 16 x 4 floats of a read cover all 64 banks;
+//   - a chunk's MTR tiles (16*MTR rows of dW) are finished after the batch has been summed over for both terms
+//     and are stored (or merged into the old weights) before the next chunk starts.
+// Images, strips and fields at the ragged end: waves past the last field of the row shadow that field and store
+// nothing; vectors past the image row are clamped into it and only reach those waves.
+template <int MTR, int NB, int NSLOT, int RV, bool SSQ>
+__global__ __launch_bounds__(512, 2) void lc_bwd_weights_strip_kernel(
+    Geom g, const float *__restrict__ x1, const float *__restrict__ dy1, const float *__restrict__ x2,
+    const float *__restrict__ dy2, float beta, float gamma, float *__restrict__ out, float *__restrict__ ssq,
+    int strips_per_row, int sq4) {
+    constexpr int NLOC = 8, NTHR = 512, RS = RV * 4, BT = 4 * NB, BUF = NSLOT * NTHR * 4;
+    static_assert(NB % 4 == 0, "batch steps are read from LDS in groups of four");
+    static_assert((4 * (NB - 1) * RS + 16 * (MTR - 1)) * 4 < 65536, "LDS read offsets are 16-bit immediates");
+    extern __shared__ __attribute__((aligned(16))) float xs[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 15, kk = lane >> 4;
+    const int work = remap_xcd(blockIdx.x, gridDim.x);
+    const int i = work / strips_per_row, j0 = (work - i * strips_per_row) * NLOC;
+    const int j = j0 + wave;
+    const bool active = j < g.LW;
+    const int loc = i * g.LW + (active ? j : g.LW - 1);
+    const int f0 = blockIdx.y * 16;
+    const int SC = g.S * g.C, WC = g.W * g.C;
+    const size_t img = (size_t)g.H * WC;
+    const int col0 = j0 * SC;
+    const bool two = x2 != nullptr;
+
+    // B operands: dy[4s+kk][loc][f0+m] for every batch step s, of both terms
+    float dyr[2][NB];
+    {
+        const float *d1 = dy1 + ((size_t)kk * g.L + loc) * g.F + f0 + m;
+        const float *d2 = (two ? dy2 : dy1) + ((size_t)kk * g.L + loc) * g.F + f0 + m;
+        const size_t dstep = (size_t)4 * g.L * g.F;
+#pragma unroll
+        for (int s = 0; s < NB; ++s) {
+            dyr[0][s] = d1[s * dstep];
+            dyr[1][s] = d2[s * dstep];
+        }
+    }
+
+    // where this lane's vector of load q comes from: bytes past the chunk's first vector (image 0, image row
+    // i*S + kh, column col0); pad vectors and the slack behind the last row load that first vector
+    unsigned goff[NSLOT];
+    {
+        const int lim = WC - col0 - 4;
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) {
+            const int P = q * NTHR + tid, b = P / RV, v = P - b * RV;
+            const bool data = b < BT && v < sq4;
+            goff[q] = data ? (unsigned)(((size_t)b * img + min(4 * v, max(lim, 0))) * 4) : 0u;
+        }
+    }
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) float *)xs + wave * 64 * 16;
+    auto stage = [&](const float *src, int kh, int buf) {
+        gbyte_ptr base = (gbyte_ptr)(src + (size_t)(i * g.S + kh) * WC + col0);
+        const unsigned l = lds0 + buf * (BUF * 4);
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) load_lds16(base, goff[q], l + q * (NTHR * 16));
+    };
+
+    const float *abase = xs + kk * RS + wave * SC + m;
+    f32x4 acc[MTR];
+    // batch steps of one chunk and term out of LDS buffer buf: groups of four steps, the next group's reads issued
+    // behind the first MFMAs of the current one
+    auto contract = [&](int term, int buf) {
+        const float *ar = abase + buf * BUF;
+        float a[2][4][MTR];
+        auto read_group = [&](int gs, float (&dst)[4][MTR]) {
+#pragma unroll
+            for (int ss = 0; ss < 4; ++ss)
+#pragma unroll
+                for (int t = 0; t < MTR; ++t) dst[ss][t] = ar[4 * (4 * gs + ss) * RS + 16 * t];
+        };
+        read_group(0, a[0]);
+#pragma unroll
+        for (int gs = 0; gs < NB / 4; ++gs) {
+#pragma unroll
+            for (int ss = 0; ss < 4; ++ss) {
+#pragma unroll
+                for (int t = 0; t < MTR; ++t)
+                    acc[t] = mfma16(a[gs & 1][ss][t], dyr[term][4 * gs + ss], acc[t]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (ss == 0 && gs + 1 < NB / 4) {
+                    read_group(gs + 1, a[(gs + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    };
+    float sq = 0.f;      // sum of squares of the values this lane stored (one filter: f0 + m)
+    // rows kh*RC + 16t + 4kk + r of dW (or of the updated weights) from the chunk's accumulators
+    auto epilogue = [&](int kh) {
+        float *ol = out + ((size_t)loc * g.K + (size_t)kh * g.RC + 4 * kk) * g.F + f0 + m;
+        if (beta == 0.f) {
+#pragma unroll
+            for (int t = 0; t < MTR; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float v = gamma * acc[t][r];
+                    ol[(size_t)(16 * t + r) * g.F] = v;
+                    if constexpr (SSQ) sq += v * v;
+                }
+        } else {
+            float old[MTR][4];
+#pragma unroll
+            for (int t = 0; t < MTR; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) old[t][r] = ol[(size_t)(16 * t + r) * g.F];
+#pragma unroll
+            for (int t = 0; t < MTR; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float v = gamma * acc[t][r] + beta * old[t][r];
+                    ol[(size_t)(16 * t + r) * g.F] = v;
+                    if constexpr (SSQ) sq += v * v;
+                }
+        }
+    };
+    // the chunk's last term: its epilogue, then wait until this lane's x loads of the next chunk have landed.  Behind
+    // those loads the wave has issued only the epilogue's stores and loads (none if it stores nothing).
+    auto finish_chunk = [&](int kh) {
+        if (active) {
+            epilogue(kh);
+            if (beta == 0.f) wait_loads<4 * MTR>();
+            else wait_loads<8 * MTR>();
+        } else {
+            wait_loads<0>();
+        }
+    };
+
+    stage(x1, 0, 0);
+    wait_loads<0>();
+    // The compiler's own wait insertion must see the dy loads finished here: otherwise it keeps waiting for them
+    // inside the loop, by counts that know nothing of the x loads in flight there and so wait for those as well.
+#pragma unroll
+    for (int s = 0; s < NB; ++s) {
+        asm volatile("" : "+v"(dyr[0][s]));
+        asm volatile("" : "+v"(dyr[1][s]));
+    }
+    __syncthreads();
+    int u = 0;       // chunk-terms done: the buffer in use is u & 1
+    for (int kh = 0; kh < g.R; ++kh) {
+        const int khn = kh + 1 < g.R ? kh + 1 : kh;      // the last chunk loads itself once more (values unused)
+#pragma unroll
+        for (int t = 0; t < MTR; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (two) {
+            stage(x2, kh, (u + 1) & 1);
+            contract(0, u & 1);
+            wait_loads<0>();      // nothing was issued behind the x loads
+            __syncthreads();
+            ++u;
+            stage(x1, khn, (u + 1) & 1);
+            contract(1, u & 1);
+        } else {
+            stage(x1, khn, (u + 1) & 1);
+            contract(0, u & 1);
+        }
+        finish_chunk(kh);
+        __syncthreads();
+        ++u;
+    }
+    if constexpr (SSQ) {
+        // per filter: lanes (m, kk = 0..3) hold the partial sums of the filter's rows; one partial per field
+        sq += __shfl_xor(sq, 16, 64);
+        sq += __shfl_xor(sq, 32, 64);
+        if (active && kk == 0) ssq[(size_t)loc * g.F + f0 + m] = sq;
+    }
+}
+
 namespace {
 
 // Host check of a lc_bwd_weights_fast_kernel launch.  tparam = {G, VA, NT, PF, bytes per operand element};
@@ -415,6 +599,56 @@ int launch_fast(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *
     return LC_OK;
 }
 
+// Host check of a lc_bwd_weights_strip_kernel launch.  tparam = {MTR, NB, NSLOT, RV}; arg = {strips per field row, sq4}.
+int check_backward_weights_strip(const Geom &g, const LaunchPlan &p) {
+    const int MTR = p.tparam[0], NB = p.tparam[1], NSLOT = p.tparam[2], RV = p.tparam[3];
+    const int strips = p.arg[0], sq4 = p.arg[1];
+    const int SC = g.S * g.C, WC = g.W * g.C;
+    LC_PLAN_REQUIRE(p, p.block == 512);
+    // the whole batch per chunk; a patch row in whole tiles of 16; filters in whole tiles
+    LC_PLAN_REQUIRE(p, g.B == 4 * NB && NB % 4 == 0 && g.RC == 16 * MTR && g.F % 16 == 0);
+    LC_PLAN_REQUIRE(p, (int)p.grid[1] == g.F / 16 && p.grid[2] == 1);
+    LC_PLAN_REQUIRE(p, strips == ceil_div(g.LW, 8) && (long long)p.grid[0] == (long long)strips * g.LH);
+    // 16-byte vectors of x from every strip's start; the staged strip covers the eight windows and fits an LDS row
+    LC_PLAN_REQUIRE(p, WC % 4 == 0 && (8 * SC) % 4 == 0 && 4 * sq4 >= g.RC + 7 * SC && sq4 <= RV);
+    // the 64 floats of an LDS read (16 consecutive ones of four rows) fall into 64 banks
+    LC_PLAN_REQUIRE(p, (4 * RV) % 64 == 16 || (4 * RV) % 64 == 48);
+    LC_PLAN_REQUIRE(p, (long long)NSLOT * 512 >= (long long)g.B * RV && p.lds_bytes >= (size_t)2 * NSLOT * 512 * 16);
+    // LDS read offsets are 16-bit immediates; the kernel's waits count at most 8*MTR loads and stores
+    LC_PLAN_REQUIRE(p, (4 * (NB - 1) * 4 * RV + 16 * (MTR - 1)) * 4 < 65536 && 8 * MTR <= 63);
+    // 32-bit byte offsets into x; clamped vectors stay inside the image row
+    LC_PLAN_REQUIRE(p, (long long)g.B * g.H * g.W * g.C * 4 < (1LL << 32) && WC - (strips - 1) * 8 * SC >= 4);
+    return LC_OK;
+}
+
+template <int MTR, int NB, int NSLOT, int RV>
+bool backward_weights_strip_fits(const Geom &g) {
+    const int SC = g.S * g.C, WC = g.W * g.C, strips = (g.LW + 7) / 8;
+    const int sq4 = ((g.RC + 7 * SC + 3) & ~3) / 4;
+    return g.B == 4 * NB && g.RC == 16 * MTR && g.F == 16 && WC % 4 == 0 && (8 * SC) % 4 == 0 && sq4 <= RV &&
+           (g.B * RV + 511) / 512 <= NSLOT && (long long)g.B * g.H * g.W * g.C * 4 < (1LL << 32) &&
+           WC - (strips - 1) * 8 * SC >= 4;
+}
+
+template <int MTR, int NB, int NSLOT, int RV>
+int launch_strip(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2, float beta,
+                 float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s) {
+    const int strips = (g.LW + 7) / 8;
+    const int sq4 = ((g.RC + 7 * g.S * g.C + 3) & ~3) / 4;
+    const size_t lds = (size_t)2 * NSLOT * 512 * 16;
+    dim3 grid(strips * g.LH, g.F / 16);
+    const LaunchPlan plan = make_plan("lc_bwd_weights_strip", {MTR, NB, NSLOT, RV}, {strips, sq4}, grid, 512, lds);
+    if (int rc = check_backward_weights_strip(g, plan)) return rc;
+    if (kblocks_out) *kblocks_out = 1;       // one partial sum of squares per field and filter
+    if (ssq)
+        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_strip_kernel<MTR, NB, NSLOT, RV, true>), s, g, x1,
+                  dy1, x2, dy2, beta, gamma, out, ssq, strips, sq4);
+    else
+        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_strip_kernel<MTR, NB, NSLOT, RV, false>), s, g, x1,
+                  dy1, x2, dy2, beta, gamma, out, ssq, strips, sq4);
+    return LC_OK;
+}
+
 // widest vector (4, 2, 1 floats) that never straddles two patch rows
 int patch_vector_width(const Geom &g) {
     for (int v = 4; v > 1; v >>= 1)
@@ -435,6 +669,13 @@ template <typename T>
 int launch_backward_weights_fast_path(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy2, float beta,
                                       float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s, bool *done) {
     *done = false;
+    if constexpr (sizeof(T) == 4) {
+        // 16 filters per field, a batch of 128, patch rows of 48 elements: strips of eight fields out of LDS
+        if (backward_weights_strip_fits<3, 32, 7, 28>(g)) {
+            *done = true;
+            return launch_strip<3, 32, 7, 28>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+        }
+    }
     const int va = patch_vector_width(g);
     if ((g.B & 3) == 0 && va == 4) {
         if (g.F % 64 == 0) { *done = true; return launch_fast_pf<1, 4, 4>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s); }

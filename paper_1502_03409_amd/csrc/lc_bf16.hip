@@ -239,7 +239,7 @@ bool bf16_shape_supported(const Geom &g) {
 }
 
 // Order of preference, every pass: the workgroup-tiled kernels (wide layers), the strip-sharing / pipelined / transposing
-// kernels of the narrow layers (faster than the one-wave-per-task kernels of this file wherever both apply: cfg2
+// kernels of the narrow layers (faster than the one-wave-per-task kernels of this file wherever both apply: the small 32 x 32 x 4 layer
 // 30 / 13 / 9 us against 37 / 21 / 10 us), the kernels of this file, the fp32 kernels on bf16 storage.
 // Host checks of the one-wave-per-task kernels of this file.  tparam = {MT}; arg as listed per function.
 namespace {

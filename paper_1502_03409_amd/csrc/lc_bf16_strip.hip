@@ -1,5 +1,5 @@
 // bf16 operands on the layers whose patch rows are not multiples of 16 values or whose filters come in blocks of 16
-// or 32 (workloads cfg3 and cfg5): lc_forward with the strip-sharing decomposition of the fp32 pipelined kernel
+// or 32: lc_forward with the strip-sharing decomposition of the fp32 pipelined kernel
 // (Sec. 3.1's untied fields overlap by R-S pixels, so a strip of adjacent fields shares the image rows it reads) and
 // v_mfma_f32_16x16x16_bf16 in place of the fp32 matrix instruction.
 //
@@ -271,7 +271,7 @@ int launch_strip_nb(const Geom &g, const bf16_t *x, const bf16_t *w, const float
 }
 
 // Batch tiles of 64 images: three workgroups fit a compute unit and the second tile of a strip finds the weights in
-// L2.  128-image tiles (two per compute unit, one round of 512 plus a remainder launch for cfg3's 552 strips)
+// L2.  128-image tiles (two per compute unit, one round of 512 plus a remainder launch where the strips do not fill a second round)
 // measured slower: 114 against 106 us.
 template <int NT>
 int launch_strip_mt(const Geom &g, const bf16_t *x, const bf16_t *w, const float *bias, float alpha, float *y, int CQ,
@@ -419,16 +419,16 @@ int launch_rows(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, fl
     return LC_OK;
 }
 
-// one step in flight and four waves per SIMD measured as fast as two steps and three waves (cfg3: 150 vs 153 us)
+// one step in flight and four waves per SIMD measured as fast as two steps and three waves (104 x 104 x 12 input, 10 x 10 fields, 32 filters, batch 128: 150 vs 153 us)
 template <int G, int NT>
 int launch_rows_pf(const Geom &g, const bf16_t *x, const bf16_t *dy, float beta, float *out, hipStream_t s) {
     return launch_rows<G, NT, 1>(g, x, dy, beta, out, s);
 }
 
 // The weight gradient with the patches shared through LDS.  In the kernel above every wave fetches its own
-// 1200 x 128 patch, and those 8-byte loads are what binds it (cfg3: 152 us, 88 us with the patch loads compiled out).
+// 1200 x 128 patch, and those 8-byte loads are what binds it (same layer: 152 us, 88 us with the patch loads compiled out).
 // Here a workgroup takes four adjacent fields and stages, per patch row, the image-row strip they share (as the
-// forward kernel does; 2.5x fewer patch bytes in cfg3, fetched once); wave = field.  Per patch row a wave contracts
+// forward kernel does; 2.5x fewer patch bytes on that layer, fetched once); wave = field.  Per patch row a wave contracts
 // over the whole batch: lane (m,kk) reads the patch values 64 blk + 4 m .. +3 of the four images 16 s + 4 kk .. +3
 // from LDS and transposes them in registers into four operands; the dy operands of all steps sit in registers for
 // the whole kernel (batches up to 128 images).  The 64 x 16 NT tile of a patch row is stored as soon as it is

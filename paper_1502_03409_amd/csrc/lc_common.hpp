@@ -69,6 +69,51 @@ __device__ __forceinline__ float fget(const typename FVec<N>::T &v, int i) {
 }
 
 
+// ---------------------------------------------------------------------------------------------
+// Loads whose waits are written by hand.  The kernels that use them keep a fixed program order of their memory
+// operations and wait with explicit counts (the memory counter retires loads, and on this chip stores, in the order
+// they were issued), because the compiler's wait insertion, which does not know the order of a loop's iterations,
+// waits for more than is needed and so for loads that have just been issued.  Inline assembly is invisible to that
+// insertion: nothing here is waited for unless the kernel says so.
+typedef const __attribute__((address_space(1))) char *gbyte_ptr;
+
+// The base pointers and LDS addresses below are "s" operands: a value the compiler does not hold in scalar registers
+// fails to assemble (it is never moved there silently).  Every memory instruction is preceded by five wait states
+// (s_nop 4): that is what the hardware needs between a vector-ALU write of a scalar register (a v_readfirstlane the
+// compiler may have scheduled right in front of the statement) and a memory instruction that reads it as its base,
+// and the compiler's hazard handling does not look inside inline assembly.  It also covers the one wait state between
+// the write of m0 and the LDS-direct load that uses it.
+//
+// 16 bytes per lane from base + off straight into LDS: lane i's vector lands at lds_addr + 16 i (lds_addr: byte
+// address inside the workgroup's LDS, the same for the whole wave, as is base)
+__device__ __forceinline__ void load_lds16(gbyte_ptr base, unsigned off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(off), "s"(base)
+                 : "memory");
+}
+// N consecutive floats (1, 2 or 4) per lane from base + off into registers; the value may be used only after
+// wait_loads has been called on it
+template <int N>
+__device__ __forceinline__ typename FVec<N>::T load_nowait(gbyte_ptr base, unsigned off) {
+    typename FVec<N>::T v;
+    if constexpr (N == 1)
+        asm volatile("s_nop 4\n\tglobal_load_dword %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
+    else if constexpr (N == 2)
+        asm volatile("s_nop 4\n\tglobal_load_dwordx2 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
+    else
+        asm volatile("s_nop 4\n\tglobal_load_dwordx4 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
+    return v;
+}
+// wait until at most N of the memory operations issued so far are in flight; v: a value one of the finished loads
+// delivers (ties the wait to the value's uses)
+template <int N, typename V>
+__device__ __forceinline__ void wait_loads(V &v) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Operand storage.  T = float, or bf16_t: bf16 bit patterns that are widened to fp32 (exactly) on their way to
 // LDS or to the B operand, so the same fp32 MFMAs serve both; bf16 storage halves the bytes fetched.
 typedef unsigned short bf16_t;

@@ -374,31 +374,6 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void lc_forward_fast_kern
 //         chunk c:  [NSLOT x loads of chunk c+1]  then per k-step p: wait, MFMAs, [one weight load, of k-step p+U]
 //     so the weights of k-step p are followed by U-1 younger weight loads and, for p < U, by the chunk's x loads.
 // The last chunk loads its own x and weights once more (valid addresses, values unused) so that the counts hold.
-typedef const __attribute__((address_space(1))) char *gbyte_ptr;
-
-__device__ __forceinline__ void fwd_load_lds16(gbyte_ptr base, unsigned off, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(off), "s"(base)
-                 : "memory");
-}
-// NT consecutive floats per lane into registers; usable only after fwd_wait has been called on the value
-template <int NT>
-__device__ __forceinline__ typename FVec<NT>::T fwd_load_nowait(gbyte_ptr base, unsigned off) {
-    typename FVec<NT>::T v;
-    if constexpr (NT == 1) asm volatile("global_load_dword %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
-    else if constexpr (NT == 2) asm volatile("global_load_dwordx2 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
-    else asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
-    return v;
-}
-// wait until at most N of the loads issued so far are in flight; v is a value one of the finished loads delivers
-template <int N, typename V>
-__device__ __forceinline__ void fwd_wait(V &v) {
-    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void fwd_wait() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 template <int MT, int NT, int NLOC, int NW, int SPC, int NRT, int NSLOT, int U, int NBUF>
 __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_forward_direct_kernel(
     Geom g, const float *__restrict__ x, const float *__restrict__ w, const float *__restrict__ bias, float alpha,
@@ -446,7 +421,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
     auto wchunk = [&](int kh) -> gbyte_ptr { return wloc + (size_t)kh * g.RC * g.F * 4; };
     WV wr[U];
 #pragma unroll
-    for (int p = 0; p < U; ++p) wr[p] = fwd_load_nowait<NT>(wloc + (size_t)step_row(p) * g.F * 4, step_lane(p));
+    for (int p = 0; p < U; ++p) wr[p] = load_nowait<NT>(wloc + (size_t)step_row(p) * g.F * 4, step_lane(p));
 
     // where this lane's vector of load q comes from: bytes past the chunk's first vector (image b0, image row
     // i*S + kh, column col0)
@@ -467,7 +442,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
         gbyte_ptr base = (gbyte_ptr)(x + (size_t)b0 * img + (size_t)(i * g.S + kh) * WC + col0);
         const unsigned l = lds0 + buf * (BUF * 4);
 #pragma unroll
-        for (int q = 0; q < NSLOT; ++q) fwd_load_lds16(base, goff[q], l + q * (NTHR * 16));
+        for (int q = 0; q < NSLOT; ++q) load_lds16(base, goff[q], l + q * (NTHR * 16));
     };
 
     // the lane's four floats of group gi, patch row r of the chunk, image m + 16 mt: abase + mt*16*RS + r*sq4*4 + 16 gi
@@ -475,7 +450,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
     const float *abaseT = xs + (lane & 15) * RS + wl * SC + 16 * NG4 + GT * kk;
     if constexpr (NBUF == 2) {
         stage(0, 0);
-        fwd_wait<0>();
+        wait_loads<0>();
         __syncthreads();
     }
     int c = 0;
@@ -489,7 +464,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
         } else {
             if (c > 0) __syncthreads();      // everybody is through with the previous chunk
             stage(kh, 0);
-            fwd_wait<0>();
+            wait_loads<0>();
             __syncthreads();
         }
         gbyte_ptr wc = wchunk(kh), wn = wchunk(khn);
@@ -522,8 +497,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
                 for (int t = 0; t < G; ++t) {
                     const int p = r * SPC + 4 * gi + t;       // k-step of the chunk
                     // (the loop is unrolled: p is a constant by the time this is compiled)
-                    if (p < U) fwd_wait<U - 1 + NSLOT>(wr[p % U]);
-                    else fwd_wait<U - 1>(wr[p % U]);
+                    if (p < U) wait_loads<U - 1 + NSLOT>(wr[p % U]);
+                    else wait_loads<U - 1>(wr[p % U]);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
@@ -539,20 +514,20 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
                     const int pn = p + U;                     // the k-step whose weights take this ring slot
                     gbyte_ptr wp = pn < NS ? wc : wn;
                     const int pp = pn < NS ? pn : pn - NS;
-                    wr[p % U] = fwd_load_nowait<NT>(wp + (size_t)step_row(pp) * g.F * 4, step_lane(pp));
+                    wr[p % U] = load_nowait<NT>(wp + (size_t)step_row(pp) * g.F * 4, step_lane(pp));
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
         if constexpr (NBUF == 2) {
             // this lane's x loads of the next chunk have landed (the NS weight loads behind them may fly on)
-            fwd_wait<NS>();
+            wait_loads<NS>();
             __syncthreads();
         }
     }
     // the weights loaded last are not used: they must have landed before their registers are given up
 #pragma unroll
-    for (int p = 0; p < U; ++p) fwd_wait<0>(wr[p]);
+    for (int p = 0; p < U; ++p) wait_loads<0>(wr[p]);
 
     if (!active) return;
     if (alpha_dev) alpha = *alpha_dev;
@@ -805,7 +780,7 @@ int launch_fast_tiered(const Geom &g, const T *x, const T *w, const float *bias,
                     (size_t)16 * MT * fast_row_stride(c * sqc) * 4 <= 52 * 1024 && c <= 15) { nr = c; break; }
         }
     }
-    // 32-image tiles, two patch rows of 12 k-steps in eight staging slots (cfg2): compile-time counts
+    // 32-image tiles, two patch rows of 12 k-steps in eight staging slots: compile-time counts
     if constexpr (MT == 2 && UNR == 6 && sizeof(T) == 4) {
         const int sq4 = ((CQ + (NLOC - 1) * g.S * g.C + 3) & ~3) / 4;
         if (CQ == g.RC && (CQ >> 2) == 12 && nr == 2 && g.R % 2 == 0 && (32 * 2 * sq4 + 255) / 256 == 8 &&

@@ -845,7 +845,7 @@ int launch_l2pool_fwd(const float *x, float *y, int B, int H, int W, int C, int 
     const size_t patch_bytes = (size_t)(kPoolTH + ks - 1) * (kPoolTW + ks - 1) * C * sizeof(float);
     if (C % 4 == 0 && st == 1 && ks == 3 && Ho > 0 && Wo > 0 && B > 0) {
         // segments of RS rows, a multiple of the four rows a thread has in flight: enough segments for about
-        // sixteen waves per compute unit (cfg3's shape: 8 rows 11.7 us, 4 rows 12.1 us, 16 rows 13.5 us)
+        // sixteen waves per compute unit (48 x 48 x 32 maps, batch 128: 8 rows 11.7 us, 4 rows 12.1 us, 16 rows 13.5 us)
         const int CV = C / 4;
         const long long cols = (long long)B * Wo * CV;
         const long long want = std::max<long long>((256LL * 16 * 64 + cols - 1) / cols, 1);

@@ -258,6 +258,23 @@ def check_plans(g, op, dtype, plans, replay):
             seen = covered_backward_data_fast(g, p)
             want = {(ri, ws * NCELL, bt) for ri in range(cdiv(g.H, g.S)) for ws in range(strips) for bt in range(nbt)}
             assert set(seen) == want and all(v == 1 for v in seen.values()), g
+    elif fams == {"lc_bwd_weights_strip"}:
+        # strips of eight fields (one per wave), the whole batch per chunk, x staged straight into LDS
+        p = plans[0]
+        MTR, NB, NSLOT, RV = p["tparam"][:4]
+        strips, sq4 = p["arg"][:2]
+        SC, WC = g.S * g.C, g.W * g.C
+        assert p["block"] == 512 and g.B == 4 * NB and NB % 4 == 0 and g.R * g.C == 16 * MTR and g.F % 16 == 0
+        assert list(p["grid"][:2]) == [cdiv(g.LW, 8) * g.LH, g.F // 16] and strips == cdiv(g.LW, 8)
+        assert WC % 4 == 0 and (8 * SC) % 4 == 0 and g.R * g.C + 7 * SC <= 4 * sq4 and sq4 <= RV
+        assert (4 * RV) % 64 in (16, 48)                       # an LDS read's 16 floats x 4 rows: 64 banks
+        assert NSLOT * 512 >= g.B * RV and p["lds_bytes"] == 2 * NSLOT * 512 * 16 <= LDS_PER_CU
+        assert (4 * (NB - 1) * 4 * RV + 16 * (MTR - 1)) * 4 < 65536 and 8 * MTR <= 63
+        assert g.B * g.H * WC * 4 < 2 ** 32 and WC - (strips - 1) * 8 * SC >= 4
+        # largest clamped offset ends inside x
+        img = g.H * WC
+        row = (g.LH - 1) * g.S + g.R - 1
+        assert (g.B - 1) * img + row * WC + (strips - 1) * 8 * SC + min(4 * sq4 - 4, WC - (strips - 1) * 8 * SC - 4) + 4 <= g.B * img
     elif fams == {"lc_bwd_weights_fast"} or fams == {"lc_bwd_weights_generic"} or fams == {"lc_bwd_weights_bf16_rows"}:
         p = plans[0]
         kblocks, ntasks = p["arg"][:2]
@@ -352,3 +369,95 @@ def test_bf16_is_never_refused_on_shape_alone():
         G = lc.geom(*g.as_tuple())
         for op in OPS:
             assert len(lc.plan_query(G, op, B.LC_BF16)) >= 1
+
+
+# ------------------------------------------------------------------------- addresses of the hand-scheduled kernels
+def _x_strip_offsets_inside(g, BT, NRT, NSLOT, NTHR, RV, sq4, NLOC, strips, nbt, works):
+    """Element offsets into x of every lane's 16-byte load of the kernels that stage strips of fields straight into
+    LDS (forward: NRT patch rows per chunk and batch tiles; weight gradient: one row, the whole batch)."""
+    SC, WC = g.S * g.C, g.W * g.C
+    img = g.H * WC
+    tid = np.arange(NTHR)
+    for work in works:
+        i, j0 = work // strips, (work % strips) * NLOC
+        col0 = j0 * SC
+        lim = WC - col0 - 4
+        for bt in range(nbt):
+            b0 = bt * BT
+            for q in range(NSLOT):
+                P = q * NTHR + tid
+                b, v = P // RV, P % RV
+                r, vv = v // sq4, v % sq4
+                data = (b < BT) & (r < NRT)
+                goff = np.where(data, np.minimum(b, g.B - 1 - b0) * img + r * WC + np.minimum(4 * vv, max(lim, 0)), 0)
+                for kh in (0, g.R - NRT):
+                    a = b0 * img + (i * g.S + kh) * WC + col0 + goff
+                    assert a.min() >= 0 and a.max() + 4 <= g.B * img, (g, work, bt, q, kh)
+
+
+@pytest.mark.parametrize("name", ["cfg5_s1", "cfg5_s2", "cfg2", "stage_small"])
+def test_hand_scheduled_kernels_stay_inside_their_tensors(name):
+    """The kernels with inline-assembly loads compute their addresses from offsets worked out once per workgroup;
+    this replays that arithmetic for every workgroup of the launch plan and checks each address against its tensor."""
+    g = wl.LCGeom(B=128, H=36, W=40, C=3, R=16, S=2, F=16) if name == "stage_small" else wl.CONFIG_GEOM[name]
+    G = lc.geom(*g.as_tuple())
+    SC, WC, RC = g.S * g.C, g.W * g.C, g.R * g.C
+    seen = set()
+    for op in OPS:
+        for p in lc.plan_query(G, op):
+            seen.add(p["kernel"])
+            if p["kernel"] == "lc_forward_direct":
+                MT, NT, NLOC, U, NW, _, SPC, NRT, NSLOT, NBUF = p["tparam"][:10]
+                _, sq4, RS, _, first, count, nbt, strips = p["arg"][:8]
+                _x_strip_offsets_inside(g, 16 * MT, NRT, NSLOT, 64 * NW, RS // 4, sq4, NLOC, strips, nbt,
+                                        range(first, first + count))
+                # rows of w[l] a chunk's k-steps contract: groups of 16 (lane kk takes rows 4kk..4kk+3) and a tail group
+                rows = [kh * RC + r * RC + (16 * (s_ // 4) + (s_ & 3) + 12 if s_ // 4 < SPC // 4
+                                           else 16 * (SPC // 4) + (s_ - 4 * (SPC // 4)) + 3 * (SPC % 4))
+                        for kh in range(0, g.R, NRT) for r in range(NRT) for s_ in range(SPC)]
+                assert max(rows) < g.K
+            elif p["kernel"] == "lc_bwd_weights_strip":
+                MTR, NB, NSLOT, RV = p["tparam"][:4]
+                strips, sq4 = p["arg"][:2]
+                _x_strip_offsets_inside(g, 4 * NB, 1, NSLOT, 512, RV, sq4, 8, strips, 1, range(strips * g.LH))
+                assert ((4 * NB - 1) * g.L + g.L - 1) * g.F + g.F - 1 < g.B * g.L * g.F
+                assert ((g.L - 1) * g.K + (g.R - 1) * RC + 15 + 16 * (MTR - 1)) * g.F + g.F - 1 < g.L * g.K * g.F
+            elif p["kernel"] == "lc_bwd_data_direct":
+                MT, NT, NCELL, AP, NW = p["tparam"][:5]
+                strips, RS, nbt = p["arg"][:3]
+                BT, RV, NTHR = 16 * MT, RS // 4, 64 * NW
+                R4, NV = RV - 1, 16 * MT * (RS // 4)
+                NSLOT = cdiv(NV, NTHR)
+                dyimg, nfh = g.L * g.F, g.F // 16
+                tid = np.arange(NTHR)
+                for ri in range(cdiv(g.H, g.S)):
+                    a_lo, a_hi = max(0, ri - (g.LH - 1)), min(AP - 1, ri)
+                    if a_hi < a_lo:
+                        continue
+                    for ws in range(strips):
+                        jlo = ws * NCELL - (AP - 1)
+                        for bt in range(nbt):
+                            b0 = bt * BT
+                            for q in range(NSLOT):
+                                P = q * NTHR + tid
+                                b, v = P // RV, P % RV
+                                j = jlo + (v >> 2)
+                                ok = (P < NV) & (v < R4) & (b0 + b < g.B) & (j >= 0) & (j < g.LW)
+                                goff = np.where(ok, b * dyimg + j * g.F + (v & 3) * 4, 0)
+                                live = ok | ~((P < NV) & (v < R4))
+                                # every wave of every load has a live lane (the kernel's waits count on it)
+                                assert live.reshape(-1, 64).any(axis=1).all()
+                                for a in (a_lo, a_hi):
+                                    for fh in (0, nfh - 1):
+                                        ad = b0 * dyimg + (ri - a) * g.LW * g.F + fh * 16 + goff
+                                        assert ad.min() >= 0 and ad.max() + 4 <= g.B * dyimg, (g, ri, ws, bt, q)
+                        for wc in range(NCELL):
+                            for a in (a_lo, a_hi):
+                                for ap in range(AP):
+                                    j = min(max(ws * NCELL + wc - ap, 0), g.LW - 1)
+                                    base = (((ri - a) * g.LW + j) * g.K + g.S * a * RC + g.S * ap * g.C) * g.F
+                                    nn = np.arange(g.S * SC)
+                                    kn = ((nn // SC) * RC + nn % SC) * g.F
+                                    assert base >= 0 and base + (nfh - 1) * 16 + kn.max() + 16 <= g.L * g.K * g.F
+    if name == "cfg5_s1":
+        assert {"lc_forward_direct", "lc_bwd_data_direct", "lc_bwd_weights_strip"} <= seen

@@ -511,6 +511,9 @@ SAE_CASES = {
     "floor": (wl.LCGeom(B=12, H=23, W=23, C=4, R=6, S=2, F=8), "halfnormal"),
     "ragged": (wl.LCGeom(B=7, H=14, W=17, C=3, R=5, S=3, F=10), "gaussian"),
     "stage_like": (wl.LCGeom(B=32, H=32, W=32, C=3, R=16, S=2, F=16), "pink"),
+    # the first stage of the three-stage workload on a small image: 16 filters, patch rows of 48, a batch of 128 (the
+    # forward and weight-gradient kernels that stage strips of eight fields straight into LDS, both gradient terms)
+    "stage_b128": (wl.LCGeom(B=128, H=36, W=40, C=3, R=16, S=2, F=16), "pink"),
     "wide": (wl.LCGeom(B=80, H=12, W=14, C=8, R=4, S=2, F=128), "halfnormal"),       # the workgroup-tiled forward inside the step
     "cells128": (wl.LCGeom(B=72, H=10, W=12, C=32, R=4, S=2, F=32), "halfnormal"),   # the workgroup-tiled backward data inside the step
     # one field covering its whole input: the dense last layer of Sec. 3.1 scaled down (forward cut into slices)
