@@ -517,6 +517,17 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bw
                 if (live[q]) load_lds16(base, goff[q], l + q * (NTHR * 16));
         };
 
+        // With two buffers, the dy loads of the next chunk go out a few at a time (SPS per step) behind the MFMAs of the
+        // first half of the steps instead of all at the chunk's start, where they queue up in the compute unit's one
+        // address unit with the waves, which issue in order, standing behind them; in the first half, so that the last
+        // one has half a chunk to land.
+        constexpr bool kSpread = NBUF == 2;
+        constexpr int NSP = AP / 2 > 0 ? AP / 2 : 1, SPS = (NSLOT + NSP - 1) / NSP;
+        constexpr int kLastDmaStep = (NSLOT - 1) / SPS;
+        auto dma_in_step = [&](int ap) -> int {
+            const int lo = ap * SPS, hi = (ap + 1) * SPS < NSLOT ? (ap + 1) * SPS : NSLOT;
+            return hi > lo ? hi - lo : 0;
+        };
         Chunk c0 = {a_lo, 0}, c1 = after(c0);     // chunks c and c+1
         // the lane's dy vector of image m + 16 mt under the wave's cell at step a' lies at
         // abase + mt*16*RS + (AP-1-a')*16: field column wc - a' + AP - 1 of the staged strip
@@ -529,8 +540,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bw
         for (int c = 0; c < nchunks; ++c) {
             const Chunk cn = c + 1 < nchunks ? c1 : c0;
             const float *arow = abase;
+            gbyte_ptr dnext = (gbyte_ptr)(dy + (size_t)b0 * dyimg + (size_t)((ri - cn.a) * g.LW) * g.F + cn.fh * 16);
+            const unsigned lnext = lds0 + ((c + 1) & 1) * (BUF * 4);
             if constexpr (NBUF == 2) {
-                stage(cn, (c + 1) & 1);
+                if constexpr (!kSpread) stage(cn, (c + 1) & 1);
                 arow += (c & 1) * BUF;
             } else {
                 // one buffer, and several workgroups on a compute unit to work while this one waits for its dy
@@ -548,8 +561,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bw
                 const bool inside = wi - ap >= 0 && wi - ap < g.LW;   // a field column outside the grid contributes
                                                                       // nothing: its MFMAs are skipped (by the whole wave)
                 if constexpr (NBUF == 2) {
+                    // behind the weights of step a': those of the other AP-1 steps and every dy load but this step's own
+                    // (the loop is unrolled: a' is a constant by the time this is compiled)
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) wait_loads<AP * NT - NT + NSLOT>(wb[ap][nt]);
+                    for (int nt = 0; nt < NT; ++nt)
+                        wait_loads_minus<AP * NT - NT + NSLOT, SPS>(kSpread ? dma_in_step(ap) : 0, wb[ap][nt]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 auto mfmas = [&](int t) {
@@ -573,6 +589,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bw
                 __builtin_amdgcn_sched_barrier(0);
                 if (inside) { mfmas(2); mfmas(3); }
                 __builtin_amdgcn_sched_barrier(0);
+                if constexpr (kSpread) {
+#pragma unroll
+                    for (int q = ap * SPS; q < (ap + 1) * SPS && q < NSLOT; ++q)
+                        if (live[q]) load_lds16(dnext, goff[q], lnext + q * (NTHR * 16));
+                }
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) wb[ap][nt] = load_nowait<4>(pn, kn[nt]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -581,7 +602,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_bw
                 // this lane's dy loads of the next chunk have landed (the AP*NT weight loads behind them may fly on);
                 // behind the barrier, everybody's have, and everybody is through with the buffer the chunk after next
                 // overwrites
-                wait_loads<AP * NT>();
+                if constexpr (kSpread) wait_loads<(AP - kLastDmaStep) * NT>();
+                else wait_loads<AP * NT>();
                 __syncthreads();
             }
             c0 = c1; c1 = after(c1);

@@ -394,14 +394,15 @@ int launch_nt(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *dy
 //     and are stored (or merged into the old weights) before the next chunk starts.
 // Images, strips and fields at the ragged end: waves past the last field of the row shadow that field and store
 // nothing; vectors past the image row are clamped into it and only reach those waves.
-template <int MTR, int NB, int NSLOT, int RV, bool SSQ>
-__global__ __launch_bounds__(512, 2) void lc_bwd_weights_strip_kernel(
+template <int NLOC, int MTR, int NB, int NSLOT, int RV, bool SSQ>
+__global__ __launch_bounds__(64 * NLOC, NLOC == 8 ? 2 : 1) void lc_bwd_weights_strip_kernel(
     Geom g, const float *__restrict__ x1, const float *__restrict__ dy1, const float *__restrict__ x2,
     const float *__restrict__ dy2, float beta, float gamma, float *__restrict__ out, float *__restrict__ ssq,
     int strips_per_row, int sq4) {
-    constexpr int NLOC = 8, NTHR = 512, RS = RV * 4, BT = 4 * NB, BUF = NSLOT * NTHR * 4;
-    static_assert(NB % 4 == 0, "batch steps are read from LDS in groups of four");
-    static_assert((4 * (NB - 1) * RS + 16 * (MTR - 1)) * 4 < 65536, "LDS read offsets are 16-bit immediates");
+    constexpr int NTHR = 64 * NLOC, RS = RV * 4, BT = 4 * NB, BUF = NSLOT * NTHR * 4;
+    constexpr int NG = NB / 2;                // batch steps are read from LDS in groups of two
+    static_assert(NB % 16 == 0 && NSLOT <= NG / 2, "one x load per group in the first half of a chunk's groups");
+    static_assert((4 * (NB / 2 - 1) * RS + 16 * (MTR - 1)) * 4 < 65536, "LDS read offsets are 16-bit immediates");
     extern __shared__ __attribute__((aligned(16))) float xs[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -443,84 +444,63 @@ __global__ __launch_bounds__(512, 2) void lc_bwd_weights_strip_kernel(
         }
     }
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) float *)xs + wave * 64 * 16;
-    auto stage = [&](const float *src, int kh, int buf) {
-        gbyte_ptr base = (gbyte_ptr)(src + (size_t)(i * g.S + kh) * WC + col0);
-        const unsigned l = lds0 + buf * (BUF * 4);
-#pragma unroll
-        for (int q = 0; q < NSLOT; ++q) load_lds16(base, goff[q], l + q * (NTHR * 16));
-    };
 
     const float *abase = xs + kk * RS + wave * SC + m;
     f32x4 acc[MTR];
-    // batch steps of one chunk and term out of LDS buffer buf: groups of four steps, the next group's reads issued
-    // behind the first MFMAs of the current one
-    auto contract = [&](int term, int buf) {
+    // The rows of out a chunk finishes: kh*RC + 16t + 4kk + r.  The address is a scalar base (field, chunk, row) plus
+    // the lane's offset, so the epilogue has no address arithmetic in vector registers.
+    const unsigned olane = (unsigned)((4 * kk * g.F + m) * 4);
+    auto out_row = [&](int kh, int t, int r) -> gbyte_ptr {
+        return (gbyte_ptr)(out + ((size_t)loc * g.K + (size_t)kh * g.RC + 16 * t + r) * g.F + f0);
+    };
+    float old[MTR][4];      // beta != 0: the rows' old values, requested at the start of the chunk's last term
+
+    // Batch steps of one chunk and term out of LDS buffer buf: groups of two steps, the next group's reads issued
+    // behind the first MFMAs of the current one.  The x loads of the chunk-term after this one (row kh_next of
+    // src_next, into the other buffer) go out one per group over the first groups: issued all at once at the
+    // chunk's start they queue up in the compute unit's one address unit (16 cycles per load) and the waves, which
+    // issue in order, stand behind them before their first MFMA; in the first half, so that the last one has half a
+    // chunk to land.
+    auto contract = [&](int term, int buf, const float *src_next, int kh_next) {
+        gbyte_ptr nbase = (gbyte_ptr)(src_next + (size_t)(i * g.S + kh_next) * WC + col0);
+        const unsigned nl = lds0 + (buf ^ 1) * (BUF * 4);
         const float *ar = abase + buf * BUF;
-        float a[2][4][MTR];
-        auto read_group = [&](int gs, float (&dst)[4][MTR]) {
+        const float *ar2 = ar + 4 * (NB / 2) * RS;        // second half of the batch (16-bit read offsets)
+        float a[2][2][MTR];
+        auto read_group = [&](int gs, float (&dst)[2][MTR]) {
 #pragma unroll
-            for (int ss = 0; ss < 4; ++ss)
+            for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
-                for (int t = 0; t < MTR; ++t) dst[ss][t] = ar[4 * (4 * gs + ss) * RS + 16 * t];
+                for (int t = 0; t < MTR; ++t) {
+                    const int s = 2 * gs + ss;
+                    dst[ss][t] = s < NB / 2 ? ar[4 * s * RS + 16 * t] : ar2[4 * (s - NB / 2) * RS + 16 * t];
+                }
         };
         read_group(0, a[0]);
 #pragma unroll
-        for (int gs = 0; gs < NB / 4; ++gs) {
+        for (int gs = 0; gs < NG; ++gs) {
 #pragma unroll
-            for (int ss = 0; ss < 4; ++ss) {
+            for (int ss = 0; ss < 2; ++ss) {
 #pragma unroll
                 for (int t = 0; t < MTR; ++t)
-                    acc[t] = mfma16(a[gs & 1][ss][t], dyr[term][4 * gs + ss], acc[t]);
+                    acc[t] = mfma16(a[gs & 1][ss][t], dyr[term][2 * gs + ss], acc[t]);
                 __builtin_amdgcn_sched_barrier(0);
-                if (ss == 0 && gs + 1 < NB / 4) {
-                    read_group(gs + 1, a[(gs + 1) & 1]);
+                if (ss == 0) {
+                    if (gs + 1 < NG) read_group(gs + 1, a[(gs + 1) & 1]);
+                    if (gs < NSLOT) load_lds16(nbase, goff[gs], nl + gs * (NTHR * 16));
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
     };
     float sq = 0.f;      // sum of squares of the values this lane stored (one filter: f0 + m)
-    // rows kh*RC + 16t + 4kk + r of dW (or of the updated weights) from the chunk's accumulators
-    auto epilogue = [&](int kh) {
-        float *ol = out + ((size_t)loc * g.K + (size_t)kh * g.RC + 4 * kk) * g.F + f0 + m;
-        if (beta == 0.f) {
-#pragma unroll
-            for (int t = 0; t < MTR; ++t)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float v = gamma * acc[t][r];
-                    ol[(size_t)(16 * t + r) * g.F] = v;
-                    if constexpr (SSQ) sq += v * v;
-                }
-        } else {
-            float old[MTR][4];
-#pragma unroll
-            for (int t = 0; t < MTR; ++t)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) old[t][r] = ol[(size_t)(16 * t + r) * g.F];
-#pragma unroll
-            for (int t = 0; t < MTR; ++t)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float v = gamma * acc[t][r] + beta * old[t][r];
-                    ol[(size_t)(16 * t + r) * g.F] = v;
-                    if constexpr (SSQ) sq += v * v;
-                }
-        }
-    };
-    // the chunk's last term: its epilogue, then wait until this lane's x loads of the next chunk have landed.  Behind
-    // those loads the wave has issued only the epilogue's stores and loads (none if it stores nothing).
-    auto finish_chunk = [&](int kh) {
-        if (active) {
-            epilogue(kh);
-            if (beta == 0.f) wait_loads<4 * MTR>();
-            else wait_loads<8 * MTR>();
-        } else {
-            wait_loads<0>();
-        }
-    };
 
-    stage(x1, 0, 0);
+    // initial chunk: all its x loads at once
+    {
+        gbyte_ptr base = (gbyte_ptr)(x1 + (size_t)(i * g.S) * WC + col0);
+#pragma unroll
+        for (int q = 0; q < NSLOT; ++q) load_lds16(base, goff[q], lds0 + q * (NTHR * 16));
+    }
     wait_loads<0>();
     // The compiler's own wait insertion must see the dy loads finished here: otherwise it keeps waiting for them
     // inside the loop, by counts that know nothing of the x loads in flight there and so wait for those as well.
@@ -536,18 +516,42 @@ __global__ __launch_bounds__(512, 2) void lc_bwd_weights_strip_kernel(
 #pragma unroll
         for (int t = 0; t < MTR; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         if (two) {
-            stage(x2, kh, (u + 1) & 1);
-            contract(0, u & 1);
+            contract(0, u & 1, x2, kh);
             wait_loads<0>();      // nothing was issued behind the x loads
             __syncthreads();
             ++u;
-            stage(x1, khn, (u + 1) & 1);
-            contract(1, u & 1);
-        } else {
-            stage(x1, khn, (u + 1) & 1);
-            contract(0, u & 1);
         }
-        finish_chunk(kh);
+        // The chunk's last term.  Memory operations of this wave from here to the barrier, in order: the rows' old
+        // values (4*MTR loads; beta != 0 and the wave stores at all), the NSLOT x loads of the next chunk-term, the
+        // 4*MTR stores of the epilogue.  The old values are waited for with the x loads still in flight, and the
+        // barrier with the stores still in flight.
+        const bool merge = active && beta != 0.f;
+        if (merge) {
+#pragma unroll
+            for (int t = 0; t < MTR; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) old[t][r] = load_nowait<1>(out_row(kh, t, r), olane);
+        }
+        contract(two ? 1 : 0, u & 1, x1, khn);
+        if (active) {
+            if (merge) {
+#pragma unroll
+                for (int t = 0; t < MTR; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) wait_loads<NSLOT>(old[t][r]);
+            }
+#pragma unroll
+            for (int t = 0; t < MTR; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float v = merge ? gamma * acc[t][r] + beta * old[t][r] : gamma * acc[t][r];
+                    store_nowait(out_row(kh, t, r), olane, v);
+                    if constexpr (SSQ) sq += v * v;
+                }
+            wait_loads<4 * MTR>();      // the x loads of the next chunk-term have landed; the stores may fly on
+        } else {
+            wait_loads<0>();
+        }
         __syncthreads();
         ++u;
     }
@@ -599,52 +603,55 @@ int launch_fast(const Geom &g, const T *x1, const T *dy1, const T *x2, const T *
     return LC_OK;
 }
 
-// Host check of a lc_bwd_weights_strip_kernel launch.  tparam = {MTR, NB, NSLOT, RV}; arg = {strips per field row, sq4}.
+// Host check of a lc_bwd_weights_strip_kernel launch.  tparam = {MTR, NB, NSLOT, RV, NLOC}; arg = {strips per field row,
+// sq4}.
 int check_backward_weights_strip(const Geom &g, const LaunchPlan &p) {
-    const int MTR = p.tparam[0], NB = p.tparam[1], NSLOT = p.tparam[2], RV = p.tparam[3];
+    const int MTR = p.tparam[0], NB = p.tparam[1], NSLOT = p.tparam[2], RV = p.tparam[3], NLOC = p.tparam[4];
     const int strips = p.arg[0], sq4 = p.arg[1];
-    const int SC = g.S * g.C, WC = g.W * g.C;
-    LC_PLAN_REQUIRE(p, p.block == 512);
+    const int SC = g.S * g.C, WC = g.W * g.C, NTHR = 64 * NLOC;
+    LC_PLAN_REQUIRE(p, (NLOC == 8 || NLOC == 16) && (int)p.block == NTHR);
     // the whole batch per chunk; a patch row in whole tiles of 16; filters in whole tiles
-    LC_PLAN_REQUIRE(p, g.B == 4 * NB && NB % 4 == 0 && g.RC == 16 * MTR && g.F % 16 == 0);
+    LC_PLAN_REQUIRE(p, g.B == 4 * NB && NB % 16 == 0 && g.RC == 16 * MTR && g.F % 16 == 0);
     LC_PLAN_REQUIRE(p, (int)p.grid[1] == g.F / 16 && p.grid[2] == 1);
-    LC_PLAN_REQUIRE(p, strips == ceil_div(g.LW, 8) && (long long)p.grid[0] == (long long)strips * g.LH);
-    // 16-byte vectors of x from every strip's start; the staged strip covers the eight windows and fits an LDS row
-    LC_PLAN_REQUIRE(p, WC % 4 == 0 && (8 * SC) % 4 == 0 && 4 * sq4 >= g.RC + 7 * SC && sq4 <= RV);
+    LC_PLAN_REQUIRE(p, strips == ceil_div(g.LW, NLOC) && (long long)p.grid[0] == (long long)strips * g.LH);
+    // 16-byte vectors of x from every strip's start; the staged strip covers the NLOC windows and fits an LDS row
+    LC_PLAN_REQUIRE(p, WC % 4 == 0 && (NLOC * SC) % 4 == 0 && 4 * sq4 >= g.RC + (NLOC - 1) * SC && sq4 <= RV);
     // the 64 floats of an LDS read (16 consecutive ones of four rows) fall into 64 banks
     LC_PLAN_REQUIRE(p, (4 * RV) % 64 == 16 || (4 * RV) % 64 == 48);
-    LC_PLAN_REQUIRE(p, (long long)NSLOT * 512 >= (long long)g.B * RV && p.lds_bytes >= (size_t)2 * NSLOT * 512 * 16);
-    // LDS read offsets are 16-bit immediates; the kernel's waits count at most 8*MTR loads and stores
-    LC_PLAN_REQUIRE(p, (4 * (NB - 1) * 4 * RV + 16 * (MTR - 1)) * 4 < 65536 && 8 * MTR <= 63);
-    // 32-bit byte offsets into x; clamped vectors stay inside the image row
-    LC_PLAN_REQUIRE(p, (long long)g.B * g.H * g.W * g.C * 4 < (1LL << 32) && WC - (strips - 1) * 8 * SC >= 4);
+    LC_PLAN_REQUIRE(p, (long long)NSLOT * NTHR >= (long long)g.B * RV && p.lds_bytes >= (size_t)2 * NSLOT * NTHR * 16);
+    // LDS read offsets (half the batch per base register) are 16-bit immediates; one x load per group of two batch
+    // steps in the first half of a chunk; the kernel's waits count at most 4*MTR + NSLOT loads and stores
+    LC_PLAN_REQUIRE(p, (4 * (NB / 2 - 1) * 4 * RV + 16 * (MTR - 1)) * 4 < 65536 && NSLOT <= NB / 4 && 4 * MTR + NSLOT <= 63);
+    // 32-bit byte offsets into x and into a field's K x F block of out; clamped vectors stay inside the image row
+    LC_PLAN_REQUIRE(p, (long long)g.B * g.H * g.W * g.C * 4 < (1LL << 32) && (long long)g.K * g.F * 4 < (1LL << 31) &&
+                           WC - (strips - 1) * NLOC * SC >= 4);
     return LC_OK;
 }
 
-template <int MTR, int NB, int NSLOT, int RV>
+template <int NLOC, int MTR, int NB, int NSLOT, int RV>
 bool backward_weights_strip_fits(const Geom &g) {
-    const int SC = g.S * g.C, WC = g.W * g.C, strips = (g.LW + 7) / 8;
-    const int sq4 = ((g.RC + 7 * SC + 3) & ~3) / 4;
-    return g.B == 4 * NB && g.RC == 16 * MTR && g.F == 16 && WC % 4 == 0 && (8 * SC) % 4 == 0 && sq4 <= RV &&
-           (g.B * RV + 511) / 512 <= NSLOT && (long long)g.B * g.H * g.W * g.C * 4 < (1LL << 32) &&
-           WC - (strips - 1) * 8 * SC >= 4;
+    const int SC = g.S * g.C, WC = g.W * g.C, strips = (g.LW + NLOC - 1) / NLOC;
+    const int sq4 = ((g.RC + (NLOC - 1) * SC + 3) & ~3) / 4;
+    return g.B == 4 * NB && g.RC == 16 * MTR && g.F == 16 && WC % 4 == 0 && (NLOC * SC) % 4 == 0 && sq4 <= RV &&
+           (g.B * RV + 64 * NLOC - 1) / (64 * NLOC) <= NSLOT && (long long)g.B * g.H * g.W * g.C * 4 < (1LL << 32) &&
+           WC - (strips - 1) * NLOC * SC >= 4;
 }
 
-template <int MTR, int NB, int NSLOT, int RV>
+template <int NLOC, int MTR, int NB, int NSLOT, int RV>
 int launch_strip(const Geom &g, const float *x1, const float *dy1, const float *x2, const float *dy2, float beta,
                  float gamma, float *out, float *ssq, int *kblocks_out, hipStream_t s) {
-    const int strips = (g.LW + 7) / 8;
-    const int sq4 = ((g.RC + 7 * g.S * g.C + 3) & ~3) / 4;
-    const size_t lds = (size_t)2 * NSLOT * 512 * 16;
+    const int strips = (g.LW + NLOC - 1) / NLOC;
+    const int sq4 = ((g.RC + (NLOC - 1) * g.S * g.C + 3) & ~3) / 4;
+    const size_t lds = (size_t)2 * NSLOT * 64 * NLOC * 16;
     dim3 grid(strips * g.LH, g.F / 16);
-    const LaunchPlan plan = make_plan("lc_bwd_weights_strip", {MTR, NB, NSLOT, RV}, {strips, sq4}, grid, 512, lds);
+    const LaunchPlan plan = make_plan("lc_bwd_weights_strip", {MTR, NB, NSLOT, RV, NLOC}, {strips, sq4}, grid, 64 * NLOC, lds);
     if (int rc = check_backward_weights_strip(g, plan)) return rc;
     if (kblocks_out) *kblocks_out = 1;       // one partial sum of squares per field and filter
     if (ssq)
-        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_strip_kernel<MTR, NB, NSLOT, RV, true>), s, g, x1,
+        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_strip_kernel<NLOC, MTR, NB, NSLOT, RV, true>), s, g, x1,
                   dy1, x2, dy2, beta, gamma, out, ssq, strips, sq4);
     else
-        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_strip_kernel<MTR, NB, NSLOT, RV, false>), s, g, x1,
+        LC_LAUNCH(plan, "lc_backward_weights launch", (lc_bwd_weights_strip_kernel<NLOC, MTR, NB, NSLOT, RV, false>), s, g, x1,
                   dy1, x2, dy2, beta, gamma, out, ssq, strips, sq4);
     return LC_OK;
 }
@@ -671,9 +678,15 @@ int launch_backward_weights_fast_path(const Geom &g, const T *x1, const T *dy1, 
     *done = false;
     if constexpr (sizeof(T) == 4) {
         // 16 filters per field, a batch of 128, patch rows of 48 elements: strips of eight fields out of LDS
-        if (backward_weights_strip_fits<3, 32, 7, 28>(g)) {
+        // sixteen fields per workgroup (four waves per SIMD) where that idles no more waves at the end of a field
+        // row than eight do
+        if ((g.LW + 15) / 16 * 2 == (g.LW + 7) / 8 && backward_weights_strip_fits<16, 3, 32, 5, 36>(g)) {
             *done = true;
-            return launch_strip<3, 32, 7, 28>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+            return launch_strip<16, 3, 32, 5, 36>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
+        }
+        if (backward_weights_strip_fits<8, 3, 32, 7, 28>(g)) {
+            *done = true;
+            return launch_strip<8, 3, 32, 7, 28>(g, x1, dy1, x2, dy2, beta, gamma, out, ssq, kblocks_out, s);
         }
     }
     const int va = patch_vector_width(g);

@@ -103,6 +103,10 @@ __device__ __forceinline__ typename FVec<N>::T load_nowait(gbyte_ptr base, unsig
         asm volatile("s_nop 4\n\tglobal_load_dwordx4 %0, %1, %2" : "=&v"(v) : "v"(off), "s"(base) : "memory");
     return v;
 }
+// one float per lane to base + off; counted by the memory counter like a load, never waited for unless the kernel does
+__device__ __forceinline__ void store_nowait(gbyte_ptr base, unsigned off, float v) {
+    asm volatile("s_nop 4\n\tglobal_store_dword %0, %1, %2" ::"v"(off), "v"(v), "s"(base) : "memory");
+}
 // wait until at most N of the memory operations issued so far are in flight; v: a value one of the finished loads
 // delivers (ties the wait to the value's uses)
 template <int N, typename V>
@@ -112,6 +116,16 @@ __device__ __forceinline__ void wait_loads(V &v) {
 template <int N>
 __device__ __forceinline__ void wait_loads() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// wait_loads<BASE - d>(v) for a d in 0..MAXD that is a constant only after the surrounding loop has been unrolled
+template <int BASE, int MAXD, typename V>
+__device__ __forceinline__ void wait_loads_minus(int d, V &v) {
+    if constexpr (MAXD == 0) {
+        wait_loads<BASE>(v);
+    } else {
+        if (d == MAXD) wait_loads<BASE - MAXD>(v);
+        else wait_loads_minus<BASE, MAXD - 1>(d, v);
+    }
 }
 
 // Operand storage.  T = float, or bf16_t: bf16 bit patterns that are widened to fp32 (exactly) on their way to

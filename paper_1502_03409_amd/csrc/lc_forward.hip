@@ -444,6 +444,17 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
 #pragma unroll
         for (int q = 0; q < NSLOT; ++q) load_lds16(base, goff[q], l + q * (NTHR * 16));
     };
+    // With two buffers and a ring as deep as a chunk, the x loads of the next chunk go out one or a few at a time
+    // behind the MFMAs of the first half of the k-steps (SPS per step) instead of all at the chunk's start, where they
+    // queue up in the compute unit's one address unit with the waves, which issue in order, standing behind them;
+    // in the first half, so that the last one has half a chunk to land.
+    constexpr bool kSpread = NBUF == 2 && U == NS;
+    constexpr int NSP = NS / 2 > 0 ? NS / 2 : 1, SPS = (NSLOT + NSP - 1) / NSP;
+    constexpr int kLastDmaStep = (NSLOT - 1) / SPS;
+    auto dma_in_step = [&](int p) -> int {     // x loads issued in k-step p
+        const int lo = p * SPS, hi = (p + 1) * SPS < NSLOT ? (p + 1) * SPS : NSLOT;
+        return hi > lo ? hi - lo : 0;
+    };
 
     // the lane's four floats of group gi, patch row r of the chunk, image m + 16 mt: abase + mt*16*RS + r*sq4*4 + 16 gi
     const float *abase = xs + (lane & 15) * RS + wl * SC + 4 * kk;
@@ -457,8 +468,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
     for (int kh = 0; kh < g.R; kh += NRT, ++c) {
         const int khn = kh + NRT < g.R ? kh + NRT : kh;       // the last chunk reloads itself
         const float *arow = abase, *arowT = abaseT;
+        gbyte_ptr xnext = (gbyte_ptr)(x + (size_t)b0 * img + (size_t)(i * g.S + khn) * WC + col0);
+        const unsigned lnext = lds0 + ((c + 1) & 1) * (BUF * 4);
         if constexpr (NBUF == 2) {
-            stage(khn, (c + 1) & 1);
+            if constexpr (!kSpread) stage(khn, (c + 1) & 1);
             arow += (c & 1) * BUF;
             arowT += (c & 1) * BUF;
         } else {
@@ -497,8 +510,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
                 for (int t = 0; t < G; ++t) {
                     const int p = r * SPC + 4 * gi + t;       // k-step of the chunk
                     // (the loop is unrolled: p is a constant by the time this is compiled)
-                    if (p < U) wait_loads<U - 1 + NSLOT>(wr[p % U]);
-                    else wait_loads<U - 1>(wr[p % U]);
+                    if constexpr (kSpread) {
+                        // behind the weights of k-step p: the other NS-1 weight loads and every x load but this step's own
+                        wait_loads_minus<NS - 1 + NSLOT, SPS>(dma_in_step(p), wr[p % U]);
+                    } else {
+                        if (p < U) wait_loads<U - 1 + NSLOT>(wr[p % U]);
+                        else wait_loads<U - 1>(wr[p % U]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
@@ -511,6 +529,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
                         if (gi + 1 < NG) read_group(r, gi + 1, a[cur ^ 1]);
                         else if (r + 1 < NRT) read_group(r + 1, 0, a[cur ^ 1]);
                     }
+                    if constexpr (kSpread) {
+#pragma unroll
+                        for (int q = p * SPS; q < (p + 1) * SPS && q < NSLOT; ++q)
+                            load_lds16(xnext, goff[q], lnext + q * (NTHR * 16));
+                    }
                     const int pn = p + U;                     // the k-step whose weights take this ring slot
                     gbyte_ptr wp = pn < NS ? wc : wn;
                     const int pp = pn < NS ? pn : pn - NS;
@@ -520,8 +543,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 8 ? 2 : 1) * (3 - NBUF)) void lc_fo
             }
         }
         if constexpr (NBUF == 2) {
-            // this lane's x loads of the next chunk have landed (the NS weight loads behind them may fly on)
-            wait_loads<NS>();
+            // this lane's x loads of the next chunk have landed (the weight loads behind the last of them may fly on)
+            if constexpr (kSpread) wait_loads<NS - kLastDmaStep>();
+            else wait_loads<NS>();
             __syncthreads();
         }
     }
@@ -856,6 +880,12 @@ int launch_fast_wide(const Geom &g, const T *x, const T *w, const float *bias, f
 #else
             constexpr int kBuf = 2;
 #endif
+            // sixteen fields per workgroup (four waves per SIMD) where that idles no more waves at the end of a field
+            // row than eight do: the per-chunk costs that do not shrink with the chunk (barrier, first LDS reads) are
+            // spread over twice the MFMAs (57 fields per row, 128 x 128 x 3 input: 121 -> 107 us)
+            if ((g.LW + 15) / 16 * 2 == (g.LW + 7) / 8 && forward_direct_fits<8, 16, 16, 12, 1, 5>(g))
+                return launch_direct<8, 1, 16, 16, 12, 1, 5, 12, 2>(g, x, w, bias, alpha, alpha_dev, y, 0,
+                                                                    ((g.LW + 15) / 16) * g.LH, s);
             if (forward_direct_fits<8, 8, 8, 12, 1, 6>(g))
                 return launch_direct<8, 1, 8, 8, 12, 1, 6, 12, kBuf>(g, x, w, bias, alpha, alpha_dev, y, 0, ntask, s);
         }

@@ -259,22 +259,24 @@ def check_plans(g, op, dtype, plans, replay):
             want = {(ri, ws * NCELL, bt) for ri in range(cdiv(g.H, g.S)) for ws in range(strips) for bt in range(nbt)}
             assert set(seen) == want and all(v == 1 for v in seen.values()), g
     elif fams == {"lc_bwd_weights_strip"}:
-        # strips of eight fields (one per wave), the whole batch per chunk, x staged straight into LDS
+        # strips of NLOC fields (one per wave), the whole batch per chunk, x staged straight into LDS
         p = plans[0]
-        MTR, NB, NSLOT, RV = p["tparam"][:4]
+        MTR, NB, NSLOT, RV, NLOC = p["tparam"][:5]
         strips, sq4 = p["arg"][:2]
-        SC, WC = g.S * g.C, g.W * g.C
-        assert p["block"] == 512 and g.B == 4 * NB and NB % 4 == 0 and g.R * g.C == 16 * MTR and g.F % 16 == 0
-        assert list(p["grid"][:2]) == [cdiv(g.LW, 8) * g.LH, g.F // 16] and strips == cdiv(g.LW, 8)
-        assert WC % 4 == 0 and (8 * SC) % 4 == 0 and g.R * g.C + 7 * SC <= 4 * sq4 and sq4 <= RV
+        SC, WC, NTHR = g.S * g.C, g.W * g.C, 64 * p["tparam"][4]
+        assert NLOC in (8, 16) and p["block"] == NTHR and g.B == 4 * NB and NB % 16 == 0
+        assert g.R * g.C == 16 * MTR and g.F % 16 == 0
+        assert list(p["grid"][:2]) == [cdiv(g.LW, NLOC) * g.LH, g.F // 16] and strips == cdiv(g.LW, NLOC)
+        assert WC % 4 == 0 and (NLOC * SC) % 4 == 0 and g.R * g.C + (NLOC - 1) * SC <= 4 * sq4 and sq4 <= RV
         assert (4 * RV) % 64 in (16, 48)                       # an LDS read's 16 floats x 4 rows: 64 banks
-        assert NSLOT * 512 >= g.B * RV and p["lds_bytes"] == 2 * NSLOT * 512 * 16 <= LDS_PER_CU
-        assert (4 * (NB - 1) * 4 * RV + 16 * (MTR - 1)) * 4 < 65536 and 8 * MTR <= 63
-        assert g.B * g.H * WC * 4 < 2 ** 32 and WC - (strips - 1) * 8 * SC >= 4
+        assert NSLOT * NTHR >= g.B * RV and p["lds_bytes"] == 2 * NSLOT * NTHR * 16 <= LDS_PER_CU
+        assert (4 * (NB // 2 - 1) * 4 * RV + 16 * (MTR - 1)) * 4 < 65536 and NSLOT <= NB // 4 and 4 * MTR + NSLOT <= 63
+        assert g.B * g.H * WC * 4 < 2 ** 32 and g.K * g.F * 4 < 2 ** 31 and WC - (strips - 1) * NLOC * SC >= 4
         # largest clamped offset ends inside x
         img = g.H * WC
         row = (g.LH - 1) * g.S + g.R - 1
-        assert (g.B - 1) * img + row * WC + (strips - 1) * 8 * SC + min(4 * sq4 - 4, WC - (strips - 1) * 8 * SC - 4) + 4 <= g.B * img
+        last = (strips - 1) * NLOC * SC
+        assert (g.B - 1) * img + row * WC + last + min(4 * sq4 - 4, WC - last - 4) + 4 <= g.B * img
     elif fams == {"lc_bwd_weights_fast"} or fams == {"lc_bwd_weights_generic"} or fams == {"lc_bwd_weights_bf16_rows"}:
         p = plans[0]
         kblocks, ntasks = p["arg"][:2]
@@ -417,9 +419,9 @@ def test_hand_scheduled_kernels_stay_inside_their_tensors(name):
                         for kh in range(0, g.R, NRT) for r in range(NRT) for s_ in range(SPC)]
                 assert max(rows) < g.K
             elif p["kernel"] == "lc_bwd_weights_strip":
-                MTR, NB, NSLOT, RV = p["tparam"][:4]
+                MTR, NB, NSLOT, RV, NLOC = p["tparam"][:5]
                 strips, sq4 = p["arg"][:2]
-                _x_strip_offsets_inside(g, 4 * NB, 1, NSLOT, 512, RV, sq4, 8, strips, 1, range(strips * g.LH))
+                _x_strip_offsets_inside(g, 4 * NB, 1, NSLOT, 64 * NLOC, RV, sq4, NLOC, strips, 1, range(strips * g.LH))
                 assert ((4 * NB - 1) * g.L + g.L - 1) * g.F + g.F - 1 < g.B * g.L * g.F
                 assert ((g.L - 1) * g.K + (g.R - 1) * RC + 15 + 16 * (MTR - 1)) * g.F + g.F - 1 < g.L * g.K * g.F
             elif p["kernel"] == "lc_bwd_data_direct":
