@@ -179,7 +179,8 @@ int lcn_variant_bwd_static(const float *x, const float *mu, const float *rstd, c
  * Preconditions the host cannot check (alpha lives on the device): with LC_SAE_LEARN_ALPHA alpha must be
  * non-zero, because its gradient sum (W x) * dJ/dh is formed as (1/alpha) sum h * dJ/dh; with alpha = 0 the
  * encoder is dead anyway (h = 0 for every input) and the step leaves alpha at NaN.  With LC_SAE_PROJECT_ROWS a
- * filter whose updated values are all exactly zero has no direction and is left as it is (zeros). */
+ * filter whose updated values are all exactly zero has no direction and is left as it is (zeros).  With
+ * eps_sparse = 0 the sparsity term is |h|, whose gradient at h = 0 is taken as 0. */
 int sae_step(const lc_geom_t *g, const float *x, float *w, float *b, float *alpha, float lambda,
              float eps_sparse, float lr, uint32_t flags, float *h_out, float *cost_out, void *ws,
              size_t ws_bytes, void *hip_stream);

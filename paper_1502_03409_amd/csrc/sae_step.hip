@@ -15,7 +15,9 @@ namespace lc {
 
 namespace {
 
-constexpr int kPartials = 1024;     // per-block partial sums of the sparsity reductions
+constexpr int kPartials = 1024;     // upper bound of the scalar residual pass's partial sums
+constexpr int kSparsityThreads = 1024;
+constexpr int kSparsityBlocks = 256;   // one workgroup per compute unit: the ticket counter sees few arrivals
 constexpr int kPartialsMax = 65536;  // upper bound of the residual pass's partial sums
 
 __device__ __forceinline__ float block_sum(float v, float *sh) {
@@ -31,11 +33,14 @@ __device__ __forceinline__ float block_sum(float v, float *sh) {
 }
 
 // r = xh + b - x;  u = (2/B) r (written over xh);  part[block] = sum r^2;  dbp[chunk][e] = sum over the
-// chunk's images of u.  Grid: x over image elements (float4 per thread), y over chunks of the batch.
+// chunk's images of u.  Grid: x over image elements (float4 per thread), y over chunks of the batch.  The loads of
+// four images are in flight together.  Block (0,0) also clears the ticket counter of the sparsity pass.
 __global__ __launch_bounds__(256) void sae_residual_kernel(float *__restrict__ xh_u, const float *__restrict__ x,
                                                            const float *__restrict__ b, int B, int img4, int bchunk,
-                                                           float *__restrict__ dbp, float *__restrict__ part) {
+                                                           float *__restrict__ dbp, float *__restrict__ part,
+                                                           unsigned *__restrict__ ticket) {
     __shared__ float sh[4];
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *ticket = 0u;
     const int e = blockIdx.x * 256 + threadIdx.x;
     float sq = 0.f;
     if (e < img4) {
@@ -43,7 +48,25 @@ __global__ __launch_bounds__(256) void sae_residual_kernel(float *__restrict__ x
         const float scale = 2.0f / (float)B;
         f32x4 db = (f32x4){0.f, 0.f, 0.f, 0.f};
         const int n0 = blockIdx.y * bchunk, n1 = min(B, n0 + bchunk);
-        for (int n = n0; n < n1; ++n) {
+        int n = n0;
+        for (; n + 4 <= n1; n += 4) {
+            f32x4 a[4], c[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const size_t o = (size_t)(n + t) * img4 + e;
+                a[t] = ((const f32x4 *)xh_u)[o];
+                c[t] = ((const f32x4 *)x)[o];
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const f32x4 r = a[t] + be - c[t];
+                sq += (r[0] * r[0] + r[1] * r[1]) + (r[2] * r[2] + r[3] * r[3]);
+                const f32x4 u = scale * r;
+                ((f32x4 *)xh_u)[(size_t)(n + t) * img4 + e] = u;
+                db += u;
+            }
+        }
+        for (; n < n1; ++n) {
             const size_t o = (size_t)n * img4 + e;
             const f32x4 r = ((const f32x4 *)xh_u)[o] + be - ((const f32x4 *)x)[o];
             sq += (r[0] * r[0] + r[1] * r[1]) + (r[2] * r[2] + r[3] * r[3]);
@@ -61,8 +84,10 @@ __global__ __launch_bounds__(256) void sae_residual_kernel(float *__restrict__ x
 // over the whole batch; b is updated in place.
 __global__ __launch_bounds__(256) void sae_residual_scalar_kernel(float *__restrict__ xh_u,
                                                                   const float *__restrict__ x, float *__restrict__ b,
-                                                                  int B, int img, float lr, float *__restrict__ part) {
+                                                                  int B, int img, float lr, float *__restrict__ part,
+                                                                  unsigned *__restrict__ ticket) {
     __shared__ float sh[4];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;
     float sq = 0.f;
     for (int e = blockIdx.x * 256 + threadIdx.x; e < img; e += gridDim.x * 256) {
         const float be = b[e];
@@ -82,55 +107,102 @@ __global__ __launch_bounds__(256) void sae_residual_scalar_kernel(float *__restr
     if (threadIdx.x == 0) part[blockIdx.x] = t;
 }
 
-// s = sqrt(h^2+eps);  gh <- alpha * (gh + (lambda/B) h / s);  part0 += s;  part1 += h * gh_before_alpha.
-__global__ __launch_bounds__(256) void sae_sparsity_kernel(const float *__restrict__ h, float *__restrict__ gh,
-                                                           const float *__restrict__ alpha_dev, float lam_over_b,
-                                                           float eps, long long n, float *__restrict__ part_s,
-                                                           float *__restrict__ part_hg) {
-    __shared__ float sh[4];
-    const float alpha = *alpha_dev;
+// What the last workgroup of the sparsity pass does with the partial sums of a step.
+struct SaeTail {
+    unsigned *ticket;          // cleared by the residual pass of the same step
+    const float *part_r;       // partial sums of r^2
+    int n_r;
+    float lambda, lr;
+    int B, learn_alpha;
+    float *alpha_dev, *cost_out;
+    float *bias;               // b -= lr * sum over the batch chunks of dbp, by the workgroups behind the first n_s
+    const float *dbp;
+    int img, nchunk;
+};
+
+// Workgroups [0, n_s):  s = sqrt(h^2+eps);  gh <- alpha * (gh + (lambda/B) h / s);  part_s[block] = sum s;
+// part_hg[block] = sum h * gh_before_alpha; four values per lane and four vectors in flight.
+// Workgroups [n_s, ...): b -= lr * sum over the batch chunks of dbp, in a fixed order (b is not read any more after
+// the residual pass).
+// The workgroup of the first n_s that finishes last (a ticket counter: the only atomic of the step, it orders
+// nothing but who does the summing) adds the partial sums in a fixed order: cost = (sum r^2 + lambda sum s) / B and
+// optionally alpha -= lr * (sum h*gh) / alpha (d h / d alpha = h / alpha); every other workgroup has read alpha by
+// then.
+__global__ __launch_bounds__(kSparsityThreads) void sae_sparsity_kernel(const float *__restrict__ h, float *__restrict__ gh,
+                                                           float lam_over_b, float eps, long long n, int n_s,
+                                                           float *__restrict__ part_s, float *__restrict__ part_hg,
+                                                           SaeTail tl) {
+    __shared__ float sh[kSparsityThreads / 64];
+    __shared__ unsigned last;
+    if ((int)blockIdx.x >= n_s) {
+        const int e = ((int)blockIdx.x - n_s) * kSparsityThreads + threadIdx.x;
+        if (e >= tl.img) return;
+        float s = 0.f;
+        for (int c = 0; c < tl.nchunk; ++c) s += tl.dbp[(size_t)c * tl.img + e];
+        tl.bias[e] -= tl.lr * s;
+        return;
+    }
+    const float alpha = *tl.alpha_dev;
     float ss = 0.f, hg = 0.f;
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256) {
-        const float hv = h[e];
-        const float s = sqrtf(hv * hv + eps);
-        const float g = gh[e] + lam_over_b * hv / s;
-        ss += s;
+    // s = v * rsq(v) with v = h^2 + eps and h / s = h * rsq(v): one reciprocal square root (1 ulp) instead of a
+    // correctly rounded square root and a division, which together cost some forty instructions per value
+    auto one = [&](float hv, float gv) {
+        const float v = hv * hv + eps;
+        const float r = v > 0.f ? __builtin_amdgcn_rsqf(v) : 0.f;     // eps = 0 and h = 0: gradient of |h| taken as 0
+        const float g = gv + lam_over_b * (hv * r);
+        ss += v * r;
         hg += hv * g;
-        gh[e] = alpha * g;
+        return alpha * g;
+    };
+    constexpr int U = 4;    // vectors of h and of gh in flight per lane
+    const long long nv = n / 4, stride = (long long)n_s * kSparsityThreads;
+    long long e = (long long)blockIdx.x * kSparsityThreads + threadIdx.x;
+    for (; e < nv; e += U * stride) {
+        f32x4 hv[U], gv[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j)
+            if (e + j * stride < nv) {
+                hv[j] = ((const f32x4 *)h)[e + j * stride];
+                gv[j] = ((const f32x4 *)gh)[e + j * stride];
+            }
+#pragma unroll
+        for (int j = 0; j < U; ++j)
+            if (e + j * stride < nv) {
+                f32x4 o;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) o[c] = one(hv[j][c], gv[j][c]);
+                ((f32x4 *)gh)[e + j * stride] = o;
+            }
+    }
+    if (blockIdx.x == 0 && (long long)threadIdx.x < n - 4 * nv) {       // up to three values behind the last vector
+        const long long t = 4 * nv + threadIdx.x;
+        gh[t] = one(h[t], gh[t]);
     }
     const float t0 = block_sum(ss, sh);
     const float t1 = block_sum(hg, sh);
-    if (threadIdx.x == 0) { part_s[blockIdx.x] = t0; part_hg[blockIdx.x] = t1; }
-}
-
-// Last kernel of a step.  Block 0: cost = (sum r^2 + lambda sum s) / B and optionally
-// alpha -= lr * (sum h*gh) / alpha (d h / d alpha = h / alpha).  Blocks 1..: b -= lr * sum over the batch chunks
-// of dbp, in a fixed order (deterministic); b is not read any more after the residual pass.
-__global__ __launch_bounds__(256) void sae_finalize_kernel(const float *__restrict__ part_r, int n_r,
-                                                           const float *__restrict__ part_s,
-                                                           const float *__restrict__ part_hg, int n_s, float lambda,
-                                                           int B, float lr, int learn_alpha, float *alpha_dev,
-                                                           float *__restrict__ cost_out, float *__restrict__ bias,
-                                                           const float *__restrict__ dbp, int img, int nchunk) {
-    if (blockIdx.x > 0) {
-        const int e = (blockIdx.x - 1) * 256 + threadIdx.x;
-        if (e >= img) return;
-        float s = 0.f;
-        for (int c = 0; c < nchunk; ++c) s += dbp[(size_t)c * img + e];
-        bias[e] -= lr * s;
-        return;
+    if (threadIdx.x == 0) {
+        // The partial sums and the ticket go through agent-scope accesses, which no XCD's L2 keeps to itself, and
+        // the ticket is taken only once the two stores have been acknowledged; a release fence here would make
+        // every workgroup write back the whole L2 (measured: the kernel four times as long).
+        __hip_atomic_store(part_s + blockIdx.x, t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(part_hg + blockIdx.x, t1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const unsigned k = __hip_atomic_fetch_add(tl.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = (k == (unsigned)n_s - 1u) ? 1u : 0u;
     }
-    __shared__ float sh[4];
+    __syncthreads();
+    if (!last) return;
+    // every other workgroup's sums were acknowledged before its ticket; part_r comes from an earlier kernel
     float a = 0.f, b = 0.f, c = 0.f;
-    for (int i = threadIdx.x; i < n_r; i += 256) a += part_r[i];
-    for (int i = threadIdx.x; i < n_s; i += 256) { b += part_s[i]; c += part_hg[i]; }
+    for (int i = threadIdx.x; i < tl.n_r; i += kSparsityThreads) a += tl.part_r[i];
+    for (int i = threadIdx.x; i < n_s; i += kSparsityThreads) {
+        b += __hip_atomic_load(part_s + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        c += __hip_atomic_load(part_hg + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     const float ta = block_sum(a, sh), tb = block_sum(b, sh), tc = block_sum(c, sh);
     if (threadIdx.x == 0) {
-        *cost_out = (ta + lambda * tb) / (float)B;
-        if (learn_alpha) {
-            const float al = *alpha_dev;
-            *alpha_dev = al - lr * tc / al;
-        }
+        *tl.cost_out = (ta + tl.lambda * tb) / (float)tl.B;
+        if (tl.learn_alpha) *tl.alpha_dev = alpha - tl.lr * tc / alpha;
     }
 }
 
@@ -195,6 +267,7 @@ int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *al
     float *part_r = (float *)p; p += align256(kPartialsMax * 4);
     float *part_s = (float *)p; p += align256(kPartialsMax * 4);
     float *part_hg = (float *)p; p += align256(kPartialsMax * 4);
+    unsigned *ticket = (unsigned *)(part_hg + kSparsityBlocks);     // behind the sums this array ever holds
     float *ssq = (float *)p;  p += align256((size_t)g.L * backward_weights_max_kblocks(g) * g.F * 4);
     float *inv = (float *)p;  p += align256((size_t)g.L * g.F * 4);
     void *fwd_ws = p;
@@ -205,27 +278,37 @@ int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *al
     int rc;
     if ((rc = launch_forward_f32(g, x, w, nullptr, 1.f, alpha, h, s, fwd_ws, fwd_ws_bytes)) != LC_OK) return rc;
     if ((rc = launch_backward_data_f32(g, h, w, u, s)) != LC_OK) return rc;
-    int n_r, bias_chunks = 0;     // bias_chunks > 0: the b update waits for the finalize kernel
+    int n_r, bias_chunks = 0;     // bias_chunks > 0: the b update waits for the sparsity pass
     if ((img & 3) == 0 && (img / 4 + 255) / 256 * kBatchChunks <= kPartialsMax) {
         const int img4 = img / 4, gx = (img4 + 255) / 256;
         const int nchunk = g.B < kBatchChunks ? g.B : kBatchChunks, bchunk = (g.B + nchunk - 1) / nchunk;
         const int gy = (g.B + bchunk - 1) / bchunk;
         const LaunchPlan plan = make_plan("sae_residual", {4}, {img4, bchunk}, dim3(gx, gy), 256, 0);
         LC_PLAN_REQUIRE(plan, gx * gy <= kPartialsMax && gy <= kBatchChunks && (long long)gy * bchunk >= g.B);
-        LC_LAUNCH(plan, "sae_step residual launch", sae_residual_kernel, s, u, x, b, g.B, img4, bchunk, dbp, part_r);
+        LC_LAUNCH(plan, "sae_step residual launch", sae_residual_kernel, s, u, x, b, g.B, img4, bchunk, dbp, part_r,
+                  ticket);
         bias_chunks = gy;
         n_r = gx * gy;
     } else {
         n_r = (int)((img + 255) / 256 < kPartials ? (img + 255) / 256 : kPartials);
         const LaunchPlan plan = make_plan("sae_residual", {1}, {img}, dim3(n_r), 256, 0);
-        LC_LAUNCH(plan, "sae_step residual launch", sae_residual_scalar_kernel, s, u, x, b, g.B, img, lr, part_r);
+        LC_LAUNCH(plan, "sae_step residual launch", sae_residual_scalar_kernel, s, u, x, b, g.B, img, lr, part_r,
+                  ticket);
     }
     if ((rc = launch_forward_f32(g, u, w, nullptr, 1.f, nullptr, gh, s, fwd_ws, fwd_ws_bytes)) != LC_OK) return rc;
-    const int n_s = (int)((nh + 255) / 256 < (size_t)kPartials ? (nh + 255) / 256 : kPartials);
+    // four values per lane, four vectors per trip: at most kSparsityBlocks workgroups, at least one
+    const size_t nsw = (nh / 4 + 4 * kSparsityThreads - 1) / (4 * kSparsityThreads);
+    const int n_s = (int)(nsw < 1 ? 1 : nsw < (size_t)kSparsityBlocks ? nsw : kSparsityBlocks);
     {
-        const LaunchPlan plan = make_plan("sae_sparsity", {}, {n_s}, dim3(n_s), 256, 0);
-        LC_LAUNCH(plan, "sae_step sparsity launch", sae_sparsity_kernel, s, h, gh, alpha, lambda / (float)g.B, eps_sparse,
-                  (long long)nh, part_s, part_hg);
+        // the workgroups behind the first n_s update b; the last of the first n_s to finish writes the cost
+        const int bias_blocks = bias_chunks > 0 ? (img + kSparsityThreads - 1) / kSparsityThreads : 0;
+        const LaunchPlan plan = make_plan("sae_sparsity", {}, {n_s, n_r, bias_chunks}, dim3(n_s + bias_blocks),
+                                          kSparsityThreads, 0);
+        LC_PLAN_REQUIRE(plan, n_s >= 1 && n_s <= kSparsityBlocks && n_r <= kPartialsMax);
+        const SaeTail tl = {ticket, part_r, n_r, lambda, lr, g.B, (flags & LC_SAE_LEARN_ALPHA) ? 1 : 0, alpha, cost_out,
+                            b, dbp, img, bias_chunks};
+        LC_LAUNCH(plan, "sae_step sparsity launch", sae_sparsity_kernel, s, h, gh, lambda / (float)g.B, eps_sparse,
+                  (long long)nh, n_s, part_s, part_hg, tl);
     }
     // w <- w - lr * ( patch(u) h^T + patch(x) (alpha gh)^T ), with the sums of squares of the new weights on the side
     int kblocks = 0;
@@ -246,10 +329,6 @@ int launch_sae_step(const Geom &g, const float *x, float *w, float *b, float *al
         else
             LC_LAUNCH(pr, "sae_step projection launch", sae_rescale_kernel<1>, s, w, inv, g.F, KF, nw);
     }
-    const int bias_blocks = bias_chunks > 0 ? (int)((img + 255) / 256) : 0;
-    const LaunchPlan pf = make_plan("sae_finalize", {}, {n_r, n_s, bias_chunks}, dim3(1 + bias_blocks), 256, 0);
-    LC_LAUNCH(pf, "sae_step finalize launch", sae_finalize_kernel, s, part_r, n_r, part_s, part_hg, n_s, lambda, g.B, lr,
-              (flags & LC_SAE_LEARN_ALPHA) ? 1 : 0, alpha, cost_out, b, dbp, (int)img, bias_chunks);
     return LC_OK;
 }
 
