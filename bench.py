@@ -7,7 +7,8 @@ One "step" is one pass of the whole hot path over one synthetic mini-batch of wo
 share of a first layer: B=128, 200x200x3 pink-noise images, 20x20x3 fields at stride 4, 32 filters per
 location), inputs already resident in HBM:
 
-    lc_forward -> l2pool_fwd -> lcn_fwd -> lcn_bwd -> l2pool_bwd -> lc_backward_data -> lc_backward_weights
+    lc_forward -> l2pool_lcn_fwd (L2 pooling and LCN forward as one call) -> lcn_bwd -> l2pool_bwd
+               -> lc_backward_data -> lc_backward_weights
 
 `value` is the algorithmic flop of the three layer contractions (3 x 2*B*K*F*L) divided by the time of
 the whole step.  The JSON line also carries per-kernel times (HIP events on the launch stream, in untimed
@@ -93,12 +94,11 @@ def main() -> int:
     dx = torch.empty((g.B, g.H, g.W, g.C), device="cuda")
     dw = torch.empty((g.LH, g.LW, g.K, g.F), device="cuda")
 
-    names = ["lc_forward", "l2pool_fwd", "lcn_fwd", "lcn_bwd", "l2pool_bwd", "lc_backward_data",
-             "lc_backward_weights"]
+    names = ["lc_forward", "l2pool_lcn_fwd", "lcn_bwd", "l2pool_bwd", "lc_backward_data", "lc_backward_weights"]
     calls = [
         lambda: lc.lc_forward(G, xd, wd, None, 1.0, y),
-        lambda: lc.l2pool_fwd(y, p, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS),
-        lambda: lc.lcn_fwd(p, n, mu, rstd, wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS),
+        lambda: lc.l2pool_lcn_fwd(y, p, n, mu, rstd, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS, wl.LCN_KSIZE,
+                                  wl.LCN_SIGMA, wl.LCN_EPS),
         lambda: lc.lcn_bwd(p, mu, rstd, dn, dp, wl.LCN_KSIZE, wl.LCN_SIGMA),
         lambda: lc.l2pool_bwd(y, p, dp, dyd, wl.POOL_KSIZE, wl.POOL_STRIDE),
         lambda: lc.lc_backward_data(G, dyd, wd, dx),
@@ -175,8 +175,7 @@ def main() -> int:
         warnings.append(f"{dom}: {kern_ms[dom]:.4f} ms in the per-kernel breakdown against {dom_ms:.4f} ms in the "
                         "timed region (more than 3 % apart: clocks not settled, or another process on the GPU)")
     nbytes = {
-        "l2pool_fwd": 4 * (y.numel() + p.numel()),
-        "lcn_fwd": 4 * (2 * p.numel() + 2 * mu.numel()),
+        "l2pool_lcn_fwd": 4 * (y.numel() + 2 * p.numel() + 2 * mu.numel()),     # y read; p, n, mu, rstd written
         "lcn_bwd": 4 * (3 * p.numel() + 2 * mu.numel()),
         "l2pool_bwd": 4 * (2 * y.numel() + 2 * p.numel()),
     }
@@ -227,7 +226,7 @@ def main() -> int:
 
 def bench_sae(lc, wl, np, torch, dev, steps, warmup):
     """cfg5: all three stages take one SGD step on the same mini-batch; stage s+1 reads
-    lcn_fwd(l2pool_fwd(h_s)).  Returns images/s of the whole three-stage step: the sequential schedule (flags 0 as
+    l2pool_lcn_fwd(h_s).  Returns images/s of the whole three-stage step: the sequential schedule (flags 0 as
     the workload states it, and with row projection and learned alpha), and the layer pipeline of Sec. 3.1 with a
     forward-only copy of each stage refreshed every P steps."""
     from paper_1502_03409_amd.pipeline import SaePipeline
@@ -290,8 +289,8 @@ def bench_sae(lc, wl, np, torch, dev, steps, warmup):
             for st in stages:
                 lc.sae_step(st["G"], st["x"], st["w"], st["b"], st["alpha"], wl.SAE_LAMBDA, wl.SAE_EPS, lr, flags,
                             st["h"], st["cost"], st["ws"])
-                lc.l2pool_fwd(st["h"], st["p"], wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS)
-                lc.lcn_fwd(st["p"], st["n"], st["mu"], st["rstd"], wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)
+                lc.l2pool_lcn_fwd(st["h"], st["p"], st["n"], st["mu"], st["rstd"], wl.POOL_KSIZE, wl.POOL_STRIDE,
+                                  wl.POOL_EPS, wl.LCN_KSIZE, wl.LCN_SIGMA, wl.LCN_EPS)
 
         ms = timed(step)
         return line(ms, {"flags": flags, "lr": lr, "costs": [round(float(st["cost"].item()), 4) for st in stages]})

@@ -130,6 +130,15 @@ int l2pool_bwd(const float *x, const float *y, const float *dy, float *dx, int32
 int lcn_fwd(const float *x, float *y, float *mu, float *rstd, int32_t B, int32_t H, int32_t W, int32_t C,
             int32_t ksize, float gauss_sigma, float eps, void *hip_stream);
 
+/* l2pool_fwd followed by lcn_fwd of its result, as one call (the order the workloads chain them after each
+ * layer, Sec. 3.1): p = l2pool_fwd(x), then y, mu, rstd = lcn_fwd(p).  x [B,H,W,C]; p and y [B,Ho,Wo,C];
+ * mu, rstd [B,Ho,Wo]; all four are outputs (p is what l2pool_bwd and lcn_bwd read later).  Results are those of the
+ * two calls up to fp32 rounding order.  3x3 windows at stride 1 over 8, 16, 32 or 64 channels run as one kernel
+ * that never reads p back; other shapes run the two kernels one after the other.  Arguments as in the two calls. */
+int l2pool_lcn_fwd(const float *x, float *p, float *y, float *mu, float *rstd, int32_t B, int32_t H, int32_t W,
+                   int32_t C, int32_t pool_ksize, int32_t pool_stride, float pool_eps, int32_t lcn_ksize,
+                   float gauss_sigma, float lcn_eps, void *hip_stream);
+
 /* Gradient of lcn_fwd with respect to x, given the saved mu and rstd (the clamp of the variance at zero is
  * taken as inactive).  dx [B,H,W,C] overwritten. */
 int lcn_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B,

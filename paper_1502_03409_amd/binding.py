@@ -25,7 +25,7 @@ _STATUS = {0: "LC_OK", -1: "LC_EINVAL", -2: "LC_ENULL", -3: "LC_EALIGN", -4: "LC
            -5: "LC_EUNSUPPORTED", -6: "LC_EHIP", -7: "LC_EINTERNAL"}
 
 EXPORTS = ("lc_geom_derive", "lc_workspace_bytes", "lc_forward", "lc_forward_dev_scale", "lc_backward_data", "lc_backward_weights",
-           "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
+           "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "l2pool_lcn_fwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
            "lcn_variant_bwd", "lcn_variant_bwd_static", "sae_step", "lc_last_error", "lc_plan_query")
 
 
@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
         L.l2pool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, f32, vp]
         L.l2pool_bwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
         L.lcn_fwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, vp]
+        L.l2pool_lcn_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, i32, f32, f32, vp]
         L.lcn_bwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp]
         L.lcn_variant_workspace_bytes.argtypes = [i32, i32, i32, i32, C.c_uint32]
         L.lcn_variant_workspace_bytes.restype = C.c_size_t
@@ -208,6 +209,17 @@ def lcn_fwd(x, y, mu, rstd, ksize: int, gauss_sigma: float, eps: float) -> None:
         _dev(x, None, torch.float32, "x"), _dev(y, x.shape, torch.float32, "y"),
         _dev(mu, (B, H, W), torch.float32, "mu"), _dev(rstd, (B, H, W), torch.float32, "rstd"),
         B, H, W, Cc, ksize, gauss_sigma, eps, _stream()))
+
+
+def l2pool_lcn_fwd(x, p, y, mu, rstd, pool_ksize: int, pool_stride: int, pool_eps: float, lcn_ksize: int,
+                   gauss_sigma: float, lcn_eps: float) -> None:
+    B, H, W, Cc = x.shape
+    Ho, Wo = _pool_out(H, pool_ksize, pool_stride), _pool_out(W, pool_ksize, pool_stride)
+    _check("l2pool_lcn_fwd", lib().l2pool_lcn_fwd(
+        _dev(x, None, torch.float32, "x"), _dev(p, (B, Ho, Wo, Cc), torch.float32, "p"),
+        _dev(y, (B, Ho, Wo, Cc), torch.float32, "y"), _dev(mu, (B, Ho, Wo), torch.float32, "mu"),
+        _dev(rstd, (B, Ho, Wo), torch.float32, "rstd"), B, H, W, Cc, pool_ksize, pool_stride, pool_eps, lcn_ksize,
+        gauss_sigma, lcn_eps, _stream()))
 
 
 def lcn_bwd(x, mu, rstd, dy, dx, ksize: int, gauss_sigma: float) -> None:

@@ -222,6 +222,27 @@ int lcn_fwd(const float *x, float *y, float *mu, float *rstd, int32_t B, int32_t
     return launch_lcn(0, x, nullptr, y, mu, rstd, B, H, W, C, ksize, gauss_sigma, eps, (hipStream_t)hip_stream);
 }
 
+int l2pool_lcn_fwd(const float *x, float *p, float *y, float *mu, float *rstd, int32_t B, int32_t H, int32_t W,
+                   int32_t C, int32_t pool_ksize, int32_t pool_stride, float pool_eps, int32_t lcn_ksize,
+                   float gauss_sigma, float lcn_eps, void *hip_stream) {
+    if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;
+    if (pool_ksize < 1 || pool_stride < 1 || pool_ksize > H || pool_ksize > W || !(pool_eps >= 0.f)) return LC_EINVAL;
+    if (lcn_ksize < 1 || lcn_ksize > 15 || (lcn_ksize & 1) == 0 || !(gauss_sigma > 0.f) || !(lcn_eps >= 0.f))
+        return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(p); LC_REQUIRE_PTR(y); LC_REQUIRE_PTR(mu); LC_REQUIRE_PTR(rstd);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(p); LC_REQUIRE_ALIGNED(y); LC_REQUIRE_ALIGNED(mu); LC_REQUIRE_ALIGNED(rstd);
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (pool_ksize == 3 && pool_stride == 1) {
+        bool done = false;
+        const int rc = launch_pool_lcn_fused(x, p, y, mu, rstd, B, H, W, C, pool_eps, lcn_ksize, gauss_sigma, lcn_eps, s,
+                                             &done);
+        if (done || rc != LC_OK) return rc;
+    }
+    const int Ho = (H - pool_ksize) / pool_stride + 1, Wo = (W - pool_ksize) / pool_stride + 1;
+    if (int rc = launch_l2pool_fwd(x, p, B, H, W, C, pool_ksize, pool_stride, pool_eps, s)) return rc;
+    return launch_lcn(0, p, nullptr, y, mu, rstd, B, Ho, Wo, C, lcn_ksize, gauss_sigma, lcn_eps, s);
+}
+
 int lcn_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B, int32_t H,
             int32_t W, int32_t C, int32_t ksize, float gauss_sigma, void *hip_stream) {
     if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;

@@ -269,6 +269,9 @@ int launch_l2pool_bwd(const float *x, const float *y, const float *dy, float *dx
 // zero_pad: pixels outside the image count as zeros and the window keeps its full-window normalisation.
 int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
                int C, int ks, float sigma, float eps, hipStream_t s, int zero_pad = 0, float *field = nullptr);
+// 3x3 stride-1 pooling and the one-stage pooled LCN of its result in one kernel; *done: whether the shape took it
+int launch_pool_lcn_fused(const float *x, float *p, float *out, float *mu, float *rstd, int B, int H, int W, int C,
+                          float peps, int ks, float sigma, float eps, hipStream_t s, bool *done);
 // LCN variants (flags as in lc.h: per-channel statistics, zero-padded borders, two stages)
 size_t lcn_variant_scratch_bytes(int B, int H, int W, int C, unsigned flags);
 int launch_lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int B, int H, int W, int C, int ks,

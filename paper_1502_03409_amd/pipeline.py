@@ -94,8 +94,7 @@ class SaePipeline:
                 st.wf.copy_(st.w, non_blocking=True)
                 st.alphaf.copy_(st.alpha, non_blocking=True)
             lc.lc_forward_dev_scale(st.g, x_in, st.wf, None, st.alphaf, st.hf, st.fws)
-            lc.l2pool_fwd(st.hf, st.p, *self.pool)
-            lc.lcn_fwd(st.p, st.n[t % 2], st.mu, st.rstd, *self.lcn)
+            lc.l2pool_lcn_fwd(st.hf, st.p, st.n[t % 2], st.mu, st.rstd, *self.pool, *self.lcn)
             if sm is not None:
                 ev = torch.cuda.Event()
                 ev.record(sm)

@@ -85,6 +85,12 @@ def test_argument_validation_happens_before_any_launch():
     assert L.lcn_fwd(FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 5, 0.0, 1e-4, None) == B.LC_EINVAL     # sigma
     assert L.lcn_fwd(FAKE, FAKE, None, FAKE, 1, 8, 8, 4, 5, 1.0, 1e-4, None) == B.LC_ENULL
     assert L.lcn_bwd(FAKE, FAKE, FAKE, FAKE, None, 1, 8, 8, 4, 5, 1.0, None) == B.LC_ENULL
+    # the fused pooling + LCN call checks both halves' arguments
+    assert L.l2pool_lcn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 9, 1, 0.0, 5, 1.0, 1e-4, None) == B.LC_EINVAL
+    assert L.l2pool_lcn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 3, 1, 0.0, 4, 1.0, 1e-4, None) == B.LC_EINVAL
+    assert L.l2pool_lcn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 3, 1, 0.0, 5, 0.0, 1e-4, None) == B.LC_EINVAL
+    assert L.l2pool_lcn_fwd(FAKE, None, FAKE, FAKE, FAKE, 1, 8, 8, 4, 3, 1, 0.0, 5, 1.0, 1e-4, None) == B.LC_ENULL
+    assert L.l2pool_lcn_fwd(FAKE, FAKE, FAKE, FAKE + 4, FAKE, 1, 8, 8, 4, 3, 1, 0.0, 5, 1.0, 1e-4, None) == B.LC_EALIGN
     # LCN variants: unknown flag bits, the two-stage gradient without its scratch, aliased output
     assert L.lcn_variant_fwd(FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 5, 1.0, 1e-4, 8, None) == B.LC_EINVAL
     assert L.lcn_variant_fwd(FAKE, FAKE, FAKE, None, 1, 8, 8, 4, 5, 1.0, 1e-4, 7, None) == B.LC_ENULL

@@ -419,6 +419,41 @@ def test_lcn_matches_oracle(shape, ks):
     assert rel_fro(host(dx), oracle.lcn_bwd(x, ref_mu, ref_rstd, dy, ks, wl.LCN_SIGMA)) <= TOL
 
 
+# l2pool_lcn_fwd: (input shape, pooling window, pooling stride, LCN window)
+POOL_LCN_SHAPES = [((4, 46, 46, 32), 3, 1, 5),      # cfg3's maps: two bands of 22 rows, 13 rows per lane
+                   ((3, 57, 57, 16), 3, 1, 5),      # cfg5 stage 1: four lanes per pixel, four segments
+                   ((5, 25, 25, 32), 3, 1, 5),      # cfg5 stage 2
+                   ((130, 9, 9, 32), 3, 1, 5),      # cfg5 stage 3: one band per image, most lanes idle
+                   ((2, 31, 40, 8), 3, 1, 3),       # two lanes per pixel, 3x3 LCN window
+                   ((2, 20, 13, 64), 3, 1, 7),      # sixteen lanes per pixel (two columns per wave), 7x7 window
+                   ((1, 3, 3, 16), 3, 1, 5),        # one pooled pixel
+                   ((2, 4, 90, 32), 3, 1, 5),       # a row of 88 pooled pixels: 15 waves per segment
+                   ((2, 70, 30, 32), 3, 1, 5),      # tall maps: more bands than the chip needs, so that a lane's rows fit
+                   ((2, 12, 120, 32), 3, 1, 5),     # rows too long for one workgroup: the two kernels one after the other
+                   ((2, 17, 19, 5), 3, 1, 5),       # channels no multiple of four: the two kernels
+                   ((2, 21, 21, 16), 2, 2, 5),      # another pooling window: the two kernels
+                   ((128, 46, 46, 32), 3, 1, 5)]    # last: cfg3 at full size
+
+
+@pytest.mark.parametrize("shape,pk,ps,lk", POOL_LCN_SHAPES)
+def test_l2pool_lcn_fwd_matches_oracle(shape, pk, ps, lk):
+    """The fused call against the oracle's pooling followed by the oracle's LCN (the order Sec. 3.1's layers chain
+    them), every output: p, y, mu, rstd."""
+    print(f"case pool+lcn {shape} {pk} {ps} {lk}", flush=True)
+    x = wl.feature_maps(*shape, seed=5)
+    ref_p = oracle.l2pool_fwd(x, pk, ps, wl.POOL_EPS)
+    ref_y, ref_mu, ref_rstd = oracle.lcn_fwd(ref_p, lk, wl.LCN_SIGMA, wl.LCN_EPS)
+    p = torch.full(ref_p.shape, float("nan"), device="cuda")
+    y = torch.full(ref_p.shape, float("nan"), device="cuda")
+    mu = torch.full(ref_p.shape[:3], float("nan"), device="cuda")
+    rstd = torch.full(ref_p.shape[:3], float("nan"), device="cuda")
+    lc.l2pool_lcn_fwd(dev(x), p, y, mu, rstd, pk, ps, wl.POOL_EPS, lk, wl.LCN_SIGMA, wl.LCN_EPS)
+    for nm, got, ref in (("p", p, ref_p), ("mu", mu, ref_mu), ("rstd", rstd, ref_rstd), ("y", y, ref_y)):
+        e = rel_fro(host(got), ref)
+        print(f"  {nm} rel err {e:.2e}", flush=True)
+        assert e <= TOL
+
+
 LCN_VARIANT_SHAPES = [((2, 9, 10, 3), 5), ((3, 20, 37, 32), 5), ((1, 3, 2, 5), 5), ((2, 33, 17, 6), 7),
                       ((1, 5, 40, 130), 3), ((2, 35, 18, 12), 15), ((8, 44, 44, 32), 5)]
 
