@@ -7,7 +7,7 @@ One "step" is one pass of the whole hot path over one synthetic mini-batch of wo
 share of a first layer: B=128, 200x200x3 pink-noise images, 20x20x3 fields at stride 4, 32 filters per
 location), inputs already resident in HBM:
 
-    lc_forward -> l2pool_lcn_fwd (L2 pooling and LCN forward as one call) -> lcn_bwd -> l2pool_bwd
+    lc_forward -> l2pool_lcn_fwd (L2 pooling, then LCN) -> lcn_l2pool_bwd (their gradients)
                -> lc_backward_data -> lc_backward_weights
 
 `value` is the algorithmic flop of the three layer contractions (3 x 2*B*K*F*L) divided by the time of
@@ -94,13 +94,12 @@ def main() -> int:
     dx = torch.empty((g.B, g.H, g.W, g.C), device="cuda")
     dw = torch.empty((g.LH, g.LW, g.K, g.F), device="cuda")
 
-    names = ["lc_forward", "l2pool_lcn_fwd", "lcn_bwd", "l2pool_bwd", "lc_backward_data", "lc_backward_weights"]
+    names = ["lc_forward", "l2pool_lcn_fwd", "lcn_l2pool_bwd", "lc_backward_data", "lc_backward_weights"]
     calls = [
         lambda: lc.lc_forward(G, xd, wd, None, 1.0, y),
         lambda: lc.l2pool_lcn_fwd(y, p, n, mu, rstd, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.POOL_EPS, wl.LCN_KSIZE,
                                   wl.LCN_SIGMA, wl.LCN_EPS),
-        lambda: lc.lcn_bwd(p, mu, rstd, dn, dp, wl.LCN_KSIZE, wl.LCN_SIGMA),
-        lambda: lc.l2pool_bwd(y, p, dp, dyd, wl.POOL_KSIZE, wl.POOL_STRIDE),
+        lambda: lc.lcn_l2pool_bwd(y, p, mu, rstd, dn, dp, dyd, wl.POOL_KSIZE, wl.POOL_STRIDE, wl.LCN_KSIZE, wl.LCN_SIGMA),
         lambda: lc.lc_backward_data(G, dyd, wd, dx),
         lambda: lc.lc_backward_weights(G, xd, dyd, 0.0, dw),
     ]
@@ -176,8 +175,8 @@ def main() -> int:
                         "timed region (more than 3 % apart: clocks not settled, or another process on the GPU)")
     nbytes = {
         "l2pool_lcn_fwd": 4 * (y.numel() + 2 * p.numel() + 2 * mu.numel()),     # y read; p, n, mu, rstd written
-        "lcn_bwd": 4 * (3 * p.numel() + 2 * mu.numel()),
-        "l2pool_bwd": 4 * (2 * y.numel() + 2 * p.numel()),
+        # p, dn, mu, rstd and y read, dy written (the intermediate between the two gradients is not counted)
+        "lcn_l2pool_bwd": 4 * (2 * p.numel() + 2 * mu.numel() + 2 * y.numel()),
     }
     kernels = {}
     for nm in names:

@@ -139,6 +139,15 @@ int l2pool_lcn_fwd(const float *x, float *p, float *y, float *mu, float *rstd, i
                    int32_t C, int32_t pool_ksize, int32_t pool_stride, float pool_eps, int32_t lcn_ksize,
                    float gauss_sigma, float lcn_eps, void *hip_stream);
 
+/* Gradient of l2pool_lcn_fwd with respect to x, as one call: dp = lcn_bwd(p, mu, rstd, dy), dx = l2pool_bwd(x, p, dp).
+ * x [B,H,W,C] is the pooling input, p, mu, rstd what l2pool_lcn_fwd left, dy [B,Ho,Wo,C] the gradient with respect
+ * to its y.  scratch [B,Ho,Wo,C] (fp32, 16-byte aligned, caller-owned) holds the intermediate: dp, or dp / p where the
+ * kernels hand that over instead (the pooling gradient then reads one array less); its contents after the call are
+ * unspecified.  dx [B,H,W,C] is overwritten.  Results are those of the two calls up to fp32 rounding order. */
+int lcn_l2pool_bwd(const float *x, const float *p, const float *mu, const float *rstd, const float *dy,
+                   float *scratch, float *dx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t pool_ksize,
+                   int32_t pool_stride, int32_t lcn_ksize, float gauss_sigma, void *hip_stream);
+
 /* Gradient of lcn_fwd with respect to x, given the saved mu and rstd (the clamp of the variance at zero is
  * taken as inactive).  dx [B,H,W,C] overwritten. */
 int lcn_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B,

@@ -25,7 +25,7 @@ _STATUS = {0: "LC_OK", -1: "LC_EINVAL", -2: "LC_ENULL", -3: "LC_EALIGN", -4: "LC
            -5: "LC_EUNSUPPORTED", -6: "LC_EHIP", -7: "LC_EINTERNAL"}
 
 EXPORTS = ("lc_geom_derive", "lc_workspace_bytes", "lc_forward", "lc_forward_dev_scale", "lc_backward_data", "lc_backward_weights",
-           "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "l2pool_lcn_fwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
+           "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "l2pool_lcn_fwd", "lcn_l2pool_bwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
            "lcn_variant_bwd", "lcn_variant_bwd_static", "sae_step", "lc_last_error", "lc_plan_query")
 
 
@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
         L.l2pool_bwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
         L.lcn_fwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, vp]
         L.l2pool_lcn_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, i32, f32, f32, vp]
+        L.lcn_l2pool_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp]
         L.lcn_bwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp]
         L.lcn_variant_workspace_bytes.argtypes = [i32, i32, i32, i32, C.c_uint32]
         L.lcn_variant_workspace_bytes.restype = C.c_size_t
@@ -220,6 +221,17 @@ def l2pool_lcn_fwd(x, p, y, mu, rstd, pool_ksize: int, pool_stride: int, pool_ep
         _dev(y, (B, Ho, Wo, Cc), torch.float32, "y"), _dev(mu, (B, Ho, Wo), torch.float32, "mu"),
         _dev(rstd, (B, Ho, Wo), torch.float32, "rstd"), B, H, W, Cc, pool_ksize, pool_stride, pool_eps, lcn_ksize,
         gauss_sigma, lcn_eps, _stream()))
+
+
+def lcn_l2pool_bwd(x, p, mu, rstd, dy, scratch, dx, pool_ksize: int, pool_stride: int, lcn_ksize: int,
+                   gauss_sigma: float) -> None:
+    B, H, W, Cc = x.shape
+    oshape = (B, _pool_out(H, pool_ksize, pool_stride), _pool_out(W, pool_ksize, pool_stride), Cc)
+    _check("lcn_l2pool_bwd", lib().lcn_l2pool_bwd(
+        _dev(x, None, torch.float32, "x"), _dev(p, oshape, torch.float32, "p"), _dev(mu, oshape[:3], torch.float32, "mu"),
+        _dev(rstd, oshape[:3], torch.float32, "rstd"), _dev(dy, oshape, torch.float32, "dy"),
+        _dev(scratch, oshape, torch.float32, "scratch"), _dev(dx, x.shape, torch.float32, "dx"),
+        B, H, W, Cc, pool_ksize, pool_stride, lcn_ksize, gauss_sigma, _stream()))
 
 
 def lcn_bwd(x, mu, rstd, dy, dx, ksize: int, gauss_sigma: float) -> None:

@@ -243,6 +243,21 @@ int l2pool_lcn_fwd(const float *x, float *p, float *y, float *mu, float *rstd, i
     return launch_lcn(0, p, nullptr, y, mu, rstd, B, Ho, Wo, C, lcn_ksize, gauss_sigma, lcn_eps, s);
 }
 
+int lcn_l2pool_bwd(const float *x, const float *p, const float *mu, const float *rstd, const float *dy,
+                   float *scratch, float *dx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t pool_ksize,
+                   int32_t pool_stride, int32_t lcn_ksize, float gauss_sigma, void *hip_stream) {
+    if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;
+    if (pool_ksize < 1 || pool_stride < 1 || pool_ksize > H || pool_ksize > W) return LC_EINVAL;
+    if (lcn_ksize < 1 || lcn_ksize > 15 || (lcn_ksize & 1) == 0 || !(gauss_sigma > 0.f)) return LC_EINVAL;
+    LC_REQUIRE_PTR(x); LC_REQUIRE_PTR(p); LC_REQUIRE_PTR(mu); LC_REQUIRE_PTR(rstd); LC_REQUIRE_PTR(dy);
+    LC_REQUIRE_PTR(scratch); LC_REQUIRE_PTR(dx);
+    LC_REQUIRE_ALIGNED(x); LC_REQUIRE_ALIGNED(p); LC_REQUIRE_ALIGNED(mu); LC_REQUIRE_ALIGNED(rstd); LC_REQUIRE_ALIGNED(dy);
+    LC_REQUIRE_ALIGNED(scratch); LC_REQUIRE_ALIGNED(dx);
+    if (scratch == dy || scratch == p || dx == x) return LC_EINVAL;
+    return launch_lcn_pool_bwd(x, p, mu, rstd, dy, scratch, dx, B, H, W, C, pool_ksize, pool_stride, lcn_ksize,
+                               gauss_sigma, (hipStream_t)hip_stream);
+}
+
 int lcn_bwd(const float *x, const float *mu, const float *rstd, const float *dy, float *dx, int32_t B, int32_t H,
             int32_t W, int32_t C, int32_t ksize, float gauss_sigma, void *hip_stream) {
     if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;

@@ -272,6 +272,10 @@ int launch_lcn(int mode, const float *x, const float *dy, float *out, float *mu,
 // 3x3 stride-1 pooling and the one-stage pooled LCN of its result in one kernel; *done: whether the shape took it
 int launch_pool_lcn_fused(const float *x, float *p, float *out, float *mu, float *rstd, int B, int H, int W, int C,
                           float peps, int ks, float sigma, float eps, hipStream_t s, bool *done);
+// lcn_bwd followed by l2pool_bwd (the gradient of pooling + LCN with respect to the pooling input)
+int launch_lcn_pool_bwd(const float *x, const float *p, const float *mu, const float *rstd, const float *dn,
+                        float *scratch, float *dx, int B, int H, int W, int C, int pks, int pst, int ks, float sigma,
+                        hipStream_t s);
 // LCN variants (flags as in lc.h: per-channel statistics, zero-padded borders, two stages)
 size_t lcn_variant_scratch_bytes(int B, int H, int W, int C, unsigned flags);
 int launch_lcn_variant_fwd(const float *x, float *y, float *mu, float *rstd, int B, int H, int W, int C, int ks,

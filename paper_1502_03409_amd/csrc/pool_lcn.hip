@@ -184,6 +184,7 @@ constexpr int kPoolTH = 8, kPoolTW = 16;
 // MODE 0: y = sqrt(eps + window sum of x^2) on a tile of outputs.
 // MODE 1: dx = x * (window sum of dy/y) on a tile of inputs; the patch holds dy/y at outputs
 //         (row-ks+1 .. row, col-ks+1 .. col), zero where no such output exists.
+// MODE 2: the same with dy/y handed in as one array (in `dy`; `y` is not read).
 template <int MODE>
 __global__ __launch_bounds__(256) void l2pool_tile_kernel(const float *__restrict__ x, const float *__restrict__ y,
                                                           const float *__restrict__ dy, float *__restrict__ out,
@@ -218,14 +219,14 @@ __global__ __launch_bounds__(256) void l2pool_tile_kernel(const float *__restric
                     v[q] = *(const f32x4 *)(x + o);
                 } else {
                     v[q] = *(const f32x4 *)(dy + o);
-                    v2[q] = *(const f32x4 *)(y + o);
+                    if (MODE == 1) v2[q] = *(const f32x4 *)(y + o);
                 }
             }
         }
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const int e = e0 + 256 * q;
-            if (e < npatch) *(f32x4 *)(patch + (size_t)e * 4) = MODE == 0 ? v[q] * v[q] : v[q] / v2[q];
+            if (e < npatch) *(f32x4 *)(patch + (size_t)e * 4) = MODE == 0 ? v[q] * v[q] : MODE == 1 ? v[q] / v2[q] : v[q];
         }
     }
     __syncthreads();
@@ -654,7 +655,7 @@ template <int LPP, int MODE, int NTHR, int NV>
 __global__ __launch_bounds__(NTHR) void lcn_band_kernel(const float *__restrict__ x, const float *__restrict__ dy,
                                                         float *__restrict__ out, float *__restrict__ mu,
                                                         float *__restrict__ rstd, int H, int W, int ks, float eps,
-                                                        GaussTaps taps, int RB, int bands, int zpad) {
+                                                        GaussTaps taps, int RB, int bands, int zpad, int divx) {
     constexpr int C = 4 * LPP, NH = 2;
     extern __shared__ __attribute__((aligned(16))) float band_lds[];
     const int r = (ks - 1) / 2, MW = W + 2 * r, MH = RB + 2 * r;
@@ -805,8 +806,12 @@ __global__ __launch_bounds__(NTHR) void lcn_band_kernel(const float *__restrict_
         } else {
             const float rs = rstd[pix];
             const float4 d = dv[q];
-            *(float4 *)(out + pix * C + gl * 4) = make_float4(d.x * rs + u - xq.x * v, d.y * rs + u - xq.y * v,
-                                                             d.z * rs + u - xq.z * v, d.w * rs + u - xq.w * v);
+            float4 o = make_float4(d.x * rs + u - xq.x * v, d.y * rs + u - xq.y * v, d.z * rs + u - xq.z * v,
+                                   d.w * rs + u - xq.w * v);
+            // divx: the gradient divided by x itself, which is what the backward pass of a pooling layer in front
+            // of this one sums up (x is that layer's output, positive)
+            if (divx) o = make_float4(o.x / xq.x, o.y / xq.y, o.z / xq.z, o.w / xq.w);
+            *(float4 *)(out + pix * C + gl * 4) = o;
         }
     }
 }
@@ -1040,7 +1045,7 @@ namespace {
 // kernel pays where a band is at least 8 rows and two window radii high; below that the 16x16 tiles re-read less.
 template <int LPP, int MODE>
 int launch_lcn_band_lpp(const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
-                        int ks, float eps, const GaussTaps &taps, hipStream_t s, int zero_pad, bool *done) {
+                        int ks, float eps, const GaussTaps &taps, hipStream_t s, int zero_pad, bool *done, int divx) {
     constexpr int NTHR = kBandThreads, NV = 8;
     const int r = (ks - 1) / 2;
     const int rb_max = (NTHR * NV) / (W * LPP);
@@ -1053,16 +1058,17 @@ int launch_lcn_band_lpp(const float *x, const float *dy, float *out, float *mu, 
     if (int rc_lds = allow_dynamic_lds((const void *)kern, lds, "lcn: hipFuncSetAttribute")) return rc_lds;
     *done = true;
     hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(NTHR), lds, s, x, dy, out, mu, rstd, H, W, ks, eps, taps, RB,
-                       bands, zero_pad);
+                       bands, zero_pad, divx);
     LC_HIP_LAUNCH_CHECK("lcn launch");
     return LC_OK;
 }
 
 int launch_lcn_band(int mode, const float *x, const float *dy, float *out, float *mu, float *rstd, int B, int H, int W,
-                    int C, int ks, float eps, const GaussTaps &taps, hipStream_t s, int zero_pad, bool *done) {
-#define LC_BAND(LPP_)                                                                                               \
-    return mode == 0 ? launch_lcn_band_lpp<LPP_, 0>(x, dy, out, mu, rstd, B, H, W, ks, eps, taps, s, zero_pad, done) \
-                     : launch_lcn_band_lpp<LPP_, 1>(x, dy, out, mu, rstd, B, H, W, ks, eps, taps, s, zero_pad, done)
+                    int C, int ks, float eps, const GaussTaps &taps, hipStream_t s, int zero_pad, bool *done,
+                    int divx = 0) {
+#define LC_BAND(LPP_)                                                                                                  \
+    return mode == 0 ? launch_lcn_band_lpp<LPP_, 0>(x, dy, out, mu, rstd, B, H, W, ks, eps, taps, s, zero_pad, done, 0) \
+                     : launch_lcn_band_lpp<LPP_, 1>(x, dy, out, mu, rstd, B, H, W, ks, eps, taps, s, zero_pad, done, divx)
     switch (C) {
         case 4: LC_BAND(1);
         case 8: LC_BAND(2);
@@ -1089,6 +1095,39 @@ int launch_pool_lcn_band(const LaunchPlan &plan, const float *x, float *p, float
 }
 
 }  // namespace
+
+// Gradient of l2pool_lcn_fwd with respect to its input: lcn_bwd, then l2pool_bwd, with `scratch` ([B,Ho,Wo,C]) between
+// them.  Where the band kernel and the tile kernel apply, the first leaves its gradient already divided by p there,
+// so the second reads one array less.
+int launch_lcn_pool_bwd(const float *x, const float *p, const float *mu, const float *rstd, const float *dn,
+                        float *scratch, float *dx, int B, int H, int W, int C, int pks, int pst, int ks, float sigma,
+                        hipStream_t s) {
+    const int Ho = (H - pks) / pst + 1, Wo = (W - pks) / pst + 1;
+    GaussTaps taps;
+    if (!make_taps(ks, sigma, &taps)) return LC_EINVAL;
+    const size_t patch_bytes = (size_t)(kPoolTH + pks - 1) * (kPoolTW + pks - 1) * C * sizeof(float);
+    const int th = (H + kPoolTH - 1) / kPoolTH, tw = (W + kPoolTW - 1) / kPoolTW;
+    const long long nblk = (long long)B * th * tw;
+    if (C % 4 == 0 && pst == 1 && pks <= kPoolMaxK && patch_bytes <= 64 * 1024 && nblk <= 0x7fffffffLL) {
+        bool done = false;
+        if (int rc = launch_lcn_band(1, p, dn, scratch, const_cast<float *>(mu), const_cast<float *>(rstd), B, Ho, Wo, C,
+                                     ks, 0.f, taps, s, 0, &done, 1))
+            return rc;
+        if (done) {
+            auto kern = l2pool_tile_kernel<2>;
+            if (int rc_lds = allow_dynamic_lds((const void *)kern, patch_bytes, "lcn_l2pool_bwd: hipFuncSetAttribute"))
+                return rc_lds;
+            hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), patch_bytes, s, x, (const float *)nullptr,
+                               (const float *)scratch, dx, H, W, C, Ho, Wo, pks, 0.f, tw, th * tw);
+            LC_HIP_LAUNCH_CHECK("lcn_l2pool_bwd launch");
+            return LC_OK;
+        }
+    }
+    if (int rc = launch_lcn(1, p, dn, scratch, const_cast<float *>(mu), const_cast<float *>(rstd), B, Ho, Wo, C, ks, sigma,
+                            0.f, s))
+        return rc;
+    return launch_l2pool_bwd(x, p, scratch, dx, B, H, W, C, pks, pst, s);
+}
 
 // Host check of a pool_lcn_band_kernel launch.  tparam = {LPP, RPT}; arg = {PB, bands, WPS, rpt, H, W, ks, B}.
 int check_pool_lcn_band(const LaunchPlan &p) {

@@ -86,6 +86,9 @@ def test_argument_validation_happens_before_any_launch():
     assert L.lcn_fwd(FAKE, FAKE, None, FAKE, 1, 8, 8, 4, 5, 1.0, 1e-4, None) == B.LC_ENULL
     assert L.lcn_bwd(FAKE, FAKE, FAKE, FAKE, None, 1, 8, 8, 4, 5, 1.0, None) == B.LC_ENULL
     # the fused pooling + LCN call checks both halves' arguments
+    assert L.lcn_l2pool_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 3, 0, 5, 1.0, None) == B.LC_EINVAL
+    assert L.lcn_l2pool_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 1, 8, 8, 4, 3, 1, 5, 1.0, None) == B.LC_ENULL
+    assert L.lcn_l2pool_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 3, 1, 5, 1.0, None) == B.LC_EINVAL  # scratch is dy
     assert L.l2pool_lcn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 9, 1, 0.0, 5, 1.0, 1e-4, None) == B.LC_EINVAL
     assert L.l2pool_lcn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 3, 1, 0.0, 4, 1.0, 1e-4, None) == B.LC_EINVAL
     assert L.l2pool_lcn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 8, 8, 4, 3, 1, 0.0, 5, 0.0, 1e-4, None) == B.LC_EINVAL

@@ -454,6 +454,26 @@ def test_l2pool_lcn_fwd_matches_oracle(shape, pk, ps, lk):
         assert e <= TOL
 
 
+@pytest.mark.parametrize("shape,pk,ps,lk", POOL_LCN_SHAPES)
+def test_lcn_l2pool_bwd_matches_oracle(shape, pk, ps, lk):
+    """The fused gradient call against the oracle's LCN gradient followed by its pooling gradient, fed the oracle's
+    saved p, mu and rstd so that only the gradient is under test."""
+    print(f"case lcn+pool bwd {shape} {pk} {ps} {lk}", flush=True)
+    x = wl.feature_maps(*shape, seed=6)
+    ref_p = oracle.l2pool_fwd(x, pk, ps, wl.POOL_EPS)
+    _, ref_mu, ref_rstd = oracle.lcn_fwd(ref_p, lk, wl.LCN_SIGMA, wl.LCN_EPS)
+    dn = wl.feature_maps(*ref_p.shape, seed=7)
+    ref_dp = oracle.lcn_bwd(ref_p, ref_mu, ref_rstd, dn, lk, wl.LCN_SIGMA)
+    ref_dx = oracle.l2pool_bwd(x, ref_p, ref_dp, pk, ps)
+    f32 = lambda a: dev(np.asarray(a, dtype=np.float32))
+    scratch = torch.full(ref_p.shape, float("nan"), device="cuda")
+    dx = torch.full(shape, float("nan"), device="cuda")
+    lc.lcn_l2pool_bwd(dev(x), f32(ref_p), f32(ref_mu), f32(ref_rstd), dev(dn), scratch, dx, pk, ps, lk, wl.LCN_SIGMA)
+    e = rel_fro(host(dx), ref_dx)
+    print(f"  dx rel err {e:.2e}", flush=True)
+    assert e <= TOL
+
+
 LCN_VARIANT_SHAPES = [((2, 9, 10, 3), 5), ((3, 20, 37, 32), 5), ((1, 3, 2, 5), 5), ((2, 33, 17, 6), 7),
                       ((1, 5, 40, 130), 3), ((2, 35, 18, 12), 15), ((8, 44, 44, 32), 5)]
 
