@@ -1012,7 +1012,9 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
             if (ntt == 4) LC_BD(4, 4, 4);
             LC_BD(4, 4, 2);
         } else if (ap == 5) {
-            // fp32, filters in blocks of 32: whole-line chunks (5 x 5 covering fields, 104 x 104 x 12 input, batch 128: 243 -> 233 us)
+            // fp32, filters in blocks of 32: whole-line chunks (5 x 5 covering fields, 104 x 104 x 12 input, batch 128: 243 -> 233 us;
+            // on a 200 x 200 x 3 input under 46 x 46 fields of 32 filters the kernel that loads dy straight into LDS takes
+            // 224 us against this one's 220, with 128-image tiles 263 us (two buffers) and 278 us (one))
             if constexpr (sizeof(T) == 4) {
                 if (ntt <= 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 5, 2>(g, (const float *)dy, (const float *)w, dx, s); }
             }
@@ -1023,9 +1025,6 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
             // one tile of cell values per wave: eight cells per workgroup share the staged fields
             if (ntt == 1) {
                 *done = true;
-#ifdef LC_BD_NBUF1
-                if constexpr (sizeof(T) == 4) return launch_direct<4, 1, 8, 8, 8, 1>(g, dy, w, dx, s);
-#endif
                 return launch_fast<4, 1, 8, 8, 8>(g, dy, w, dx, s);
             }
             LC_BD(8, 2, 2);

@@ -875,11 +875,6 @@ int launch_fast_wide(const Geom &g, const T *x, const T *w, const float *bias, f
         // whole patch rows of 12 k-steps that need every staging slot: the variant with compile-time counts
         const int sq4 = ((CQ + 7 * g.S * g.C + 3) & ~3) / 4;
         if constexpr (sizeof(T) == 4) {
-#ifdef LC_FWD_NBUF1
-            constexpr int kBuf = 1;
-#else
-            constexpr int kBuf = 2;
-#endif
             // sixteen fields per workgroup (four waves per SIMD) where that idles no more waves at the end of a field
             // row than eight do: the per-chunk costs that do not shrink with the chunk (barrier, first LDS reads) are
             // spread over twice the MFMAs (57 fields per row, 128 x 128 x 3 input: 121 -> 107 us)
@@ -887,7 +882,7 @@ int launch_fast_wide(const Geom &g, const T *x, const T *w, const float *bias, f
                 return launch_direct<8, 1, 16, 16, 12, 1, 5, 12, 2>(g, x, w, bias, alpha, alpha_dev, y, 0,
                                                                     ((g.LW + 15) / 16) * g.LH, s);
             if (forward_direct_fits<8, 8, 8, 12, 1, 6>(g))
-                return launch_direct<8, 1, 8, 8, 12, 1, 6, 12, kBuf>(g, x, w, bias, alpha, alpha_dev, y, 0, ntask, s);
+                return launch_direct<8, 1, 8, 8, 12, 1, 6, 12, 2>(g, x, w, bias, alpha, alpha_dev, y, 0, ntask, s);
         }
         if (sizeof(T) == 4 && CQ == g.RC && spr == 12 && (128 * sq4 + 511) / 512 == kFwdStageSlotsWide &&
             (long long)g.B * g.H * g.W * g.C < (1LL << 31))
