@@ -39,6 +39,12 @@ typedef struct {
  * for this shape and dtype) or LC_EINTERNAL. */
 int lc_plan_query(const lc_geom_t *g, int op, int dtype, lc_launch_t *out, int32_t max_out, int32_t *n_out);
 
+/* Host only.  The launch l2pool_lcn_fwd would make for a [B,H,W,C] map where it runs as one kernel, planned and
+ * checked as in the call: *n_out = 1 and out[0] holds it; *n_out = 0 where the call runs l2pool_fwd's and lcn_fwd's
+ * kernels one after the other (those keep no plan records).  Returns LC_OK, LC_EINVAL or LC_EINTERNAL. */
+int l2pool_lcn_plan_query(int32_t B, int32_t H, int32_t W, int32_t C, int32_t pool_ksize, int32_t pool_stride,
+                          int32_t lcn_ksize, float gauss_sigma, lc_launch_t *out, int32_t max_out, int32_t *n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ _STATUS = {0: "LC_OK", -1: "LC_EINVAL", -2: "LC_ENULL", -3: "LC_EALIGN", -4: "LC
 
 EXPORTS = ("lc_geom_derive", "lc_workspace_bytes", "lc_forward", "lc_forward_dev_scale", "lc_backward_data", "lc_backward_weights",
            "l2pool_fwd", "l2pool_bwd", "lcn_fwd", "lcn_bwd", "l2pool_lcn_fwd", "lcn_l2pool_bwd", "lcn_variant_workspace_bytes", "lcn_variant_fwd",
-           "lcn_variant_bwd", "lcn_variant_bwd_static", "sae_step", "lc_last_error", "lc_plan_query")
+           "lcn_variant_bwd", "lcn_variant_bwd_static", "sae_step", "lc_last_error", "lc_plan_query", "l2pool_lcn_plan_query")
 
 
 class LcGeom(C.Structure):
@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
         L.sae_step.argtypes = [G, vp, vp, vp, vp, f32, f32, f32, u32, vp, vp, vp, sz, vp]
         L.lc_last_error.restype = C.c_char_p
         L.lc_plan_query.argtypes = [G, C.c_int, C.c_int, C.POINTER(LcLaunch), i32, C.POINTER(i32)]
+        L.l2pool_lcn_plan_query.argtypes = [i32, i32, i32, i32, i32, i32, i32, f32, C.POINTER(LcLaunch), i32, C.POINTER(i32)]
         for name in EXPORTS:
             if name not in ("lc_workspace_bytes", "lc_last_error"):
                 getattr(L, name).restype = C.c_int
@@ -117,6 +118,20 @@ def plan_query(g: LcGeom, op: int, dtype: int = LC_F32, max_out: int = 16):
     return [{"kernel": out[i].kernel.decode(), "tparam": list(out[i].tparam), "arg": list(out[i].arg),
              "grid": tuple(out[i].grid), "block": int(out[i].block), "lds_bytes": int(out[i].lds_bytes)}
             for i in range(n.value)]
+
+
+def l2pool_lcn_plan_query(shape, pool_ksize: int, pool_stride: int, lcn_ksize: int, gauss_sigma: float = 1.0):
+    """The one-kernel launch of ``l2pool_lcn_fwd`` for a [B,H,W,C] map as a dict, or None where the call runs the
+    two kernels one after the other (host only; nothing is launched)."""
+    out = (LcLaunch * 1)()
+    n = C.c_int32()
+    B, H, W, Cc = shape
+    _check("l2pool_lcn_plan_query", lib().l2pool_lcn_plan_query(B, H, W, Cc, pool_ksize, pool_stride, lcn_ksize,
+                                                                gauss_sigma, out, 1, C.byref(n)))
+    if n.value == 0:
+        return None
+    return {"kernel": out[0].kernel.decode(), "tparam": list(out[0].tparam), "arg": list(out[0].arg),
+            "grid": tuple(out[0].grid), "block": int(out[0].block), "lds_bytes": int(out[0].lds_bytes)}
 
 
 def _stream() -> int:

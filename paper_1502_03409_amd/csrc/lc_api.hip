@@ -195,6 +195,26 @@ int lc_plan_query(const lc_geom_t *g, int op, int dtype, lc_launch_t *out, int32
 
 static int check_map(int32_t B, int32_t H, int32_t W, int32_t C) { return check_map_dims(B, H, W, C); }
 
+int l2pool_lcn_plan_query(int32_t B, int32_t H, int32_t W, int32_t C, int32_t pool_ksize, int32_t pool_stride,
+                          int32_t lcn_ksize, float gauss_sigma, lc_launch_t *out, int32_t max_out, int32_t *n_out) {
+    if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;
+    if (pool_ksize < 1 || pool_stride < 1 || pool_ksize > H || pool_ksize > W) return LC_EINVAL;
+    if (lcn_ksize < 1 || lcn_ksize > 15 || (lcn_ksize & 1) == 0 || !(gauss_sigma > 0.f)) return LC_EINVAL;
+    if (max_out < 0 || (max_out > 0 && !out) || !n_out) return LC_EINVAL;
+    *n_out = 0;
+    if (pool_ksize != 3 || pool_stride != 1) return LC_OK;
+    float *ff = (float *)(uintptr_t)0x100000;      // never dereferenced: nothing is launched
+    std::vector<LaunchPlan> plans;
+    bool done = false;
+    g_capture = &plans;
+    const int rc = launch_pool_lcn_fused(ff, ff, ff, ff, ff, B, H, W, C, 1e-6f, lcn_ksize, gauss_sigma, 1e-4f, nullptr, &done);
+    g_capture = nullptr;
+    if (rc != LC_OK) return rc;
+    *n_out = (int32_t)plans.size();
+    for (int32_t k = 0; k < max_out && k < (int32_t)plans.size(); ++k) out[k] = plans[k];
+    return LC_OK;
+}
+
 int l2pool_fwd(const float *x, float *y, int32_t B, int32_t H, int32_t W, int32_t C, int32_t ksize, int32_t stride,
                float eps, void *hip_stream) {
     if (check_map(B, H, W, C) != LC_OK) return LC_EINVAL;

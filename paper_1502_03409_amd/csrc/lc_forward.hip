@@ -932,6 +932,8 @@ int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float 
         // strip finds the weights in L2).  A layer too small to fill one round of two workgroups per CU at that
         // tile size steps down to smaller wave tiles until it does: finer workgroups spread evenly over the CUs.
         int mt = g.B > 64 && g.F % 64 != 0 ? 8 : g.B > 32 ? 4 : 2, nt = 4;
+        // (larger tiles with fewer workgroups measured slower: a 55 x 55 x 16 input under 6 x 6 fields at stride 2,
+        // 32 filters, batch 128: 53 us with 64-image tiles and 350 workgroups against 42 us with 32-image tiles and 700)
         while (fast_workgroups(g, mt, nt) < kComputeUnits * kBigTilesPerCu && (mt > 2 || nt > 1)) {
             if (nt > 1 && (nt >= mt || mt == 2)) nt >>= 1; else mt >>= 1;
         }

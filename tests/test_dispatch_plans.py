@@ -463,3 +463,69 @@ def test_hand_scheduled_kernels_stay_inside_their_tensors(name):
                                     assert base >= 0 and base + (nfh - 1) * 16 + kn.max() + 16 <= g.L * g.K * g.F
     if name == "cfg5_s1":
         assert {"lc_forward_direct", "lc_bwd_data_direct", "lc_bwd_weights_strip"} <= seen
+
+
+# ------------------------------------------------------------------------------------ fused pooling + LCN forward
+def replay_pool_lcn_band(shape, ks, p):
+    """Replays pool_lcn_band_kernel's lane arithmetic for one image: which lane produces which pooled pixel, which
+    rows of x it loads, which map cells and outputs it writes."""
+    B, H, W, C = shape
+    LPP, RPT = p["tparam"][:2]
+    PB, bands, WPS, rpt = p["arg"][:4]
+    assert p["arg"][4:8] == [H, W, ks, B] and LPP * 4 == C
+    Hp, Wp, r = H - 2, W - 2, (ks - 1) // 2
+    MH, MW = PB + 2 * r, Wp + 2 * r
+    CPW, OPW = 64 // LPP, 64 // LPP - 2
+    assert p["block"] == 1024 and p["grid"] == (B * bands, 1, 1)
+    assert 1 <= rpt <= RPT <= 13 and 1 <= WPS <= 16 and WPS * OPW >= Wp and (16 // WPS) * rpt >= MH
+    assert PB * bands >= Hp > PB * (bands - 1)
+    assert p["lds_bytes"] >= (2 * MH * MW + 2 * PB * Wp + MH + Wp + 15) * 4 and p["lds_bytes"] <= 64 * 1024
+    owned = np.zeros((Hp, Wp), dtype=np.int32)
+    for band in range(bands):
+        r0 = band * PB
+        cells = np.zeros((MH, Wp), dtype=np.int32)
+        for wave in range(16):
+            seg, ws = divmod(wave, WPS)
+            hrow0 = seg * rpt
+            for cw in range(CPW):
+                col = ws * OPW + cw
+                for t in range(RPT):
+                    hrow, prow = hrow0 + t, r0 - r + hrow0 + t
+                    valid = t < rpt and hrow < MH and 0 <= prow < Hp and cw < OPW and col < Wp
+                    if not valid:
+                        continue
+                    # the three rows of x under this pooled row are among the lane's loads, inside the image, and the
+                    # two columns to the right come from lanes of the same wave
+                    assert t + 2 < rpt + 2 and 0 <= prow and prow + 2 < H and col + 2 < W and cw + 2 < CPW
+                    cells[hrow, col] += 1
+                    if r0 <= prow < r0 + PB:
+                        owned[prow, col] += 1
+        rows = np.arange(MH) + r0 - r
+        inside = (rows >= 0) & (rows < Hp)
+        assert (cells[inside] == 1).all() and (cells[~inside] == 0).all(), (shape, ks, p)
+    assert (owned == 1).all(), (shape, ks, p)
+
+
+def test_fused_pool_lcn_plans_cover_every_pooled_pixel_once():
+    rng = np.random.default_rng(11)
+    named = [((128, 46, 46, 32), 5), ((128, 57, 57, 16), 5), ((128, 25, 25, 32), 5), ((128, 9, 9, 32), 5),
+             ((192, 72, 72, 64), 5), ((1, 3, 3, 8), 3), ((7, 300, 90, 32), 7)]
+    fused = 0
+    for n in range(1500):
+        if n < len(named):
+            shape, ks = named[n]
+        else:
+            C_ = int(rng.choice([8, 16, 32, 64, 4, 12, 128]))
+            shape = (int(rng.integers(1, 300)), int(rng.integers(3, 140)), int(rng.integers(3, 140)), C_)
+            ks = int(rng.choice([1, 3, 5, 7, 9]))
+        p = lc.l2pool_lcn_plan_query(shape, 3, 1, ks)
+        if p is None:
+            # the fused kernel's limits: 8 to 64 channels in whole quads of a power-of-two count, rows that 16 waves cover
+            C_, Wp = shape[3], shape[2] - 2
+            assert C_ not in (8, 16, 32, 64) or -(-Wp // (256 // C_ - 2)) > 16, (shape, ks)
+            continue
+        assert p["kernel"] == "pool_lcn_band"
+        replay_pool_lcn_band(shape, ks, p)
+        fused += 1
+    assert fused > 500
+    assert lc.l2pool_lcn_plan_query((4, 20, 20, 16), 2, 2, 5) is None      # other pooling windows: the two kernels
