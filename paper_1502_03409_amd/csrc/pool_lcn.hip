@@ -1160,18 +1160,18 @@ int launch_pool_lcn_fused(const float *x, float *p, float *out, float *mu, float
     const int nseg = 16 / WPS;
     // bands per image: enough for one workgroup per compute unit (twice as many measured the same or slower: 25.0
     // against 26.3 us on 128 x 46 x 46 x 32 maps, 13.1 against 10.8 us on 128 x 25 x 25 x 32), and as many more as it
-    // takes for a lane's rows to fit its registers
+    // takes for a lane's rows to fit its registers and the band's maps 64 KB of LDS
     int bands = std::min(Hp, std::max(1, (256 + B - 1) / B)), PB = 0, rpt = 0;
+    size_t lds = 0;
     for (;; ++bands) {
         PB = (Hp + bands - 1) / bands;
         rpt = (PB + 2 * r + nseg - 1) / nseg;
-        if (rpt <= 13 || bands >= Hp) break;
+        lds = ((size_t)2 * (PB + 2 * r) * (Wp + 2 * r) + (size_t)2 * PB * Wp + (PB + 2 * r) + Wp + kLcnMaxK) * sizeof(float);
+        if ((rpt <= 13 && lds <= 64 * 1024) || bands >= Hp) break;
     }
-    if (rpt > 13) return LC_OK;
+    if (rpt > 13 || lds > 64 * 1024) return LC_OK;
     bands = (Hp + PB - 1) / PB;
-    const size_t lds =
-        ((size_t)2 * (PB + 2 * r) * (Wp + 2 * r) + (size_t)2 * PB * Wp + (PB + 2 * r) + Wp + kLcnMaxK) * sizeof(float);
-    if (lds > 64 * 1024 || (long long)B * bands > 0x7fffffffLL) return LC_OK;
+    if ((long long)B * bands > 0x7fffffffLL) return LC_OK;
     const int RPT = rpt <= 4 ? 4 : rpt <= 8 ? 8 : 13;
     const LaunchPlan plan = make_plan("pool_lcn_band", {LPP, RPT}, {PB, bands, WPS, rpt, H, W, ks, B},
                                       dim3((unsigned)(B * bands)), kBandThreads, lds);

@@ -429,6 +429,7 @@ POOL_LCN_SHAPES = [((4, 46, 46, 32), 3, 1, 5),      # cfg3's maps: two bands of 
                    ((1, 3, 3, 16), 3, 1, 5),        # one pooled pixel
                    ((2, 4, 90, 32), 3, 1, 5),       # a row of 88 pooled pixels: 15 waves per segment
                    ((2, 70, 30, 32), 3, 1, 5),      # tall maps: more bands than the chip needs, so that a lane's rows fit
+                   ((70, 132, 137, 8), 3, 1, 7),    # wide maps, 7x7 window: more bands still, so that the band's maps fit LDS
                    ((2, 12, 120, 32), 3, 1, 5),     # rows too long for one workgroup: the two kernels one after the other
                    ((2, 17, 19, 5), 3, 1, 5),       # channels no multiple of four: the two kernels
                    ((2, 21, 21, 16), 2, 2, 5),      # another pooling window: the two kernels
