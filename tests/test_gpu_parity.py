@@ -633,6 +633,30 @@ def test_sae_step_without_h_out_and_descent():
     assert all(c1 < c0 for c0, c1 in zip(costs, costs[1:])), costs
 
 
+def test_sae_step_is_bitwise_reproducible():
+    """The cost, the alpha step and the bias update are summed by whichever workgroup of the sparsity pass finishes
+    last, from partial sums the others have written: the same step from the same state must give the same bits every
+    time (a sum that missed a partial, or took a stale one, would not).  Shape of cfg5's second stage: the pass runs
+    as 157 workgroups plus those of the bias update."""
+    g = wl.CONFIG_GEOM["cfg5_s2"]
+    x, w, _ = wl.lc_inputs(g, "halfnormal", seed=2)
+    G = lc.geom(*g.as_tuple())
+    xd, w0 = dev(x), dev(w)
+    b0 = dev((0.01 * np.random.default_rng(4).standard_normal((g.H, g.W, g.C))).astype(np.float32))
+    ws = torch.empty(lc.workspace_bytes(G, lc.LC_OP_SAE_STEP), dtype=torch.uint8, device="cuda")
+    first = None
+    for it in range(40):
+        wd, bd = w0.clone(), b0.clone()
+        ad, cost = torch.full((1,), 0.9, device="cuda"), torch.full((1,), float("nan"), device="cuda")
+        ws.fill_(it & 0xff)       # whatever the workspace held before must not matter
+        lc.sae_step(G, xd, wd, bd, ad, wl.SAE_LAMBDA, wl.SAE_EPS, 1e-5, 3, None, cost, ws)
+        now = (host(cost).tobytes(), host(ad).tobytes(), host(bd).tobytes(), host(wd)[::7, ::5].tobytes())
+        if first is None:
+            first = now
+            assert np.isfinite(host(cost)[0])
+        assert now == first, f"call {it} differs from call 0"
+
+
 @pytest.mark.parametrize("flags", [0, 3])
 def test_cfg5_three_stage_step_full_size(flags):
     """Workload cfg5 at full size, in the launch configuration the benchmark times: every stage takes one
