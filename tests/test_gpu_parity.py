@@ -240,6 +240,10 @@ BF16_CASES = {
     "wstrip_b112": (wl.LCGeom(B=112, H=26, W=32, C=3, R=20, S=4, F=16), "pink"),            # batch short of the 128 staged rows, one filter tile
     "bd_ap5_n72": (wl.LCGeom(B=72, H=28, W=15, C=8, R=15, S=3, F=80), "halfnormal"),        # backward data: two cells per workgroup
     "bd_ap8_n24": (wl.LCGeom(B=88, H=25, W=24, C=6, R=16, S=2, F=48), "halfnormal"),
+    # wide layers on batches of 129 to 256 images: the 256-image tiles of the workgroup-tiled kernels
+    "pair_odd_row": (wl.LCGeom(B=144, H=12, W=12, C=32, R=4, S=2, F=128), "halfnormal"),     # five fields per row, 144 of 256 image rows in use
+    "pair_two_chunks": (wl.LCGeom(B=208, H=20, W=20, C=32, R=8, S=4, F=128), "halfnormal"),  # fields two chunks apart
+    "pair_c64_f256": (wl.LCGeom(B=160, H=9, W=9, C=64, R=3, S=1, F=256), "halfnormal"),      # two filter blocks, seven fields per row
     # shapes outside every aligned set: the masked kernels on bf16 storage
     "cfg1": (wl.CONFIG_GEOM["cfg1"], "gaussian"),
     "masked_ragged_a": (wl.LCGeom(B=5, H=23, W=26, C=2, R=5, S=3, F=10), "gaussian"),
