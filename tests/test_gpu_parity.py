@@ -479,6 +479,45 @@ def test_lcn_l2pool_bwd_matches_oracle(shape, pk, ps, lk):
     assert e <= TOL
 
 
+def _pool_lcn_sweep_shapes(n, seed):
+    """Seeded random maps for the fused pooling + LCN calls: channel counts inside and outside the one-kernel set,
+    map sizes from one pooled pixel to rows that need all sixteen waves, small and large batches."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        C_ = int(rng.choice([8, 16, 32, 64, 4, 12]))
+        H, W = int(rng.integers(3, 70)), int(rng.integers(3, 70))
+        B = int(rng.choice([1, 2, 3, 7, 33, 130, 300]))
+        while B * H * W * C_ > 6_000_000:       # keeps the oracle's part of a case under a second
+            B = max(1, B // 2)
+        out.append(((B, H, W, C_), int(rng.choice([3, 5, 7]))))
+    return out
+
+
+@pytest.mark.parametrize("idx", range(16))
+def test_pool_lcn_calls_sweep(idx):
+    shape, lk = _pool_lcn_sweep_shapes(16, seed=23)[idx]
+    print(f"case pool+lcn sweep {shape} lcn window {lk}", flush=True)
+    x = wl.feature_maps(*shape, seed=100 + idx)
+    ref_p = oracle.l2pool_fwd(x, 3, 1, wl.POOL_EPS)
+    ref_y, ref_mu, ref_rstd = oracle.lcn_fwd(ref_p, lk, wl.LCN_SIGMA, wl.LCN_EPS)
+    p = torch.full(ref_p.shape, float("nan"), device="cuda")
+    y = torch.full(ref_p.shape, float("nan"), device="cuda")
+    mu = torch.full(ref_p.shape[:3], float("nan"), device="cuda")
+    rstd = torch.full(ref_p.shape[:3], float("nan"), device="cuda")
+    xd = dev(x)
+    lc.l2pool_lcn_fwd(xd, p, y, mu, rstd, 3, 1, wl.POOL_EPS, lk, wl.LCN_SIGMA, wl.LCN_EPS)
+    for nm, got, ref in (("p", p, ref_p), ("mu", mu, ref_mu), ("rstd", rstd, ref_rstd), ("y", y, ref_y)):
+        assert rel_fro(host(got), ref) <= TOL, nm
+    # the gradient call on the kernel's own p, mu, rstd (which the checks above hold to the oracle's)
+    dn = wl.feature_maps(*ref_p.shape, seed=200 + idx)
+    ref_dx = oracle.l2pool_bwd(x, ref_p, oracle.lcn_bwd(ref_p, ref_mu, ref_rstd, dn, lk, wl.LCN_SIGMA), 3, 1)
+    scratch = torch.full(ref_p.shape, float("nan"), device="cuda")
+    dx = torch.full(shape, float("nan"), device="cuda")
+    lc.lcn_l2pool_bwd(xd, p, mu, rstd, dev(dn), scratch, dx, 3, 1, lk, wl.LCN_SIGMA)
+    assert rel_fro(host(dx), ref_dx) <= TOL
+
+
 LCN_VARIANT_SHAPES = [((2, 9, 10, 3), 5), ((3, 20, 37, 32), 5), ((1, 3, 2, 5), 5), ((2, 33, 17, 6), 7),
                       ((1, 5, 40, 130), 3), ((2, 35, 18, 12), 15), ((8, 44, 44, 32), 5)]
 
