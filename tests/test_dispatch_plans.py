@@ -304,13 +304,17 @@ def test_named_workloads_plan_and_cover(name):
 
 
 def test_headline_workload_takes_the_tiered_forward_plan():
-    """cfg3's forward pass: 512 strips of 128-image tiles with compile-time counts, the last 40 strips as
-    32-image tiles, together every strip once."""
+    """cfg3's forward pass: the kernel that loads x straight into LDS, 512 strips as 64-image tiles (two whole rounds
+    of 2 x 256 workgroups), the last 40 strips as 32-image tiles, together every strip once; weight ring as deep as
+    a patch row."""
     g = wl.CONFIG_GEOM["cfg3"]
     plans = lc.plan_query(lc.geom(*g.as_tuple()), B.LC_OP_FORWARD)
-    assert [p["kernel"] for p in plans] == ["lc_forward_fast", "lc_forward_fast"]
-    assert plans[0]["tparam"][:9] == [8, 2, 4, 5, 4, 4, 15, 1, 12] and plans[0]["arg"][4:6] == [0, 512]
-    assert plans[1]["tparam"][:9] == [2, 2, 4, 15, 4, 4, 15, 4, 12] and plans[1]["arg"][4:6] == [512, 40]
+    assert [p["kernel"] for p in plans] == ["lc_forward_direct", "lc_forward_direct"]
+    assert plans[0]["tparam"][:10] == [4, 2, 4, 15, 4, 4, 15, 1, 7, 2] and plans[0]["arg"][4:7] == [0, 512, 2]
+    assert plans[1]["tparam"][:10] == [2, 2, 4, 15, 4, 4, 15, 1, 4, 2] and plans[1]["arg"][4:7] == [512, 40, 4]
+    # bf16 storage keeps the kernels that stage through registers
+    plans = lc.plan_query(lc.geom(*g.as_tuple()), B.LC_OP_FORWARD, B.LC_BF16)
+    assert all(p["kernel"] != "lc_forward_direct" for p in plans)
 
 
 def test_filter_counts_off_the_tile_size_never_take_a_tiled_plan():
@@ -397,7 +401,7 @@ def _x_strip_offsets_inside(g, BT, NRT, NSLOT, NTHR, RV, sq4, NLOC, strips, nbt,
                     assert a.min() >= 0 and a.max() + 4 <= g.B * img, (g, work, bt, q, kh)
 
 
-@pytest.mark.parametrize("name", ["cfg5_s1", "cfg5_s2", "cfg2", "stage_small"])
+@pytest.mark.parametrize("name", ["cfg5_s1", "cfg5_s2", "cfg2", "cfg3", "stage_small"])
 def test_hand_scheduled_kernels_stay_inside_their_tensors(name):
     """The kernels with inline-assembly loads compute their addresses from offsets worked out once per workgroup;
     this replays that arithmetic for every workgroup of the launch plan and checks each address against its tensor."""

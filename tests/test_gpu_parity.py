@@ -125,6 +125,9 @@ LARGE = {
     # remainder launch of 32-image tiles, both with clamped staging addresses beyond the batch
     "cfg3_b72": (wl.CONFIG_GEOM["cfg3"].with_batch(72), "pink"),
     "cfg3_b127": (wl.CONFIG_GEOM["cfg3"].with_batch(127), "pink"),
+    # 96 filters (three blocks of 32), patch rows of 60 values from 10 x 10 x 6 fields, batch 130 (three 64-image
+    # tiles, the last nearly empty): the forward kernel that loads x straight into LDS, with its remainder launch
+    "direct_f96": (wl.LCGeom(B=130, H=60, W=60, C=6, R=10, S=2, F=96), "halfnormal"),
     # 16 filters per field, eight fields per workgroup: rings of 8, 6 and 5 k-steps, and 48 filters (three blocks)
     "eight_u8": (wl.LCGeom(B=100, H=102, W=102, C=4, R=8, S=2, F=16), "halfnormal"),
     "eight_u6": (wl.LCGeom(B=100, H=100, W=100, C=3, R=8, S=2, F=16), "pink"),
