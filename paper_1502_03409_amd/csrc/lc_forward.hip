@@ -945,6 +945,24 @@ int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float 
                                                                  ntask - first, s);
             }
         }
+        // the same kernel on smaller layers of 32 filters, again with a ring as deep as the patch row: patch rows of
+        // 24 k-steps on 32-image tiles where those give a round of workgroups (55 x 55 x 16 input, 6 x 6 fields at
+        // stride 2, batch 128: 41.5 -> 34.5 us; a ring of 8 k-steps: 36.0 us), patch rows of 48 k-steps on 16-image
+        // tiles and one filter tile per wave where even 32-image tiles give less than a round (23 x 23 x 32 input,
+        // 81 fields: 23.4 -> 16.4 us; 32-image tiles 18.5 us)
+        if (g.F % 32 == 0 && g.F % 64 != 0) {
+            const int ntask = ((g.LW + 3) / 4) * g.LH;
+            if (g.B > 32 && forward_direct_fits<2, 4, 4, 24, 1, 7>(g) &&
+                (long long)ntask * ((g.B + 31) / 32) * (g.F / 32) >= kComputeUnits * kBigTilesPerCu) {
+                *done_out = true;
+                return launch_direct<2, 2, 4, 4, 24, 1, 7, 24, 2>(g, x, w, bias, alpha, alpha_dev, y, 0, ntask, s);
+            }
+            if (g.B > 16 && forward_direct_fits<1, 4, 4, 48, 1, 7>(g) &&
+                (long long)ntask * ((g.B + 31) / 32) * (g.F / 16) < kComputeUnits * kBigTilesPerCu) {
+                *done_out = true;
+                return launch_direct<1, 1, 4, 4, 48, 1, 7, 48, 2>(g, x, w, bias, alpha, alpha_dev, y, 0, ntask, s);
+            }
+        }
     }
     if (aligned && g.B > 16) {
         bool done = false;

@@ -401,7 +401,7 @@ def _x_strip_offsets_inside(g, BT, NRT, NSLOT, NTHR, RV, sq4, NLOC, strips, nbt,
                     assert a.min() >= 0 and a.max() + 4 <= g.B * img, (g, work, bt, q, kh)
 
 
-@pytest.mark.parametrize("name", ["cfg5_s1", "cfg5_s2", "cfg2", "cfg3", "stage_small"])
+@pytest.mark.parametrize("name", ["cfg5_s1", "cfg5_s2", "cfg5_s3", "cfg2", "cfg3", "stage_small"])
 def test_hand_scheduled_kernels_stay_inside_their_tensors(name):
     """The kernels with inline-assembly loads compute their addresses from offsets worked out once per workgroup;
     this replays that arithmetic for every workgroup of the launch plan and checks each address against its tensor."""
