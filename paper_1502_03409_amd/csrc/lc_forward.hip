@@ -964,6 +964,19 @@ int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float 
             }
         }
     }
+    if constexpr (sizeof(T) == 4) {
+        // Wide layers (filters in blocks of 128) whose patch row is 12 k-steps, the paper's
+        // first layer among them (Sec. 5: 16x16x3 patches): the LDS-direct kernel on 64-image
+        // tiles with the whole patch row's weights in flight.  Measured on that layer at
+        // batch 192: 4.69 ms against 5.03 ms for the register-staged kernel (80 % against
+        // 74 % of the fp32 MFMA peak); a ring half as deep gives the same, two patch rows
+        // per LDS round 4.73 ms.
+        if (g.F % 128 == 0 && g.B > 32 && forward_direct_fits<4, 2, 4, 12, 1, 4>(g)) {
+            *done_out = true;
+            return launch_direct<4, 4, 2, 4, 12, 1, 4, 12, 2>(g, x, w, bias, alpha, alpha_dev, y, 0,
+                                                              ((g.LW + 1) / 2) * g.LH, s);
+        }
+    }
     if (aligned && g.B > 16) {
         bool done = false;
         int rc = LC_OK;
