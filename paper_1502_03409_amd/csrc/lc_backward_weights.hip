@@ -6,6 +6,7 @@
 // B[b][f] lanes run along f.  Waves are independent: each owns one location, MTW tiles of 16 patch
 // elements and NT tiles of 16 filters, loops over the batch four images at a time and writes its
 // MTW x NT output tiles once.
+#include <type_traits>
 #include "lc_common.hpp"
 
 namespace lc {
@@ -142,6 +143,9 @@ __device__ __forceinline__ float vget(const typename VecT<N>::T &v, int i) {
 // SSQ: also leave, per location, block of patch elements and filter, the sum of squares of the values stored (a
 // code path of its own: the plain weight gradient carries none of it).
 template <int G, int VA, int NT, int PF, typename T = float, bool SSQ = false>
+// More waves per SIMD than the registers give by themselves do not pay: with 32 filters and blocks of 128 patch
+// elements, bounds of three and four waves per SIMD took 242 and 248-290 us against 221 us at two (the loads of
+// more waves in flight evict each other's lines from the vector cache).
 __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kernel(Geom g, const T *__restrict__ x1,
                                                                   const T *__restrict__ dy1,
                                                                   const T *__restrict__ x2,
@@ -161,7 +165,24 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
     const int m = lane & 15, kk = lane >> 4;
     const int task = remap_xcd(blockIdx.x, gridDim.x) * 4 + wave;
     if (task >= ntasks) return;
-    const int loc = task / kblocks, k0 = (task - loc * kblocks) * KB;
+    // Where a wave loads more of x than of dy per batch step (G * VA > NT), tasks are ordered field row by field row,
+    // inside a row block of patch elements by block, and the fields of the row innermost: the four waves of a
+    // workgroup, and the workgroups next to it on the same XCD, then read the same image rows at the same time
+    // (horizontally adjacent fields share (R-S)/R of their patch rows), and what one of them fetched the others find
+    // in the caches (K = 1200, 32 filters, 46 fields per row, batch 128: 219 -> 201 us).  Otherwise the blocks of a
+    // field are innermost and the waves of a workgroup share the field's dy (16 x 16 x 3 patches, 384 filters in
+    // tiles of 64: 4.90 ms against 4.98 ms in the other order).
+    int loc, k0;
+    if constexpr (G * VA > NT) {
+        const int per_row = g.LW * kblocks;
+        const int i = task / per_row, rr = task - i * per_row;
+        const int kb = rr / g.LW;
+        loc = i * g.LW + (rr - kb * g.LW);
+        k0 = kb * KB;
+    } else {
+        loc = task / kblocks;
+        k0 = (task - loc * kblocks) * KB;
+    }
     const int i = loc / g.LW, j = loc - i * g.LW;
     const int f0 = blockIdx.y * NT * 16;
     const size_t img = (size_t)g.H * g.W * g.C;
@@ -187,52 +208,75 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
 
     const int nsteps = g.B >> 2;                 // B % (4*PF) == 0 on this path
     const size_t xstep = 4 * img, dstep = (size_t)4 * g.L * g.F;
-    for (int p = 0; p < 2; ++p) {
-        const T *x = p ? x2 : x1;
-        const T *dy = p ? dy2 : dy1;
-        if (!x) break;
-        gfloat_ptr xa[G];
+    // The last block of a field may reach K before its G groups of VA tiles are used up (K = 1200 in blocks of 128:
+    // the tenth block holds 48 elements, one group).  Groups that lie wholly beyond K are neither loaded nor
+    // multiplied: GA of the G groups are live, the same for the whole wave.
+    auto contract = [&](auto ga_tag) {
+        constexpr int GA = decltype(ga_tag)::value;
+        for (int p = 0; p < 2; ++p) {
+            const T *x = p ? x2 : x1;
+            const T *dy = p ? dy2 : dy1;
+            if (!x) break;
+            gfloat_ptr xa[GA];
 #pragma unroll
-        for (int gg = 0; gg < G; ++gg) xa[gg] = (gfloat_ptr)x + ((size_t)kk * img + off[gg]);
-        gfloat_ptr da = (gfloat_ptr)dy + (((size_t)kk * g.L + loc) * g.F + f0 + NT * m);
-        AV a[PF][G];
-        BR bv[PF];
-        // ring prologue: steps 0 .. PF-1
-#pragma unroll
-        for (int ss = 0; ss < PF; ++ss) {
-#pragma unroll
-            for (int gg = 0; gg < G; ++gg) { a[ss][gg] = *(const GAV *)xa[gg]; xa[gg] += xstep; }
-            bv[ss] = *(const GBV *)da; da += dstep;
-        }
-        // steady state: consume slot ss, then refill it with step s+PF
-        for (int s0 = PF; s0 < nsteps; s0 += PF) {
+            for (int gg = 0; gg < GA; ++gg) xa[gg] = (gfloat_ptr)x + ((size_t)kk * img + off[gg]);
+            gfloat_ptr da = (gfloat_ptr)dy + (((size_t)kk * g.L + loc) * g.F + f0 + NT * m);
+            AV a[PF][GA];
+            BR bv[PF];
+            // ring prologue: steps 0 .. PF-1
 #pragma unroll
             for (int ss = 0; ss < PF; ++ss) {
 #pragma unroll
-                for (int gg = 0; gg < G; ++gg)
+                for (int gg = 0; gg < GA; ++gg) { a[ss][gg] = *(const GAV *)xa[gg]; xa[gg] += xstep; }
+                bv[ss] = *(const GBV *)da; da += dstep;
+            }
+            // steady state: consume slot ss, then refill it with step s+PF
+            for (int s0 = PF; s0 < nsteps; s0 += PF) {
+#pragma unroll
+                for (int ss = 0; ss < PF; ++ss) {
+#pragma unroll
+                    for (int gg = 0; gg < GA; ++gg)
+#pragma unroll
+                        for (int t = 0; t < VA; ++t)
+#pragma unroll
+                            for (int u = 0; u < NT; ++u)
+                                acc[gg][t][u] = mfma16(raw_get<T, VA>(a[ss][gg], t), raw_get<T, NT>(bv[ss], u), acc[gg][t][u]);
+#pragma unroll
+                    for (int gg = 0; gg < GA; ++gg) { a[ss][gg] = *(const GAV *)xa[gg]; xa[gg] += xstep; }
+                    bv[ss] = *(const GBV *)da; da += dstep;
+                    // keep the refill of slot ss right behind the MFMAs that consumed it: the loads then run
+                    // PF-1 slots ahead of their use instead of being sunk to the end of the iteration
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // drain
+#pragma unroll
+            for (int ss = 0; ss < PF; ++ss)
+#pragma unroll
+                for (int gg = 0; gg < GA; ++gg)
 #pragma unroll
                     for (int t = 0; t < VA; ++t)
 #pragma unroll
                         for (int u = 0; u < NT; ++u)
                             acc[gg][t][u] = mfma16(raw_get<T, VA>(a[ss][gg], t), raw_get<T, NT>(bv[ss], u), acc[gg][t][u]);
-#pragma unroll
-                for (int gg = 0; gg < G; ++gg) { a[ss][gg] = *(const GAV *)xa[gg]; xa[gg] += xstep; }
-                bv[ss] = *(const GBV *)da; da += dstep;
-                // keep the refill of slot ss right behind the MFMAs that consumed it: the loads then run
-                // PF-1 slots ahead of their use instead of being sunk to the end of the iteration
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
-        // drain
-#pragma unroll
-        for (int ss = 0; ss < PF; ++ss)
-#pragma unroll
-            for (int gg = 0; gg < G; ++gg)
-#pragma unroll
-                for (int t = 0; t < VA; ++t)
-#pragma unroll
-                    for (int u = 0; u < NT; ++u)
-                        acc[gg][t][u] = mfma16(raw_get<T, VA>(a[ss][gg], t), raw_get<T, NT>(bv[ss], u), acc[gg][t][u]);
+    };
+    const int ga = min(G, (g.K - k0 + VA * 16 - 1) / (VA * 16));
+    if constexpr (G == 1) {
+        contract(std::integral_constant<int, 1>{});
+    } else if constexpr (G == 2) {
+        if (ga == 2) contract(std::integral_constant<int, 2>{});
+        else contract(std::integral_constant<int, 1>{});
+    } else if constexpr (G == 3) {
+        if (ga == 3) contract(std::integral_constant<int, 3>{});
+        else if (ga == 2) contract(std::integral_constant<int, 2>{});
+        else contract(std::integral_constant<int, 1>{});
+    } else {
+        static_assert(G == 4, "groups per block");
+        if (ga == 4) contract(std::integral_constant<int, 4>{});
+        else if (ga == 3) contract(std::integral_constant<int, 3>{});
+        else if (ga == 2) contract(std::integral_constant<int, 2>{});
+        else contract(std::integral_constant<int, 1>{});
     }
 
     float *ol = out + (size_t)loc * g.K * g.F + f0 + NT * m;
