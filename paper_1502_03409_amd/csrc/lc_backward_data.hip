@@ -1014,7 +1014,12 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
         } else if (ap == 5) {
             // fp32, filters in blocks of 32: whole-line chunks (5 x 5 covering fields, 104 x 104 x 12 input, batch 128: 243 -> 233 us;
             // on a 200 x 200 x 3 input under 46 x 46 fields of 32 filters the kernel that loads dy straight into LDS takes
-            // 224 us against this one's 220, with 128-image tiles 263 us (two buffers) and 278 us (one))
+            // 224 us against this one's 220, with 128-image tiles 263 us (two buffers) and 278 us (one); on 64-image
+            // tiles with one buffer 229 us at two or three waves per SIMD, with eight cells per workgroup 235 us; with
+            // twelve waves (four cells x three tiles of cell values, each wave all 128 images, so that every weight is
+            // requested once) 235 us: 650 workgroups, one per compute unit, are three rounds where the work is 2.3.
+            // Reading a step's weights as whole lines per quad of lanes (a timing build, the values in the wrong
+            // lanes) was no faster either: 229 us)
             if constexpr (sizeof(T) == 4) {
                 if (ntt <= 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 5, 2>(g, (const float *)dy, (const float *)w, dx, s); }
             }
