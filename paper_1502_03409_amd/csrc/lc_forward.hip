@@ -941,6 +941,7 @@ int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float 
                 if (int rc = launch_direct<4, 2, 4, 4, 15, 1, 7, 15, 2>(g, x, w, bias, alpha, alpha_dev, y, 0, first, s))
                     return rc;
                 if (first == ntask) return LC_OK;
+                // (the rest on 16-image tiles instead, 320 workgroups: 189 against 187 us)
                 return launch_direct<2, 2, 4, 4, 15, 1, 4, 15, 2>(g, x, w, bias, alpha, alpha_dev, y, first,
                                                                  ntask - first, s);
             }
