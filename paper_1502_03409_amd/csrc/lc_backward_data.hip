@@ -1019,7 +1019,9 @@ int launch_backward_data_fast_path(const Geom &g, const T *dy, const T *w, float
             // twelve waves (four cells x three tiles of cell values, each wave all 128 images, so that every weight is
             // requested once) 235 us: 650 workgroups, one per compute unit, are three rounds where the work is 2.3.
             // Reading a step's weights as whole lines per quad of lanes (a timing build, the values in the wrong
-            // lanes) was no faster either: 229 us)
+            // lanes) was no faster either: 229 us.  Nor does the launch lose much to its last, partly filled round of
+            // workgroups: with the 1024 workgroups of two whole rounds in one launch (180 us) and the other full-cost
+            // pairs and the edge rows in a second one on 32-image tiles (50 us) the layer took 226 us.)
             if constexpr (sizeof(T) == 4) {
                 if (ntt <= 3 && g.F % 32 == 0) { *done = true; return launch_line<4, 3, 4, 5, 2>(g, (const float *)dy, (const float *)w, dx, s); }
             }
