@@ -91,6 +91,11 @@ SMALL = {
     "bd_line_c1": (wl.LCGeom(B=64, H=40, W=30, C=1, R=10, S=2, F=32), "gaussian"),      # 4-value cells: one partly used tile
     "bd_line_f64": (wl.LCGeom(B=72, H=32, W=28, C=3, R=20, S=4, F=64), "pink"),         # two blocks of 32 filters per field row
     "bd_line4_f96": (wl.LCGeom(B=66, H=32, W=40, C=3, R=16, S=4, F=96), "pink"),        # 4x4 covering fields, three blocks of 32 filters
+    # weight gradient: last block of patch elements with fewer live groups of tiles than the others (skipped, not
+    # padded): K = 180 in blocks of 4 groups of 32, K = 36 and K = 400 in blocks of 2 groups of 64
+    "bw_groups_va2": (wl.LCGeom(B=16, H=20, W=22, C=5, R=6, S=2, F=32), "pink"),
+    "bw_groups_f16": (wl.LCGeom(B=32, H=15, W=17, C=4, R=3, S=2, F=16), "gaussian"),
+    "bw_groups_k400": (wl.LCGeom(B=48, H=22, W=26, C=4, R=10, S=2, F=32), "halfnormal"),
 }
 
 
