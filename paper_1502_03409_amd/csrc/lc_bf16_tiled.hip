@@ -455,9 +455,12 @@ __global__ __launch_bounds__(256, 2) void lc_bwd_weights_bf16_tiled_kernel(Geom 
                 if (beta != 0.f) {
                     v0 += beta * o[0];
                     v1 += beta * o[16];
+                    o[0] = v0;
+                    o[16] = v1;
+                } else {
+                    stream_store(v0, &o[0]);
+                    stream_store(v1, &o[16]);
                 }
-                o[0] = v0;
-                o[16] = v1;
                 // keeps the read-modify-write of one row from being hoisted over the others' (registers)
                 __builtin_amdgcn_sched_barrier(0);
             }

@@ -171,6 +171,13 @@ __device__ __forceinline__ f32x4 mfma16_bf16(u32x2 a, u32x2 b, f32x4 c) {
                                                      0, 0, 0);
 }
 
+// A store whose line nobody reads again soon (a weight gradient far larger than the caches, written once): marked
+// non-temporal, so that it does not push the kernel's operands out of the L2 and the Infinity Cache on its way out.
+template <typename V>
+__device__ __forceinline__ void stream_store(const V &v, V *p) {
+    __builtin_nontemporal_store(v, p);
+}
+
 void set_hip_error(hipError_t e, const char *where);
 void set_error_text(const char *text);
 
