@@ -126,8 +126,8 @@ def test_lc_primitives_match_oracle(name):
 LARGE = {
     "cfg3": (wl.CONFIG_GEOM["cfg3"], "pink"),
     "cfg4": (wl.CONFIG_GEOM["cfg4"], "halfnormal"),
-    # the grid of cfg3 with ragged batches: the forward pass runs as a main launch of 128-image tiles plus a
-    # remainder launch of 32-image tiles, both with clamped staging addresses beyond the batch
+    # the grid of cfg3 with ragged batches: the forward pass runs as a main launch of 64-image tiles plus a
+    # remainder launch of 32-image tiles, both with addresses clamped into x beyond the batch
     "cfg3_b72": (wl.CONFIG_GEOM["cfg3"].with_batch(72), "pink"),
     "cfg3_b127": (wl.CONFIG_GEOM["cfg3"].with_batch(127), "pink"),
     # 96 filters (three blocks of 32), patch rows of 60 values from 10 x 10 x 6 fields, batch 130 (three 64-image
