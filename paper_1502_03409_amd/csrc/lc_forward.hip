@@ -974,7 +974,11 @@ int launch_forward_fast_path(const Geom &g, const T *x, const T *w, const float 
         // batch 192: 4.69 ms against 5.03 ms for the register-staged kernel (80 % against
         // 74 % of the fp32 MFMA peak); a ring half as deep gives the same, two patch rows
         // per LDS round 4.73 ms.
-        if (g.F % 128 == 0 && g.B > 32 && forward_direct_fits<4, 2, 4, 12, 1, 4>(g)) {
+        // Only where its workgroups (a pair of fields x 64 images x 128 filters) fill two rounds of the chip:
+        // smaller layers keep the register-staged kernel, which steps down to smaller tiles.
+        const long long wide_wgs = (long long)((g.LW + 1) / 2) * g.LH * ((g.B + 63) / 64) * (g.F / 128);
+        if (g.F % 128 == 0 && g.B > 32 && wide_wgs >= 2 * kComputeUnits * kBigTilesPerCu &&
+            forward_direct_fits<4, 2, 4, 12, 1, 4>(g)) {
             *done_out = true;
             return launch_direct<4, 4, 2, 4, 12, 1, 4, 12, 2>(g, x, w, bias, alpha, alpha_dev, y, 0,
                                                               ((g.LW + 1) / 2) * g.LH, s);

@@ -133,9 +133,10 @@ LARGE = {
     # 96 filters (three blocks of 32), patch rows of 60 values from 10 x 10 x 6 fields, batch 130 (three 64-image
     # tiles, the last nearly empty): the forward kernel that loads x straight into LDS, with its remainder launch
     "direct_f96": (wl.LCGeom(B=130, H=60, W=60, C=6, R=10, S=2, F=96), "halfnormal"),
-    # the first layer's field (16 x 16 x 3, stride 4) with 256 filters on a 13 x 13 grid (odd: the last strip of
-    # two fields is half empty) and batch 70 (a 64-image tile and a ragged one): the same kernel on blocks of 128
-    "direct_f256": (wl.LCGeom(B=70, H=64, W=64, C=3, R=16, S=4, F=256), "pink"),
+    # the first layer's field (16 x 16 x 3, stride 4) with 256 filters on a 23 x 23 grid (odd: the last strip of
+    # two fields is half empty; large enough for two rounds of workgroups, below which the layer keeps the
+    # register-staged kernel) and batch 70 (a 64-image tile and a ragged one): the same kernel on blocks of 128
+    "direct_f256": (wl.LCGeom(B=70, H=104, W=104, C=3, R=16, S=4, F=256), "pink"),
     # 16 filters per field, eight fields per workgroup: rings of 8, 6 and 5 k-steps, and 48 filters (three blocks)
     "eight_u8": (wl.LCGeom(B=100, H=102, W=102, C=4, R=8, S=2, F=16), "halfnormal"),
     "eight_u6": (wl.LCGeom(B=100, H=100, W=100, C=3, R=8, S=2, F=16), "pink"),
