@@ -172,7 +172,8 @@ __global__ __launch_bounds__(256, G == 3 ? 2 : 1) void lc_bwd_weights_fast_kerne
     // in the caches (K = 1200, 32 filters, 46 fields per row, batch 128: 219 -> 201 us).  Otherwise the blocks of a
     // field are innermost and the waves of a workgroup share the field's dy (16 x 16 x 3 patches, 384 filters in
     // tiles of 64: 4.90 ms against 4.98 ms in the other order).  Ordering the tasks so that vertically adjacent
-    // fields' blocks over the same image rows also run together (blocks 2 i + kb in turn) took 323 us.
+    // fields' blocks over the same image rows also run together (blocks 2 i + kb in turn) took 323 us; workgroups of
+    // two, eight and sixteen waves instead of four 207, 218 and 239 us.
     int loc, k0;
     if constexpr (G * VA > NT) {
         const int per_row = g.LW * kblocks;
